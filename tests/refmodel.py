@@ -1,0 +1,240 @@
+"""Independent checkers for the CPU oracle.
+
+Nothing here calls the oracle or the HIP library.  The Transducer is evaluated
+with PyTorch CPU library routines in float64 (``LSTMCell``, ``linear``,
+``log_softmax``), and the search space is walked exhaustively: every alignment
+of the lattice is enumerated and summed per transcript, which is what a beam
+search that prunes nothing must reproduce (hypotheses with identical
+transcripts are merged: Methods, first paragraph, and Sec. 2.1 of the paper).
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+
+def logaddexp(a, b):
+    if a == -math.inf:
+        return b
+    if b == -math.inf:
+        return a
+    m = max(a, b)
+    return m + math.log(math.exp(a - m) + math.exp(b - m))
+
+
+class RefModel:
+    """float64 Transducer built from library layers."""
+
+    def __init__(self, c, w):
+        self.c = c
+        self.V = c["V"]
+        self.nd = len(c["durations"])
+        t = lambda a: torch.tensor(np.asarray(a), dtype=torch.float64)
+        self.W_enc, self.b_enc = t(w["W_enc"]), t(w["b_enc"])
+        self.W_pred, self.b_pred = t(w["W_pred"]), t(w["b_pred"])
+        self.W_out, self.b_out = t(w["W_out"]), t(w["b_out"])
+        self.emb = t(w["emb"])
+        if c["pred"] == "lstm":
+            cell = torch.nn.LSTMCell(c["E"], c["P"]).double()
+            with torch.no_grad():
+                cell.weight_ih.copy_(t(w["W_ih"]))
+                cell.weight_hh.copy_(t(w["W_hh"]))
+                cell.bias_ih.copy_(t(w["b_ih"]))
+                cell.bias_hh.copy_(t(w["b_hh"]))
+            self.cell = cell
+        self._pred_cache = {}
+
+    def f_proj(self, enc_t):
+        return torch.nn.functional.linear(torch.tensor(np.asarray(enc_t), dtype=torch.float64),
+                                          self.W_enc, self.b_enc)
+
+    def pred(self, tokens: tuple):
+        """Prediction-network output (after W_pred) and state for a transcript."""
+        if tokens in self._pred_cache:
+            return self._pred_cache[tokens]
+        c = self.c
+        with torch.no_grad():
+            if c["pred"] == "lstm":
+                if len(tokens) == 0:
+                    h0 = torch.zeros(1, c["P"], dtype=torch.float64)
+                    state = self.cell(self.emb[self.V][None], (h0, h0.clone()))
+                else:
+                    _, prev = self.pred(tokens[:-1])
+                    state = self.cell(self.emb[tokens[-1]][None], prev)
+                h = state[0][0]
+            else:
+                h = torch.zeros(c["P"], dtype=torch.float64)
+                for i in range(c["ctx"]):
+                    tok = tokens[len(tokens) - 1 - i] if len(tokens) - 1 - i >= 0 else self.V
+                    h = h + self.emb[i, tok]
+                state = None
+            g = torch.nn.functional.linear(h, self.W_pred, self.b_pred)
+        self._pred_cache[tokens] = (g, state)
+        return g, state
+
+    def logp(self, f_t, tokens: tuple):
+        """(token log-probs [V+1], duration log-probs [nd] or None)"""
+        g, _ = self.pred(tokens)
+        with torch.no_grad():
+            z = torch.nn.functional.linear(torch.relu(f_t + g), self.W_out, self.b_out)
+            lp = torch.log_softmax(z[: self.V + 1], dim=0).numpy()
+            dl = torch.log_softmax(z[self.V + 1:], dim=0).numpy() if self.nd else None
+        return lp, dl
+
+
+class TableModel:
+    """Log-probabilities read from a table [T, C, V+1] by class = hash mod C
+    (mirrors the injected mode of the decoders)."""
+
+    def __init__(self, tok, dur, V, hash_fn):
+        self.tok, self.dur, self.V, self.hash_fn = tok, dur, V, hash_fn
+        self.C = tok.shape[1]
+
+    def logp_at(self, t, tokens):
+        cls = self.hash_fn(tokens) % self.C
+        return (self.tok[t, cls].astype(np.float64),
+                None if self.dur is None else self.dur[t, cls].astype(np.float64))
+
+
+def py_hash(tokens, base=1000003, mod=2 ** 31 - 1):
+    """Eq. (1) with arbitrary-precision integers; token fed as v + 1."""
+    h = 0
+    for v in tokens:
+        h = (h * base + (v + 1)) % mod
+    return h
+
+
+def duration_rule(dlogp, durations):
+    """The decoders' reading for TDT: tokens take the most likely duration, blank
+    the most likely one that advances at least a frame (ties -> first)."""
+    best = int(np.argmax(dlogp))
+    ok = [i for i, d in enumerate(durations) if d >= 1]
+    best_b = ok[int(np.argmax([dlogp[i] for i in ok]))]
+    return durations[best], dlogp[best], durations[best_b], dlogp[best_b]
+
+
+def enumerate_alignments(logp_fn, T, V, s, durations=()):
+    """Sum of alignment probabilities per transcript, by depth-first enumeration.
+
+    ``logp_fn(t, tokens) -> (logp [V+1], dlogp or None)``.  An alignment ends
+    when it has consumed T frames; at most ``s`` tokens are emitted without
+    leaving a frame, after which only blank is possible (with its own
+    log-probability).  Returns {transcript tuple: log-sum}.
+    """
+    totals = {}
+
+    def rec(t, toks, sym, lp):
+        if t >= T:
+            totals[toks] = logaddexp(totals.get(toks, -math.inf), lp)
+            return
+        logp, dlogp = logp_fn(t, toks)
+        if durations:
+            adv_tok, x_tok, adv_blank, x_blank = duration_rule(dlogp, durations)
+        else:
+            adv_tok, x_tok, adv_blank, x_blank = 0, 0.0, 1, 0.0
+        rec(min(t + adv_blank, T), toks, 0, lp + logp[V] + x_blank)
+        if sym < s:
+            for v in range(V):
+                rec(min(t + adv_tok, T), toks + (v,), sym + 1 if adv_tok == 0 else 0, lp + logp[v] + x_tok)
+
+    rec(0, (), 0, 0.0)
+    return totals
+
+
+def forward_dp(logp_fn, T, V, s, y):
+    """Transducer forward variable for one transcript y with at most s tokens per
+    frame: alpha[t][u][c] = log-probability of having emitted y[:u], standing at
+    frame t, with c tokens emitted in it.  Blank: (t,u,c)->(t+1,u,0); token:
+    (t,u,c)->(t,u+1,c+1) if c < s.  Returns log P(y) = alpha[T][U][0]."""
+    U = len(y)
+    NEG = -math.inf
+    alpha = [[[NEG] * (s + 1) for _ in range(U + 1)] for _ in range(T + 1)]
+    alpha[0][0][0] = 0.0
+    for t in range(T):
+        for u in range(U + 1):
+            logp, _ = logp_fn(t, tuple(y[:u]))
+            for c in range(s + 1):
+                a = alpha[t][u][c]
+                if a == NEG:
+                    continue
+                alpha[t + 1][u][0] = logaddexp(alpha[t + 1][u][0], a + logp[V])
+                if u < U and c < s:
+                    alpha[t][u + 1][c + 1] = logaddexp(alpha[t][u + 1][c + 1], a + logp[y[u]])
+    return alpha[T][U][0]
+
+
+def greedy(logp_fn, T, V, s, durations=()):
+    """Standalone greedy decoder: per frame take the argmax, at most s tokens
+    before blank is forced (with its own log-probability)."""
+    t, toks, sym, score = 0, (), 0, 0.0
+    while t < T:
+        logp, dlogp = logp_fn(t, toks)
+        if durations:
+            adv_tok, x_tok, adv_blank, x_blank = duration_rule(dlogp, durations)
+        else:
+            adv_tok, x_tok, adv_blank, x_blank = 0, 0.0, 1, 0.0
+        cand = logp.copy()
+        cand[:V] += x_tok
+        cand[V] += x_blank
+        v = int(np.argmax(cand)) if sym < s else V
+        score += cand[v]
+        if v == V:
+            t, sym = t + adv_blank, 0
+        else:
+            toks = toks + (v,)
+            sym = sym + 1 if adv_tok == 0 else 0
+            t += adv_tok
+    return toks, score
+
+
+def dict_lm(lm):
+    """{(tokens...): (log10 p, log10 backoff)}"""
+    d = {}
+    for row, n, p, b in zip(lm["tokens"], lm["order"], lm["log10_prob"], lm["log10_backoff"]):
+        d[tuple(int(x) for x in row[:n])] = (float(p), float(b))
+    return d
+
+
+def dict_lm_score(d, ctx: tuple, v: int) -> float:
+    """ARPA back-off in log10 with a dictionary of tuples."""
+    if ctx + (v,) in d:
+        return d[ctx + (v,)][0]
+    if not ctx:
+        return -99.0
+    bo = d[ctx][1] if ctx in d else 0.0
+    return bo + dict_lm_score(d, ctx[1:], v)
+
+
+def aes_frame_synchronous(logp_fn, T, V, s, K):
+    """Frame-synchronous expansion search written as the classical two-set loop
+    (Sec. 2.2, "AES"): per frame, hypotheses still emitting in the frame (open)
+    are expanded round by round, those that emitted blank (closed) wait for the
+    frame to end; every round keeps the K best of all expansions and waiting
+    hypotheses, then merges equal transcripts among the waiting ones.  At most
+    s tokens per frame; no prune margin.  Returns {transcript: score}."""
+    closed = {(): 0.0}
+    for t in range(T):
+        open_, closed = closed, {}
+        for rnd in range(s + 1):
+            if not open_:
+                break
+            cands = []
+            for toks, sc in open_.items():
+                logp, _ = logp_fn(t, toks)
+                cands.append((sc + logp[V], "closed", toks))
+                if rnd < s:
+                    for v in range(V):
+                        cands.append((sc + logp[v], "open", toks + (v,)))
+            for toks, sc in closed.items():
+                cands.append((sc, "closed", toks))
+            cands.sort(key=lambda x: -x[0])
+            open_, closed = {}, {}
+            for sc, kind, toks in cands[:K]:
+                if kind == "open":
+                    assert toks not in open_
+                    open_[toks] = sc
+                else:
+                    closed[toks] = logaddexp(closed.get(toks, -math.inf), sc)
+    return closed

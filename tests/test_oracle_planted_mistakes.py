@@ -1,0 +1,60 @@
+"""Each plausible mistake, planted in a private copy of the oracle's source and
+compiled on the CPU, must make at least one pin fail.  This is the evidence that
+the pins constrain every part of the oracle and not only its happy path."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "rnnt_oracle.c")
+
+MISTAKES = [
+    ("merge key without the symbols-in-frame count",
+     "nxt[i].t == nxt[j].t && nxt[i].sym == nxt[j].sym", "nxt[i].t == nxt[j].t"),
+    ("merge keeps the maximum instead of the log-sum",
+     "nxt[i].score = logaddexp(nxt[i].score, nxt[j].score);",
+     "nxt[i].score = nxt[i].score > nxt[j].score ? nxt[i].score : nxt[j].score;"),
+    ("frame limit off by one", "const int forced = hy->sym >= s;", "const int forced = hy->sym > s;"),
+    ("symbol counter not reset when a TDT token advances",
+     "nh->sym = adv_tok[k] == 0 ? nh->sym + 1 : 0;", "nh->sym = nh->sym + 1;"),
+    ("blank takes the tokens' duration", "tot[V] += dl[best_b];", "tot[V] += dl[best];"),
+    ("frame index not clamped", "if (nh->t > T_b) nh->t = T_b;", ""),
+    ("AES waiting rule dropped", "int active = hy->t < T_b && (J->algo == 0 || hy->t == t_cur);",
+     "int active = hy->t < T_b;"),
+    ("recurrent bias dropped", "gate[q] = gi[r] + (double)w->b_ih[r] + gh[r] + (double)w->b_hh[r];",
+     "gate[q] = gi[r] + (double)w->b_ih[r] + gh[r];"),
+    ("forget and input gates swapped", "double cn = fg * c_in[p] + ig * gg;", "double cn = ig * c_in[p] + fg * gg;"),
+    ("ReLU dropped", "a[j] = opnd(c, s > 0.0 ? s : 0.0);", "a[j] = opnd(c, s);"),
+    ("blank not rescored under fusion", "tot[V] = (lm && c->lm_rule != 3) ? (1.0 + lambda) * logp[V] : logp[V];",
+     "tot[V] = logp[V];"),
+    ("non-blank mass term dropped", "else tot[v] = logp[v] + lambda * (nb + lm[v]);",
+     "else tot[v] = logp[v] + lambda * lm[v];"),
+    ("back-off weight ignored", "double bo = c >= 0 ? (double)lm->backoff[c] : 0.0;", "double bo = 0.0;"),
+    ("back-off drops the newest token instead of the oldest", "return bo + lm_q10(lm, ctx + 1, n - 1, v);",
+     "return bo + lm_q10(lm, ctx, n - 1, v);"),
+    ("hash feeds the raw token", "(uint64_t)nh->hash * ORC_HASH_BASE + (uint64_t)(v + 1)",
+     "(uint64_t)nh->hash * ORC_HASH_BASE + (uint64_t)(v)"),
+    ("ties broken by the higher index", "return x->idx < y->idx ? -1 : (x->idx > y->idx ? 1 : 0);",
+     "return x->idx > y->idx ? -1 : (x->idx < y->idx ? 1 : 0);"),
+    ("prune margin applied to the fused score's maximum only for tokens", "for (int v = 0; v <= V; ++v)\n      if (logp[v] < mx - c->gamma) tot[v] = -INFINITY;",
+     "for (int v = 0; v < V; ++v)\n      if (logp[v] < mx - c->gamma) tot[v] = -INFINITY;"),
+    ("bf16 rounding truncates", "u += 0x7fffu + lsb;", "u += 0;"),
+]
+
+
+@pytest.mark.parametrize("name,old,new", MISTAKES, ids=[m[0] for m in MISTAKES])
+def test_planted_mistake_is_caught(tmp_path, name, old, new):
+    src = open(SRC).read()
+    assert src.count(old) >= 1, "the oracle's source changed: update this mistake"
+    mutated = tmp_path / "mutated.c"
+    mutated.write_text(src.replace(old, new, 1))
+    lib = tmp_path / "libmutated.so"
+    subprocess.check_call(["gcc", "-O1", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", str(lib), str(mutated),
+                           "-lm"])
+    env = dict(os.environ, RNNT_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                        "-p", "no:cacheprovider"], env=env, cwd=ROOT, capture_output=True, text=True)
+    assert r.returncode != 0, f"no pin noticed: {name}"
+    assert "failed" in r.stdout
