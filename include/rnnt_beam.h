@@ -1,0 +1,179 @@
+/*
+ * rnnt_beam: batched beam search (ALSD++ / AES++) for RNN-T and TDT Transducers
+ * on one AMD MI355X (gfx950).  C ABI; every step of the decoding path runs in
+ * HIP kernels inside the library.
+ *
+ * Problem statement (paper, Methods and Sec. 2.1-2.3): given the encoder output
+ * of a batch of audio streams and a Transducer (prediction network + joint
+ * network), optionally an n-gram LM over the same vocabulary with weight
+ * lambda, keep exactly `beam` hypotheses per stream, expand / merge / prune them
+ * step by step, and return the `beam` best transcripts per stream.
+ *
+ * Conventions
+ *   - Return value 0 = success, negative = error (see RNNT_E_*).  No exception or
+ *     abort crosses this boundary; rnnt_beam_last_error() gives a message.
+ *   - "device" pointers are HIP device memory on the current device, "host"
+ *     pointers ordinary host memory.  All matrices are row-major float32.
+ *   - Token ids are 0..V-1, blank is V.  TDT duration logits follow the blank.
+ *   - The caller owns every array it passes in.  Weights and LM arrays are
+ *     re-packed into library-owned device memory by the create calls and may be
+ *     freed afterwards.  The handle owns workspace, hypothesis tree and graphs.
+ *   - H, P, D and E must be multiples of 32; beam <= 16.
+ */
+#ifndef RNNT_BEAM_H
+#define RNNT_BEAM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rnnt_beam rnnt_beam_t; /* opaque decoder handle */
+typedef struct rnnt_lm rnnt_lm_t;     /* opaque n-gram LM */
+
+typedef enum { RNNT_ALSD = 0, RNNT_AES = 1 } rnnt_algo_t;
+typedef enum { RNNT_MODEL_RNNT = 0, RNNT_MODEL_TDT = 1 } rnnt_model_t;
+typedef enum { RNNT_PRED_LSTM = 0, RNNT_PRED_STATELESS = 1 } rnnt_pred_t;
+typedef enum { RNNT_F32 = 0, RNNT_BF16_JOINT = 1 } rnnt_prec_t;
+
+enum {
+  RNNT_OK = 0,
+  RNNT_E_ARG = -1,       /* bad argument, or a shape beyond max_B / max_T / max_beam */
+  RNNT_E_NOMEM = -2,     /* device or host allocation failed */
+  RNNT_E_HIP = -3,       /* a HIP call failed */
+  RNNT_E_NONFINITE = -4, /* NaN or Inf found in the encoder projection of the last decode */
+  RNNT_E_NORESULT = -5   /* results requested before any decode */
+};
+
+/* Plain data, versioned by struct_size (= sizeof(rnnt_config_t)). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t model;             /* rnnt_model_t */
+  int32_t pred;              /* rnnt_pred_t */
+  int32_t prec;              /* rnnt_prec_t: RNNT_BF16_JOINT rounds the operands of the three
+                                joint-network products (W_enc, W_pred, W_out and their inputs)
+                                to bfloat16; sums, soft-max and the LSTM stay float32 */
+  int32_t D, H, P, E, V;     /* encoder dim, joint hidden, prediction hidden, embedding dim, tokens */
+  int32_t n_durations;       /* TDT: number of duration classes (<= 8), else 0 */
+  int32_t durations[8];      /* TDT: frames advanced by each class, e.g. {0,1,2,3,4} */
+  int32_t stateless_context; /* stateless prediction network: tokens of context (<= 4) */
+  int32_t max_B, max_T, max_beam; /* workspace sizing */
+  int32_t max_symbols;       /* s: most tokens a hypothesis may emit without leaving a frame
+                                (Sec. 2.2, "a maximum of s expansions per frame") */
+  float prune_margin;        /* AES++ only: a token whose log-probability is more than this below
+                                the best one of its hypothesis is not expanded; INFINITY = off */
+  int32_t use_graph;         /* 1: replay the per-step kernels as a captured HIP graph (Sec. 2.1,
+                                "CUDA Graphs"); 0: launch them one by one */
+} rnnt_config_t;
+
+/* Device pointers, float32, caller-owned.  Unused ones may be NULL. */
+typedef struct {
+  const float *W_enc;  /* [H, D]   encoder projection of the joint */
+  const float *b_enc;  /* [H] */
+  const float *W_pred; /* [H, P]   prediction projection of the joint */
+  const float *b_pred; /* [H] */
+  const float *W_out;  /* [V+1+n_durations, H] output layer of the joint */
+  const float *b_out;  /* [V+1+n_durations] */
+  const float *emb;    /* LSTM: [V+1, E] (row V = start symbol); stateless: [ctx, V+1, P] */
+  const float *W_ih;   /* [4P, E]  LSTM, gate order (i, f, g, o) */
+  const float *W_hh;   /* [4P, P] */
+  const float *b_ih;   /* [4P] */
+  const float *b_hh;   /* [4P] */
+} rnnt_weights_t;
+
+/*
+ * Create a decoder.  Joint network: z = W_out ReLU(W_enc enc_t + b_enc + W_pred h + b_pred) + b_out,
+ * token log-probabilities = log-softmax of z[0..V], TDT durations = log-softmax of the rest.
+ * Prediction network: one LSTM layer fed with emb[last token], or the sum of
+ * position-specific embeddings of the last `stateless_context` tokens.
+ * Weights are re-packed (and folded where possible) on the device.
+ */
+int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *weights, rnnt_beam_t **out);
+
+/*
+ * Build an n-gram LM (ARPA semantics, Sec. 2.3 "Language model fusion") from host arrays:
+ * n n-grams, ngram_tokens [n, order] padded with -1 on the right, ngram_order [n] in 1..order,
+ * log10 probability and log10 back-off weight of each.  Every unigram must be present.
+ * Score of token v after a transcript: p(ctx v) if stored, else backoff(ctx) + score with the
+ * oldest context token dropped; ctx = the last order-1 tokens.  The table is stored on the
+ * device as a hash of contexts with successor lists.
+ */
+int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const int8_t *ngram_order,
+                   const float *log10_prob, const float *log10_backoff, int32_t V, rnnt_lm_t **out);
+
+/*
+ * Decode a batch (Sec. 2.1-2.3).  enc: device [B, T, D]; lengths: device [B] frames per utterance
+ * (values outside 0..T are clamped and reported as RNNT_E_ARG by rnnt_beam_results).
+ * algo: RNNT_ALSD (length-synchronous, every unfinished hypothesis is expanded at every step) or
+ * RNNT_AES (frame-synchronous, hypotheses that left the frame wait for the others).
+ * lm may be NULL; with an LM the fused score is Eq. (4) of the paper (blank scored as
+ * (1 + lambda) ln p(blank), tokens as ln p + lambda ln((1 - p(blank)) p_LM)), combined before the
+ * beam is cut (late pruning).  An LM together with a finite prune_margin is rejected.
+ * Work is enqueued on hip_stream (a hipStream_t, NULL = default stream); the call returns once
+ * the data-dependent number of steps has been enqueued.  Results stay valid until the next decode.
+ */
+int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T,
+                     int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream);
+
+/*
+ * Wait for the last decode and copy its n-best lists to host memory: tokens [B, beam, cap]
+ * (positions beyond the length are left untouched; transcripts longer than cap are truncated),
+ * lens [B, beam] (-1 for an empty slot), scores [B, beam] (log-probability, -inf for an empty
+ * slot), n_steps [B] (beam-search steps each utterance took).  Hypotheses are ordered by
+ * (score descending, slot ascending).  Any pointer may be NULL.
+ */
+int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *lens, double *scores,
+                      int32_t *n_steps);
+
+/*
+ * Test hook: decode with the joint and prediction networks bypassed.  Hypothesis (b, k) standing at
+ * frame t reads token log-probabilities tok_logp[b, t, c, 0..V] and duration log-probabilities
+ * dur_logp[b, t, c, :] (NULL for RNN-T) with class c = hash_k mod C, where hash_k is the rolling
+ * hash of Eq. (1).  Both arrays are device float32 and are taken as already normalised.
+ */
+int rnnt_beam_decode_injected(rnnt_beam_t *h, const float *tok_logp, const float *dur_logp, int32_t C,
+                              const int32_t *lengths, int32_t B, int32_t T, int32_t beam, int32_t algo,
+                              void *hip_stream);
+
+/*
+ * Test hook: the hypothesis tree of the last decode (Sec. 2.1, "Efficient hypothesis storing"),
+ * copied to host arrays [S, B, beam] with S = max over n_steps: for the slot filled at that step,
+ * the parent slot at the previous step (-1 = empty slot), the token appended (>= 0), -1 for blank,
+ * -2 for a waiting hypothesis, -3 for an empty slot, and the slot it was merged into by
+ * recombination (itself if it survived, -1 if empty).  Entries of steps an utterance did not take
+ * are -9.  Pointers may be NULL; s_cap = rows available in the arrays.
+ */
+int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t *merged_into, int32_t s_cap);
+
+/*
+ * Test hooks for single stages, all device float32, synchronous:
+ *   rnnt_beam_debug_encproj : f_proj [B*T, H] of the last decode is copied to host `out`.
+ *   rnnt_beam_debug_lm      : LM scores (natural log) of every token after each of n contexts;
+ *                             ctx_tokens host [n, order-1], most recent token first, -1 = none;
+ *                             out host [n, V].
+ */
+int rnnt_beam_debug_encproj(rnnt_beam_t *h, float *out, int64_t n_floats);
+int rnnt_lm_debug_query(const rnnt_lm_t *lm, const int32_t *ctx_tokens, int32_t n, float *out);
+
+/* Time, in milliseconds, between the first and the last kernel of the last decode (HIP events on
+ * the decode's stream); negative if unavailable.  Synchronises. */
+float rnnt_beam_last_decode_ms(rnnt_beam_t *h);
+
+/*
+ * Per-kernel timing of the last decode, measured with HIP events on the decode's stream when
+ * profiling was switched on with rnnt_beam_set_profiling(h, 1) (plain launches are used instead
+ * of the graph for that decode).  names: up to n_cap pointers to static strings; ms / calls:
+ * total milliseconds and launch count per kernel.  Returns the number of kernels, or < 0.
+ */
+int rnnt_beam_set_profiling(rnnt_beam_t *h, int32_t on);
+int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_t *calls, int32_t n_cap);
+
+const char *rnnt_beam_last_error(const rnnt_beam_t *h); /* NULL handle: error of the last failed create */
+void rnnt_beam_destroy(rnnt_beam_t *h);
+void rnnt_lm_destroy(rnnt_lm_t *lm);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNNT_BEAM_H */

@@ -150,11 +150,12 @@ def decode(c: dict, w: dict | None, enc, lengths, beam=None, algo=None, lm: LM |
     lens = np.zeros((B, beam), np.int32)
     scores = np.zeros((B, beam), np.float64)
     n_steps = np.zeros(B, np.int32)
-    lp = lt = lm_ = None
+    lp = lt = lm_ = lg = None
     if log:
         lp = np.full((B, S_cap, beam), -9, np.int32)
         lt = np.full((B, S_cap, beam), -9, np.int32)
         lm_ = np.full((B, S_cap, beam), -9, np.int32)
+        lg = np.full((B, S_cap), np.inf, np.float64)
     st = sl = None
     n_snap = 0
     if snap_every:
@@ -168,11 +169,11 @@ def decode(c: dict, w: dict | None, enc, lengths, beam=None, algo=None, lm: LM |
     used = L.orc_decode(C.byref(cfg), C.byref(W.struct), _ptr(enc_a), _ptr(lengths), C.c_int(B), C.c_int(T),
                         C.c_int(beam), C.c_int(algo), lm.handle if lm is not None else None,
                         C.c_double(lm_weight), _ptr(tok), _ptr(dur), C.c_int(Cc), _ptr(tokens), C.c_int(cap),
-                        _ptr(lens), _ptr(scores), _ptr(n_steps), _ptr(lp), _ptr(lt), _ptr(lm_), C.c_int(S_cap),
+                        _ptr(lens), _ptr(scores), _ptr(n_steps), _ptr(lp), _ptr(lt), _ptr(lm_), _ptr(lg), C.c_int(S_cap),
                         _ptr(st), _ptr(sl), C.c_int(snap_every), C.c_int(n_snap), _ptr(min_gap), _ptr(coll),
                         _ptr(n_cut), _ptr(max_logp), C.c_int(n_threads))
     return dict(tokens=tokens, lens=lens, scores=scores, n_steps=n_steps, log_parent=lp, log_token=lt,
-                log_merged=lm_, snap_tokens=st, snap_lens=sl, min_gap=min_gap, collisions=coll, n_cut=n_cut,
+                log_merged=lm_, log_gap=lg, snap_tokens=st, snap_lens=sl, min_gap=min_gap, collisions=coll, n_cut=n_cut,
                 max_logp=max_logp, threads=used, cap=cap)
 
 

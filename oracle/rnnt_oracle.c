@@ -498,6 +498,7 @@ typedef struct {
   /* outputs */
   int32_t *tokens; int cap; int32_t *lens; double *scores; /* [beam, cap], [beam], [beam] */
   int32_t *log_parent, *log_token, *log_merged; int S_cap;  /* [S_cap, beam] each, nullable */
+  double *log_gap;        /* [S_cap] smallest margin by which a decision of the step was taken, nullable */
   int32_t *snap_tokens, *snap_lens; int snap_every, n_snap; /* [n_snap, beam, cap], [n_snap, beam] */
   int n_steps;
   double min_gap;
@@ -575,6 +576,7 @@ static void decode_utterance(utt_job *J) {
       }
     if (!unfinished || step >= step_cap) break;
 
+    double step_gap = INFINITY;
     for (int64_t i = 0; i < n_cand; ++i) {
       cand[i].val = -INFINITY;
       cand[i].idx = i;
@@ -606,11 +608,11 @@ static void decode_utterance(utt_job *J) {
           for (int d = 0; d < c->n_dur; ++d) tmp_in[V + 1 + d] = (double)drow[d];
         }
         orc_score_row(c, NULL, tmp_in, c->model == 1 ? tmp_in + V + 1 : NULL, J->lm ? hy->lm : NULL, J->lambda,
-                      use_gamma, forced, tot, logp, &adv_tok[k], &adv_blank[k], &J->min_gap);
+                      use_gamma, forced, tot, logp, &adv_tok[k], &adv_blank[k], &step_gap);
       } else {
         joint_impl(c, w, f_proj + (size_t)hy->t * H, hy->g, z, J->w_ready);
         orc_score_row(c, z, NULL, NULL, J->lm ? hy->lm : NULL, J->lambda, use_gamma, forced, tot, logp,
-                      &adv_tok[k], &adv_blank[k], &J->min_gap);
+                      &adv_tok[k], &adv_blank[k], &step_gap);
       }
       for (int v = 0; v <= V; ++v) {
         cand[(int64_t)k * (V + 1) + v].val = hy->score + tot[v];
@@ -640,7 +642,7 @@ static void decode_utterance(utt_job *J) {
     for (int i = 0; i < K && i + 1 < n_cand; ++i)
       if (isfinite(cand[i].val) && isfinite(cand[i + 1].val)) {
         double gap = cand[i].val - cand[i + 1].val;
-        if (gap < J->min_gap) J->min_gap = gap;
+        if (gap < step_gap) step_gap = gap;
       }
     for (int64_t i = K; i < n_cand; ++i)
       if (isfinite(cand[i].val)) J->n_cut++; else break;
@@ -653,11 +655,13 @@ static void decode_utterance(utt_job *J) {
           int64_t i = (int64_t)k * (V + 1) + v;
           if (unpruned[i] >= thr - 1e-3) {
             double dist = fabs(rowlogp[i] - (rowmax[k] - c->gamma));
-            if (dist < J->min_gap) J->min_gap = dist;
+            if (dist < step_gap) step_gap = dist;
           }
         }
       }
     }
+    if (step_gap < J->min_gap) J->min_gap = step_gap;
+    if (J->log_gap && step < J->S_cap) J->log_gap[step] = step_gap;
 
     /* expansion of the selected candidates into the new slots */
     for (int j = 0; j < K; ++j) {
@@ -780,14 +784,15 @@ static void decode_utterance(utt_job *J) {
  * Outputs (caller-allocated): tokens [B, beam, cap] (untouched beyond lens),
  * lens [B, beam] (-1 = dead), scores [B, beam], n_steps [B]; logs
  * [B, S_cap, beam] (nullable): parent slot, token (>= 0 token, -1 blank,
- * -2 stay, -3 dead), merged_into (-1 dead); snapshots every snap_every steps
+ * -2 stay, -3 dead), merged_into (-1 dead); log_gap [B, S_cap]; snapshots every snap_every steps
  * (nullable); min_gap [B], collisions [B], n_cut [B], max_logp [B].
  * Returns the number of threads used.
  */
 int orc_decode(const orc_config *cfg, const orc_weights *w, const float *enc, const int32_t *lengths, int B, int T,
                int beam, int algo, const orc_lm *lm, double lambda, const float *inj_tok, const float *inj_dur,
                int C, int32_t *tokens, int cap, int32_t *lens, double *scores, int32_t *n_steps,
-               int32_t *log_parent, int32_t *log_token, int32_t *log_merged, int S_cap, int32_t *snap_tokens,
+               int32_t *log_parent, int32_t *log_token, int32_t *log_merged, double *log_gap, int S_cap,
+               int32_t *snap_tokens,
                int32_t *snap_lens, int snap_every, int n_snap, double *min_gap, int64_t *collisions,
                int64_t *n_cut, double *max_logp, int n_threads) {
   int used = 1;
@@ -840,6 +845,7 @@ int orc_decode(const orc_config *cfg, const orc_weights *w, const float *enc, co
     J.log_parent = log_parent ? log_parent + (size_t)b * S_cap * beam : NULL;
     J.log_token = log_token ? log_token + (size_t)b * S_cap * beam : NULL;
     J.log_merged = log_merged ? log_merged + (size_t)b * S_cap * beam : NULL;
+    J.log_gap = log_gap ? log_gap + (size_t)b * S_cap : NULL;
     J.snap_every = snap_every;
     J.n_snap = n_snap;
     J.snap_tokens = snap_tokens ? snap_tokens + (size_t)b * n_snap * beam * cap : NULL;

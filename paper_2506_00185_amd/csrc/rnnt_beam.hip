@@ -1,0 +1,707 @@
+// Host side of the rnnt_beam C ABI: weight packing, workspace, the step loop
+// (captured as a HIP graph), results.  See include/rnnt_beam.h for the contract.
+#include "../../include/rnnt_beam.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "kernels.h"
+#include "lm.h"
+
+using namespace rb;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+inline float host_bf16_round(float x) {
+  uint32_t u;
+  memcpy(&u, &x, 4);
+  if ((u & 0x7f800000u) == 0x7f800000u) return x;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  memcpy(&x, &u, 4);
+  return x;
+}
+
+struct KernelTimer {
+  const char *name;
+  float ms;
+  int calls;
+};
+
+enum { KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_COUNT };
+const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init", "k_joint", "k_select",
+                                      "k_lm_rows",           "k_lstm", "k_pred_proj", "k_backtrace"};
+
+}  // namespace
+
+struct rnnt_beam {
+  rnnt_config_t cfg;
+  std::string err;
+  int N = 0, n_chunks = 0, M_max = 0, S_max = 0, cap = 0, pc_chunks = 0;
+  std::vector<void *> allocs;
+  // packed weights
+  float *W_enc = nullptr, *b_enc = nullptr, *W_pred = nullptr, *b_pred = nullptr, *W_out = nullptr,
+        *b_out = nullptr, *W_hh = nullptr, *G = nullptr, *tab = nullptr;
+  // workspace
+  float *f_proj = nullptr, *g_proj[2] = {nullptr, nullptr}, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
+  float *lm_rows = nullptr;
+  double *score = nullptr;
+  int *t = nullptr, *sym = nullptr, *len = nullptr, *last = nullptr, *ctx = nullptr, *lengths = nullptr;
+  uint32_t *hash = nullptr;
+  int *src_row = nullptr, *tok = nullptr;
+  float *p_max = nullptr, *p_sum = nullptr, *p_key = nullptr, *zs = nullptr;
+  int *p_idx = nullptr;
+  int *tree_parent = nullptr, *tree_token = nullptr, *tree_merged = nullptr;
+  int *finished = nullptr, *utt_steps = nullptr, *ctrl = nullptr;  // ctrl: n_finished, done, step_base, bad_arg, nonfinite
+  int *h_done = nullptr, *h_done_dev = nullptr;                    // pinned host word and its device alias
+  int *out_tokens = nullptr, *out_lens = nullptr, *out_steps = nullptr;
+  double *out_scores = nullptr;
+  // last decode
+  bool have_result = false;
+  int last_B = 0, last_K = 0, last_T = 0;
+  hipStream_t last_stream = nullptr;
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_chunk[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev_k0 = nullptr, ev_k1 = nullptr;
+  bool profiling = false;
+  KernelTimer timers[KT_COUNT];
+  // graphs of one chunk of steps, keyed by the launch shape
+  typedef std::tuple<int, int, int, int, const void *, uint32_t> GraphKey;
+  std::map<GraphKey, hipGraphExec_t> graphs;
+};
+
+namespace {
+
+#define RB_HIP(h, call)                                                                              \
+  do {                                                                                               \
+    hipError_t e_ = (call);                                                                          \
+    if (e_ != hipSuccess) {                                                                          \
+      (h)->err = std::string(#call) + ": " + hipGetErrorString(e_);                                  \
+      return e_ == hipErrorOutOfMemory ? RNNT_E_NOMEM : RNNT_E_HIP;                                  \
+    }                                                                                                \
+  } while (0)
+
+template <typename T>
+int dev_alloc(rnnt_beam *h, T **p, size_t n) {
+  void *q = nullptr;
+  RB_HIP(h, hipMalloc(&q, (n ? n : 1) * sizeof(T)));
+  h->allocs.push_back(q);
+  *p = static_cast<T *>(q);
+  return RNNT_OK;
+}
+
+template <typename T>
+int upload(rnnt_beam *h, T **p, const std::vector<T> &v) {
+  int rc = dev_alloc(h, p, v.size());
+  if (rc) return rc;
+  RB_HIP(h, hipMemcpy(*p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return RNNT_OK;
+}
+
+int download(rnnt_beam *h, std::vector<float> &v, const float *dev, size_t n) {
+  v.resize(n);
+  RB_HIP(h, hipMemcpy(v.data(), dev, n * sizeof(float), hipMemcpyDeviceToHost));
+  return RNNT_OK;
+}
+
+int fail(rnnt_beam *h, int code, const std::string &msg) {
+  h->err = msg;
+  return code;
+}
+
+int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
+
+int launch_gemm(rnnt_beam *h, hipStream_t s, const float *A, const float *B, const float *bias, float *C, int M, int N,
+                int K, int round_ops, int *nonfinite) {
+  dim3 grid((N + 63) / 64, (M + 63) / 64);
+  hipLaunchKernelGGL(k_gemm_nt, grid, dim3(256), 0, s, A, B, bias, C, M, N, K, round_ops, nonfinite);
+  RB_HIP(h, hipGetLastError());
+  return RNNT_OK;
+}
+
+int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
+  const rnnt_config_t &c = h->cfg;
+  const int H = c.H, P = c.P, D = c.D, E = c.E, V = c.V, N = h->N;
+  const bool bf = c.prec == RNNT_BF16_JOINT;
+  std::vector<float> tmp, out;
+  int rc;
+  // encoder projection
+  if ((rc = download(h, tmp, w->W_enc, (size_t)H * D))) return rc;
+  if (bf)
+    for (auto &x : tmp) x = host_bf16_round(x);
+  if ((rc = upload(h, &h->W_enc, tmp))) return rc;
+  if ((rc = download(h, tmp, w->b_enc, H))) return rc;
+  if ((rc = upload(h, &h->b_enc, tmp))) return rc;
+  // prediction projection
+  std::vector<float> wpred, bpred;
+  if ((rc = download(h, wpred, w->W_pred, (size_t)H * P))) return rc;
+  if (bf)
+    for (auto &x : wpred) x = host_bf16_round(x);
+  if ((rc = upload(h, &h->W_pred, wpred))) return rc;
+  if ((rc = download(h, bpred, w->b_pred, H))) return rc;
+  if ((rc = upload(h, &h->b_pred, bpred))) return rc;
+  // output layer, rows padded with zeros to whole 32-column chunks
+  if ((rc = download(h, tmp, w->W_out, (size_t)N * H))) return rc;
+  out.assign((size_t)h->n_chunks * 32 * H, 0.f);
+  for (size_t i = 0; i < (size_t)N * H; ++i) out[i] = bf ? host_bf16_round(tmp[i]) : tmp[i];
+  if ((rc = upload(h, &h->W_out, out))) return rc;
+  if ((rc = download(h, tmp, w->b_out, N))) return rc;
+  out.assign((size_t)h->n_chunks * 32, 0.f);
+  for (int i = 0; i < N; ++i) out[i] = tmp[i];
+  if ((rc = upload(h, &h->b_out, out))) return rc;
+
+  if (c.pred == RNNT_PRED_LSTM) {
+    // gate rows re-ordered so that rows 4u..4u+3 of a 32-row tile hold gates (i, f, g, o) of unit 8*tile + u
+    auto packed_row = [&](int r) {  // r = packed row -> original row
+      const int tile = r / 32, ul = (r % 32) / 4, gate = r % 4;
+      return gate * P + tile * 8 + ul;
+    };
+    std::vector<float> whh, wih, bih, bhh, emb;
+    if ((rc = download(h, whh, w->W_hh, (size_t)4 * P * P))) return rc;
+    if ((rc = download(h, wih, w->W_ih, (size_t)4 * P * E))) return rc;
+    if ((rc = download(h, bih, w->b_ih, (size_t)4 * P))) return rc;
+    if ((rc = download(h, bhh, w->b_hh, (size_t)4 * P))) return rc;
+    std::vector<float> whh_p((size_t)4 * P * P), wih_p((size_t)4 * P * E), b_p((size_t)4 * P);
+    for (int r = 0; r < 4 * P; ++r) {
+      const int o = packed_row(r);
+      memcpy(&whh_p[(size_t)r * P], &whh[(size_t)o * P], sizeof(float) * P);
+      memcpy(&wih_p[(size_t)r * E], &wih[(size_t)o * E], sizeof(float) * E);
+      b_p[r] = bih[o] + bhh[o];
+    }
+    if ((rc = upload(h, &h->W_hh, whh_p))) return rc;
+    // G[v] = W_ih emb[v] + b_ih + b_hh for every token (and the start symbol): one GEMM at create
+    float *d_wih = nullptr, *d_b = nullptr, *d_emb = nullptr;
+    if ((rc = upload(h, &d_wih, wih_p))) return rc;
+    if ((rc = upload(h, &d_b, b_p))) return rc;
+    if ((rc = download(h, emb, w->emb, (size_t)(V + 1) * E))) return rc;
+    if ((rc = upload(h, &d_emb, emb))) return rc;
+    if ((rc = dev_alloc(h, &h->G, (size_t)(V + 1) * 4 * P))) return rc;
+    if ((rc = launch_gemm(h, nullptr, d_emb, d_wih, d_b, h->G, V + 1, 4 * P, E, 0, nullptr))) return rc;
+  } else {
+    // stateless: tab[i][v] = W_pred emb_i[v] (+ b_pred for i = 0), so that the per-step
+    // prediction network is a gather-add inside the joint kernel
+    const int ctx = c.stateless_context;
+    std::vector<float> emb;
+    if ((rc = download(h, emb, w->emb, (size_t)ctx * (V + 1) * P))) return rc;
+    float *d_emb = nullptr;
+    if ((rc = upload(h, &d_emb, emb))) return rc;
+    if ((rc = dev_alloc(h, &h->tab, (size_t)ctx * (V + 1) * H))) return rc;
+    for (int i = 0; i < ctx; ++i)
+      if ((rc = launch_gemm(h, nullptr, d_emb + (size_t)i * (V + 1) * P, h->W_pred, i == 0 ? h->b_pred : nullptr,
+                            h->tab + (size_t)i * (V + 1) * H, V + 1, H, P, bf ? 1 : 0, nullptr)))
+        return rc;
+  }
+  RB_HIP(h, hipDeviceSynchronize());
+  return RNNT_OK;
+}
+
+struct StepPlan {
+  int B, K, T, algo, M;
+  const rnnt_lm_t *lm;
+  float lambda;
+  const float *inj_tok, *inj_dur;
+  int C;
+};
+
+// timing wrapper used in profiling mode: synchronous, one kernel at a time
+struct ScopedKernelTime {
+  rnnt_beam *h;
+  hipStream_t s;
+  int which;
+  ScopedKernelTime(rnnt_beam *h_, hipStream_t s_, int w) : h(h_), s(s_), which(w) {
+    if (h->profiling) hipEventRecord(h->ev_k0, s);
+  }
+  ~ScopedKernelTime() {
+    if (h->profiling) {
+      hipEventRecord(h->ev_k1, s);
+      hipEventSynchronize(h->ev_k1);
+      float ms = 0.f;
+      hipEventElapsedTime(&ms, h->ev_k0, h->ev_k1);
+      h->timers[which].ms += ms;
+      h->timers[which].calls += 1;
+    }
+  }
+};
+
+int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bump) {
+  const rnnt_config_t &c = h->cfg;
+  int *done = h->ctrl + 1, *step_base = h->ctrl + 2;
+  const int m_tiles = (p.M + 31) / 32;
+  if (c.pred == RNNT_PRED_LSTM && !p.inj_tok) {
+    {
+      ScopedKernelTime tm(h, s, KT_LSTM);
+      hipLaunchKernelGGL(k_lstm, dim3(4 * c.P / 32, m_tiles), dim3(256), 0, s, h->W_hh, h->G, h->h[cur], h->c[cur],
+                         h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, c.P, done);
+    }
+    {
+      ScopedKernelTime tm(h, s, KT_PREDPROJ);
+      hipLaunchKernelGGL(k_pred_proj, dim3(c.H / 32, m_tiles), dim3(256), 0, s, h->W_pred, h->b_pred, h->h[cur ^ 1],
+                         h->g_proj[cur ^ 1], p.M, c.P, c.H, c.prec == RNNT_BF16_JOINT ? 1 : 0, done, step_base, bump);
+    }
+  } else if (bump) {
+    hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done);
+  }
+  RB_HIP(h, hipGetLastError());
+  return RNNT_OK;
+}
+
+int launch_lm(rnnt_beam *h, hipStream_t s, const StepPlan &p) {
+  if (!p.lm) return RNNT_OK;
+  ScopedKernelTime tm(h, s, KT_LM);
+  lm_launch_rows(p.lm, h->ctx, h->len, h->lm_rows, p.M, h->ctrl + 1, s);
+  RB_HIP(h, hipGetLastError());
+  return RNNT_OK;
+}
+
+// one beam-search step; cur = parity of the prediction-network state it reads
+int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, int cur, int bump) {
+  const rnnt_config_t &c = h->cfg;
+  int *n_finished = h->ctrl, *done = h->ctrl + 1, *step_base = h->ctrl + 2;
+  const int kt = beam_template(p.K);
+  int n_chunks;
+  if (p.inj_tok) {
+    InjectArgs a;
+    a.tok_logp = p.inj_tok;
+    a.dur_logp = p.inj_dur;
+    a.C = p.C;
+    a.t = h->t;
+    a.hash = h->hash;
+    a.lengths = h->lengths;
+    a.M = p.M; a.K = p.K; a.T = p.T; a.V = c.V; a.ND = c.n_durations;
+    a.p_key = h->p_key;
+    a.p_idx = h->p_idx;
+    a.zs = h->zs;
+    a.done = done;
+    n_chunks = 64;
+    ScopedKernelTime tm(h, s, KT_JOINT);
+    if (kt == 4) hipLaunchKernelGGL(k_inject<4>, dim3(p.M), dim3(64), 0, s, a);
+    else if (kt == 8) hipLaunchKernelGGL(k_inject<8>, dim3(p.M), dim3(64), 0, s, a);
+    else hipLaunchKernelGGL(k_inject<16>, dim3(p.M), dim3(64), 0, s, a);
+  } else {
+    JointArgs a;
+    a.f_proj = h->f_proj;
+    a.g_proj = c.pred == RNNT_PRED_LSTM ? h->g_proj[cur] : nullptr;
+    a.tab = h->tab;
+    a.ctx_tok = h->ctx;
+    a.n_ctx = c.stateless_context;
+    a.t = h->t;
+    a.lengths = h->lengths;
+    a.W = h->W_out;
+    a.bias = h->b_out;
+    a.lm = p.lm ? h->lm_rows : nullptr;
+    a.lambda = p.lambda;
+    a.M = p.M; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
+    a.n_chunks = h->n_chunks;
+    a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
+    a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_key = h->p_key; a.p_idx = h->p_idx; a.zs = h->zs;
+    a.done = done;
+    n_chunks = h->n_chunks;
+    dim3 grid(h->n_chunks, (p.M + 31) / 32);
+    ScopedKernelTime tm(h, s, KT_JOINT);
+    if (kt == 4) hipLaunchKernelGGL(k_joint<4>, grid, dim3(256), 0, s, a);
+    else if (kt == 8) hipLaunchKernelGGL(k_joint<8>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(k_joint<16>, grid, dim3(256), 0, s, a);
+  }
+  RB_HIP(h, hipGetLastError());
+  {
+    SelectArgs a;
+    a.score = h->score; a.t = h->t; a.sym = h->sym; a.len = h->len; a.last = h->last; a.hash = h->hash;
+    a.ctx = h->ctx;
+    a.lengths = h->lengths;
+    a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_key = h->p_key; a.p_idx = h->p_idx; a.zs = h->zs;
+    a.n_chunks = n_chunks;
+    a.normalized = p.inj_tok ? 1 : 0;
+    a.B = p.B; a.K = p.K; a.V = c.V; a.ND = c.n_durations;
+    for (int i = 0; i < 8; ++i) a.dur[i] = c.durations[i];
+    a.algo = p.algo;
+    a.max_sym = c.max_symbols;
+    a.gamma = c.prune_margin;
+    a.has_lm = p.lm ? 1 : 0;
+    a.lambda = p.lambda;
+    a.src_row = h->src_row; a.tok = h->tok;
+    a.tree_parent = h->tree_parent; a.tree_token = h->tree_token; a.tree_merged = h->tree_merged;
+    a.S_max = h->S_max;
+    a.step_base = step_base;
+    a.step_off = step_off;
+    a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
+    a.h_done = h->h_done_dev;
+    ScopedKernelTime tm(h, s, KT_SELECT);
+    hipLaunchKernelGGL(k_select, dim3(p.B), dim3(256), 0, s, a);
+  }
+  RB_HIP(h, hipGetLastError());
+  int rc = launch_lm(h, s, p);
+  if (rc) return rc;
+  return launch_pred(h, s, p, cur, bump);
+}
+
+constexpr int kChunkSteps = 8;  // steps per graph launch (even: the state parity flips every step)
+
+int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const StepPlan &p, hipStream_t s) {
+  const rnnt_config_t &c = h->cfg;
+  int *n_finished = h->ctrl, *done = h->ctrl + 1, *step_base = h->ctrl + 2, *bad_arg = h->ctrl + 3,
+      *nonfinite = h->ctrl + 4;
+  h->have_result = false;
+  // the previous decode may still be writing the pinned completion word
+  if (h->last_stream) RB_HIP(h, hipStreamSynchronize(h->last_stream));
+  for (int i = 0; i < KT_COUNT; ++i) h->timers[i] = KernelTimer{kKernelNames[i], 0.f, 0};
+  RB_HIP(h, hipEventRecord(h->ev_begin, s));
+  {
+    InitArgs a;
+    a.score = h->score; a.t = h->t; a.sym = h->sym; a.len = h->len; a.last = h->last; a.hash = h->hash;
+    a.ctx = h->ctx;
+    a.lengths_in = lengths;
+    a.lengths = h->lengths;
+    a.src_row = h->src_row; a.tok = h->tok;
+    const bool lstm = c.pred == RNNT_PRED_LSTM && !p.inj_tok;
+    a.h0 = lstm ? h->h[1] : nullptr;
+    a.c0 = lstm ? h->c[1] : nullptr;
+    a.P = c.P;
+    a.B = p.B; a.K = p.K; a.T = p.T; a.V = c.V;
+    a.lstm = lstm ? 1 : 0;
+    a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
+    a.step_base = step_base; a.bad_arg = bad_arg;
+    a.h_done = h->h_done_dev;
+    *reinterpret_cast<volatile int *>(h->h_done) = 0;
+    ScopedKernelTime tm(h, s, KT_INIT);
+    hipLaunchKernelGGL(k_fill_int, dim3(1), dim3(64), 0, s, bad_arg, 0, 2);  // bad_arg, nonfinite
+    hipLaunchKernelGGL(k_init, dim3(256), dim3(256), 0, s, a);
+  }
+  RB_HIP(h, hipGetLastError());
+  if (!p.inj_tok) {
+    ScopedKernelTime tm(h, s, KT_ENCPROJ);
+    int rc = launch_gemm(h, s, enc, h->W_enc, h->b_enc, h->f_proj, p.B * p.T, c.H, c.D,
+                         c.prec == RNNT_BF16_JOINT ? 1 : 0, nonfinite);
+    if (rc) return rc;
+  }
+  // prediction network on the start symbol (reads parity 1, writes parity 0), LM on the empty context
+  int rc = launch_pred(h, s, p, 1, 0);
+  if (rc) return rc;
+  if ((rc = launch_lm(h, s, p))) return rc;
+
+  const int max_steps = h->S_max;
+  const bool use_graph = c.use_graph && !h->profiling && !p.inj_tok;
+  hipGraphExec_t exec = nullptr;
+  if (use_graph) {
+    uint32_t lbits;
+    memcpy(&lbits, &p.lambda, 4);
+    rnnt_beam::GraphKey key(p.B, p.K, p.algo, p.T, (const void *)p.lm, lbits);
+    auto it = h->graphs.find(key);
+    if (it == h->graphs.end()) {
+      hipStream_t cs;
+      RB_HIP(h, hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+      hipGraph_t graph;
+      RB_HIP(h, hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
+      for (int i = 0; i < kChunkSteps; ++i) {
+        rc = launch_step(h, cs, p, i, i & 1, i == kChunkSteps - 1 ? kChunkSteps : 0);
+        if (rc) break;
+      }
+      hipError_t e = hipStreamEndCapture(cs, &graph);
+      if (rc) return rc;
+      RB_HIP(h, e);
+      RB_HIP(h, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
+      RB_HIP(h, hipGraphDestroy(graph));
+      RB_HIP(h, hipStreamDestroy(cs));
+      h->graphs[key] = exec;
+    } else {
+      exec = it->second;
+    }
+  }
+  // The number of steps depends on the data.  Chunks of steps are enqueued ahead of the
+  // device; a pinned word written by the selection kernel tells the host when every
+  // utterance has finished.  Kernels of steps enqueued after that point return at once.
+  int enq = 0, chunk_i = 0;
+  while (enq < max_steps) {
+    if (*reinterpret_cast<volatile int *>(h->h_done)) break;
+    if (use_graph) {
+      RB_HIP(h, hipGraphLaunch(exec, s));
+    } else {
+      for (int i = 0; i < kChunkSteps; ++i)
+        if ((rc = launch_step(h, s, p, i, i & 1, i == kChunkSteps - 1 ? kChunkSteps : 0))) return rc;
+    }
+    enq += kChunkSteps;
+    RB_HIP(h, hipEventRecord(h->ev_chunk[chunk_i & 3], s));
+    if (chunk_i >= 2) RB_HIP(h, hipEventSynchronize(h->ev_chunk[(chunk_i - 2) & 3]));
+    ++chunk_i;
+  }
+  {
+    BacktraceArgs a;
+    a.score = h->score;
+    a.len = h->len;
+    a.tree_parent = h->tree_parent;
+    a.tree_token = h->tree_token;
+    a.utt_steps = h->utt_steps;
+    a.step_base = step_base;
+    a.K = p.K;
+    a.S_max = h->S_max;
+    a.cap = h->cap;
+    const size_t lds = (size_t)h->S_max * p.K * 2 * sizeof(int);
+    a.use_lds = lds <= 64 * 1024;
+    a.out_tokens = h->out_tokens; a.out_lens = h->out_lens; a.out_scores = h->out_scores; a.out_steps = h->out_steps;
+    ScopedKernelTime tm(h, s, KT_BACKTRACE);
+    hipLaunchKernelGGL(k_backtrace, dim3(p.B), dim3(64), a.use_lds ? lds : 0, s, a);
+  }
+  RB_HIP(h, hipGetLastError());
+  RB_HIP(h, hipEventRecord(h->ev_end, s));
+  h->have_result = true;
+  h->last_B = p.B;
+  h->last_K = p.K;
+  h->last_T = p.T;
+  h->last_stream = s;
+  return RNNT_OK;
+}
+
+int check_shapes(rnnt_beam *h, int B, int T, int beam, int algo) {
+  const rnnt_config_t &c = h->cfg;
+  if (B < 1 || B > c.max_B) return fail(h, RNNT_E_ARG, "B outside 1..max_B");
+  if (T < 1 || T > c.max_T) return fail(h, RNNT_E_ARG, "T outside 1..max_T");
+  if (beam < 1 || beam > c.max_beam) return fail(h, RNNT_E_ARG, "beam outside 1..max_beam");
+  if (algo != RNNT_ALSD && algo != RNNT_AES) return fail(h, RNNT_E_ARG, "unknown algo");
+  return RNNT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_beam_t **out) {
+  if (out) *out = nullptr;
+  if (!cfg || !w || !out || cfg->struct_size != sizeof(rnnt_config_t)) {
+    g_create_error = "NULL argument or struct_size mismatch";
+    return RNNT_E_ARG;
+  }
+  rnnt_beam *h = new (std::nothrow) rnnt_beam();
+  if (!h) return RNNT_E_NOMEM;
+  h->cfg = *cfg;
+  const rnnt_config_t &c = h->cfg;
+  auto bad = [&](const char *msg) {
+    g_create_error = msg;
+    delete h;
+    return RNNT_E_ARG;
+  };
+  if (c.D < 32 || c.H < 32 || c.P < 32 || c.D % 32 || c.H % 32 || c.P % 32) return bad("D, H, P must be multiples of 32");
+  if (c.V < 1) return bad("V < 1");
+  if (c.model != RNNT_MODEL_RNNT && c.model != RNNT_MODEL_TDT) return bad("unknown model");
+  if (c.model == RNNT_MODEL_TDT && (c.n_durations < 1 || c.n_durations > 8)) return bad("TDT needs 1..8 durations");
+  if (c.model == RNNT_MODEL_RNNT && c.n_durations != 0) return bad("n_durations must be 0 for RNN-T");
+  if (c.model == RNNT_MODEL_TDT) {
+    bool adv = false;
+    for (int i = 0; i < c.n_durations; ++i) {
+      if (c.durations[i] < 0) return bad("negative duration");
+      adv |= c.durations[i] >= 1;
+    }
+    if (!adv) return bad("TDT needs a duration >= 1");
+  }
+  if (c.pred == RNNT_PRED_LSTM) {
+    if (c.E < 32 || c.E % 32) return bad("E must be a multiple of 32");
+    if (!w->emb || !w->W_ih || !w->W_hh || !w->b_ih || !w->b_hh) return bad("LSTM weights missing");
+  } else if (c.pred == RNNT_PRED_STATELESS) {
+    if (c.stateless_context < 1 || c.stateless_context > 4) return bad("stateless_context outside 1..4");
+    if (!w->emb) return bad("embedding tables missing");
+  } else {
+    return bad("unknown prediction network");
+  }
+  if (!w->W_enc || !w->b_enc || !w->W_pred || !w->b_pred || !w->W_out || !w->b_out) return bad("joint weights missing");
+  if (c.max_B < 1 || c.max_T < 1 || c.max_beam < 1 || c.max_beam > kMaxBeam) return bad("max_B/max_T/max_beam");
+  if (c.max_symbols < 1) return bad("max_symbols < 1");
+  if (!(c.prune_margin >= 0.f)) return bad("prune_margin must be >= 0 (INFINITY = off)");
+
+  h->N = c.V + 1 + c.n_durations;
+  h->n_chunks = (h->N + 31) / 32;
+  h->pc_chunks = h->n_chunks > 64 ? h->n_chunks : 64;
+  h->M_max = c.max_B * c.max_beam;
+  h->S_max = c.max_T * (c.max_symbols + 1);
+  h->cap = c.max_T * c.max_symbols + 1;
+  const size_t M = h->M_max;
+  int rc = RNNT_OK;
+  auto A = [&](int r) {
+    if (!rc) rc = r;
+  };
+  A(pack_weights(h, w));
+  A(dev_alloc(h, &h->f_proj, (size_t)c.max_B * c.max_T * c.H));
+  for (int i = 0; i < 2; ++i) {
+    A(dev_alloc(h, &h->g_proj[i], M * c.H));
+    A(dev_alloc(h, &h->h[i], M * c.P));
+    A(dev_alloc(h, &h->c[i], M * c.P));
+  }
+  A(dev_alloc(h, &h->lm_rows, M * c.V));
+  A(dev_alloc(h, &h->score, M));
+  A(dev_alloc(h, &h->t, M));
+  A(dev_alloc(h, &h->sym, M));
+  A(dev_alloc(h, &h->len, M));
+  A(dev_alloc(h, &h->last, M));
+  A(dev_alloc(h, &h->hash, M));
+  A(dev_alloc(h, &h->ctx, M * kCtxMax));
+  A(dev_alloc(h, &h->lengths, (size_t)c.max_B));
+  A(dev_alloc(h, &h->src_row, M));
+  A(dev_alloc(h, &h->tok, M));
+  A(dev_alloc(h, &h->p_max, M * h->pc_chunks));
+  A(dev_alloc(h, &h->p_sum, M * h->pc_chunks));
+  A(dev_alloc(h, &h->p_key, M * h->pc_chunks * c.max_beam));
+  A(dev_alloc(h, &h->p_idx, M * h->pc_chunks * c.max_beam));
+  A(dev_alloc(h, &h->zs, M * (1 + 8)));
+  const size_t tree = (size_t)c.max_B * h->S_max * c.max_beam;
+  A(dev_alloc(h, &h->tree_parent, tree));
+  A(dev_alloc(h, &h->tree_token, tree));
+  A(dev_alloc(h, &h->tree_merged, tree));
+  A(dev_alloc(h, &h->finished, (size_t)c.max_B));
+  A(dev_alloc(h, &h->utt_steps, (size_t)c.max_B));
+  A(dev_alloc(h, &h->ctrl, 8));
+  A(dev_alloc(h, &h->out_tokens, M * h->cap));
+  A(dev_alloc(h, &h->out_lens, M));
+  A(dev_alloc(h, &h->out_scores, M));
+  A(dev_alloc(h, &h->out_steps, (size_t)c.max_B));
+  if (!rc) {
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&h->h_done), 64, hipHostMallocMapped);
+    if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&h->h_done_dev), h->h_done, 0);
+    if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
+    if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
+    if (e == hipSuccess) e = hipEventCreate(&h->ev_k0);
+    if (e == hipSuccess) e = hipEventCreate(&h->ev_k1);
+    for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&h->ev_chunk[i]);
+    if (e == hipSuccess) e = hipMemset(h->ctrl, 0, 8 * sizeof(int));
+    if (e != hipSuccess) {
+      h->err = std::string("create: ") + hipGetErrorString(e);
+      rc = RNNT_E_HIP;
+    }
+  }
+  if (rc) {
+    g_create_error = h->err;
+    rnnt_beam_destroy(h);
+    return rc;
+  }
+  *out = h;
+  return RNNT_OK;
+}
+
+int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T, int32_t beam,
+                     int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream) {
+  if (!h) return RNNT_E_ARG;
+  if (!enc || !lengths) return fail(h, RNNT_E_ARG, "NULL enc or lengths");
+  int rc = check_shapes(h, B, T, beam, algo);
+  if (rc) return rc;
+  if (lm && lm_vocab(lm) != h->cfg.V) return fail(h, RNNT_E_ARG, "LM vocabulary differs from the model's");
+  if (lm && algo == RNNT_AES && std::isfinite(h->cfg.prune_margin))
+    return fail(h, RNNT_E_ARG, "an LM together with a finite prune margin is not supported");
+  StepPlan p{B, beam, T, algo, B * beam, lm, lm ? lm_weight : 0.f, nullptr, nullptr, 1};
+  return run_decode(h, enc, lengths, p, static_cast<hipStream_t>(hip_stream));
+}
+
+int rnnt_beam_decode_injected(rnnt_beam_t *h, const float *tok_logp, const float *dur_logp, int32_t C,
+                              const int32_t *lengths, int32_t B, int32_t T, int32_t beam, int32_t algo,
+                              void *hip_stream) {
+  if (!h) return RNNT_E_ARG;
+  if (!tok_logp || !lengths || C < 1) return fail(h, RNNT_E_ARG, "NULL table or lengths, or C < 1");
+  if (h->cfg.n_durations > 0 && !dur_logp) return fail(h, RNNT_E_ARG, "TDT needs dur_logp");
+  int rc = check_shapes(h, B, T, beam, algo);
+  if (rc) return rc;
+  StepPlan p{B, beam, T, algo, B * beam, nullptr, 0.f, tok_logp, dur_logp, C};
+  return run_decode(h, nullptr, lengths, p, static_cast<hipStream_t>(hip_stream));
+}
+
+int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *lens, double *scores, int32_t *n_steps) {
+  if (!h) return RNNT_E_ARG;
+  if (!h->have_result) return fail(h, RNNT_E_NORESULT, "no decode has been run");
+  RB_HIP(h, hipStreamSynchronize(h->last_stream));
+  const int B = h->last_B, K = h->last_K;
+  int flags[2] = {0, 0};
+  RB_HIP(h, hipMemcpy(flags, h->ctrl + 3, sizeof(flags), hipMemcpyDeviceToHost));
+  if (lens) RB_HIP(h, hipMemcpy(lens, h->out_lens, sizeof(int) * B * K, hipMemcpyDeviceToHost));
+  if (scores) RB_HIP(h, hipMemcpy(scores, h->out_scores, sizeof(double) * B * K, hipMemcpyDeviceToHost));
+  if (n_steps) RB_HIP(h, hipMemcpy(n_steps, h->out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
+  if (tokens && cap > 0) {
+    std::vector<int> buf((size_t)B * K * h->cap), ln((size_t)B * K);
+    RB_HIP(h, hipMemcpy(buf.data(), h->out_tokens, sizeof(int) * buf.size(), hipMemcpyDeviceToHost));
+    RB_HIP(h, hipMemcpy(ln.data(), h->out_lens, sizeof(int) * ln.size(), hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < ln.size(); ++i) {
+      const int n = ln[i] < cap ? ln[i] : cap;
+      for (int u = 0; u < n; ++u) tokens[i * cap + u] = buf[i * h->cap + u];
+    }
+  }
+  if (flags[1]) return fail(h, RNNT_E_NONFINITE, "NaN or Inf in the encoder projection");
+  if (flags[0]) return fail(h, RNNT_E_ARG, "an utterance length was outside 0..T (clamped)");
+  return RNNT_OK;
+}
+
+int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t *merged_into, int32_t s_cap) {
+  if (!h) return RNNT_E_ARG;
+  if (!h->have_result) return fail(h, RNNT_E_NORESULT, "no decode has been run");
+  RB_HIP(h, hipStreamSynchronize(h->last_stream));
+  const int B = h->last_B, K = h->last_K;
+  std::vector<int> steps(B);
+  RB_HIP(h, hipMemcpy(steps.data(), h->out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
+  const int *src[3] = {h->tree_parent, h->tree_token, h->tree_merged};
+  int32_t *dst[3] = {parent, token, merged_into};
+  std::vector<int> buf((size_t)h->S_max * K);
+  for (int a = 0; a < 3; ++a) {
+    if (!dst[a]) continue;
+    for (size_t i = 0; i < (size_t)s_cap * B * K; ++i) dst[a][i] = -9;
+    for (int b = 0; b < B; ++b) {
+      RB_HIP(h, hipMemcpy(buf.data(), src[a] + (size_t)b * h->S_max * K, sizeof(int) * buf.size(),
+                          hipMemcpyDeviceToHost));
+      for (int st = 0; st < steps[b] && st < s_cap; ++st)
+        for (int k = 0; k < K; ++k) dst[a][((size_t)st * B + b) * K + k] = buf[(size_t)st * K + k];
+    }
+  }
+  return RNNT_OK;
+}
+
+int rnnt_beam_debug_encproj(rnnt_beam_t *h, float *out, int64_t n_floats) {
+  if (!h || !out) return RNNT_E_ARG;
+  if (!h->have_result) return fail(h, RNNT_E_NORESULT, "no decode has been run");
+  RB_HIP(h, hipStreamSynchronize(h->last_stream));
+  const int64_t n = (int64_t)h->last_B * h->last_T * h->cfg.H;
+  if (n_floats < n) return fail(h, RNNT_E_ARG, "buffer too small");
+  RB_HIP(h, hipMemcpy(out, h->f_proj, sizeof(float) * n, hipMemcpyDeviceToHost));
+  return RNNT_OK;
+}
+
+float rnnt_beam_last_decode_ms(rnnt_beam_t *h) {
+  if (!h || !h->have_result) return -1.f;
+  if (hipEventSynchronize(h->ev_end) != hipSuccess) return -1.f;
+  float ms = -1.f;
+  if (hipEventElapsedTime(&ms, h->ev_begin, h->ev_end) != hipSuccess) return -1.f;
+  return ms;
+}
+
+int rnnt_beam_set_profiling(rnnt_beam_t *h, int32_t on) {
+  if (!h) return RNNT_E_ARG;
+  h->profiling = on != 0;
+  return RNNT_OK;
+}
+
+int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_t *calls, int32_t n_cap) {
+  if (!h) return RNNT_E_ARG;
+  int n = 0;
+  for (int i = 0; i < KT_COUNT && n < n_cap; ++i) {
+    if (names) names[n] = h->timers[i].name ? h->timers[i].name : kKernelNames[i];
+    if (ms) ms[n] = h->timers[i].ms;
+    if (calls) calls[n] = h->timers[i].calls;
+    ++n;
+  }
+  return n;
+}
+
+const char *rnnt_beam_last_error(const rnnt_beam_t *h) { return h ? h->err.c_str() : g_create_error.c_str(); }
+
+void rnnt_beam_destroy(rnnt_beam_t *h) {
+  if (!h) return;
+  hipDeviceSynchronize();
+  for (auto &kv : h->graphs) hipGraphExecDestroy(kv.second);
+  for (void *p : h->allocs) hipFree(p);
+  if (h->h_done) hipHostFree(h->h_done);
+  hipEvent_t evs[] = {h->ev_begin, h->ev_end, h->ev_k0, h->ev_k1, h->ev_chunk[0], h->ev_chunk[1], h->ev_chunk[2],
+                      h->ev_chunk[3]};
+  for (hipEvent_t e : evs)
+    if (e) hipEventDestroy(e);
+  delete h;
+}
+
+}  // extern "C"

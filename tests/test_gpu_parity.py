@@ -1,0 +1,295 @@
+"""Parity of the HIP library with the CPU oracle, through the C ABI, on an MI355X.
+
+Bars: tree and recombination indices bit-exact when both sides read the same
+injected log-probabilities; float32 end to end: identical token sequences and
+hypothesis scores within 1e-3, except after a decision the oracle took by less
+than 1e-4; bf16-joint variant: 1e-2 for both (this library's own choice).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from gpu_common import compare, gpu_decode, gpu_decode_injected, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+TOL, TIE = 1e-3, 1e-4
+TOL_BF16, TIE_BF16 = 1e-2, 1e-2
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import paper_2506_00185_amd as A
+    A.load_library()
+    return A
+
+
+def _case(c, seed, perturb=True, zero_len=False):
+    w = S.make_weights(c, seed)
+    if perturb:
+        w = S.perturb_biases(w, seed + 1)
+    L = S.make_lengths(c, seed + 2)
+    if zero_len and len(L) > 2:
+        L[1] = 0
+        L[2] = c["T"]
+    enc = S.make_enc(c, L, seed + 3)
+    return w, L, enc
+
+
+# ---------------------------------------------------------------- single stages
+
+def test_encoder_projection_matches_oracle(amd, oracle):
+    c = S.custom_config(B=3, T=37, T_min=20, D=96, H=64, P=32, E=32, V=40, beam=2, s=2)
+    w, L, enc = _case(c, 300)
+    dec = amd.BeamDecoder(c, w)
+    gpu_decode(dec, enc, L, want_tree=False)
+    f = dec.debug_encproj(c["B"], c["T"])
+    for b, t in [(0, 0), (1, 5), (2, 36), (0, 19)]:
+        np.testing.assert_allclose(f[b * c["T"] + t], oracle.enc_proj(c, w, enc[b, t]), atol=2e-5)
+
+
+@pytest.mark.parametrize("n_target,order,V", [(1000, 4, 12), (60000, 4, 300), (30000, 6, 64), (200, 1, 50)])
+def test_lm_rows_match_oracle_lm(amd, oracle, n_target, order, V):
+    lm = S.make_lm(V=V, order=order, n_target=n_target, zipf_s=1.1, seed=n_target + order)
+    g, o = amd.NGramLM(lm), oracle.LM(lm)
+    rng = np.random.default_rng(1)
+    w = max(order - 1, 1)
+    ctx = np.full((64, w), -1, np.int32)
+    stored = lm["tokens"][lm["order"] == max(order - 1, 1)]
+    for i in range(64):
+        n = rng.integers(0, order)  # tokens of history available
+        if order > 1 and i % 3 == 0 and len(stored):
+            hist = stored[rng.integers(0, len(stored))][: order - 1][::-1]
+            n = min(n, len(hist))
+            ctx[i, :n] = hist[:n]
+        else:
+            ctx[i, :n] = rng.integers(0, V, n)
+    got = g.debug_query(ctx)
+    for i in range(64):
+        hist = [int(x) for x in ctx[i] if x >= 0][::-1]  # oldest first
+        want = o.query(hist, V)
+        np.testing.assert_allclose(got[i], want, rtol=0, atol=2e-5)
+
+
+# ------------------------------------------------------- index parity (injected)
+
+@pytest.mark.parametrize("algo", ["alsd", "aes"])
+@pytest.mark.parametrize("beam,V,model", [(4, 37, "rnnt"), (2, 5, "rnnt"), (7, 130, "rnnt"), (16, 64, "rnnt"),
+                                          (1, 37, "rnnt"), (4, 37, "tdt"), (6, 9, "tdt")])
+def test_injected_tree_and_recombination_are_bit_exact(amd, oracle, algo, beam, V, model):
+    durations = (0, 1, 2, 3, 4) if model == "tdt" else ()
+    B, T, C = 5, 14, 6
+    c = S.custom_config(B=B, T=T, T_min=3, D=32, H=32, P=32, E=32, V=V, beam=beam, s=2, algo=algo, model=model,
+                        durations=durations, gamma=1.5 if (algo == "aes" and V == 37) else float("inf"))
+    L = S.make_lengths(c, 17)
+    L[1] = 0
+    L[2] = T
+    tok, dur = S.make_injected(B, T, C, V, len(durations), seed=beam * 100 + V, levels=96 if V < 10 else 400,
+                               blank_boost=40)
+    w = S.make_weights(c, 1)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode_injected(dec, tok, dur, L)
+    o = oracle.decode(c, None, None, L, injected=(tok, dur), log=True)
+    assert np.array_equal(g["n_steps"], o["n_steps"])
+    full, exempt = compare(g, o, tol=1e-9, tie=0.0, exact_tree=True)
+    assert full == B and exempt == 0
+    assert o["collisions"].sum() == 0
+
+
+@pytest.mark.parametrize("algo", ["alsd", "aes"])
+@pytest.mark.parametrize("beam,V,model,levels,boost", [(8, 3, "rnnt", 32, 0), (16, 2, "rnnt", 16, 0),
+                                                       (4, 2, "rnnt", 16, 4), (8, 4, "tdt", 32, 0),
+                                                       (4, 3, "rnnt", 200, 100)])
+def test_injected_merge_heavy_tables_are_bit_exact(amd, oracle, algo, beam, V, model, levels, boost):
+    """Tiny vocabularies and closely spaced (often tied) log-probabilities: many hypotheses with equal
+    transcripts meet in the beam, so recombination and the tie-break order carry the result."""
+    durations = (0, 1, 2, 3, 4) if model == "tdt" else ()
+    B, T, C = 5, 14, 6
+    c = S.custom_config(B=B, T=T, T_min=3, D=32, H=32, P=32, E=32, V=V, beam=beam, s=2, algo=algo, model=model,
+                        durations=durations)
+    L = S.make_lengths(c, 17)
+    L[1] = 0
+    L[2] = T
+    tok, dur = S.make_injected(B, T, C, V, len(durations), seed=beam * 100 + V, levels=levels, blank_boost=boost)
+    dec = amd.BeamDecoder(c, S.make_weights(c, 1))
+    g = gpu_decode_injected(dec, tok, dur, L)
+    o = oracle.decode(c, None, None, L, injected=(tok, dur), log=True)
+    assert np.array_equal(g["n_steps"], o["n_steps"])
+    full, exempt = compare(g, o, tol=1e-9, tie=0.0, exact_tree=True)
+    assert full == B and exempt == 0
+    n = o["n_steps"].max()
+    slots = np.arange(beam)[None, None, :]
+    m = o["log_merged"][:, :n]
+    assert np.sum((m >= 0) & (m != slots)) >= 3, "the table does not exercise recombination"
+
+
+def test_injected_tree_walk_gives_the_transcripts(amd, oracle):
+    """Back-trace through (parent, token) on the host reproduces what the library reports."""
+    B, T, C, V, beam = 3, 10, 4, 20, 5
+    c = S.custom_config(B=B, T=T, D=32, H=32, P=32, E=32, V=V, beam=beam, s=3)
+    L = np.array([10, 7, 1], np.int32)
+    tok, _ = S.make_injected(B, T, C, V, 0, seed=5, blank_boost=100)
+    dec = amd.BeamDecoder(c, S.make_weights(c, 1))
+    g = gpu_decode_injected(dec, tok, None, L)
+    o = oracle.decode(c, None, None, L, injected=(tok, None), log=True, snap_every=1)
+    for b in range(B):
+        n = g["n_steps"][b]
+        for step in range(1, n + 1):
+            for k in range(beam):
+                want_len = o["snap_lens"][b, step - 1, k]
+                if want_len < 0:
+                    continue
+                toks, slot = [], k
+                for st in range(step - 1, -1, -1):
+                    tk = g["token"][st, b, slot]
+                    if tk >= 0:
+                        toks.append(tk)
+                    slot = g["parent"][st, b, slot]
+                toks.reverse()
+                assert toks == list(o["snap_tokens"][b, step - 1, k, :want_len])
+
+
+# ------------------------------------------------------------ float32 end to end
+
+@pytest.mark.parametrize("algo", ["alsd", "aes"])
+@pytest.mark.parametrize("beam", [1, 3, 4])
+def test_config1_tiny(amd, oracle, algo, beam):
+    c = S.config(1, algo=algo, beam=beam)
+    w, L, enc = S.make_weights(c), S.make_lengths(c), None
+    enc = S.make_enc(c, L)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 1
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("rnnt_alsd_ragged", dict(B=6, T=24, T_min=5, beam=4, s=3, algo="alsd")),
+    ("rnnt_alsd_two_row_tiles", dict(B=6, T=16, T_min=8, beam=7, s=2, algo="alsd")),
+    ("rnnt_aes", dict(B=5, T=20, T_min=6, beam=4, s=2, algo="aes")),
+    ("rnnt_aes_margin", dict(B=5, T=20, T_min=6, beam=4, s=2, algo="aes", gamma=2.3)),
+    ("tdt_aes_margin", dict(B=7, T=40, T_min=10, beam=4, s=2, algo="aes", gamma=2.3, model="tdt",
+                            durations=(0, 1, 2, 3, 4))),
+    ("tdt_alsd", dict(B=4, T=30, T_min=10, beam=5, s=2, algo="alsd", model="tdt", durations=(0, 1, 2, 3, 4))),
+    ("beam16", dict(B=3, T=12, T_min=6, beam=16, s=2, algo="alsd")),
+])
+def test_full_width_model_small_batch(amd, oracle, name, kw):
+    """Real layer widths (V = 1024 + blank spans 33 column chunks with a ragged tail), small batch."""
+    c = S.custom_config(D=1024, H=640, P=640, E=640, V=1024, blank_bias=3.0, **kw)
+    w, L, enc = _case(c, 400 + len(name), zero_len=True)
+    if c["model"] == "tdt":
+        w["b_out"][c["V"] + 2] += 2.0
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == c["B"]
+    assert full >= c["B"] // 2, (full, exempt)
+    assert g["lens"][1, 0] == 0 and g["scores"][1, 0] == 0.0 and g["n_steps"][1] == 0  # the empty utterance
+
+
+def test_odd_shapes(amd, oracle):
+    """Vocabulary, batch and frame counts that are not multiples of any tile size."""
+    c = S.custom_config(B=9, T=11, T_min=1, D=96, H=160, P=96, E=64, V=77, beam=5, s=2, algo="alsd")
+    w, L, enc = _case(c, 500)
+    dec = amd.BeamDecoder(c, w, max_B=12, max_T=15, max_beam=8)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 9 and full >= 5
+
+
+def test_stateless_prediction_network(amd, oracle):
+    c = S.custom_config(B=4, T=20, T_min=8, D=128, H=160, P=160, E=160, V=300, beam=10, s=2, algo="aes",
+                        pred="stateless", ctx=2, blank_bias=3.0)
+    w, L, enc = _case(c, 600)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 4 and full >= 2
+
+
+@pytest.mark.parametrize("pred", ["lstm", "stateless"])
+def test_bf16_joint_variant(amd, oracle, pred):
+    c = S.custom_config(B=4, T=20, T_min=8, D=128, H=160, P=160, E=160, V=300, beam=4, s=2, algo="alsd",
+                        pred=pred, ctx=2 if pred == "stateless" else 0, prec="bf16", blank_bias=3.0)
+    w, L, enc = _case(c, 700)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL_BF16, TIE_BF16)
+    assert full + exempt == 4
+    # the variant must differ from the float32 run, or the rounding is not happening
+    o32 = oracle.decode(dict(c, prec="f32"), w, enc, L)
+    assert not np.allclose(o32["scores"], o["scores"], atol=1e-6)
+
+
+def test_lm_fusion(amd, oracle):
+    V = 300
+    c = S.custom_config(B=4, T=16, T_min=8, D=128, H=160, P=160, E=160, V=V, beam=8, s=3, algo="alsd",
+                        blank_bias=3.0)
+    w, L, enc = _case(c, 800)
+    lm = S.make_lm(V=V, order=4, n_target=40000, zipf_s=1.1, seed=3)
+    glm, olm = amd.NGramLM(lm), oracle.LM(lm)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.3)
+    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.3, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 4 and full >= 2
+    # weight 0 gives the run without LM
+    g0 = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.0)
+    g1 = gpu_decode(dec, enc, L)
+    np.testing.assert_array_equal(g0["tokens"], g1["tokens"])
+    np.testing.assert_allclose(g0["scores"], g1["scores"], atol=1e-9)
+    assert not np.array_equal(g["scores"], g1["scores"])
+
+
+# ------------------------------------------------------------- behaviour of the ABI
+
+def test_graph_replay_equals_plain_launches_and_repeats(amd):
+    c = S.custom_config(B=5, T=20, T_min=6, D=128, H=160, P=160, E=160, V=300, beam=4, s=3, algo="alsd")
+    w, L, enc = _case(c, 900)
+    a = amd.BeamDecoder(c, w, use_graph=True)
+    b = amd.BeamDecoder(c, w, use_graph=False)
+    ra = [gpu_decode(a, enc, L) for _ in range(3)]
+    rb = gpu_decode(b, enc, L)
+    for r in ra:
+        for key in ("tokens", "lens", "scores", "n_steps", "parent", "token", "merged"):
+            np.testing.assert_array_equal(r[key], rb[key])
+    # a different batch on the same handle, then the first one again
+    L2 = L.copy()
+    L2[0] = 3
+    r2 = gpu_decode(a, enc, L2)
+    assert r2["n_steps"][0] <= 3 * 4
+    r3 = gpu_decode(a, enc, L)
+    np.testing.assert_array_equal(r3["scores"], rb["scores"])
+
+
+def test_error_paths(amd):
+    import torch
+    from paper_2506_00185_amd import RnntBeamError
+    c = S.custom_config(B=2, T=8, D=32, H=32, P=32, E=32, V=10, beam=2, s=2)
+    w, L, enc = _case(c, 950)
+    dec = amd.BeamDecoder(c, w)
+    r = dec.__class__.results
+    with pytest.raises(RnntBeamError, match="-5"):
+        dec._shape = (2, 2)
+        dec.results()
+    with pytest.raises(RnntBeamError, match="-1"):
+        dec.decode(to_gpu(enc, torch.float32), to_gpu(L, torch.int32), beam=3)  # beyond max_beam
+    with pytest.raises(RnntBeamError):
+        amd.BeamDecoder(dict(c, H=33), w)  # unsupported width
+    bad = enc.copy()
+    bad[1, 2, 3] = np.nan
+    dec.decode(to_gpu(bad, torch.float32), to_gpu(L, torch.int32))
+    assert dec.results(check=False)["rc"] == -4
+    Lbad = L.copy()
+    Lbad[0] = 99
+    dec.decode(to_gpu(enc, torch.float32), to_gpu(Lbad, torch.int32))
+    assert dec.results(check=False)["rc"] == -1
+    g = gpu_decode(dec, enc, L, want_tree=False)  # the handle still works
+    assert g["rc"] == 0 and np.all(g["lens"][:, 0] >= 0)
