@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched beam-search path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: encoder projection,
+then the data-dependent number of beam-search steps (joint, selection / tree /
+recombination, prediction network, optional LM), then the back-trace, plus the
+copy of the n-best lists to the host.  The workload is the RNN-T ALSD++ case of
+batch 32, T = 125 frames (10 s of audio each), beam 4, float32, with synthetic
+inputs of the model's shapes resident in HBM before the clock starts.
+
+Prints ONE JSON line: metric = RTFx (audio seconds decoded per wall second).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X, dense fp32 matrix
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+
+
+def kernel_flops(name: str, c: dict, M: int, B: int, T: int) -> float:
+    """Algorithmic floating-point operations of one launch (multiply-add = 2)."""
+    nd = len(c["durations"])
+    if name == "k_lstm":  # recurrent half of the gates; the embedding half is a table made at create
+        return 2.0 * M * c["P"] * 4 * c["P"]
+    if name == "k_joint":
+        return 2.0 * M * c["H"] * (c["V"] + 1 + nd)
+    if name == "k_pred_proj":
+        return 2.0 * M * c["P"] * c["H"]
+    if name.startswith("k_gemm_nt"):
+        return 2.0 * B * T * c["D"] * c["H"]
+    return 0.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="workload id (2 = the headline case)")
+    ap.add_argument("--variant", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-graph", action="store_true", help="launch the step kernels one by one")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-utts", type=int, default=16, help="utterances the oracle decodes for the CPU baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (utterances would be sharded "
+              "across GPUs with no collective in the loop); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    import paper_2506_00185_amd as A
+
+    assert torch.cuda.is_available(), "needs an MI355X"
+    c = S.config(args.config, prec=args.variant if args.config == 2 else S.CONFIGS[args.config]["prec"])
+    w = S.make_weights(c)
+    L = S.make_lengths(c)
+    enc = S.make_enc(c, L)
+    lm = None
+    if c["lm"]:
+        lm = A.NGramLM(S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"], 1000 * c["id"] + 3))
+    dec = A.BeamDecoder(c, w, use_graph=not args.no_graph)
+    d_enc = torch.as_tensor(enc).cuda().contiguous()
+    d_len = torch.as_tensor(L).cuda().contiguous()
+    audio_s = S.audio_seconds(L)
+    B, T, K = c["B"], c["T"], c["beam"]
+
+    def one_pass(beam=None):
+        dec.decode(d_enc, d_len, beam=beam, lm=lm, lm_weight=c["lm_weight"])
+        return dec.results()
+
+    for _ in range(args.warmup):
+        r = one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        r = one_pass()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = dt / args.steps * 1e3
+    value = audio_s * args.steps / dt
+    n_steps = int(r["n_steps"].max())
+    gpu_ms = dec.last_decode_ms()
+
+    # same kernels at beam 1 (greedy)
+    for _ in range(2):
+        one_pass(beam=1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(max(3, args.steps // 2)):
+        r1 = one_pass(beam=1)
+    torch.cuda.synchronize()
+    ms_beam1 = (time.perf_counter() - t0) / max(3, args.steps // 2) * 1e3
+
+    # per-kernel durations, HIP events on the decode's stream (one kernel at a time, no graph)
+    dec.set_profiling(True)
+    one_pass()
+    kt = dec.kernel_times()
+    dec.set_profiling(False)
+    kernels = {n: dict(total_ms=round(t, 4), launches=k, avg_us=round(t / k * 1e3, 3) if k else None,
+                       tflops=round(kernel_flops(n, c, B * K, B, T) / (t / k * 1e-3) / 1e12, 3) if k and t > 0 else None)
+               for n, (t, k) in kt.items() if k}
+    loop = {n: v for n, v in kernels.items() if n in ("k_joint", "k_select", "k_lstm", "k_pred_proj", "k_lm_rows")}
+    dom = max(loop, key=lambda n: loop[n]["total_ms"])
+    flops = kernel_flops(dom, c, B * K, B, T)
+    peak = PEAK_BF16_MFMA_TFLOPS if (dom == "k_joint" and c["prec"] == "bf16") else PEAK_FP32_MFMA_TFLOPS
+    achieved = flops / (loop[dom]["avg_us"] * 1e-6) / 1e12 if flops else 0.0
+    roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
+                    frac=round(achieved / peak, 5), traffic=None, avg_us=loop[dom]["avg_us"],
+                    flops_per_launch=flops)
+    jf = kernel_flops("k_joint", c, B * K, B, T)
+    joint_peak = PEAK_BF16_MFMA_TFLOPS if c["prec"] == "bf16" else PEAK_FP32_MFMA_TFLOPS
+    joint_util = jf / (loop["k_joint"]["avg_us"] * 1e-6) / 1e12 / joint_peak
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_utt = min(args.cpu_utts, B)
+        olm = oracle.LM(S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"],
+                                  1000 * c["id"] + 3)) if c["lm"] else None
+        t0 = time.perf_counter()
+        o = oracle.decode(dict(c, B=n_utt), w, enc[:n_utt], L[:n_utt], lm=olm, lm_weight=c["lm_weight"])
+        cdt = time.perf_counter() - t0
+        cpu = dict(value=round(S.audio_seconds(L[:n_utt]) / cdt, 2), unit="audio-s/s", cores=int(o["threads"]),
+                   kind="oracle", sample=f"first {n_utt} of {B} utterances of the same workload, {cdt:.1f} s wall")
+        # the sampled utterances double as a check of this run
+        same = sum(int(np.array_equal(o["tokens"][b, 0, :o["lens"][b, 0]], r["tokens"][b, 0, :r["lens"][b, 0]]))
+                   for b in range(n_utt))
+        cpu["best_hypothesis_identical"] = f"{same}/{n_utt}"
+
+    out = {
+        "metric": "batched beam decode throughput (audio-s/s, RTFx) at beam %d" % K,
+        "value": round(value, 1), "unit": "audio-s/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if c["prec"] == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": c["name"] + ("" if c["prec"] == "f32" or args.config != 2 else "_bf16joint"),
+                   "B": B, "T": T, "beam": K, "algo": c["algo"], "V": c["V"], "max_symbols": c["s"],
+                   "graph": not args.no_graph, "audio_s_per_pass": audio_s},
+        "beam_search_steps": n_steps, "us_per_beam_step": round(gpu_ms * 1e3 / max(n_steps, 1), 3),
+        "gpu_ms_per_pass": round(gpu_ms, 4), "beam1_ms_per_pass": round(ms_beam1, 4),
+        "beam_over_greedy": round(ms / ms_beam1, 4), "joint_mfma_util": round(joint_util, 5),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,38 +52,63 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const float *__restrict__ A, co
 }
 
 // ---------------------------------------------------------------------------
-// Split-K 32 x 32 tile shared by the three per-step contractions: the 4 waves
-// of a block each take a quarter of K (K % 32 == 0), partial tiles are summed
-// through LDS into wave 0.  a_at(k) / b_at(k) return 4 consecutive k of this
-// lane's row of the "vocabulary side" / "hypothesis side" operand.
+// Split-K 32 x 32 tile shared by the three per-step contractions.  The WAVES
+// waves of a block each take a slice of K and leave their partial tile in LDS;
+// tile_value() then sums the partials of one output element, so that the
+// epilogues can spread over every thread of the block instead of one wave
+// (these kernels are bound by the instruction latency of their longest wave).
+// a_at(k) / b_at(k) return 4 consecutive k of this lane's row of the "output
+// row" / "hypothesis" operand.
+// ITERS > 0: K == WAVES * ITERS * 8 and every load is issued before the first
+// matrix instruction; ITERS == 0: any K with K % (8 * WAVES) == 0, plain loop.
+// red: WAVES * 64 * 17 floats of LDS (lane-major, padded: conflict-free both ways).
 // ---------------------------------------------------------------------------
-template <class AL, class BL>
-__device__ __forceinline__ floatx16 splitk_tile(AL a_at, BL b_at, int K, float *red /* [3 * 16 * 64] */) {
+constexpr int kRedStride = 17;
+
+template <int WAVES, int ITERS, class AL, class BL>
+__device__ __forceinline__ void splitk_partials(AL a_at, BL b_at, int K, float *red) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
-  const int kw = K >> 2;
+  const int kw = K / WAVES;
   floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  const int kend = (wave + 1) * kw;
-#pragma unroll 5
-  for (int k = wave * kw + 4 * half; k < kend; k += 8) {
-    const float4 a = a_at(k);
-    const float4 b = b_at(k);
-    acc = mfma32(a.x, b.x, acc);
-    acc = mfma32(a.y, b.y, acc);
-    acc = mfma32(a.z, b.z, acc);
-    acc = mfma32(a.w, b.w, acc);
-  }
-  if (wave > 0) {
+  const int kbeg = wave * kw + 4 * half;
+  if constexpr (ITERS > 0) {
+    float4 av[ITERS], bv[ITERS];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) red[((wave - 1) * 16 + r) * 64 + lane] = acc[r];
+    for (int i = 0; i < ITERS; ++i) av[i] = a_at(kbeg + 8 * i);
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) bv[i] = b_at(kbeg + 8 * i);
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      acc = mfma32(av[i].x, bv[i].x, acc);
+      acc = mfma32(av[i].y, bv[i].y, acc);
+      acc = mfma32(av[i].z, bv[i].z, acc);
+      acc = mfma32(av[i].w, bv[i].w, acc);
+    }
+  } else {
+    const int kend = (wave + 1) * kw;
+    for (int k = kbeg; k < kend; k += 8) {
+      const float4 a = a_at(k);
+      const float4 b = b_at(k);
+      acc = mfma32(a.x, b.x, acc);
+      acc = mfma32(a.y, b.y, acc);
+      acc = mfma32(a.z, b.z, acc);
+      acc = mfma32(a.w, b.w, acc);
+    }
   }
+  float *mine = red + (wave * 64 + lane) * kRedStride;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) mine[r] = acc[r];
   __syncthreads();
-  if (wave == 0) {
+}
+
+// element (output row i, hypothesis j) of the finished 32 x 32 tile
+template <int WAVES>
+__device__ __forceinline__ float tile_value(const float *red, int i, int j) {
+  const int r = 4 * (i >> 3) + (i & 3), src = ((i >> 2) & 1) * 32 + j;
+  float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < 3; ++w)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[r] += red[(w * 16 + r) * 64 + lane];
-  }
-  return acc;
+  for (int w = 0; w < WAVES; ++w) s += red[(w * 64 + src) * kRedStride + r];
+  return s;
 }
 
 // Sorted list of the KT best (key, index) pairs seen by one lane.
@@ -116,19 +141,21 @@ struct TopList {
   }
 };
 
+// Operand layout of the per-step contractions ("k4-major"): element (row, k) of a
+// matrix with R rows sits at ((k / 4) * R + row) * 4 + k % 4.  A wave's 16-byte
+// loads of 32 consecutive rows at one k then cover whole cache lines (512 B
+// contiguous per half-wave), for weights and activations alike.
+__host__ __device__ inline size_t k4_index(int k, int row, int rows) {
+  return ((size_t)(k >> 2) * rows + row) * 4 + (k & 3);
+}
+
 struct JointArgs {
-  const float *f_proj;  // [B * T, H]
-  const float *g_proj;  // [M, H] prediction projection (LSTM), or NULL
-  const float *tab;     // stateless: [ctx][V + 1][H] folded embedding tables
-  const int *ctx_tok;   // [M][kCtxMax] most recent token first, -1 = none
-  int n_ctx;
-  const int *t;         // [M] frame of each hypothesis
-  const int *lengths;   // [B]
-  const float *W;       // [n_chunks * 32, H] output layer, zero rows beyond V + 1 + ND
-  const float *bias;    // [n_chunks * 32]
-  const float *lm;      // [M, V] natural-log LM scores or NULL
+  const float *pre;   // k4-major [H][Mp]: f_proj[b, t_m] + prediction projection of hypothesis m
+  const float *W;     // k4-major [H][n_chunks * 32] output layer, zero rows beyond V + 1 + ND
+  const float *bias;  // [n_chunks * 32]
+  const float *lm;    // [M, V] natural-log LM scores or NULL
   float lambda;
-  int M, K, T, H, V, ND, n_chunks, round_ops;
+  int M, Mp, K, H, V, ND, n_chunks, round_ops;
   float *p_max, *p_sum;  // [M, n_chunks] soft-max statistics of the chunk's token logits
   float *p_key;          // [M, n_chunks, K] best keys z + lambda * lm of the chunk
   int *p_idx;            // [M, n_chunks, K] their token ids
@@ -137,123 +164,122 @@ struct JointArgs {
 };
 
 // Joint network for a tile of 32 hypotheses x 32 output columns:
-//   z[n] = W_out[n] . ReLU(f_proj[b, t_m] + g_m) + b_out[n]
+//   z[n] = W_out[n] . ReLU(pre_m) + b_out[n],  pre_m = f_proj[b, t_m] + g_m
 // with the soft-max statistics and the K best keys of the chunk in the epilogue,
-// so that the [M, V + 1] logits never reach memory.
-template <int KT>
-__global__ __launch_bounds__(256) void k_joint(JointArgs a) {
+// so that the [M, V + 1] logits never reach memory.  Epilogue: LPH = 2 * WAVES
+// lanes share a hypothesis, each holds 32 / LPH columns; the best K of the chunk
+// are found in K rounds of an LPH-lane arg-max.
+template <int WAVES, int ITERS>
+__global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
   if (*reinterpret_cast<const volatile int *>(a.done)) return;
-  __shared__ float red[3 * 16 * 64];
-  const int lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+  __shared__ float red[WAVES * 64 * kRedStride];
+  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int chunk = blockIdx.x, n0 = chunk * 32, m0 = blockIdx.y * 32;
-  const int m = m0 + col;
-  const bool mvalid = m < a.M;
-  const int mm = mvalid ? m : a.M - 1;
-  const int b = mm / a.K;
-  const int T_b = a.lengths[b];
-  int tt = a.t[mm];
-  tt = tt < T_b ? tt : T_b - 1;
-  tt = tt < 0 ? 0 : tt;
-  const float *fp = a.f_proj + ((size_t)b * a.T + tt) * a.H;
-  const float *gp = a.g_proj ? a.g_proj + (size_t)mm * a.H : nullptr;
-  const float *tp[4] = {nullptr, nullptr, nullptr, nullptr};
-  if (!gp) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (i < a.n_ctx) {
-        int tk = a.ctx_tok[mm * kCtxMax + i];
-        tk = tk < 0 ? a.V : tk;
-        tp[i] = a.tab + ((size_t)i * (a.V + 1) + tk) * a.H;
-      }
+  {
+    const int Np = a.n_chunks * 32;
+    const float *wp = a.W + (size_t)(n0 + col) * 4;
+    const float *pp = a.pre + (size_t)(m0 + col) * 4;
+    const int Mp = a.Mp, round_ops = a.round_ops;
+    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * Np * 4); };
+    auto b_at = [&](int k) {
+      float4 f = *reinterpret_cast<const float4 *>(pp + (size_t)(k >> 2) * Mp * 4);
+      f.x = fmaxf(f.x, 0.f); f.y = fmaxf(f.y, 0.f); f.z = fmaxf(f.z, 0.f); f.w = fmaxf(f.w, 0.f);
+      if (round_ops) f = bf16_round4(f);
+      return f;
+    };
+    splitk_partials<WAVES, ITERS>(a_at, b_at, a.H, red);
   }
-  const float *wp = a.W + (size_t)(n0 + col) * a.H;
-  const int round_ops = a.round_ops;
-  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + k); };
-  auto b_at = [&](int k) {
-    float4 f = *reinterpret_cast<const float4 *>(fp + k);
-    if (gp) {
-      const float4 g = *reinterpret_cast<const float4 *>(gp + k);
-      f.x += g.x; f.y += g.y; f.z += g.z; f.w += g.w;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (tp[i]) {
-          const float4 g = *reinterpret_cast<const float4 *>(tp[i] + k);
-          f.x += g.x; f.y += g.y; f.z += g.z; f.w += g.w;
-        }
-    }
-    f.x = fmaxf(f.x, 0.f); f.y = fmaxf(f.y, 0.f); f.z = fmaxf(f.z, 0.f); f.w = fmaxf(f.w, 0.f);
-    if (round_ops) f = bf16_round4(f);
-    return f;
-  };
-  floatx16 acc = splitk_tile(a_at, b_at, a.H, red);
-  if (threadIdx.x >= 64) return;
 
-  // epilogue (wave 0): lane holds 16 logits of hypothesis m
-  TopList<KT> top;
-  top.init();
-  float mx = -INFINITY, sum = 0.f;
+  // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
+  const int j = tid / LPH, e = tid % LPH, i0 = e * VPL;
+  const int m = m0 + j;
+  const bool mvalid = m < a.M;
   const int nz = 1 + a.ND;
+  float key[VPL];
+  int idx[VPL];
+  float mx = -INFINITY;
+  float zv[VPL];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int nb = n0 + 8 * q + 4 * half;
-    const float4 bias = *reinterpret_cast<const float4 *>(a.bias + nb);
-    const float bz[4] = {bias.x, bias.y, bias.z, bias.w};
-    float lz[4] = {0.f, 0.f, 0.f, 0.f};
-    if (a.lm) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) lz[e] = nb + e < a.V ? a.lm[(size_t)mm * a.V + nb + e] : 0.f;
+  for (int q = 0; q < VPL; ++q) {
+    const int n = n0 + i0 + q;
+    const float z = tile_value<WAVES>(red, i0 + q, j) + a.bias[n];
+    zv[q] = z;
+    key[q] = -INFINITY;
+    idx[q] = 0x7fffffff;
+    if (n < a.V) {
+      key[q] = (a.lm && mvalid) ? z + a.lambda * a.lm[(size_t)m * a.V + n] : z;
+      idx[q] = n;
+      mx = fmaxf(mx, z);
+    } else if (n < a.V + nz && mvalid) {
+      a.zs[(size_t)m * nz + (n - a.V)] = z;
     }
+  }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int n = nb + e;
-      const float z = acc[4 * q + e] + bz[e];
-      if (n < a.V) {
-        const float key = a.lm ? z + a.lambda * lz[e] : z;
-        if (z > mx) {
-          sum = sum * __expf(mx - z) + 1.f;
-          mx = z;
-        } else {
-          sum += __expf(z - mx);
-        }
-        top.insert(key, n);
-      } else if (n < a.V + nz && mvalid) {
-        a.zs[(size_t)m * nz + (n - a.V)] = z;
+  for (int o = 1; o < LPH; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q)
+    if (n0 + i0 + q < a.V) sum += __expf(zv[q] - mx);
+#pragma unroll
+  for (int o = 1; o < LPH; o <<= 1) sum += __shfl_xor(sum, o);
+  // local order of this lane's candidates (VPL is 2 or 4: a few compare-exchanges)
+#pragma unroll
+  for (int x = 0; x < VPL; ++x)
+#pragma unroll
+    for (int y = 0; y + 1 < VPL - x; ++y)
+      if (comes_before(key[y + 1], idx[y + 1], key[y], idx[y])) {
+        const float tv = key[y]; key[y] = key[y + 1]; key[y + 1] = tv;
+        const int ti = idx[y]; idx[y] = idx[y + 1]; idx[y + 1] = ti;
+      }
+  // K rounds: the best remaining candidate among the LPH lanes of the hypothesis
+  float my_key[2] = {-INFINITY, -INFINITY};  // lane e keeps the winners of rounds e and e + LPH
+  int my_idx[2] = {0x7fffffff, 0x7fffffff};
+  for (int r = 0; r < a.K; ++r) {
+    float bv = key[0];
+    int bi = idx[0];
+#pragma unroll
+    for (int o = 1; o < LPH; o <<= 1) {
+      const float v2 = __shfl_xor(bv, o);
+      const int i2 = __shfl_xor(bi, o);
+      if (comes_before(v2, i2, bv, bi)) {
+        bv = v2;
+        bi = i2;
+      }
+    }
+    if (bi == idx[0]) {  // mine was taken: move my list up
+#pragma unroll
+      for (int q = 0; q + 1 < VPL; ++q) {
+        key[q] = key[q + 1];
+        idx[q] = idx[q + 1];
+      }
+      key[VPL - 1] = -INFINITY;
+      idx[VPL - 1] = 0x7fffffff;
+    }
+    if (e == (r & (LPH - 1))) {
+      if (r < LPH) {
+        my_key[0] = bv;
+        my_idx[0] = bi;
+      } else {
+        my_key[1] = bv;
+        my_idx[1] = bi;
       }
     }
   }
-  // the two lanes that share a hypothesis (l and l ^ 32) combine
-  {
-    const float mx2 = __shfl_xor(mx, 32), sum2 = __shfl_xor(sum, 32);
-    const float mm2 = fmaxf(mx, mx2);
-    float s = 0.f;
-    if (mx > -INFINITY) s += sum * __expf(mx - mm2);
-    if (mx2 > -INFINITY) s += sum2 * __expf(mx2 - mm2);
-    mx = mm2;
-    sum = s;
-  }
-  {
-    // every lane takes a copy of its partner's list, then inserts it; both end with the same merged list
-    float pv[KT];
-    int pi[KT];
-#pragma unroll
-    for (int j = 0; j < KT; ++j) {
-      pv[j] = __shfl_xor(top.v[j], 32);
-      pi[j] = __shfl_xor(top.i[j], 32);
-    }
-#pragma unroll
-    for (int j = 0; j < KT; ++j) top.insert(pv[j], pi[j]);
-  }
-  if (half == 0 && mvalid) {
+  if (mvalid) {
     const size_t pc = (size_t)m * a.n_chunks + chunk;
-    a.p_max[pc] = mx;
-    a.p_sum[pc] = sum;
-#pragma unroll
-    for (int j = 0; j < KT; ++j)
-      if (j < a.K) {
-        a.p_key[pc * a.K + j] = top.v[j];
-        a.p_idx[pc * a.K + j] = top.i[j];
-      }
+    if (e == 0) {
+      a.p_max[pc] = mx;
+      a.p_sum[pc] = sum;
+    }
+    if (e < a.K) {
+      a.p_key[pc * a.K + e] = my_key[0];
+      a.p_idx[pc * a.K + e] = my_idx[0];
+    }
+    if (LPH + e < a.K) {
+      a.p_key[pc * a.K + LPH + e] = my_key[1];
+      a.p_idx[pc * a.K + LPH + e] = my_idx[1];
+    }
   }
 }
 
@@ -315,6 +341,7 @@ struct SelectArgs {
   const int *p_idx;
   const float *zs;
   int n_chunks;
+  int stage;       // 1: the block copies its candidate lists into (dynamic) LDS first
   int normalized;  // 1: keys are log-probabilities already (injected mode)
   // configuration
   int B, K, V, ND;
@@ -375,6 +402,37 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 #pragma unroll
     for (int i = 0; i < kCtxMax; ++i) s_ctx[tid][i] = a.ctx[m * kCtxMax + i];
   }
+  // candidate lists of the K rows of this utterance: contiguous in memory; one coalesced copy into LDS
+  // turns the many dependent reads below into a single round trip
+  extern __shared__ float stage[];
+  const int ncand = a.n_chunks * K;
+  const float *keys_b = a.p_key + (size_t)m_base * ncand;
+  const int *idxs_b = a.p_idx + (size_t)m_base * ncand;
+  const float *pmax_b = a.p_max + (size_t)m_base * a.n_chunks;
+  const float *psum_b = a.p_sum + (size_t)m_base * a.n_chunks;
+  const float *zs_b = a.zs + (size_t)m_base * nz;
+  if (a.stage) {
+    float *s_keys = stage;
+    int *s_idx = reinterpret_cast<int *>(stage + K * ncand);
+    float *s_pmax = stage + 2 * K * ncand;
+    float *s_psum = s_pmax + K * a.n_chunks;
+    float *s_zs = s_psum + K * a.n_chunks;
+    for (int i = tid; i < K * ncand; i += 256) {
+      s_keys[i] = keys_b[i];
+      s_idx[i] = idxs_b[i];
+    }
+    if (!a.normalized)
+      for (int i = tid; i < K * a.n_chunks; i += 256) {
+        s_pmax[i] = pmax_b[i];
+        s_psum[i] = psum_b[i];
+      }
+    for (int i = tid; i < K * nz; i += 256) s_zs[i] = zs_b[i];
+    keys_b = s_keys;
+    idxs_b = s_idx;
+    pmax_b = s_pmax;
+    psum_b = s_psum;
+    zs_b = s_zs;
+  }
   __syncthreads();
   int t_cur = T_b;
   for (int k = 0; k < K; ++k)
@@ -388,7 +446,6 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
 
   // ---- per hypothesis: the K best tokens and blank, as total scores
   for (int k = wave; k < K; k += 4) {
-    const int m = m_base + k;
     const int kind = s_kind[k];
     if (kind != 2) {
       if (lane <= K) {
@@ -397,9 +454,10 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
       }
       continue;
     }
-    const int ncand = a.n_chunks * K;
-    const float *keys = a.p_key + (size_t)m * ncand;
-    const int *idxs = a.p_idx + (size_t)m * ncand;
+    const float *keys = keys_b + (size_t)k * ncand;
+    const int *idxs = idxs_b + (size_t)k * ncand;
+    const float *pmax = pmax_b + (size_t)k * a.n_chunks, *psum = psum_b + (size_t)k * a.n_chunks;
+    const float *zsr = zs_b + (size_t)k * nz;
     // K rounds of "best remaining candidate"
     float my_key = -INFINITY;  // lane j keeps the j-th winner
     int my_idx = 0x7fffffff;
@@ -428,15 +486,15 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     }
     // soft-max statistics
     double lse_all = 0.0, lse_nb = 0.0, max_nb;
-    const double zb = (double)a.zs[(size_t)m * nz];
+    const double zb = (double)zsr[0];
     if (!a.normalized) {
       float mx = -INFINITY;
-      for (int c = lane; c < a.n_chunks; c += 64) mx = fmaxf(mx, a.p_max[(size_t)m * a.n_chunks + c]);
+      for (int c = lane; c < a.n_chunks; c += 64) mx = fmaxf(mx, pmax[c]);
       mx = wave_max(mx);
       double s = 0.0;
       for (int c = lane; c < a.n_chunks; c += 64) {
-        const float pm = a.p_max[(size_t)m * a.n_chunks + c];
-        if (pm > -INFINITY) s += (double)a.p_sum[(size_t)m * a.n_chunks + c] * exp((double)pm - (double)mx);
+        const float pm = pmax[c];
+        if (pm > -INFINITY) s += (double)(psum[c] * __expf(pm - mx));
       }
       s = wave_sum(s);
       lse_nb = (double)mx + log(s);
@@ -455,7 +513,7 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
       double dl[8];
       double dmx = -INFINITY;
       for (int d = 0; d < a.ND; ++d) {
-        dl[d] = (double)a.zs[(size_t)m * nz + 1 + d];
+        dl[d] = (double)zsr[1 + d];
         dmx = fmax(dmx, dl[d]);
       }
       if (!a.normalized) {
@@ -657,71 +715,143 @@ __device__ __forceinline__ float tanh_f(float x) {
   return x < 0.f ? -r : r;
 }
 
-__global__ __launch_bounds__(256) void k_lstm(const float *__restrict__ Whh, const float *__restrict__ G,
-                                              const float *__restrict__ h_cur, const float *__restrict__ c_cur,
-                                              float *__restrict__ h_nxt, float *__restrict__ c_nxt,
-                                              const int *__restrict__ src_row, const int *__restrict__ tok, int M,
-                                              int P, const int *done) {
+// W_hh: k4-major [P][4P] with the gate rows re-ordered; h: k4-major [P][Mp]; c: row-major [M][P].
+template <int WAVES, int ITERS>
+__global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ Whh, const float *__restrict__ G,
+                                                     const float *__restrict__ h_cur,
+                                                     const float *__restrict__ c_cur, float *__restrict__ h_nxt,
+                                                     float *__restrict__ c_nxt, const int *__restrict__ src_row,
+                                                     const int *__restrict__ tok, int M, int Mp, int P,
+                                                     const int *done) {
   if (*reinterpret_cast<const volatile int *>(done)) return;
-  __shared__ float red[3 * 16 * 64];
-  const int lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int tile = blockIdx.x, m = blockIdx.y * 32 + col;
-  const bool mvalid = m < M;
-  const int src = mvalid ? src_row[m] : 0;
-  const float *wp = Whh + (size_t)(tile * 32 + col) * P;
-  const float *hp = h_cur + (size_t)src * P;
-  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + k); };
-  auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + k); };
-  floatx16 acc = splitk_tile(a_at, b_at, P, red);
-  if (threadIdx.x >= 64 || !mvalid) return;
-  const int token = tok[m];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int ul = 2 * q + half, u = tile * 8 + ul;
-    float c, h;
-    if (token >= 0) {
-      const float4 g4 = *reinterpret_cast<const float4 *>(G + (size_t)token * 4 * P + tile * 32 + 4 * ul);
-      const float gi = acc[4 * q + 0] + g4.x, gf = acc[4 * q + 1] + g4.y, gg = acc[4 * q + 2] + g4.z,
-                  go = acc[4 * q + 3] + g4.w;
-      c = sigmoid_f(gf) * c_cur[(size_t)src * P + u] + sigmoid_f(gi) * tanh_f(gg);
-      h = sigmoid_f(go) * tanh_f(c);
-    } else {
-      c = c_cur[(size_t)src * P + u];
-      h = h_cur[(size_t)src * P + u];
-    }
-    c_nxt[(size_t)m * P + u] = c;
-    h_nxt[(size_t)m * P + u] = h;
+  __shared__ float red[WAVES * 64 * kRedStride];
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
+  const int tile = blockIdx.x, m0 = blockIdx.y * 32;
+  // epilogue role of this thread: (hypothesis j, unit ul of the 8 units of the tile); its inputs are
+  // requested now so that they arrive while the contraction runs
+  const int j = tid >> 3, ul = tid & 7, u = tile * 8 + ul;
+  const int me = m0 + j;
+  const bool evalid = tid < 256 && me < M;
+  int e_src = 0, e_tok = -1;
+  float c_old = 0.f, h_old = 0.f;
+  float4 g4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (evalid) {
+    e_src = src_row[me];
+    e_tok = tok[me];
+    c_old = c_cur[(size_t)e_src * P + u];
+    h_old = h_cur[k4_index(u, e_src, Mp)];
+    if (e_tok >= 0) g4 = *reinterpret_cast<const float4 *>(G + (size_t)e_tok * 4 * P + tile * 32 + 4 * ul);
   }
+  {
+    const int m = m0 + col;
+    const int src = m < M ? src_row[m] : 0;
+    const int R = 4 * P;
+    const float *wp = Whh + (size_t)(tile * 32 + col) * 4;
+    const float *hp = h_cur + (size_t)src * 4;
+    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R * 4); };
+    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
+    splitk_partials<WAVES, ITERS>(a_at, b_at, P, red);
+  }
+  if (!evalid) return;
+  float c = c_old, h = h_old;
+  if (e_tok >= 0) {
+    const float gi = tile_value<WAVES>(red, 4 * ul + 0, j) + g4.x;
+    const float gf = tile_value<WAVES>(red, 4 * ul + 1, j) + g4.y;
+    const float gg = tile_value<WAVES>(red, 4 * ul + 2, j) + g4.z;
+    const float go = tile_value<WAVES>(red, 4 * ul + 3, j) + g4.w;
+    c = sigmoid_f(gf) * c_old + sigmoid_f(gi) * tanh_f(gg);
+    h = sigmoid_f(go) * tanh_f(c);
+  }
+  c_nxt[(size_t)me * P + u] = c;
+  h_nxt[k4_index(u, me, Mp)] = h;
 }
 
-// g_proj[m] = W_pred h[m] + b_pred
-__global__ __launch_bounds__(256) void k_pred_proj(const float *__restrict__ Wp, const float *__restrict__ bias,
-                                                   const float *__restrict__ h, float *__restrict__ g, int M, int P,
-                                                   int H, int round_ops, const int *done, int *step_base,
-                                                   int bump) {
-  if (*reinterpret_cast<const volatile int *>(done)) return;
-  __shared__ float red[3 * 16 * 64];
-  const int lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
-  const int tile = blockIdx.x, m = blockIdx.y * 32 + col;
-  const bool mvalid = m < M;
-  const float *wp = Wp + (size_t)(tile * 32 + col) * P;
-  const float *hp = h + (size_t)(mvalid ? m : 0) * P;
-  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + k); };
-  auto b_at = [&](int k) {
-    float4 v = *reinterpret_cast<const float4 *>(hp + k);
-    if (round_ops) v = bf16_round4(v);
-    return v;
-  };
-  floatx16 acc = splitk_tile(a_at, b_at, P, red);
-  if (bump && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *step_base += bump;
-  if (threadIdx.x >= 64 || !mvalid) return;
+// pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
+// W_pred: k4-major [P][H]; h: k4-major [P][Mp]; f_proj: row-major [B * T, H].
+struct PredProjArgs {
+  const float *Wp, *bias, *h, *f_proj;
+  const int *t, *lengths;
+  float *pre;
+  int M, Mp, K, T, P, H, round_ops;
+  const int *done;
+  int *step_base;
+  int bump;
+};
+
+template <int WAVES, int ITERS>
+__global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
+  if (*reinterpret_cast<const volatile int *>(a.done)) return;
+  __shared__ float red[WAVES * 64 * kRedStride];
+  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
+  const int tile = blockIdx.x, m0 = blockIdx.y * 32;
+  // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1); the frame's projection is requested early
+  const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
+  const int me = m0 + j;
+  float fv[VPL], bv[VPL];
+  if (me < a.M) {
+    const int b = me / a.K;
+    const int T_b = a.lengths[b];
+    int tt = a.t[me];
+    tt = tt < T_b ? tt : T_b - 1;
+    tt = tt < 0 ? 0 : tt;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int j = tile * 32 + 8 * q + 4 * half;
-    const float4 bv = *reinterpret_cast<const float4 *>(bias + j);
-    float4 o = make_float4(acc[4 * q] + bv.x, acc[4 * q + 1] + bv.y, acc[4 * q + 2] + bv.z, acc[4 * q + 3] + bv.w);
-    *reinterpret_cast<float4 *>(g + (size_t)m * H + j) = o;
+    for (int q = 0; q < VPL; ++q) {
+      fv[q] = a.f_proj[((size_t)b * a.T + tt) * a.H + o0 + q];
+      bv[q] = a.bias[o0 + q];
+    }
   }
+  {
+    const float *wp = a.Wp + (size_t)(tile * 32 + col) * 4;
+    const float *hp = a.h + (size_t)(m0 + col) * 4;
+    const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
+    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * H * 4); };
+    auto b_at = [&](int k) {
+      float4 v = *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4);
+      if (round_ops) v = bf16_round4(v);
+      return v;
+    };
+    splitk_partials<WAVES, ITERS>(a_at, b_at, a.P, red);
+  }
+  if (a.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.step_base += a.bump;
+  if (me >= a.M) return;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q)
+    a.pre[k4_index(o0 + q, me, a.Mp)] = tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + bv[q] + fv[q];
+}
+
+// Stateless prediction network: pre[m] = f_proj[b, t_m] + sum_i tab_i[token_i of m] (tables folded
+// with W_pred and b_pred at create).  One thread per (hypothesis, group of 4 outputs).
+struct StatelessPreArgs {
+  const float *f_proj, *tab;
+  const int *ctx_tok, *t, *lengths;
+  float *pre;
+  int M, Mp, K, T, H, V, n_ctx;
+  const int *done;
+  int *step_base;
+  int bump;
+};
+
+__global__ __launch_bounds__(256) void k_stateless_pre(StatelessPreArgs a) {
+  if (*reinterpret_cast<const volatile int *>(a.done)) return;
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  if (a.bump && gid == 0) *a.step_base += a.bump;
+  const int H4 = a.H >> 2;
+  const int m = gid / H4, o4 = gid % H4;
+  if (m >= a.M) return;
+  const int b = m / a.K;
+  const int T_b = a.lengths[b];
+  int tt = a.t[m];
+  tt = tt < T_b ? tt : T_b - 1;
+  tt = tt < 0 ? 0 : tt;
+  float4 v = *reinterpret_cast<const float4 *>(a.f_proj + ((size_t)b * a.T + tt) * a.H + 4 * o4);
+  for (int i = 0; i < a.n_ctx; ++i) {
+    int tk = a.ctx_tok[m * kCtxMax + i];
+    tk = tk < 0 ? a.V : tk;
+    const float4 g = *reinterpret_cast<const float4 *>(a.tab + ((size_t)i * (a.V + 1) + tk) * a.H + 4 * o4);
+    v.x += g.x; v.y += g.y; v.z += g.z; v.w += g.w;
+  }
+  *reinterpret_cast<float4 *>(a.pre + ((size_t)o4 * a.Mp + m) * 4) = v;
 }
 
 __global__ void k_fill_int(int *p, int value, int n) {
@@ -746,8 +876,8 @@ struct InitArgs {
   const int *lengths_in;
   int *lengths;
   int *src_row, *tok;
-  float *h0, *c0;  // [M, P] zeroed state the first LSTM step reads (nullable)
-  int P;
+  float *h0, *c0;  // zeroed state the first LSTM step reads (nullable), n_state floats each
+  size_t n_state;
   int B, K, T, V, lstm;
   int *finished, *utt_steps, *n_finished, *done, *step_base, *bad_arg;
   volatile int *h_done;
@@ -787,7 +917,7 @@ __global__ void k_init(InitArgs a) {
     a.tok[gid] = (a.lstm && k == 0) ? a.V : -1;
   }
   if (a.h0) {
-    const size_t n = (size_t)M * a.P;
+    const size_t n = a.n_state;
     for (size_t i = gid; i < n; i += (size_t)gridDim.x * blockDim.x) {
       a.h0[i] = 0.f;
       a.c0[i] = 0.f;

@@ -46,13 +46,13 @@ const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init", "k_joint"
 struct rnnt_beam {
   rnnt_config_t cfg;
   std::string err;
-  int N = 0, n_chunks = 0, M_max = 0, S_max = 0, cap = 0, pc_chunks = 0;
+  int N = 0, n_chunks = 0, M_max = 0, Mp = 0, S_max = 0, cap = 0, pc_chunks = 0;
   std::vector<void *> allocs;
   // packed weights
   float *W_enc = nullptr, *b_enc = nullptr, *W_pred = nullptr, *b_pred = nullptr, *W_out = nullptr,
         *b_out = nullptr, *W_hh = nullptr, *G = nullptr, *tab = nullptr;
   // workspace
-  float *f_proj = nullptr, *g_proj[2] = {nullptr, nullptr}, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
+  float *f_proj = nullptr, *pre = nullptr, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
   float *lm_rows = nullptr;
   double *score = nullptr;
   int *t = nullptr, *sym = nullptr, *len = nullptr, *last = nullptr, *ctx = nullptr, *lengths = nullptr;
@@ -127,6 +127,14 @@ int launch_gemm(rnnt_beam *h, hipStream_t s, const float *A, const float *B, con
   return RNNT_OK;
 }
 
+// row-major [rows, K] -> k4-major [K][rows_padded] (rows beyond `rows` are zero)
+std::vector<float> to_k4(const std::vector<float> &src, int rows, int K, int rows_padded) {
+  std::vector<float> out((size_t)K * rows_padded, 0.f);
+  for (int r = 0; r < rows; ++r)
+    for (int k = 0; k < K; ++k) out[k4_index(k, r, rows_padded)] = src[(size_t)r * K + k];
+  return out;
+}
+
 int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
   const rnnt_config_t &c = h->cfg;
   const int H = c.H, P = c.P, D = c.D, E = c.E, V = c.V, N = h->N;
@@ -140,19 +148,21 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
   if ((rc = upload(h, &h->W_enc, tmp))) return rc;
   if ((rc = download(h, tmp, w->b_enc, H))) return rc;
   if ((rc = upload(h, &h->b_enc, tmp))) return rc;
-  // prediction projection
+  // prediction projection (row-major copy for the table folding, k4-major for the per-step kernel)
   std::vector<float> wpred, bpred;
   if ((rc = download(h, wpred, w->W_pred, (size_t)H * P))) return rc;
   if (bf)
     for (auto &x : wpred) x = host_bf16_round(x);
-  if ((rc = upload(h, &h->W_pred, wpred))) return rc;
+  float *d_wpred_rm = nullptr;
+  if ((rc = upload(h, &d_wpred_rm, wpred))) return rc;
+  if ((rc = upload(h, &h->W_pred, to_k4(wpred, H, P, H)))) return rc;
   if ((rc = download(h, bpred, w->b_pred, H))) return rc;
   if ((rc = upload(h, &h->b_pred, bpred))) return rc;
   // output layer, rows padded with zeros to whole 32-column chunks
   if ((rc = download(h, tmp, w->W_out, (size_t)N * H))) return rc;
-  out.assign((size_t)h->n_chunks * 32 * H, 0.f);
-  for (size_t i = 0; i < (size_t)N * H; ++i) out[i] = bf ? host_bf16_round(tmp[i]) : tmp[i];
-  if ((rc = upload(h, &h->W_out, out))) return rc;
+  if (bf)
+    for (auto &x : tmp) x = host_bf16_round(x);
+  if ((rc = upload(h, &h->W_out, to_k4(tmp, N, H, h->n_chunks * 32)))) return rc;
   if ((rc = download(h, tmp, w->b_out, N))) return rc;
   out.assign((size_t)h->n_chunks * 32, 0.f);
   for (int i = 0; i < N; ++i) out[i] = tmp[i];
@@ -176,7 +186,7 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
       memcpy(&wih_p[(size_t)r * E], &wih[(size_t)o * E], sizeof(float) * E);
       b_p[r] = bih[o] + bhh[o];
     }
-    if ((rc = upload(h, &h->W_hh, whh_p))) return rc;
+    if ((rc = upload(h, &h->W_hh, to_k4(whh_p, 4 * P, P, 4 * P)))) return rc;
     // G[v] = W_ih emb[v] + b_ih + b_hh for every token (and the start symbol): one GEMM at create
     float *d_wih = nullptr, *d_b = nullptr, *d_emb = nullptr;
     if ((rc = upload(h, &d_wih, wih_p))) return rc;
@@ -195,7 +205,7 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
     if ((rc = upload(h, &d_emb, emb))) return rc;
     if ((rc = dev_alloc(h, &h->tab, (size_t)ctx * (V + 1) * H))) return rc;
     for (int i = 0; i < ctx; ++i)
-      if ((rc = launch_gemm(h, nullptr, d_emb + (size_t)i * (V + 1) * P, h->W_pred, i == 0 ? h->b_pred : nullptr,
+      if ((rc = launch_gemm(h, nullptr, d_emb + (size_t)i * (V + 1) * P, d_wpred_rm, i == 0 ? h->b_pred : nullptr,
                             h->tab + (size_t)i * (V + 1) * H, V + 1, H, P, bf ? 1 : 0, nullptr)))
         return rc;
   }
@@ -235,19 +245,45 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
   const rnnt_config_t &c = h->cfg;
   int *done = h->ctrl + 1, *step_base = h->ctrl + 2;
   const int m_tiles = (p.M + 31) / 32;
-  if (c.pred == RNNT_PRED_LSTM && !p.inj_tok) {
+  if (p.inj_tok) {
+    if (bump) hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done);
+  } else if (c.pred == RNNT_PRED_LSTM) {
     {
       ScopedKernelTime tm(h, s, KT_LSTM);
-      hipLaunchKernelGGL(k_lstm, dim3(4 * c.P / 32, m_tiles), dim3(256), 0, s, h->W_hh, h->G, h->h[cur], h->c[cur],
-                         h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, c.P, done);
+      const dim3 grid(4 * c.P / 32, m_tiles);
+#define RB_LSTM(W, I)                                                                                         \
+  hipLaunchKernelGGL((k_lstm<W, I>), grid, dim3(W * 64), 0, s, h->W_hh, h->G, h->h[cur], h->c[cur], h->h[cur ^ 1], \
+                     h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done)
+      if (c.P == 640) RB_LSTM(8, 10);
+      else if (c.P % 64 == 0) RB_LSTM(8, 0);
+      else RB_LSTM(4, 0);
+#undef RB_LSTM
     }
     {
+      PredProjArgs a;
+      a.Wp = h->W_pred; a.bias = h->b_pred; a.h = h->h[cur ^ 1]; a.f_proj = h->f_proj;
+      a.t = h->t; a.lengths = h->lengths;
+      a.pre = h->pre;
+      a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
+      a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
+      a.done = done; a.step_base = step_base; a.bump = bump;
       ScopedKernelTime tm(h, s, KT_PREDPROJ);
-      hipLaunchKernelGGL(k_pred_proj, dim3(c.H / 32, m_tiles), dim3(256), 0, s, h->W_pred, h->b_pred, h->h[cur ^ 1],
-                         h->g_proj[cur ^ 1], p.M, c.P, c.H, c.prec == RNNT_BF16_JOINT ? 1 : 0, done, step_base, bump);
+      const dim3 grid(c.H / 32, m_tiles);
+#define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), 0, s, a)
+      if (c.P == 640) RB_PRED(8, 10);
+      else if (c.P % 64 == 0) RB_PRED(8, 0);
+      else RB_PRED(4, 0);
+#undef RB_PRED
     }
-  } else if (bump) {
-    hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done);
+  } else {
+    StatelessPreArgs a;
+    a.f_proj = h->f_proj; a.tab = h->tab; a.ctx_tok = h->ctx; a.t = h->t; a.lengths = h->lengths;
+    a.pre = h->pre;
+    a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
+    a.done = done; a.step_base = step_base; a.bump = bump;
+    ScopedKernelTime tm(h, s, KT_PREDPROJ);
+    const int n = p.M * (c.H / 4);
+    hipLaunchKernelGGL(k_stateless_pre, dim3((n + 255) / 256), dim3(256), 0, s, a);
   }
   RB_HIP(h, hipGetLastError());
   return RNNT_OK;
@@ -287,18 +323,12 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     else hipLaunchKernelGGL(k_inject<16>, dim3(p.M), dim3(64), 0, s, a);
   } else {
     JointArgs a;
-    a.f_proj = h->f_proj;
-    a.g_proj = c.pred == RNNT_PRED_LSTM ? h->g_proj[cur] : nullptr;
-    a.tab = h->tab;
-    a.ctx_tok = h->ctx;
-    a.n_ctx = c.stateless_context;
-    a.t = h->t;
-    a.lengths = h->lengths;
+    a.pre = h->pre;
     a.W = h->W_out;
     a.bias = h->b_out;
     a.lm = p.lm ? h->lm_rows : nullptr;
     a.lambda = p.lambda;
-    a.M = p.M; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
+    a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
     a.n_chunks = h->n_chunks;
     a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
     a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_key = h->p_key; a.p_idx = h->p_idx; a.zs = h->zs;
@@ -306,9 +336,12 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     n_chunks = h->n_chunks;
     dim3 grid(h->n_chunks, (p.M + 31) / 32);
     ScopedKernelTime tm(h, s, KT_JOINT);
-    if (kt == 4) hipLaunchKernelGGL(k_joint<4>, grid, dim3(256), 0, s, a);
-    else if (kt == 8) hipLaunchKernelGGL(k_joint<8>, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(k_joint<16>, grid, dim3(256), 0, s, a);
+#define RB_JOINT(W, I) hipLaunchKernelGGL((k_joint<W, I>), grid, dim3(W * 64), 0, s, a)
+    (void)kt;
+    if (c.H == 640) RB_JOINT(8, 10);
+    else if (c.H % 64 == 0) RB_JOINT(8, 0);
+    else RB_JOINT(4, 0);
+#undef RB_JOINT
   }
   RB_HIP(h, hipGetLastError());
   {
@@ -333,8 +366,11 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.step_off = step_off;
     a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
     a.h_done = h->h_done_dev;
+    const size_t stage_bytes =
+        sizeof(float) * ((size_t)2 * p.K * n_chunks * p.K + (size_t)2 * p.K * n_chunks + (size_t)p.K * (1 + c.n_durations));
+    a.stage = stage_bytes <= 40 * 1024;
     ScopedKernelTime tm(h, s, KT_SELECT);
-    hipLaunchKernelGGL(k_select, dim3(p.B), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_select, dim3(p.B), dim3(256), a.stage ? stage_bytes : 0, s, a);
   }
   RB_HIP(h, hipGetLastError());
   int rc = launch_lm(h, s, p);
@@ -363,7 +399,7 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     const bool lstm = c.pred == RNNT_PRED_LSTM && !p.inj_tok;
     a.h0 = lstm ? h->h[1] : nullptr;
     a.c0 = lstm ? h->c[1] : nullptr;
-    a.P = c.P;
+    a.n_state = (size_t)c.P * h->Mp;
     a.B = p.B; a.K = p.K; a.T = p.T; a.V = c.V;
     a.lstm = lstm ? 1 : 0;
     a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
@@ -517,6 +553,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   h->n_chunks = (h->N + 31) / 32;
   h->pc_chunks = h->n_chunks > 64 ? h->n_chunks : 64;
   h->M_max = c.max_B * c.max_beam;
+  h->Mp = (h->M_max + 31) / 32 * 32;
   h->S_max = c.max_T * (c.max_symbols + 1);
   h->cap = c.max_T * c.max_symbols + 1;
   const size_t M = h->M_max;
@@ -526,10 +563,10 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   };
   A(pack_weights(h, w));
   A(dev_alloc(h, &h->f_proj, (size_t)c.max_B * c.max_T * c.H));
+  A(dev_alloc(h, &h->pre, (size_t)h->Mp * c.H));
   for (int i = 0; i < 2; ++i) {
-    A(dev_alloc(h, &h->g_proj[i], M * c.H));
-    A(dev_alloc(h, &h->h[i], M * c.P));
-    A(dev_alloc(h, &h->c[i], M * c.P));
+    A(dev_alloc(h, &h->h[i], (size_t)h->Mp * c.P));
+    A(dev_alloc(h, &h->c[i], (size_t)h->Mp * c.P));
   }
   A(dev_alloc(h, &h->lm_rows, M * c.V));
   A(dev_alloc(h, &h->score, M));
