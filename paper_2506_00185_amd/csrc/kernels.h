@@ -65,30 +65,46 @@ __global__ __launch_bounds__(256) void k_gemm_nt(const float *__restrict__ A, co
 // ---------------------------------------------------------------------------
 constexpr int kRedStride = 17;
 
+// Operand registers of one wave: ITERS > 0 keeps every 16-byte load of the wave's K slice in flight at once.
+template <int ITERS>
+struct SplitKOperands {
+  float4 a[ITERS > 0 ? ITERS : 1], b[ITERS > 0 ? ITERS : 1];
+};
+
+// issue the loads (ITERS > 0 only; the plain loop of ITERS == 0 loads as it goes)
 template <int WAVES, int ITERS, class AL, class BL>
-__device__ __forceinline__ void splitk_partials(AL a_at, BL b_at, int K, float *red) {
+__device__ __forceinline__ void splitk_load(SplitKOperands<ITERS> &op, AL a_at, BL b_at, int K) {
+  if constexpr (ITERS > 0) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+    const int kbeg = wave * (K / WAVES) + 4 * half;
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) op.a[i] = a_at(kbeg + 8 * i);
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) op.b[i] = b_at(kbeg + 8 * i);
+  }
+}
+
+// matrix instructions of the wave's K slice, partial tile to LDS, block barrier.
+// fb: applied to each hypothesis-side operand just before use (ReLU, rounding).
+template <int WAVES, int ITERS, class AL, class BL, class FB>
+__device__ __forceinline__ void splitk_mma(SplitKOperands<ITERS> &op, AL a_at, BL b_at, FB fb, int K, float *red) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int kw = K / WAVES;
   floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  const int kbeg = wave * kw + 4 * half;
   if constexpr (ITERS > 0) {
-    float4 av[ITERS], bv[ITERS];
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) av[i] = a_at(kbeg + 8 * i);
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) bv[i] = b_at(kbeg + 8 * i);
 #pragma unroll
     for (int i = 0; i < ITERS; ++i) {
-      acc = mfma32(av[i].x, bv[i].x, acc);
-      acc = mfma32(av[i].y, bv[i].y, acc);
-      acc = mfma32(av[i].z, bv[i].z, acc);
-      acc = mfma32(av[i].w, bv[i].w, acc);
+      const float4 b = fb(op.b[i]);
+      acc = mfma32(op.a[i].x, b.x, acc);
+      acc = mfma32(op.a[i].y, b.y, acc);
+      acc = mfma32(op.a[i].z, b.z, acc);
+      acc = mfma32(op.a[i].w, b.w, acc);
     }
   } else {
-    const int kend = (wave + 1) * kw;
+    const int kbeg = wave * kw + 4 * half, kend = (wave + 1) * kw;
     for (int k = kbeg; k < kend; k += 8) {
       const float4 a = a_at(k);
-      const float4 b = b_at(k);
+      const float4 b = fb(b_at(k));
       acc = mfma32(a.x, b.x, acc);
       acc = mfma32(a.y, b.y, acc);
       acc = mfma32(a.z, b.z, acc);
@@ -171,7 +187,6 @@ struct JointArgs {
 // are found in K rounds of an LPH-lane arg-max.
 template <int WAVES, int ITERS>
 __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
-  if (*reinterpret_cast<const volatile int *>(a.done)) return;
   __shared__ float red[WAVES * 64 * kRedStride];
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
@@ -182,13 +197,17 @@ __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
     const float *pp = a.pre + (size_t)(m0 + col) * 4;
     const int Mp = a.Mp, round_ops = a.round_ops;
     auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * Np * 4); };
-    auto b_at = [&](int k) {
-      float4 f = *reinterpret_cast<const float4 *>(pp + (size_t)(k >> 2) * Mp * 4);
+    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(pp + (size_t)(k >> 2) * Mp * 4); };
+    auto fb = [&](float4 f) {
       f.x = fmaxf(f.x, 0.f); f.y = fmaxf(f.y, 0.f); f.z = fmaxf(f.z, 0.f); f.w = fmaxf(f.w, 0.f);
       if (round_ops) f = bf16_round4(f);
       return f;
     };
-    splitk_partials<WAVES, ITERS>(a_at, b_at, a.H, red);
+    SplitKOperands<ITERS> op;
+    splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
+    // the loop is over: nothing below may run (checked once the operand loads are on their way)
+    if (*reinterpret_cast<const volatile int *>(a.done)) return;
+    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
   }
 
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
@@ -342,6 +361,7 @@ struct SelectArgs {
   const float *zs;
   int n_chunks;
   int stage;       // 1: the block copies its candidate lists into (dynamic) LDS first
+  int use_ctx;     // 1: the token history of each hypothesis is kept (stateless prediction network, LM)
   int normalized;  // 1: keys are log-probabilities already (injected mode)
   // configuration
   int B, K, V, ND;
@@ -362,19 +382,14 @@ struct SelectArgs {
   volatile int *h_done;  // pinned host word, set when every utterance has finished
 };
 
+__device__ __forceinline__ float logaddexp_f(float a, float b) {
+  const float m = fmaxf(a, b), d = fminf(a, b) - m;  // d <= 0
+  return d > -INFINITY ? m + log1pf(expf(d)) : m;
+}
+
 __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
-  if (*reinterpret_cast<volatile int *>(a.done)) return;
   const int b = blockIdx.x, K = a.K, V = a.V, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m_base = b * K;
-  if (a.finished[b]) {
-    if (tid < K) {
-      a.src_row[m_base + tid] = m_base + tid;
-      a.tok[m_base + tid] = -1;
-    }
-    return;
-  }
-  const int S = *a.step_base + a.step_off;
-  const int T_b = a.lengths[b];
   const int nz = 1 + a.ND;
 
   __shared__ double s_score[kMaxBeam];
@@ -382,15 +397,19 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   __shared__ uint32_t s_hash[kMaxBeam];
   __shared__ int s_ctx[kMaxBeam][kCtxMax];
   __shared__ int s_advt[kMaxBeam], s_advb[kMaxBeam];
-  __shared__ double rc_val[kMaxBeam][kMaxBeam + 1];
-  __shared__ int rc_tok[kMaxBeam][kMaxBeam + 1];
+  __shared__ double rc_val[kMaxBeam * (kMaxBeam + 1)];
+  __shared__ int rc_flat[kMaxBeam * (kMaxBeam + 1)];
   __shared__ double sel_val[kMaxBeam];
-  __shared__ int sel_k[kMaxBeam], sel_v[kMaxBeam];
-  // new state
+  __shared__ int sel_flat[kMaxBeam];
   __shared__ double n_score[kMaxBeam];
   __shared__ int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
   __shared__ uint32_t n_hash[kMaxBeam];
 
+  // every load of the prologue is issued before anything waits on one of them
+  const int fin = a.finished[b];
+  const int done = *reinterpret_cast<volatile int *>(a.done);
+  const int S = *a.step_base + a.step_off;
+  const int T_b = a.lengths[b];
   if (tid < K) {
     const int m = m_base + tid;
     s_score[tid] = a.score[m];
@@ -399,11 +418,11 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     s_len[tid] = a.len[m];
     s_last[tid] = a.last[m];
     s_hash[tid] = a.hash[m];
-#pragma unroll
-    for (int i = 0; i < kCtxMax; ++i) s_ctx[tid][i] = a.ctx[m * kCtxMax + i];
+    sel_val[tid] = -INFINITY;
+    sel_flat[tid] = -1;
   }
+  if (a.use_ctx && tid < K * kCtxMax) s_ctx[tid / kCtxMax][tid % kCtxMax] = a.ctx[m_base * kCtxMax + tid];
   // candidate lists of the K rows of this utterance: contiguous in memory; one coalesced copy into LDS
-  // turns the many dependent reads below into a single round trip
   extern __shared__ float stage[];
   const int ncand = a.n_chunks * K;
   const float *keys_b = a.p_key + (size_t)m_base * ncand;
@@ -433,6 +452,14 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     psum_b = s_psum;
     zs_b = s_zs;
   }
+  if (done) return;
+  if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
+    if (tid < K) {
+      a.src_row[m_base + tid] = m_base + tid;
+      a.tok[m_base + tid] = -1;
+    }
+    return;
+  }
   __syncthreads();
   int t_cur = T_b;
   for (int k = 0; k < K; ++k)
@@ -444,13 +471,17 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   }
   __syncthreads();
 
-  // ---- per hypothesis: the K best tokens and blank, as total scores
+  // ---- per hypothesis (one wave each): the K best tokens and blank, as total scores.
+  // Candidate c of the utterance is rc[k * (K + 1) + e]: e < K tokens, e == K blank / stay.
   for (int k = wave; k < K; k += 4) {
     const int kind = s_kind[k];
+    double *rv = rc_val + k * (K + 1);
+    int *rf = rc_flat + k * (K + 1);
+    const int flat0 = k * (V + 1);
     if (kind != 2) {
       if (lane <= K) {
-        rc_val[k][lane] = (kind == 1 && lane == K) ? s_score[k] : -INFINITY;
-        rc_tok[k][lane] = V;
+        rv[lane] = (kind == 1 && lane == K) ? s_score[k] : -INFINITY;
+        rf[lane] = flat0 + V;
       }
       continue;
     }
@@ -458,68 +489,98 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     const int *idxs = idxs_b + (size_t)k * ncand;
     const float *pmax = pmax_b + (size_t)k * a.n_chunks, *psum = psum_b + (size_t)k * a.n_chunks;
     const float *zsr = zs_b + (size_t)k * nz;
-    // K rounds of "best remaining candidate"
-    float my_key = -INFINITY;  // lane j keeps the j-th winner
+    // K rounds of "best remaining candidate"; lane j keeps the j-th winner
+    float my_key = -INFINITY;
     int my_idx = 0x7fffffff;
-    float last_v = INFINITY;
-    int last_i = -1;
-    for (int j = 0; j < K; ++j) {
-      float bv = -INFINITY;
-      int bi = 0x7fffffff;
-      for (int c = lane; c < ncand; c += 64) {
-        const float v = keys[c];
-        const int i = idxs[c];
-        const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
-        if (eligible && comes_before(v, i, bv, bi)) {
-          bv = v;
-          bi = i;
+    if (ncand <= 256) {
+      float ck[4];
+      int ci[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = lane + 64 * q;
+        ck[q] = c < ncand ? keys[c] : -INFINITY;
+        ci[q] = c < ncand ? idxs[c] : 0x7fffffff;
+      }
+      for (int j = 0; j < K; ++j) {
+        float bv = ck[0];
+        int bi = ci[0];
+#pragma unroll
+        for (int q = 1; q < 4; ++q)
+          if (comes_before(ck[q], ci[q], bv, bi)) {
+            bv = ck[q];
+            bi = ci[q];
+          }
+        wave_best(bv, bi);
+        if (lane == j) {
+          my_key = bv;
+          my_idx = bi;
         }
+        if (bv == -INFINITY) break;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (ci[q] == bi) ck[q] = -INFINITY;  // token ids are unique within a row
       }
-      wave_best(bv, bi);
-      if (lane == j) {
-        my_key = bv;
-        my_idx = bi;
+    } else {
+      float last_v = INFINITY;
+      int last_i = -1;
+      for (int j = 0; j < K; ++j) {
+        float bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int c = lane; c < ncand; c += 64) {
+          const float v = keys[c];
+          const int i = idxs[c];
+          const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
+          if (eligible && comes_before(v, i, bv, bi)) {
+            bv = v;
+            bi = i;
+          }
+        }
+        wave_best(bv, bi);
+        if (lane == j) {
+          my_key = bv;
+          my_idx = bi;
+        }
+        last_v = bv;
+        last_i = bi;
+        if (bv == -INFINITY) break;
       }
-      last_v = bv;
-      last_i = bi;
-      if (bv == -INFINITY) break;
     }
-    // soft-max statistics
-    double lse_all = 0.0, lse_nb = 0.0, max_nb;
-    const double zb = (double)zsr[0];
+    // soft-max statistics (float transcendental math, scores accumulate in double)
+    float lse_all = 0.f, lse_nb = 0.f, max_nb;
+    const float zb = zsr[0];
     if (!a.normalized) {
       float mx = -INFINITY;
       for (int c = lane; c < a.n_chunks; c += 64) mx = fmaxf(mx, pmax[c]);
       mx = wave_max(mx);
-      double s = 0.0;
+      float sm = 0.f;
       for (int c = lane; c < a.n_chunks; c += 64) {
         const float pm = pmax[c];
-        if (pm > -INFINITY) s += (double)(psum[c] * __expf(pm - mx));
+        if (pm > -INFINITY) sm += psum[c] * __expf(pm - mx);
       }
-      s = wave_sum(s);
-      lse_nb = (double)mx + log(s);
-      lse_all = logaddexp_d(lse_nb, zb);
-      max_nb = (double)mx;
+      sm = wave_sum(sm);
+      lse_nb = mx + logf(sm);
+      lse_all = logaddexp_f(lse_nb, zb);
+      max_nb = mx;
     } else {
-      max_nb = (double)__shfl(my_key, 0);
+      max_nb = __shfl(my_key, 0);
     }
-    const double logp_b = zb - lse_all;
-    const double nb = lse_nb - lse_all;
-    const double maxlogp = fmax(max_nb, zb) - lse_all;
+    const double logp_b = (double)zb - (double)lse_all;
+    const double nb = (double)lse_nb - (double)lse_all;
+    const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
     // TDT: one duration per candidate
     double x_tok = 0.0, x_blank = 0.0;
     int adv_tok = 0, adv_blank = 1;
     if (a.ND > 0) {
-      double dl[8];
-      double dmx = -INFINITY;
+      float dl[8];
+      float dmx = -INFINITY;
       for (int d = 0; d < a.ND; ++d) {
-        dl[d] = (double)zsr[1 + d];
-        dmx = fmax(dmx, dl[d]);
+        dl[d] = zsr[1 + d];
+        dmx = fmaxf(dmx, dl[d]);
       }
       if (!a.normalized) {
-        double s = 0.0;
-        for (int d = 0; d < a.ND; ++d) s += exp(dl[d] - dmx);
-        const double l = dmx + log(s);
+        float sm = 0.f;
+        for (int d = 0; d < a.ND; ++d) sm += expf(dl[d] - dmx);
+        const float l = dmx + logf(sm);
         for (int d = 0; d < a.ND; ++d) dl[d] -= l;
       }
       int best = -1, best_b = -1;
@@ -527,8 +588,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
         if (best < 0 || dl[d] > dl[best]) best = d;
         if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
       }
-      x_tok = dl[best];
-      x_blank = dl[best_b];
+      x_tok = (double)dl[best];
+      x_blank = (double)dl[best_b];
       adv_tok = a.dur[best];
       adv_blank = a.dur[best_b];
     }
@@ -539,17 +600,17 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     if (lane < K) {
       double val = -INFINITY;
       if (my_key > -INFINITY && !forced) {
-        const double lp = (double)my_key - lse_all;  // pre-LM log-probability when no LM is fused
+        const double lp = (double)my_key - (double)lse_all;  // pre-LM log-probability when no LM is fused
         if (!(use_gamma && lp < thr)) val = sc + lp + (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok;
       }
-      rc_val[k][lane] = val;
-      rc_tok[k][lane] = my_idx;
+      rv[lane] = val;
+      rf[lane] = flat0 + (my_idx < V ? my_idx : V - 1);
     }
     if (lane == K) {
       double val = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
       if (use_gamma && logp_b < thr && !forced) val = -INFINITY;
-      rc_val[k][K] = sc + val + x_blank;
-      rc_tok[k][K] = V;
+      rv[K] = sc + val + x_blank;
+      rf[K] = flat0 + V;
       s_advt[k] = adv_tok;
       s_advb[k] = adv_blank;
     }
@@ -559,29 +620,40 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   // ---- the Beam best of all K * (K + 1) candidates, by (value desc, k * (V + 1) + v asc)
   if (wave == 0) {
     const int n = K * (K + 1);
-    double last_v = INFINITY;
-    long long last_i = -1;
-    for (int j = 0; j < K; ++j) {
-      double bv = -INFINITY;
-      long long bi = 0x7fffffffffffffffll;
-      for (int c = lane; c < n; c += 64) {
-        const int k = c / (K + 1), e = c % (K + 1);
-        const double v = rc_val[k][e];
-        const long long i = (long long)k * (V + 1) + rc_tok[k][e];
-        const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
-        if (eligible && comes_before(v, i, bv, bi)) {
-          bv = v;
-          bi = i;
+    if (n <= 64) {
+      // few candidates: each lane counts how many come before its own; that count is its new slot
+      const double mv = lane < n ? rc_val[lane] : -INFINITY;
+      const int mf = lane < n ? rc_flat[lane] : 0x7fffffff;
+      int rank = 0;
+      for (int c = 0; c < n; ++c) rank += comes_before(rc_val[c], rc_flat[c], mv, mf) ? 1 : 0;
+      if (mv > -INFINITY && rank < K) {
+        sel_val[rank] = mv;
+        sel_flat[rank] = mf;
+      }
+    } else {
+      double last_v = INFINITY;
+      int last_i = -1;
+      for (int j = 0; j < K; ++j) {
+        double bv = -INFINITY;
+        int bi = 0x7fffffff;
+        for (int c = lane; c < n; c += 64) {
+          const double v = rc_val[c];
+          const int i = rc_flat[c];
+          const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
+          if (eligible && comes_before(v, i, bv, bi)) {
+            bv = v;
+            bi = i;
+          }
         }
+        wave_best(bv, bi);
+        if (lane == 0 && bv > -INFINITY) {
+          sel_val[j] = bv;
+          sel_flat[j] = bi;
+        }
+        last_v = bv;
+        last_i = bi;
+        if (!(bv > -INFINITY)) break;
       }
-      wave_best(bv, bi);
-      if (lane == 0) {
-        sel_val[j] = bv;
-        sel_k[j] = bv > -INFINITY ? (int)(bi / (V + 1)) : -1;
-        sel_v[j] = bv > -INFINITY ? (int)(bi % (V + 1)) : -1;
-      }
-      last_v = bv;
-      last_i = bi;
     }
   }
   __syncthreads();
@@ -592,6 +664,8 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   if (tid < K) {
     const int j = tid;
     const double val = sel_val[j];
+#pragma unroll
+    for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = -1;
     if (!(val > -INFINITY)) {
       n_live[j] = 0;
       n_score[j] = -INFINITY;
@@ -600,15 +674,15 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
       n_len[j] = 0;
       n_last[j] = -1;
       n_hash[j] = 0;
-#pragma unroll
-      for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = -1;
     } else {
-      const int k = sel_k[j], v = sel_v[j];
+      const int k = sel_flat[j] / (V + 1), v = sel_flat[j] % (V + 1);
       parent = k;
       int t = s_t[k], sym = s_sym[k], len = s_len[k], last = s_last[k];
       uint32_t hash = s_hash[k];
+      if (a.use_ctx) {
 #pragma unroll
-      for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = s_ctx[k][i];
+        for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = s_ctx[k][i];
+      }
       if (s_kind[k] == 1) {
         code = -2;
       } else if (v == V) {
@@ -671,8 +745,10 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     a.len[m] = n_len[j];
     a.last[m] = n_last[j];
     a.hash[m] = n_hash[j];
+    if (a.use_ctx) {
 #pragma unroll
-    for (int i = 0; i < kCtxMax; ++i) a.ctx[m * kCtxMax + i] = ctx_new[i];
+      for (int i = 0; i < kCtxMax; ++i) a.ctx[m * kCtxMax + i] = ctx_new[i];
+    }
     a.src_row[m] = parent >= 0 ? m_base + parent : m;
     a.tok[m] = appended;
     if (S < a.S_max) {
@@ -681,15 +757,10 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
       a.tree_token[ti] = code;
       a.tree_merged[ti] = merged;
     }
-    // second pass over shared state needs the surviving flags
-    s_kind[j] = live ? 1 : 0;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    bool unfinished = false;
-    for (int j = 0; j < K; ++j)
-      if (s_kind[j] && n_t[j] < T_b) unfinished = true;
-    if (!unfinished || S + 1 >= T_b * (a.max_sym + 1)) {
+    // finished when no surviving slot has frames left
+    const bool open = live && n_t[j] < T_b;
+    const unsigned long long any_open = __ballot(open);
+    if (j == 0 && (any_open == 0ull || S + 1 >= T_b * (a.max_sym + 1))) {
       a.finished[b] = 1;
       a.utt_steps[b] = S + 1;
       __threadfence();
@@ -723,35 +794,36 @@ __global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ W
                                                      float *__restrict__ c_nxt, const int *__restrict__ src_row,
                                                      const int *__restrict__ tok, int M, int Mp, int P,
                                                      const int *done) {
-  if (*reinterpret_cast<const volatile int *>(done)) return;
   __shared__ float red[WAVES * 64 * kRedStride];
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int tile = blockIdx.x, m0 = blockIdx.y * 32;
+  const int m = m0 + col;
+  const int src = m < M ? src_row[m] : 0;
+  const int R = 4 * P;
+  const float *wp = Whh + (size_t)(tile * 32 + col) * 4;
+  const float *hp = h_cur + (size_t)src * 4;
+  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R * 4); };
+  auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
+  auto fb = [](float4 v) { return v; };
+  SplitKOperands<ITERS> op;
+  splitk_load<WAVES, ITERS>(op, a_at, b_at, P);
   // epilogue role of this thread: (hypothesis j, unit ul of the 8 units of the tile); its inputs are
-  // requested now so that they arrive while the contraction runs
+  // requested now, behind the operand loads, so that they arrive while the contraction runs
   const int j = tid >> 3, ul = tid & 7, u = tile * 8 + ul;
   const int me = m0 + j;
   const bool evalid = tid < 256 && me < M;
-  int e_src = 0, e_tok = -1;
+  int e_tok = -1;
   float c_old = 0.f, h_old = 0.f;
   float4 g4 = make_float4(0.f, 0.f, 0.f, 0.f);
   if (evalid) {
-    e_src = src_row[me];
+    const int e_src = src_row[me];
     e_tok = tok[me];
     c_old = c_cur[(size_t)e_src * P + u];
     h_old = h_cur[k4_index(u, e_src, Mp)];
     if (e_tok >= 0) g4 = *reinterpret_cast<const float4 *>(G + (size_t)e_tok * 4 * P + tile * 32 + 4 * ul);
   }
-  {
-    const int m = m0 + col;
-    const int src = m < M ? src_row[m] : 0;
-    const int R = 4 * P;
-    const float *wp = Whh + (size_t)(tile * 32 + col) * 4;
-    const float *hp = h_cur + (size_t)src * 4;
-    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R * 4); };
-    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
-    splitk_partials<WAVES, ITERS>(a_at, b_at, P, red);
-  }
+  if (*reinterpret_cast<const volatile int *>(done)) return;
+  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, P, red);
   if (!evalid) return;
   float c = c_old, h = h_old;
   if (e_tok >= 0) {
@@ -780,12 +852,20 @@ struct PredProjArgs {
 
 template <int WAVES, int ITERS>
 __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
-  if (*reinterpret_cast<const volatile int *>(a.done)) return;
   __shared__ float red[WAVES * 64 * kRedStride];
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int tile = blockIdx.x, m0 = blockIdx.y * 32;
-  // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1); the frame's projection is requested early
+  const float *wp = a.Wp + (size_t)(tile * 32 + col) * 4;
+  const float *hp = a.h + (size_t)(m0 + col) * 4;
+  const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
+  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * H * 4); };
+  auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
+  auto fb = [&](float4 v) { return round_ops ? bf16_round4(v) : v; };
+  SplitKOperands<ITERS> op;
+  splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
+  // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1); the frame's projection is requested
+  // behind the operand loads
   const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
   const int me = m0 + j;
   float fv[VPL], bv[VPL];
@@ -801,18 +881,8 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
       bv[q] = a.bias[o0 + q];
     }
   }
-  {
-    const float *wp = a.Wp + (size_t)(tile * 32 + col) * 4;
-    const float *hp = a.h + (size_t)(m0 + col) * 4;
-    const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
-    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * H * 4); };
-    auto b_at = [&](int k) {
-      float4 v = *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4);
-      if (round_ops) v = bf16_round4(v);
-      return v;
-    };
-    splitk_partials<WAVES, ITERS>(a_at, b_at, a.P, red);
-  }
+  if (*reinterpret_cast<const volatile int *>(a.done)) return;
+  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
   if (a.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll

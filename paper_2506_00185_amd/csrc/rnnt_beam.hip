@@ -352,6 +352,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_key = h->p_key; a.p_idx = h->p_idx; a.zs = h->zs;
     a.n_chunks = n_chunks;
     a.normalized = p.inj_tok ? 1 : 0;
+    a.use_ctx = (c.pred == RNNT_PRED_STATELESS || p.lm) ? 1 : 0;
     a.B = p.B; a.K = p.K; a.V = c.V; a.ND = c.n_durations;
     for (int i = 0; i < 8; ++i) a.dur[i] = c.durations[i];
     a.algo = p.algo;

@@ -1,0 +1,62 @@
+"""The five workloads at full size, in the launch configuration the benchmark
+times (graph replay).  The whole batch is decoded on the GPU; the oracle decodes
+a sample of the utterances (they are independent of each other) and the
+comparison is the same as in the small cases: trees identical up to the first
+near tie, then identical transcripts and scores within tolerance."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from gpu_common import compare, gpu_decode
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # config, variant, sampled utterances, tol, tie
+    (1, "f32", [0], 1e-3, 1e-4),
+    (2, "f32", list(range(0, 32, 2)), 1e-3, 1e-4),
+    (2, "bf16", list(range(0, 32, 4)), 5e-2, 2e-2),
+    (3, "f32", list(range(0, 64, 3)), 1e-3, 1e-4),
+    (4, "f32", [0, 9, 18, 27], 1e-3, 1e-4),
+    (5, "bf16", [0, 63, 127], 5e-2, 2e-2),
+]
+
+
+@pytest.mark.parametrize("cid,variant,rows,tol,tie", CASES, ids=[f"config{c[0]}_{c[1]}" for c in CASES])
+def test_workload_at_full_size(oracle, cid, variant, rows, tol, tie):
+    import paper_2506_00185_amd as A
+    c = S.config(cid, prec=variant)
+    w = S.make_weights(c)
+    L = S.make_lengths(c)
+    enc = S.make_enc(c, L)
+    glm = olm = None
+    if c["lm"]:
+        lm = S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"], 1000 * cid + 3)
+        glm, olm = A.NGramLM(lm), oracle.LM(lm)
+    dec = A.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=c["lm_weight"])
+    assert g["rc"] == 0
+    # properties that hold for every utterance of the batch, sampled or not
+    max_adv = max(c["durations"]) if c["durations"] else 1  # frames one step can consume
+    assert np.all(g["n_steps"] <= L * (c["s"] + 1)) and np.all(g["n_steps"] * max_adv >= L)
+    assert np.all(g["scores"][:, 0] <= 0) and np.all(np.isfinite(g["scores"][:, 0]))
+    live = g["lens"] >= 0
+    assert np.all(live[:, 0])
+    assert np.all(g["lens"][live] <= (L[:, None] * c["s"] * np.ones_like(g["lens"]))[live])
+    sc = np.where(live, g["scores"], -np.inf)
+    assert np.all(np.diff(sc, axis=1) <= 0)  # n-best sorted
+    for b in range(c["B"]):  # the same transcript never twice in an n-best list
+        seen = set()
+        for j in range(c["beam"]):
+            if live[b, j]:
+                key = tuple(g["tokens"][b, j, : g["lens"][b, j]])
+                assert key not in seen
+                seen.add(key)
+    # sampled utterances against the oracle
+    rows = [r for r in rows if r < c["B"]]
+    o = oracle.decode(dict(c, B=len(rows)), w, enc[rows], L[rows], lm=olm, lm_weight=c["lm_weight"], log=True)
+    assert o["collisions"].sum() == 0
+    full, exempt = compare(g, o, tol, tie, rows=rows)
+    print(f"config {cid} {variant}: {full} of {len(rows)} sampled utterances identical end to end, "
+          f"{exempt} left the oracle's path after a near tie (< {tie})")
+    assert full + exempt == len(rows)

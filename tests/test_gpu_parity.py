@@ -3,7 +3,9 @@
 Bars: tree and recombination indices bit-exact when both sides read the same
 injected log-probabilities; float32 end to end: identical token sequences and
 hypothesis scores within 1e-3, except after a decision the oracle took by less
-than 1e-4; bf16-joint variant: 1e-2 for both (this library's own choice).
+than 1e-4; bf16-joint variant: scores within 5e-2, near tie below 2e-2 (this library's own
+choice: a bf16 rounding boundary crossed on one side only moves a logit by about 5e-4, and a
+few hundred such events add up over a decode).
 """
 import math
 
@@ -16,7 +18,7 @@ from gpu_common import compare, gpu_decode, gpu_decode_injected, to_gpu
 pytestmark = pytest.mark.gpu
 
 TOL, TIE = 1e-3, 1e-4
-TOL_BF16, TIE_BF16 = 1e-2, 1e-2
+TOL_BF16, TIE_BF16 = 5e-2, 2e-2
 
 
 @pytest.fixture(scope="module")
