@@ -41,33 +41,6 @@ __device__ __forceinline__ double logaddexp_d(double a, double b) {
   return m + log(exp(a - m) + exp(b - m));
 }
 
-template <typename T>
-__device__ __forceinline__ T wave_max(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    T w = __shfl_xor(v, o);
-    v = w > v ? w : v;
-  }
-  return v;
-}
-
-template <typename T>
-__device__ __forceinline__ T wave_min(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    T w = __shfl_xor(v, o);
-    v = w < v ? w : v;
-  }
-  return v;
-}
-
-template <typename T>
-__device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
-}
-
 // Candidate order used everywhere a "best" is chosen: larger value first, then
 // smaller index.  Returns true if (v1, i1) comes before (v2, i2).
 template <typename V, typename I>
@@ -75,18 +48,116 @@ __device__ __forceinline__ bool comes_before(V v1, I i1, V v2, I i2) {
   return v1 > v2 || (v1 == v2 && i1 < i2);
 }
 
-// Wave-wide best of (value, index) under comes_before; every lane gets the winner.
-template <typename V, typename I>
-__device__ __forceinline__ void wave_best(V &v, I &i) {
+// ---- cross-lane exchange without the LDS crossbar --------------------------
+// __shfl_* compiles to ds_bpermute (LDS latency, ~100+ cycles per exchange); a
+// data-parallel-primitive move costs one VALU instruction.  The four patterns
+// below are butterflies inside a row of 16 lanes: lane ^ 1, lane ^ 2, then the
+// mirror of each half row (pairs quads) and the mirror of the row (pairs halves).
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1, 0, 3, 2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2, 3, 0, 1]
+constexpr int kDppHalfMirror = 0x141; // row_half_mirror
+constexpr int kDppMirror = 0x140;     // row_mirror
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(dpp_i<CTRL>(__float_as_int(v)));
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = dpp_i<CTRL>((int)(b & 0xffffffffll)), hi = dpp_i<CTRL>((int)(b >> 32));
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ float readlane_f(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ double readlane_d(double v, int lane) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), lane);
+  const int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+// all-reduce over aligned groups of LANES (4, 8 or 16) lanes
+template <int LANES>
+__device__ __forceinline__ float group_max(float v) {
+  v = fmaxf(v, dpp_f<kDppXor1>(v));
+  v = fmaxf(v, dpp_f<kDppXor2>(v));
+  if constexpr (LANES >= 8) v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+  if constexpr (LANES >= 16) v = fmaxf(v, dpp_f<kDppMirror>(v));
+  return v;
+}
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+  v += dpp_f<kDppXor1>(v);
+  v += dpp_f<kDppXor2>(v);
+  if constexpr (LANES >= 8) v += dpp_f<kDppHalfMirror>(v);
+  if constexpr (LANES >= 16) v += dpp_f<kDppMirror>(v);
+  return v;
+}
+template <int CTRL, typename V>
+__device__ __forceinline__ void best_step(V &v, int &i) {
+  V v2;
+  if constexpr (sizeof(V) == 8) v2 = dpp_d<CTRL>(v); else v2 = dpp_f<CTRL>(v);
+  const int i2 = dpp_i<CTRL>(i);
+  if (comes_before(v2, i2, v, i)) {
+    v = v2;
+    i = i2;
+  }
+}
+// best (value, index) pair of an aligned group of LANES lanes, in every lane of the group
+template <int LANES, typename V>
+__device__ __forceinline__ void group_best(V &v, int &i) {
+  best_step<kDppXor1>(v, i);
+  best_step<kDppXor2>(v, i);
+  if constexpr (LANES >= 8) best_step<kDppHalfMirror>(v, i);
+  if constexpr (LANES >= 16) best_step<kDppMirror>(v, i);
+}
+
+// wave-wide versions: reduce inside the four rows, then combine the rows through scalar reads
+__device__ __forceinline__ float wave_max(float v) {
+  v = group_max<16>(v);
+  return fmaxf(fmaxf(readlane_f(v, 0), readlane_f(v, 16)), fmaxf(readlane_f(v, 32), readlane_f(v, 48)));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v = group_sum<16>(v);
+  return (readlane_f(v, 0) + readlane_f(v, 16)) + (readlane_f(v, 32) + readlane_f(v, 48));
+}
+__device__ __forceinline__ void wave_best(float &v, int &i) {
+  group_best<16>(v, i);
+  float bv = readlane_f(v, 0);
+  int bi = __builtin_amdgcn_readlane(i, 0);
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    V v2 = __shfl_xor(v, o);
-    I i2 = __shfl_xor(i, o);
-    if (comes_before(v2, i2, v, i)) {
-      v = v2;
-      i = i2;
+  for (int r = 16; r < 64; r += 16) {
+    const float v2 = readlane_f(v, r);
+    const int i2 = __builtin_amdgcn_readlane(i, r);
+    if (comes_before(v2, i2, bv, bi)) {
+      bv = v2;
+      bi = i2;
     }
   }
+  v = bv;
+  i = bi;
+}
+__device__ __forceinline__ void wave_best(double &v, int &i) {
+  group_best<16>(v, i);
+  double bv = readlane_d(v, 0);
+  int bi = __builtin_amdgcn_readlane(i, 0);
+#pragma unroll
+  for (int r = 16; r < 64; r += 16) {
+    const double v2 = readlane_d(v, r);
+    const int i2 = __builtin_amdgcn_readlane(i, r);
+    if (comes_before(v2, i2, bv, bi)) {
+      bv = v2;
+      bi = i2;
+    }
+  }
+  v = bv;
+  i = bi;
 }
 
 }  // namespace rb

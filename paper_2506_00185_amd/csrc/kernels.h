@@ -4,6 +4,20 @@
 #pragma once
 #include "device_utils.h"
 
+// Phase stamps for tuning builds (-DRB_TIMING): block (0, 0), thread 0 records the constant-rate
+// wall clock at a few points of each kernel.  Compiled out otherwise.
+#ifdef RB_TIMING
+__device__ long long rb_stamps[8 * 16];
+#define RB_STAMP(kernel, i)                                                      \
+  do {                                                                           \
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rb_stamps[(kernel) * 16 + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define RB_STAMP(kernel, i) \
+  do {                      \
+  } while (0)
+#endif
+
 namespace rb {
 
 // ---------------------------------------------------------------------------
@@ -191,6 +205,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int chunk = blockIdx.x, n0 = chunk * 32, m0 = blockIdx.y * 32;
+  RB_STAMP(0, 0);
   {
     const int Np = a.n_chunks * 32;
     const float *wp = a.W + (size_t)(n0 + col) * 4;
@@ -203,11 +218,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
       if (round_ops) f = bf16_round4(f);
       return f;
     };
+    // "every utterance has finished": requested first, looked at once the operand loads are on their way
+    const int done = *reinterpret_cast<const volatile int *>(a.done);
     SplitKOperands<ITERS> op;
     splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
-    // the loop is over: nothing below may run (checked once the operand loads are on their way)
-    if (*reinterpret_cast<const volatile int *>(a.done)) return;
+    if (done) return;
+    RB_STAMP(0, 1);
     splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
+    RB_STAMP(0, 2);
   }
 
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
@@ -234,14 +252,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
       a.zs[(size_t)m * nz + (n - a.V)] = z;
     }
   }
-#pragma unroll
-  for (int o = 1; o < LPH; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  mx = group_max<LPH>(mx);
   float sum = 0.f;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)
     if (n0 + i0 + q < a.V) sum += __expf(zv[q] - mx);
-#pragma unroll
-  for (int o = 1; o < LPH; o <<= 1) sum += __shfl_xor(sum, o);
+  sum = group_sum<LPH>(sum);
+  RB_STAMP(0, 3);
   // local order of this lane's candidates (VPL is 2 or 4: a few compare-exchanges)
 #pragma unroll
   for (int x = 0; x < VPL; ++x)
@@ -257,15 +274,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
   for (int r = 0; r < a.K; ++r) {
     float bv = key[0];
     int bi = idx[0];
-#pragma unroll
-    for (int o = 1; o < LPH; o <<= 1) {
-      const float v2 = __shfl_xor(bv, o);
-      const int i2 = __shfl_xor(bi, o);
-      if (comes_before(v2, i2, bv, bi)) {
-        bv = v2;
-        bi = i2;
-      }
-    }
+    group_best<LPH>(bv, bi);
     if (bi == idx[0]) {  // mine was taken: move my list up
 #pragma unroll
       for (int q = 0; q + 1 < VPL; ++q) {
@@ -285,6 +294,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
       }
     }
   }
+  RB_STAMP(0, 4);
   if (mvalid) {
     const size_t pc = (size_t)m * a.n_chunks + chunk;
     if (e == 0) {
@@ -360,7 +370,6 @@ struct SelectArgs {
   const int *p_idx;
   const float *zs;
   int n_chunks;
-  int stage;       // 1: the block copies its candidate lists into (dynamic) LDS first
   int use_ctx;     // 1: the token history of each hypothesis is kept (stateless prediction network, LM)
   int normalized;  // 1: keys are log-probabilities already (injected mode)
   // configuration
@@ -387,146 +396,118 @@ __device__ __forceinline__ float logaddexp_f(float a, float b) {
   return d > -INFINITY ? m + log1pf(expf(d)) : m;
 }
 
-__global__ __launch_bounds__(256) void k_select(SelectArgs a) {
-  const int b = blockIdx.x, K = a.K, V = a.V, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+// LDS scratch of one wave while it handles one utterance
+struct SelectScratch {
+  double score[kMaxBeam];
+  double rc_val[kMaxBeam * (kMaxBeam + 1)];
+  double sel_val[kMaxBeam];
+  double n_score[kMaxBeam];
+  int t[kMaxBeam], sym[kMaxBeam], len[kMaxBeam], last[kMaxBeam], kind[kMaxBeam];
+  uint32_t hash[kMaxBeam];
+  int ctx[kMaxBeam][kCtxMax];
+  int advt[kMaxBeam], advb[kMaxBeam];
+  float win_key[kMaxBeam][kMaxBeam];
+  int win_idx[kMaxBeam][kMaxBeam];
+  int rc_flat[kMaxBeam * (kMaxBeam + 1)];
+  int sel_flat[kMaxBeam];
+  int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
+  uint32_t n_hash[kMaxBeam];
+};
+
+// the lanes of one wave see each other's LDS writes after this (they run in lockstep; this
+// only stops the compiler and the memory pipeline from re-ordering)
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// One beam-search step of utterance b by one wave: the K best tokens and blank of every
+// hypothesis (LPR lanes per hypothesis, all hypotheses at once), the Beam best of those,
+// expansion, tree write, recombination, end-of-utterance detection.
+// CPL: candidates of a hypothesis a lane can keep in registers (n_chunks * K <= LPR * CPL),
+// 0 = scan them in memory at every round instead.
+template <int LPR, int CPL>
+__device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
+  const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
   const int nz = 1 + a.ND;
-
-  __shared__ double s_score[kMaxBeam];
-  __shared__ int s_t[kMaxBeam], s_sym[kMaxBeam], s_len[kMaxBeam], s_last[kMaxBeam], s_kind[kMaxBeam];
-  __shared__ uint32_t s_hash[kMaxBeam];
-  __shared__ int s_ctx[kMaxBeam][kCtxMax];
-  __shared__ int s_advt[kMaxBeam], s_advb[kMaxBeam];
-  __shared__ double rc_val[kMaxBeam * (kMaxBeam + 1)];
-  __shared__ int rc_flat[kMaxBeam * (kMaxBeam + 1)];
-  __shared__ double sel_val[kMaxBeam];
-  __shared__ int sel_flat[kMaxBeam];
-  __shared__ double n_score[kMaxBeam];
-  __shared__ int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
-  __shared__ uint32_t n_hash[kMaxBeam];
-
-  // every load of the prologue is issued before anything waits on one of them
-  const int fin = a.finished[b];
-  const int done = *reinterpret_cast<volatile int *>(a.done);
   const int S = *a.step_base + a.step_off;
   const int T_b = a.lengths[b];
-  if (tid < K) {
-    const int m = m_base + tid;
-    s_score[tid] = a.score[m];
-    s_t[tid] = a.t[m];
-    s_sym[tid] = a.sym[m];
-    s_len[tid] = a.len[m];
-    s_last[tid] = a.last[m];
-    s_hash[tid] = a.hash[m];
-    sel_val[tid] = -INFINITY;
-    sel_flat[tid] = -1;
-  }
-  if (a.use_ctx && tid < K * kCtxMax) s_ctx[tid / kCtxMax][tid % kCtxMax] = a.ctx[m_base * kCtxMax + tid];
-  // candidate lists of the K rows of this utterance: contiguous in memory; one coalesced copy into LDS
-  extern __shared__ float stage[];
-  const int ncand = a.n_chunks * K;
-  const float *keys_b = a.p_key + (size_t)m_base * ncand;
-  const int *idxs_b = a.p_idx + (size_t)m_base * ncand;
-  const float *pmax_b = a.p_max + (size_t)m_base * a.n_chunks;
-  const float *psum_b = a.p_sum + (size_t)m_base * a.n_chunks;
-  const float *zs_b = a.zs + (size_t)m_base * nz;
-  if (a.stage) {
-    float *s_keys = stage;
-    int *s_idx = reinterpret_cast<int *>(stage + K * ncand);
-    float *s_pmax = stage + 2 * K * ncand;
-    float *s_psum = s_pmax + K * a.n_chunks;
-    float *s_zs = s_psum + K * a.n_chunks;
-    for (int i = tid; i < K * ncand; i += 256) {
-      s_keys[i] = keys_b[i];
-      s_idx[i] = idxs_b[i];
-    }
-    if (!a.normalized)
-      for (int i = tid; i < K * a.n_chunks; i += 256) {
-        s_pmax[i] = pmax_b[i];
-        s_psum[i] = psum_b[i];
-      }
-    for (int i = tid; i < K * nz; i += 256) s_zs[i] = zs_b[i];
-    keys_b = s_keys;
-    idxs_b = s_idx;
-    pmax_b = s_pmax;
-    psum_b = s_psum;
-    zs_b = s_zs;
-  }
-  if (done) return;
-  if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
-    if (tid < K) {
-      a.src_row[m_base + tid] = m_base + tid;
-      a.tok[m_base + tid] = -1;
+  RB_STAMP(1, 0);
+  if (a.finished[b]) {  // a finished utterance is frozen; its slots tell the prediction step to copy
+    if (lane < K) {
+      a.src_row[m_base + lane] = m_base + lane;
+      a.tok[m_base + lane] = -1;
     }
     return;
   }
-  __syncthreads();
+  RB_STAMP(1, 1);
+  if (lane < K) {
+    const int m = m_base + lane;
+    s.score[lane] = a.score[m];
+    s.t[lane] = a.t[m];
+    s.sym[lane] = a.sym[m];
+    s.len[lane] = a.len[m];
+    s.last[lane] = a.last[m];
+    s.hash[lane] = a.hash[m];
+    s.sel_val[lane] = -INFINITY;
+    s.sel_flat[lane] = -1;
+  }
+  if (a.use_ctx)
+    for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
+
+  // ---- per hypothesis: candidate lists into registers (requested before the state is looked at)
+  const int rk = lane / LPR, e = lane % LPR;  // hypothesis and position inside its lane group
+  const bool row_ok = rk < K;
+  const int ncand = a.n_chunks * K;
+  const int krow = row_ok ? rk : 0;
+  const float *keys = a.p_key + (size_t)(m_base + krow) * ncand;
+  const int *idxs = a.p_idx + (size_t)(m_base + krow) * ncand;
+  const float *pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
+  const float *psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
+  const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
+  float ck[CPL > 0 ? CPL : 1];
+  int ci[CPL > 0 ? CPL : 1];
+  if constexpr (CPL > 0) {
+#pragma unroll
+    for (int q = 0; q < CPL; ++q) {
+      const int c = e + LPR * q;
+      const bool ok = row_ok && c < ncand;
+      ck[q] = ok ? keys[c] : -INFINITY;
+      ci[q] = ok ? idxs[c] : 0x7fffffff;
+    }
+  }
+  float st_mx = -INFINITY, st_sum = 0.f;
+  if (!a.normalized) {
+    for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, pmax[c]);
+  }
+  const float zb = zsr[0];
+  RB_STAMP(1, 2);
+  wave_sync();
   int t_cur = T_b;
   for (int k = 0; k < K; ++k)
-    if (s_score[k] > -INFINITY && s_t[k] < T_b && s_t[k] < t_cur) t_cur = s_t[k];
-  if (tid < K) {
-    int kind = 0;
-    if (s_score[tid] > -INFINITY) kind = (s_t[tid] < T_b && (a.algo == 0 || s_t[tid] == t_cur)) ? 2 : 1;
-    s_kind[tid] = kind;
-  }
-  __syncthreads();
+    if (s.score[k] > -INFINITY && s.t[k] < T_b && s.t[k] < t_cur) t_cur = s.t[k];
+  int kind = 0;
+  if (row_ok && s.score[rk] > -INFINITY) kind = (s.t[rk] < T_b && (a.algo == 0 || s.t[rk] == t_cur)) ? 2 : 1;
+  if (row_ok && e == 0) s.kind[rk] = kind;
 
-  // ---- per hypothesis (one wave each): the K best tokens and blank, as total scores.
-  // Candidate c of the utterance is rc[k * (K + 1) + e]: e < K tokens, e == K blank / stay.
-  for (int k = wave; k < K; k += 4) {
-    const int kind = s_kind[k];
-    double *rv = rc_val + k * (K + 1);
-    int *rf = rc_flat + k * (K + 1);
-    const int flat0 = k * (V + 1);
-    if (kind != 2) {
-      if (lane <= K) {
-        rv[lane] = (kind == 1 && lane == K) ? s_score[k] : -INFINITY;
-        rf[lane] = flat0 + V;
-      }
-      continue;
-    }
-    const float *keys = keys_b + (size_t)k * ncand;
-    const int *idxs = idxs_b + (size_t)k * ncand;
-    const float *pmax = pmax_b + (size_t)k * a.n_chunks, *psum = psum_b + (size_t)k * a.n_chunks;
-    const float *zsr = zs_b + (size_t)k * nz;
-    // K rounds of "best remaining candidate"; lane j keeps the j-th winner
-    float my_key = -INFINITY;
-    int my_idx = 0x7fffffff;
-    if (ncand <= 256) {
-      float ck[4];
-      int ci[4];
+  RB_STAMP(1, 3);
+  // K rounds of "best remaining candidate" in every lane group at once
+  for (int j = 0; j < K; ++j) {
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    if constexpr (CPL > 0) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = lane + 64 * q;
-        ck[q] = c < ncand ? keys[c] : -INFINITY;
-        ci[q] = c < ncand ? idxs[c] : 0x7fffffff;
-      }
-      for (int j = 0; j < K; ++j) {
-        float bv = ck[0];
-        int bi = ci[0];
-#pragma unroll
-        for (int q = 1; q < 4; ++q)
-          if (comes_before(ck[q], ci[q], bv, bi)) {
-            bv = ck[q];
-            bi = ci[q];
-          }
-        wave_best(bv, bi);
-        if (lane == j) {
-          my_key = bv;
-          my_idx = bi;
+      for (int q = 0; q < CPL; ++q)
+        if (comes_before(ck[q], ci[q], bv, bi)) {
+          bv = ck[q];
+          bi = ci[q];
         }
-        if (bv == -INFINITY) break;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (ci[q] == bi) ck[q] = -INFINITY;  // token ids are unique within a row
-      }
     } else {
-      float last_v = INFINITY;
-      int last_i = -1;
-      for (int j = 0; j < K; ++j) {
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-        for (int c = lane; c < ncand; c += 64) {
+      const float last_v = j > 0 ? s.win_key[krow][j - 1] : INFINITY;
+      const int last_i = j > 0 ? s.win_idx[krow][j - 1] : -1;
+      if (row_ok)
+        for (int c = e; c < ncand; c += LPR) {
           const float v = keys[c];
           const int i = idxs[c];
           const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
@@ -535,159 +516,172 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
             bi = i;
           }
         }
-        wave_best(bv, bi);
-        if (lane == j) {
-          my_key = bv;
-          my_idx = bi;
-        }
-        last_v = bv;
-        last_i = bi;
-        if (bv == -INFINITY) break;
-      }
     }
-    // soft-max statistics (float transcendental math, scores accumulate in double)
-    float lse_all = 0.f, lse_nb = 0.f, max_nb;
-    const float zb = zsr[0];
-    if (!a.normalized) {
-      float mx = -INFINITY;
-      for (int c = lane; c < a.n_chunks; c += 64) mx = fmaxf(mx, pmax[c]);
-      mx = wave_max(mx);
-      float sm = 0.f;
-      for (int c = lane; c < a.n_chunks; c += 64) {
-        const float pm = pmax[c];
-        if (pm > -INFINITY) sm += psum[c] * __expf(pm - mx);
-      }
-      sm = wave_sum(sm);
-      lse_nb = mx + logf(sm);
-      lse_all = logaddexp_f(lse_nb, zb);
-      max_nb = mx;
+    group_best<LPR>(bv, bi);
+    if (row_ok && e == 0) {
+      s.win_key[rk][j] = bv;
+      s.win_idx[rk][j] = bi;
+    }
+    if constexpr (CPL > 0) {
+#pragma unroll
+      for (int q = 0; q < CPL; ++q)
+        if (ci[q] == bi) ck[q] = -INFINITY;  // token ids are unique within a hypothesis
     } else {
-      max_nb = __shfl(my_key, 0);
+      wave_sync();
     }
-    const double logp_b = (double)zb - (double)lse_all;
-    const double nb = (double)lse_nb - (double)lse_all;
-    const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
-    // TDT: one duration per candidate
-    double x_tok = 0.0, x_blank = 0.0;
-    int adv_tok = 0, adv_blank = 1;
-    if (a.ND > 0) {
-      float dl[8];
-      float dmx = -INFINITY;
-      for (int d = 0; d < a.ND; ++d) {
-        dl[d] = zsr[1 + d];
-        dmx = fmaxf(dmx, dl[d]);
-      }
-      if (!a.normalized) {
-        float sm = 0.f;
-        for (int d = 0; d < a.ND; ++d) sm += expf(dl[d] - dmx);
-        const float l = dmx + logf(sm);
-        for (int d = 0; d < a.ND; ++d) dl[d] -= l;
-      }
-      int best = -1, best_b = -1;
-      for (int d = 0; d < a.ND; ++d) {
-        if (best < 0 || dl[d] > dl[best]) best = d;
-        if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
-      }
-      x_tok = (double)dl[best];
-      x_blank = (double)dl[best_b];
-      adv_tok = a.dur[best];
-      adv_blank = a.dur[best_b];
+  }
+  RB_STAMP(1, 4);
+  // soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
+  float lse_all = 0.f, lse_nb = 0.f, max_nb;
+  if (!a.normalized) {
+    st_mx = group_max<LPR>(st_mx);
+    for (int c = e; c < a.n_chunks; c += LPR) {
+      const float pm = pmax[c];
+      if (pm > -INFINITY) st_sum += psum[c] * __expf(pm - st_mx);
     }
-    const bool forced = s_sym[k] >= a.max_sym;
+    st_sum = group_sum<LPR>(st_sum);
+    lse_nb = st_mx + logf(st_sum);
+    lse_all = logaddexp_f(lse_nb, zb);
+    max_nb = st_mx;
+  }
+  wave_sync();
+  if (a.normalized) max_nb = s.win_key[krow][0];
+  const double logp_b = (double)zb - (double)lse_all;
+  const double nb = (double)lse_nb - (double)lse_all;
+  const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
+  // TDT: one duration per candidate
+  double x_tok = 0.0, x_blank = 0.0;
+  int adv_tok = 0, adv_blank = 1;
+  if (a.ND > 0) {
+    float dl[8];
+    float dmx = -INFINITY;
+    for (int d = 0; d < a.ND; ++d) {
+      dl[d] = zsr[1 + d];
+      dmx = fmaxf(dmx, dl[d]);
+    }
+    if (!a.normalized) {
+      float sm = 0.f;
+      for (int d = 0; d < a.ND; ++d) sm += expf(dl[d] - dmx);
+      const float l = dmx + logf(sm);
+      for (int d = 0; d < a.ND; ++d) dl[d] -= l;
+    }
+    int best = -1, best_b = -1;
+    for (int d = 0; d < a.ND; ++d) {
+      if (best < 0 || dl[d] > dl[best]) best = d;
+      if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
+    }
+    x_tok = (double)dl[best];
+    x_blank = (double)dl[best_b];
+    adv_tok = a.dur[best];
+    adv_blank = a.dur[best_b];
+  }
+  RB_STAMP(1, 5);
+  // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
+  if (row_ok) {
+    const bool forced = s.sym[rk] >= a.max_sym;
     const bool use_gamma = a.algo == 1 && a.gamma < INFINITY;
     const double thr = maxlogp - (double)a.gamma;
-    const double sc = s_score[k];
-    if (lane < K) {
+    const double sc = s.score[rk];
+    const int flat0 = rk * (V + 1);
+    for (int j = e; j <= K; j += LPR) {
       double val = -INFINITY;
-      if (my_key > -INFINITY && !forced) {
-        const double lp = (double)my_key - (double)lse_all;  // pre-LM log-probability when no LM is fused
-        if (!(use_gamma && lp < thr)) val = sc + lp + (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok;
+      int flat = flat0 + V;
+      if (j < K) {
+        const float wk = s.win_key[rk][j];
+        const int wi = s.win_idx[rk][j];
+        flat = flat0 + (wi < V ? wi : V - 1);
+        if (kind == 2 && wk > -INFINITY && !forced) {
+          const double lp = (double)wk - (double)lse_all;  // pre-LM log-probability when no LM is fused
+          if (!(use_gamma && lp < thr)) val = sc + lp + (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok;
+        }
+      } else if (kind == 2) {
+        double bl = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
+        if (use_gamma && logp_b < thr && !forced) bl = -INFINITY;
+        val = sc + bl + x_blank;
+        s.advt[rk] = adv_tok;
+        s.advb[rk] = adv_blank;
+      } else if (kind == 1) {
+        val = sc;  // a waiting or finished hypothesis stays as it is
       }
-      rv[lane] = val;
-      rf[lane] = flat0 + (my_idx < V ? my_idx : V - 1);
-    }
-    if (lane == K) {
-      double val = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
-      if (use_gamma && logp_b < thr && !forced) val = -INFINITY;
-      rv[K] = sc + val + x_blank;
-      rf[K] = flat0 + V;
-      s_advt[k] = adv_tok;
-      s_advb[k] = adv_blank;
+      s.rc_val[rk * (K + 1) + j] = val;
+      s.rc_flat[rk * (K + 1) + j] = flat;
     }
   }
-  __syncthreads();
+  wave_sync();
 
+  RB_STAMP(1, 6);
   // ---- the Beam best of all K * (K + 1) candidates, by (value desc, k * (V + 1) + v asc)
-  if (wave == 0) {
-    const int n = K * (K + 1);
-    if (n <= 64) {
-      // few candidates: each lane counts how many come before its own; that count is its new slot
-      const double mv = lane < n ? rc_val[lane] : -INFINITY;
-      const int mf = lane < n ? rc_flat[lane] : 0x7fffffff;
-      int rank = 0;
-      for (int c = 0; c < n; ++c) rank += comes_before(rc_val[c], rc_flat[c], mv, mf) ? 1 : 0;
-      if (mv > -INFINITY && rank < K) {
-        sel_val[rank] = mv;
-        sel_flat[rank] = mf;
-      }
-    } else {
-      double last_v = INFINITY;
-      int last_i = -1;
-      for (int j = 0; j < K; ++j) {
-        double bv = -INFINITY;
-        int bi = 0x7fffffff;
-        for (int c = lane; c < n; c += 64) {
-          const double v = rc_val[c];
-          const int i = rc_flat[c];
-          const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
-          if (eligible && comes_before(v, i, bv, bi)) {
-            bv = v;
-            bi = i;
-          }
+  const int n = K * (K + 1);
+  if (n <= 64) {
+    // few candidates: each lane counts how many come before its own; that count is its new slot
+    const double mv = lane < n ? s.rc_val[lane] : -INFINITY;
+    const int mf = lane < n ? s.rc_flat[lane] : 0x7fffffff;
+    int rank = 0;
+#pragma unroll 4
+    for (int c = 0; c < n; ++c)
+      rank += comes_before(readlane_d(mv, c), __builtin_amdgcn_readlane(mf, c), mv, mf) ? 1 : 0;
+    if (mv > -INFINITY && rank < K) {
+      s.sel_val[rank] = mv;
+      s.sel_flat[rank] = mf;
+    }
+  } else {
+    double last_v = INFINITY;
+    int last_i = -1;
+    for (int j = 0; j < K; ++j) {
+      double bv = -INFINITY;
+      int bi = 0x7fffffff;
+      for (int c = lane; c < n; c += 64) {
+        const double v = s.rc_val[c];
+        const int i = s.rc_flat[c];
+        const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
+        if (eligible && comes_before(v, i, bv, bi)) {
+          bv = v;
+          bi = i;
         }
-        wave_best(bv, bi);
-        if (lane == 0 && bv > -INFINITY) {
-          sel_val[j] = bv;
-          sel_flat[j] = bi;
-        }
-        last_v = bv;
-        last_i = bi;
-        if (!(bv > -INFINITY)) break;
       }
+      wave_best(bv, bi);
+      if (lane == 0 && bv > -INFINITY) {
+        s.sel_val[j] = bv;
+        s.sel_flat[j] = bi;
+      }
+      last_v = bv;
+      last_i = bi;
+      if (!(bv > -INFINITY)) break;
     }
   }
-  __syncthreads();
+  wave_sync();
 
+  RB_STAMP(1, 7);
   // ---- expansion into the new slots
   int code = -3, parent = -1, appended = -1;
   int ctx_new[kCtxMax];
-  if (tid < K) {
-    const int j = tid;
-    const double val = sel_val[j];
+  if (lane < K) {
+    const int j = lane;
+    const double val = s.sel_val[j];
 #pragma unroll
     for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = -1;
     if (!(val > -INFINITY)) {
-      n_live[j] = 0;
-      n_score[j] = -INFINITY;
-      n_t[j] = 0;
-      n_sym[j] = 0;
-      n_len[j] = 0;
-      n_last[j] = -1;
-      n_hash[j] = 0;
+      s.n_live[j] = 0;
+      s.n_score[j] = -INFINITY;
+      s.n_t[j] = 0;
+      s.n_sym[j] = 0;
+      s.n_len[j] = 0;
+      s.n_last[j] = -1;
+      s.n_hash[j] = 0;
     } else {
-      const int k = sel_flat[j] / (V + 1), v = sel_flat[j] % (V + 1);
+      const int k = s.sel_flat[j] / (V + 1), v = s.sel_flat[j] % (V + 1);
       parent = k;
-      int t = s_t[k], sym = s_sym[k], len = s_len[k], last = s_last[k];
-      uint32_t hash = s_hash[k];
+      int t = s.t[k], sym = s.sym[k], len = s.len[k], last = s.last[k];
+      uint32_t hash = s.hash[k];
       if (a.use_ctx) {
 #pragma unroll
-        for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = s_ctx[k][i];
+        for (int i = 0; i < kCtxMax; ++i) ctx_new[i] = s.ctx[k][i];
       }
-      if (s_kind[k] == 1) {
+      if (s.kind[k] == 1) {
         code = -2;
       } else if (v == V) {
         code = -1;
-        t += s_advb[k];
+        t += s.advb[k];
         sym = 0;
       } else {
         code = v;
@@ -695,44 +689,45 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
         len += 1;
         last = v;
         hash = (uint32_t)(((uint64_t)hash * kHashBase + (uint64_t)(v + 1)) % kHashMod);
-        t += s_advt[k];
-        sym = s_advt[k] == 0 ? sym + 1 : 0;
+        t += s.advt[k];
+        sym = s.advt[k] == 0 ? sym + 1 : 0;
 #pragma unroll
         for (int i = kCtxMax - 1; i > 0; --i) ctx_new[i] = ctx_new[i - 1];
         ctx_new[0] = v;
       }
       if (t > T_b) t = T_b;
-      n_live[j] = 1;
-      n_score[j] = val;
-      n_t[j] = t;
-      n_sym[j] = sym;
-      n_len[j] = len;
-      n_last[j] = last;
-      n_hash[j] = hash;
+      s.n_live[j] = 1;
+      s.n_score[j] = val;
+      s.n_t[j] = t;
+      s.n_sym[j] = sym;
+      s.n_len[j] = len;
+      s.n_last[j] = last;
+      s.n_hash[j] = hash;
     }
   }
-  __syncthreads();
+  wave_sync();
 
+  RB_STAMP(1, 8);
   // ---- recombination: equal (hash, length, last token, frame, symbols in frame)
-  if (tid < K) {
-    const int j = tid;
+  if (lane < K) {
+    const int j = lane;
     int merged = -1;
-    double score = n_score[j];
-    bool live = n_live[j] != 0;
+    double score = s.n_score[j];
+    bool live = s.n_live[j] != 0;
     if (live) {
       merged = j;
       for (int i = 0; i < j; ++i) {
-        if (n_live[i] && n_hash[i] == n_hash[j] && n_len[i] == n_len[j] && n_last[i] == n_last[j] &&
-            n_t[i] == n_t[j] && n_sym[i] == n_sym[j]) {
+        if (s.n_live[i] && s.n_hash[i] == s.n_hash[j] && s.n_len[i] == s.n_len[j] && s.n_last[i] == s.n_last[j] &&
+            s.n_t[i] == s.n_t[j] && s.n_sym[i] == s.n_sym[j]) {
           merged = i;
           break;
         }
       }
       if (merged == j) {
         for (int i = j + 1; i < K; ++i)
-          if (n_live[i] && n_hash[i] == n_hash[j] && n_len[i] == n_len[j] && n_last[i] == n_last[j] &&
-              n_t[i] == n_t[j] && n_sym[i] == n_sym[j])
-            score = logaddexp_d(score, n_score[i]);
+          if (s.n_live[i] && s.n_hash[i] == s.n_hash[j] && s.n_len[i] == s.n_len[j] &&
+              s.n_last[i] == s.n_last[j] && s.n_t[i] == s.n_t[j] && s.n_sym[i] == s.n_sym[j])
+            score = logaddexp_d(score, s.n_score[i]);
       } else {
         live = false;
         score = -INFINITY;
@@ -740,11 +735,11 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
     }
     const int m = m_base + j;
     a.score[m] = score;
-    a.t[m] = n_t[j];
-    a.sym[m] = n_sym[j];
-    a.len[m] = n_len[j];
-    a.last[m] = n_last[j];
-    a.hash[m] = n_hash[j];
+    a.t[m] = s.n_t[j];
+    a.sym[m] = s.n_sym[j];
+    a.len[m] = s.n_len[j];
+    a.last[m] = s.n_last[j];
+    a.hash[m] = s.n_hash[j];
     if (a.use_ctx) {
 #pragma unroll
       for (int i = 0; i < kCtxMax; ++i) a.ctx[m * kCtxMax + i] = ctx_new[i];
@@ -757,8 +752,9 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
       a.tree_token[ti] = code;
       a.tree_merged[ti] = merged;
     }
+    RB_STAMP(1, 9);
     // finished when no surviving slot has frames left
-    const bool open = live && n_t[j] < T_b;
+    const bool open = live && s.n_t[j] < T_b;
     const unsigned long long any_open = __ballot(open);
     if (j == 0 && (any_open == 0ull || S + 1 >= T_b * (a.max_sym + 1))) {
       a.finished[b] = 1;
@@ -772,6 +768,31 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
       }
     }
   }
+  RB_STAMP(1, 10);
+  wave_sync();
+}
+
+// picks the lane-group width and register budget for the beam and list sizes at hand
+__device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, SelectScratch &s) {
+  const int ncand = a.n_chunks * a.K;
+  if (a.K <= 4) {
+    if (ncand <= 16 * 12) select_utterance<16, 12>(a, b, s);
+    else select_utterance<16, 0>(a, b, s);
+  } else if (a.K <= 8) {
+    if (ncand <= 8 * 36) select_utterance<8, 36>(a, b, s);
+    else select_utterance<8, 0>(a, b, s);
+  } else {
+    select_utterance<4, 0>(a, b, s);
+  }
+}
+
+// stand-alone selection kernel: one wave per utterance, four utterances per block
+__global__ __launch_bounds__(256) void k_select(SelectArgs a) {
+  __shared__ SelectScratch scratch[4];
+  if (*reinterpret_cast<volatile int *>(a.done)) return;
+  const int wave = threadIdx.x >> 6;
+  const int b = blockIdx.x * 4 + wave;
+  if (b < a.B) select_dispatch(a, b, scratch[wave]);
 }
 
 // ---------------------------------------------------------------------------
@@ -797,6 +818,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ W
   __shared__ float red[WAVES * 64 * kRedStride];
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int tile = blockIdx.x, m0 = blockIdx.y * 32;
+  RB_STAMP(2, 0);
   const int m = m0 + col;
   const int src = m < M ? src_row[m] : 0;
   const int R = 4 * P;
@@ -805,8 +827,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ W
   auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R * 4); };
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
   auto fb = [](float4 v) { return v; };
+  const int done_flag = *reinterpret_cast<const volatile int *>(done);
   SplitKOperands<ITERS> op;
   splitk_load<WAVES, ITERS>(op, a_at, b_at, P);
+  if (done_flag) return;
   // epilogue role of this thread: (hypothesis j, unit ul of the 8 units of the tile); its inputs are
   // requested now, behind the operand loads, so that they arrive while the contraction runs
   const int j = tid >> 3, ul = tid & 7, u = tile * 8 + ul;
@@ -822,8 +846,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ W
     h_old = h_cur[k4_index(u, e_src, Mp)];
     if (e_tok >= 0) g4 = *reinterpret_cast<const float4 *>(G + (size_t)e_tok * 4 * P + tile * 32 + 4 * ul);
   }
-  if (*reinterpret_cast<const volatile int *>(done)) return;
+  RB_STAMP(2, 1);
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, P, red);
+  RB_STAMP(2, 2);
   if (!evalid) return;
   float c = c_old, h = h_old;
   if (e_tok >= 0) {
@@ -836,6 +861,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ W
   }
   c_nxt[(size_t)me * P + u] = c;
   h_nxt[k4_index(u, me, Mp)] = h;
+  RB_STAMP(2, 3);
 }
 
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
@@ -862,8 +888,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * H * 4); };
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
   auto fb = [&](float4 v) { return round_ops ? bf16_round4(v) : v; };
+  const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
   SplitKOperands<ITERS> op;
   splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
+  if (done_flag) return;
   // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1); the frame's projection is requested
   // behind the operand loads
   const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
@@ -881,7 +909,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
       bv[q] = a.bias[o0 + q];
     }
   }
-  if (*reinterpret_cast<const volatile int *>(a.done)) return;
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
   if (a.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;

@@ -367,11 +367,8 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.step_off = step_off;
     a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
     a.h_done = h->h_done_dev;
-    const size_t stage_bytes =
-        sizeof(float) * ((size_t)2 * p.K * n_chunks * p.K + (size_t)2 * p.K * n_chunks + (size_t)p.K * (1 + c.n_durations));
-    a.stage = stage_bytes <= 40 * 1024;
     ScopedKernelTime tm(h, s, KT_SELECT);
-    hipLaunchKernelGGL(k_select, dim3(p.B), dim3(256), a.stage ? stage_bytes : 0, s, a);
+    hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, a);
   }
   RB_HIP(h, hipGetLastError());
   int rc = launch_lm(h, s, p);
@@ -726,6 +723,13 @@ int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_
   }
   return n;
 }
+
+#ifdef RB_TIMING
+// tuning builds only: copy the phase stamps out (8 kernels x 16 stamps, 10 ns ticks)
+int rnnt_beam_debug_stamps(long long *out) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_stamps), sizeof(long long) * 8 * 16) == hipSuccess ? 0 : RNNT_E_HIP;
+}
+#endif
 
 const char *rnnt_beam_last_error(const rnnt_beam_t *h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
