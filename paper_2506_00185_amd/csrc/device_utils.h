@@ -118,6 +118,52 @@ __device__ __forceinline__ void group_best(V &v, int &i) {
   if constexpr (LANES >= 16) best_step<kDppMirror>(v, i);
 }
 
+// ---- candidates packed into one sortable word ---------------------------------
+// (key, index) -> 64 bits whose unsigned order is the candidate order: larger key first, then
+// smaller index.  One compare instead of three, and a pair moves as two DPP words.
+__device__ __forceinline__ uint32_t orderable(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+}
+__device__ __forceinline__ float from_orderable(uint32_t u) {
+  return __uint_as_float(u ^ (((u >> 31) - 1u) | 0x80000000u));
+}
+__device__ __forceinline__ uint64_t pack_cand(float key, int idx) {
+  return ((uint64_t)orderable(key) << 32) | (uint32_t)(0x7fffffff - idx);
+}
+__device__ __forceinline__ float cand_key(uint64_t c) { return from_orderable((uint32_t)(c >> 32)); }
+__device__ __forceinline__ int cand_idx(uint64_t c) { return 0x7fffffff - (int)(uint32_t)c; }
+// "no candidate": key -inf, index 0x7fffffff; every real candidate is larger
+__device__ __forceinline__ uint64_t no_cand() { return pack_cand(-INFINITY, 0x7fffffff); }
+
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_u64(uint64_t v) {
+  const int lo = dpp_i<CTRL>((int)(uint32_t)v), hi = dpp_i<CTRL>((int)(uint32_t)(v >> 32));
+  return ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo;
+}
+template <int CTRL>
+__device__ __forceinline__ uint64_t max_step(uint64_t v) {
+  const uint64_t w = dpp_u64<CTRL>(v);
+  return w > v ? w : v;
+}
+// largest packed candidate of an aligned group of LANES lanes, in every lane of the group
+template <int LANES>
+__device__ __forceinline__ uint64_t group_max_u64(uint64_t v) {
+  v = max_step<kDppXor1>(v);
+  v = max_step<kDppXor2>(v);
+  if constexpr (LANES >= 8) v = max_step<kDppHalfMirror>(v);
+  if constexpr (LANES >= 16) v = max_step<kDppMirror>(v);
+  return v;
+}
+template <int LANES>
+__device__ __forceinline__ int group_min_i(int v) {
+  v = min(v, dpp_i<kDppXor1>(v));
+  v = min(v, dpp_i<kDppXor2>(v));
+  if constexpr (LANES >= 8) v = min(v, dpp_i<kDppHalfMirror>(v));
+  if constexpr (LANES >= 16) v = min(v, dpp_i<kDppMirror>(v));
+  return v;
+}
+
 // wave-wide versions: reduce inside the four rows, then combine the rows through scalar reads
 __device__ __forceinline__ float wave_max(float v) {
   v = group_max<16>(v);

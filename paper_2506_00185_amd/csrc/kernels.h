@@ -179,139 +179,6 @@ __host__ __device__ inline size_t k4_index(int k, int row, int rows) {
   return ((size_t)(k >> 2) * rows + row) * 4 + (k & 3);
 }
 
-struct JointArgs {
-  const float *pre;   // k4-major [H][Mp]: f_proj[b, t_m] + prediction projection of hypothesis m
-  const float *W;     // k4-major [H][n_chunks * 32] output layer, zero rows beyond V + 1 + ND
-  const float *bias;  // [n_chunks * 32]
-  const float *lm;    // [M, V] natural-log LM scores or NULL
-  float lambda;
-  int M, Mp, K, H, V, ND, n_chunks, round_ops;
-  float *p_max, *p_sum;  // [M, n_chunks] soft-max statistics of the chunk's token logits
-  float *p_key;          // [M, n_chunks, K] best keys z + lambda * lm of the chunk
-  int *p_idx;            // [M, n_chunks, K] their token ids
-  float *zs;             // [M, 1 + ND] raw blank and duration logits
-  const int *done;
-};
-
-// Joint network for a tile of 32 hypotheses x 32 output columns:
-//   z[n] = W_out[n] . ReLU(pre_m) + b_out[n],  pre_m = f_proj[b, t_m] + g_m
-// with the soft-max statistics and the K best keys of the chunk in the epilogue,
-// so that the [M, V + 1] logits never reach memory.  Epilogue: LPH = 2 * WAVES
-// lanes share a hypothesis, each holds 32 / LPH columns; the best K of the chunk
-// are found in K rounds of an LPH-lane arg-max.
-template <int WAVES, int ITERS>
-__global__ __launch_bounds__(WAVES * 64) void k_joint(JointArgs a) {
-  __shared__ float red[WAVES * 64 * kRedStride];
-  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
-  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int chunk = blockIdx.x, n0 = chunk * 32, m0 = blockIdx.y * 32;
-  RB_STAMP(0, 0);
-  {
-    const int Np = a.n_chunks * 32;
-    const float *wp = a.W + (size_t)(n0 + col) * 4;
-    const float *pp = a.pre + (size_t)(m0 + col) * 4;
-    const int Mp = a.Mp, round_ops = a.round_ops;
-    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * Np * 4); };
-    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(pp + (size_t)(k >> 2) * Mp * 4); };
-    auto fb = [&](float4 f) {
-      f.x = fmaxf(f.x, 0.f); f.y = fmaxf(f.y, 0.f); f.z = fmaxf(f.z, 0.f); f.w = fmaxf(f.w, 0.f);
-      if (round_ops) f = bf16_round4(f);
-      return f;
-    };
-    // "every utterance has finished": requested first, looked at once the operand loads are on their way
-    const int done = *reinterpret_cast<const volatile int *>(a.done);
-    SplitKOperands<ITERS> op;
-    splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
-    if (done) return;
-    RB_STAMP(0, 1);
-    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
-    RB_STAMP(0, 2);
-  }
-
-  // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
-  const int j = tid / LPH, e = tid % LPH, i0 = e * VPL;
-  const int m = m0 + j;
-  const bool mvalid = m < a.M;
-  const int nz = 1 + a.ND;
-  float key[VPL];
-  int idx[VPL];
-  float mx = -INFINITY;
-  float zv[VPL];
-#pragma unroll
-  for (int q = 0; q < VPL; ++q) {
-    const int n = n0 + i0 + q;
-    const float z = tile_value<WAVES>(red, i0 + q, j) + a.bias[n];
-    zv[q] = z;
-    key[q] = -INFINITY;
-    idx[q] = 0x7fffffff;
-    if (n < a.V) {
-      key[q] = (a.lm && mvalid) ? z + a.lambda * a.lm[(size_t)m * a.V + n] : z;
-      idx[q] = n;
-      mx = fmaxf(mx, z);
-    } else if (n < a.V + nz && mvalid) {
-      a.zs[(size_t)m * nz + (n - a.V)] = z;
-    }
-  }
-  mx = group_max<LPH>(mx);
-  float sum = 0.f;
-#pragma unroll
-  for (int q = 0; q < VPL; ++q)
-    if (n0 + i0 + q < a.V) sum += __expf(zv[q] - mx);
-  sum = group_sum<LPH>(sum);
-  RB_STAMP(0, 3);
-  // local order of this lane's candidates (VPL is 2 or 4: a few compare-exchanges)
-#pragma unroll
-  for (int x = 0; x < VPL; ++x)
-#pragma unroll
-    for (int y = 0; y + 1 < VPL - x; ++y)
-      if (comes_before(key[y + 1], idx[y + 1], key[y], idx[y])) {
-        const float tv = key[y]; key[y] = key[y + 1]; key[y + 1] = tv;
-        const int ti = idx[y]; idx[y] = idx[y + 1]; idx[y + 1] = ti;
-      }
-  // K rounds: the best remaining candidate among the LPH lanes of the hypothesis
-  float my_key[2] = {-INFINITY, -INFINITY};  // lane e keeps the winners of rounds e and e + LPH
-  int my_idx[2] = {0x7fffffff, 0x7fffffff};
-  for (int r = 0; r < a.K; ++r) {
-    float bv = key[0];
-    int bi = idx[0];
-    group_best<LPH>(bv, bi);
-    if (bi == idx[0]) {  // mine was taken: move my list up
-#pragma unroll
-      for (int q = 0; q + 1 < VPL; ++q) {
-        key[q] = key[q + 1];
-        idx[q] = idx[q + 1];
-      }
-      key[VPL - 1] = -INFINITY;
-      idx[VPL - 1] = 0x7fffffff;
-    }
-    if (e == (r & (LPH - 1))) {
-      if (r < LPH) {
-        my_key[0] = bv;
-        my_idx[0] = bi;
-      } else {
-        my_key[1] = bv;
-        my_idx[1] = bi;
-      }
-    }
-  }
-  RB_STAMP(0, 4);
-  if (mvalid) {
-    const size_t pc = (size_t)m * a.n_chunks + chunk;
-    if (e == 0) {
-      a.p_max[pc] = mx;
-      a.p_sum[pc] = sum;
-    }
-    if (e < a.K) {
-      a.p_key[pc * a.K + e] = my_key[0];
-      a.p_idx[pc * a.K + e] = my_idx[0];
-    }
-    if (LPH + e < a.K) {
-      a.p_key[pc * a.K + LPH + e] = my_key[1];
-      a.p_idx[pc * a.K + LPH + e] = my_idx[1];
-    }
-  }
-}
-
 // Injected mode: the candidate lists come from a table of log-probabilities
 // instead of the joint network.  One wave per hypothesis; lane l fills "chunk" l.
 struct InjectArgs {
@@ -322,8 +189,7 @@ struct InjectArgs {
   const uint32_t *hash;
   const int *lengths;
   int M, K, T, V, ND;
-  float *p_key;
-  int *p_idx;
+  uint64_t *p_cand;
   float *zs;
   const int *done;
 };
@@ -345,10 +211,7 @@ __global__ __launch_bounds__(64) void k_inject(InjectArgs a) {
   const size_t pc = (size_t)m * 64 + lane;
 #pragma unroll
   for (int j = 0; j < KT; ++j)
-    if (j < a.K) {
-      a.p_key[pc * a.K + j] = top.v[j];
-      a.p_idx[pc * a.K + j] = top.i[j];
-    }
+    if (j < a.K) a.p_cand[pc * a.K + j] = pack_cand(top.v[j], top.i[j]);
   const int nz = 1 + a.ND;
   if (lane == 0) a.zs[(size_t)m * nz] = row[a.V];
   if (lane >= 1 && lane <= a.ND)
@@ -366,8 +229,8 @@ struct SelectArgs {
   int *ctx;
   const int *lengths;
   // candidate lists from k_joint / k_inject
-  const float *p_max, *p_sum, *p_key;
-  const int *p_idx;
+  const float *p_max, *p_sum;
+  const uint64_t *p_cand;  // [M, n_chunks, K] packed (key, token), each chunk's list best first
   const float *zs;
   int n_chunks;
   int use_ctx;     // 1: the token history of each hypothesis is kept (stateless prediction network, LM)
@@ -402,12 +265,11 @@ struct SelectScratch {
   double rc_val[kMaxBeam * (kMaxBeam + 1)];
   double sel_val[kMaxBeam];
   double n_score[kMaxBeam];
+  uint64_t win[kMaxBeam][kMaxBeam];
   int t[kMaxBeam], sym[kMaxBeam], len[kMaxBeam], last[kMaxBeam], kind[kMaxBeam];
   uint32_t hash[kMaxBeam];
   int ctx[kMaxBeam][kCtxMax];
   int advt[kMaxBeam], advb[kMaxBeam];
-  float win_key[kMaxBeam][kMaxBeam];
-  int win_idx[kMaxBeam][kMaxBeam];
   int rc_flat[kMaxBeam * (kMaxBeam + 1)];
   int sel_flat[kMaxBeam];
   int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
@@ -421,131 +283,164 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_wave_barrier();
 }
 
+// candidate order inside an utterance: (hypothesis k, token v) -> k * 2^20 + v, the same order as
+// k * (V + 1) + v for V < 2^20, without a division on the way back
+constexpr int kFlatShift = 20;
+
+// x mod (2^31 - 1) for x < 2^62
+__device__ __forceinline__ uint32_t mod_mersenne31(uint64_t x) {
+  uint64_t y = (x & kHashMod) + (x >> 31);
+  y = (y & kHashMod) + (y >> 31);
+  return (uint32_t)(y >= kHashMod ? y - kHashMod : y);
+}
+
 // One beam-search step of utterance b by one wave: the K best tokens and blank of every
 // hypothesis (LPR lanes per hypothesis, all hypotheses at once), the Beam best of those,
 // expansion, tree write, recombination, end-of-utterance detection.
-// CPL: candidates of a hypothesis a lane can keep in registers (n_chunks * K <= LPR * CPL),
-// 0 = scan them in memory at every round instead.
-template <int LPR, int CPL>
+// NCH > 0: a lane keeps the lists of NCH chunks in registers (n_chunks <= LPR * NCH, K <= KMAX) and
+// the K best of the hypothesis come out of a K-way merge of list heads; NCH == 0: the lists are
+// scanned in memory at every round instead (any size).
+template <int LPR, int NCH, int KMAX>
 __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
   const int nz = 1 + a.ND;
+  // ---- every load of the prologue is requested before anything waits on one of them
+  const int fin = a.finished[b];
   const int S = *a.step_base + a.step_off;
   const int T_b = a.lengths[b];
-  RB_STAMP(1, 0);
-  if (a.finished[b]) {  // a finished utterance is frozen; its slots tell the prediction step to copy
+  const int rk = lane / LPR, e = lane % LPR;  // hypothesis and position inside its lane group
+  const bool row_ok = rk < K;
+  const int krow = row_ok ? rk : 0;
+  const int ncand = a.n_chunks * K;
+  const uint64_t *cands = a.p_cand + (size_t)(m_base + krow) * ncand;
+  const float *pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
+  const float *psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
+  const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
+  double my_score = -INFINITY;
+  int my_t = 0, my_sym = 0, my_len = 0, my_last = -1;
+  uint32_t my_hash = 0;
+  if (lane < K) {
+    const int m = m_base + lane;
+    my_score = a.score[m];
+    my_t = a.t[m];
+    my_sym = a.sym[m];
+    my_len = a.len[m];
+    my_last = a.last[m];
+    my_hash = a.hash[m];
+  }
+  uint64_t list[NCH > 0 ? NCH : 1][KMAX];
+  float pm[NCH > 0 ? NCH : 1], ps[NCH > 0 ? NCH : 1];
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int q = 0; q < NCH; ++q) {
+      const int ch = e + LPR * q;
+      const bool ok = row_ok && ch < a.n_chunks;
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? cands[ch * K + j] : no_cand();
+      pm[q] = (ok && !a.normalized) ? pmax[ch] : -INFINITY;
+      ps[q] = (ok && !a.normalized) ? psum[ch] : 0.f;
+    }
+  }
+  const float zb = zsr[0];
+  float dl[8];
+  for (int d = 0; d < a.ND; ++d) dl[d] = zsr[1 + d];
+  if (a.use_ctx)
+    for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
+  if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
     if (lane < K) {
       a.src_row[m_base + lane] = m_base + lane;
       a.tok[m_base + lane] = -1;
     }
     return;
   }
-  RB_STAMP(1, 1);
   if (lane < K) {
-    const int m = m_base + lane;
-    s.score[lane] = a.score[m];
-    s.t[lane] = a.t[m];
-    s.sym[lane] = a.sym[m];
-    s.len[lane] = a.len[m];
-    s.last[lane] = a.last[m];
-    s.hash[lane] = a.hash[m];
+    s.score[lane] = my_score;
+    s.t[lane] = my_t;
+    s.sym[lane] = my_sym;
+    s.len[lane] = my_len;
+    s.last[lane] = my_last;
+    s.hash[lane] = my_hash;
     s.sel_val[lane] = -INFINITY;
     s.sel_flat[lane] = -1;
   }
-  if (a.use_ctx)
-    for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
+  // frame of the earliest unfinished hypothesis (lanes >= K hold neutral values)
+  const bool my_live = my_score > -INFINITY;
+  int t_cur = group_min_i<16>((my_live && my_t < T_b) ? my_t : T_b);
+  t_cur = __builtin_amdgcn_readlane(t_cur, 0);
+  if (lane < K) s.kind[lane] = my_live ? ((my_t < T_b && (a.algo == 0 || my_t == t_cur)) ? 2 : 1) : 0;
 
-  // ---- per hypothesis: candidate lists into registers (requested before the state is looked at)
-  const int rk = lane / LPR, e = lane % LPR;  // hypothesis and position inside its lane group
-  const bool row_ok = rk < K;
-  const int ncand = a.n_chunks * K;
-  const int krow = row_ok ? rk : 0;
-  const float *keys = a.p_key + (size_t)(m_base + krow) * ncand;
-  const int *idxs = a.p_idx + (size_t)(m_base + krow) * ncand;
-  const float *pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
-  const float *psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
-  const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
-  float ck[CPL > 0 ? CPL : 1];
-  int ci[CPL > 0 ? CPL : 1];
-  if constexpr (CPL > 0) {
+  // ---- K rounds of "best remaining candidate" in every lane group at once.
+  // Lane e keeps the winners of rounds e, e + LPR, ... (at most KMAX / LPR + 1 of them).
+  constexpr int kMine = (KMAX + LPR - 1) / LPR;
+  uint64_t mine[kMine];
 #pragma unroll
-    for (int q = 0; q < CPL; ++q) {
-      const int c = e + LPR * q;
-      const bool ok = row_ok && c < ncand;
-      ck[q] = ok ? keys[c] : -INFINITY;
-      ci[q] = ok ? idxs[c] : 0x7fffffff;
+  for (int i = 0; i < kMine; ++i) mine[i] = no_cand();
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int j = 0; j < KMAX; ++j) {
+      if (j < K) {
+        uint64_t best = list[0][0];
+#pragma unroll
+        for (int q = 1; q < NCH; ++q) best = list[q][0] > best ? list[q][0] : best;
+        best = group_max_u64<LPR>(best);
+#pragma unroll
+        for (int q = 0; q < NCH; ++q)
+          if (list[q][0] == best) {  // the winner's list moves up (real candidates are unique)
+#pragma unroll
+            for (int x = 0; x + 1 < KMAX; ++x) list[q][x] = list[q][x + 1];
+            list[q][KMAX - 1] = no_cand();
+          }
+        if (e == j % LPR) mine[j / LPR] = best;
+      }
     }
-  }
-  float st_mx = -INFINITY, st_sum = 0.f;
-  if (!a.normalized) {
-    for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, pmax[c]);
-  }
-  const float zb = zsr[0];
-  RB_STAMP(1, 2);
-  wave_sync();
-  int t_cur = T_b;
-  for (int k = 0; k < K; ++k)
-    if (s.score[k] > -INFINITY && s.t[k] < T_b && s.t[k] < t_cur) t_cur = s.t[k];
-  int kind = 0;
-  if (row_ok && s.score[rk] > -INFINITY) kind = (s.t[rk] < T_b && (a.algo == 0 || s.t[rk] == t_cur)) ? 2 : 1;
-  if (row_ok && e == 0) s.kind[rk] = kind;
-
-  RB_STAMP(1, 3);
-  // K rounds of "best remaining candidate" in every lane group at once
-  for (int j = 0; j < K; ++j) {
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    if constexpr (CPL > 0) {
-#pragma unroll
-      for (int q = 0; q < CPL; ++q)
-        if (comes_before(ck[q], ci[q], bv, bi)) {
-          bv = ck[q];
-          bi = ci[q];
-        }
-    } else {
-      const float last_v = j > 0 ? s.win_key[krow][j - 1] : INFINITY;
-      const int last_i = j > 0 ? s.win_idx[krow][j - 1] : -1;
+  } else {
+    uint64_t last = ~0ull;
+    for (int j = 0; j < K; ++j) {
+      uint64_t best = no_cand();
       if (row_ok)
         for (int c = e; c < ncand; c += LPR) {
-          const float v = keys[c];
-          const int i = idxs[c];
-          const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
-          if (eligible && comes_before(v, i, bv, bi)) {
-            bv = v;
-            bi = i;
-          }
+          const uint64_t v = cands[c];
+          if (v < last && v > best) best = v;
+        }
+      best = group_max_u64<LPR>(best);
+#pragma unroll
+      for (int i = 0; i < kMine; ++i)
+        if (e == j % LPR && i == j / LPR) mine[i] = best;
+      last = best > no_cand() ? best : no_cand() + 1;  // nothing below "no candidate" is eligible again
+    }
+  }
+  // ---- soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
+  float lse_all = 0.f, lse_nb = 0.f, max_nb = -INFINITY;
+  if (!a.normalized) {
+    float st_mx = -INFINITY, st_sum = 0.f;
+    if constexpr (NCH > 0) {
+#pragma unroll
+      for (int q = 0; q < NCH; ++q) st_mx = fmaxf(st_mx, pm[q]);
+      st_mx = group_max<LPR>(st_mx);
+#pragma unroll
+      for (int q = 0; q < NCH; ++q)
+        if (pm[q] > -INFINITY) st_sum += ps[q] * __expf(pm[q] - st_mx);
+    } else {
+      if (row_ok)
+        for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, pmax[c]);
+      st_mx = group_max<LPR>(st_mx);
+      if (row_ok)
+        for (int c = e; c < a.n_chunks; c += LPR) {
+          const float p = pmax[c];
+          if (p > -INFINITY) st_sum += psum[c] * __expf(p - st_mx);
         }
     }
-    group_best<LPR>(bv, bi);
-    if (row_ok && e == 0) {
-      s.win_key[rk][j] = bv;
-      s.win_idx[rk][j] = bi;
-    }
-    if constexpr (CPL > 0) {
-#pragma unroll
-      for (int q = 0; q < CPL; ++q)
-        if (ci[q] == bi) ck[q] = -INFINITY;  // token ids are unique within a hypothesis
-    } else {
-      wave_sync();
-    }
-  }
-  RB_STAMP(1, 4);
-  // soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
-  float lse_all = 0.f, lse_nb = 0.f, max_nb;
-  if (!a.normalized) {
-    st_mx = group_max<LPR>(st_mx);
-    for (int c = e; c < a.n_chunks; c += LPR) {
-      const float pm = pmax[c];
-      if (pm > -INFINITY) st_sum += psum[c] * __expf(pm - st_mx);
-    }
     st_sum = group_sum<LPR>(st_sum);
-    lse_nb = st_mx + logf(st_sum);
-    lse_all = logaddexp_f(lse_nb, zb);
+    lse_nb = st_mx + __logf(st_sum);
+    const float hi = fmaxf(lse_nb, zb), lo = fminf(lse_nb, zb);
+    lse_all = hi + __logf(1.f + __expf(lo - hi));
     max_nb = st_mx;
+  } else {
+    // keys are log-probabilities already; the best token of the row is round 0's winner, the largest
+    // of the winners spread over the group's lanes
+    max_nb = cand_key(group_max_u64<LPR>(mine[0]));
   }
-  wave_sync();
-  if (a.normalized) max_nb = s.win_key[krow][0];
   const double logp_b = (double)zb - (double)lse_all;
   const double nb = (double)lse_nb - (double)lse_all;
   const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
@@ -553,16 +448,11 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   double x_tok = 0.0, x_blank = 0.0;
   int adv_tok = 0, adv_blank = 1;
   if (a.ND > 0) {
-    float dl[8];
-    float dmx = -INFINITY;
-    for (int d = 0; d < a.ND; ++d) {
-      dl[d] = zsr[1 + d];
-      dmx = fmaxf(dmx, dl[d]);
-    }
     if (!a.normalized) {
-      float sm = 0.f;
-      for (int d = 0; d < a.ND; ++d) sm += expf(dl[d] - dmx);
-      const float l = dmx + logf(sm);
+      float dmx = -INFINITY, sm = 0.f;
+      for (int d = 0; d < a.ND; ++d) dmx = fmaxf(dmx, dl[d]);
+      for (int d = 0; d < a.ND; ++d) sm += __expf(dl[d] - dmx);
+      const float l = dmx + __logf(sm);
       for (int d = 0; d < a.ND; ++d) dl[d] -= l;
     }
     int best = -1, best_b = -1;
@@ -575,26 +465,34 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
     adv_tok = a.dur[best];
     adv_blank = a.dur[best_b];
   }
-  RB_STAMP(1, 5);
+  wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
   // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
   if (row_ok) {
+    const int kind = s.kind[rk];
     const bool forced = s.sym[rk] >= a.max_sym;
     const bool use_gamma = a.algo == 1 && a.gamma < INFINITY;
     const double thr = maxlogp - (double)a.gamma;
     const double sc = s.score[rk];
-    const int flat0 = rk * (V + 1);
-    for (int j = e; j <= K; j += LPR) {
-      double val = -INFINITY;
-      int flat = flat0 + V;
+    const int flat0 = rk << kFlatShift;
+    const double tok_extra = (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok - (double)lse_all;
+#pragma unroll
+    for (int i = 0; i < kMine; ++i) {
+      const int j = e + LPR * i;
       if (j < K) {
-        const float wk = s.win_key[rk][j];
-        const int wi = s.win_idx[rk][j];
-        flat = flat0 + (wi < V ? wi : V - 1);
+        const float wk = cand_key(mine[i]);
+        const int wi = cand_idx(mine[i]);
+        double val = -INFINITY;
         if (kind == 2 && wk > -INFINITY && !forced) {
           const double lp = (double)wk - (double)lse_all;  // pre-LM log-probability when no LM is fused
-          if (!(use_gamma && lp < thr)) val = sc + lp + (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok;
+          if (!(use_gamma && lp < thr)) val = sc + (double)wk + tok_extra;
         }
-      } else if (kind == 2) {
+        s.rc_val[rk * (K + 1) + j] = val;
+        s.rc_flat[rk * (K + 1) + j] = flat0 + (wi < V ? wi : V - 1);
+      }
+    }
+    if (e == LPR - 1) {  // blank / stay: the group's last lane (least loaded with winners)
+      double val = -INFINITY;
+      if (kind == 2) {
         double bl = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
         if (use_gamma && logp_b < thr && !forced) bl = -INFINITY;
         val = sc + bl + x_blank;
@@ -603,14 +501,13 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       } else if (kind == 1) {
         val = sc;  // a waiting or finished hypothesis stays as it is
       }
-      s.rc_val[rk * (K + 1) + j] = val;
-      s.rc_flat[rk * (K + 1) + j] = flat;
+      s.rc_val[rk * (K + 1) + K] = val;
+      s.rc_flat[rk * (K + 1) + K] = flat0 + V;
     }
   }
   wave_sync();
 
-  RB_STAMP(1, 6);
-  // ---- the Beam best of all K * (K + 1) candidates, by (value desc, k * (V + 1) + v asc)
+  // ---- the Beam best of all K * (K + 1) candidates, by (value desc, (k, v) asc)
   const int n = K * (K + 1);
   if (n <= 64) {
     // few candidates: each lane counts how many come before its own; that count is its new slot
@@ -651,7 +548,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   }
   wave_sync();
 
-  RB_STAMP(1, 7);
   // ---- expansion into the new slots
   int code = -3, parent = -1, appended = -1;
   int ctx_new[kCtxMax];
@@ -669,7 +565,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       s.n_last[j] = -1;
       s.n_hash[j] = 0;
     } else {
-      const int k = s.sel_flat[j] / (V + 1), v = s.sel_flat[j] % (V + 1);
+      const int k = s.sel_flat[j] >> kFlatShift, v = s.sel_flat[j] & ((1 << kFlatShift) - 1);
       parent = k;
       int t = s.t[k], sym = s.sym[k], len = s.len[k], last = s.last[k];
       uint32_t hash = s.hash[k];
@@ -688,7 +584,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         appended = v;
         len += 1;
         last = v;
-        hash = (uint32_t)(((uint64_t)hash * kHashBase + (uint64_t)(v + 1)) % kHashMod);
+        hash = mod_mersenne31((uint64_t)hash * kHashBase + (uint64_t)(v + 1));
         t += s.advt[k];
         sym = s.advt[k] == 0 ? sym + 1 : 0;
 #pragma unroll
@@ -707,7 +603,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   }
   wave_sync();
 
-  RB_STAMP(1, 8);
   // ---- recombination: equal (hash, length, last token, frame, symbols in frame)
   if (lane < K) {
     const int j = lane;
@@ -752,7 +647,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       a.tree_token[ti] = code;
       a.tree_merged[ti] = merged;
     }
-    RB_STAMP(1, 9);
     // finished when no surviving slot has frames left
     const bool open = live && s.n_t[j] < T_b;
     const unsigned long long any_open = __ballot(open);
@@ -768,22 +662,202 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       }
     }
   }
-  RB_STAMP(1, 10);
   wave_sync();
 }
 
 // picks the lane-group width and register budget for the beam and list sizes at hand
 __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, SelectScratch &s) {
-  const int ncand = a.n_chunks * a.K;
   if (a.K <= 4) {
-    if (ncand <= 16 * 12) select_utterance<16, 12>(a, b, s);
-    else select_utterance<16, 0>(a, b, s);
+    if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s);
+    else select_utterance<16, 0, 4>(a, b, s);
   } else if (a.K <= 8) {
-    if (ncand <= 8 * 36) select_utterance<8, 36>(a, b, s);
-    else select_utterance<8, 0>(a, b, s);
+    if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s);
+    else select_utterance<8, 0, 8>(a, b, s);
   } else {
-    select_utterance<4, 0>(a, b, s);
+    select_utterance<4, 0, 16>(a, b, s);
   }
+}
+
+struct MainArgs {
+  // ---- joint role
+  const float *pre;   // k4-major [H][Mp]: f_proj[b, t_m] + prediction projection of hypothesis m
+  const float *W;     // k4-major [H][n_chunks * 32] output layer, zero rows beyond V + 1 + ND
+  const float *bias;  // [n_chunks * 32]
+  const float *lm;    // [M, V] natural-log LM scores or NULL
+  float lambda;
+  int M, Mp, K, H, V, ND, n_chunks, round_ops;
+  int upt, rpt, n_jtiles;  // utterances and rows per joint tile (rpt = upt * K <= 32), number of such tiles
+  float *p_max, *p_sum;    // [M, n_chunks] soft-max statistics of the chunk's token logits
+  uint64_t *p_cand;        // [M, n_chunks, K] best (key = z + lambda * lm, token) of the chunk, packed
+  float *zs;               // [M, 1 + ND] raw blank and duration logits
+  int *tile_ctr;           // [n_jtiles] blocks of the tile that have written their lists
+  // ---- recurrent-product role (LSTM): R[m] = W_hh h[m] for every current slot
+  const float *Whh;        // k4-major [P][4P], gate rows re-ordered (NULL: no such blocks)
+  const float *h_cur;      // k4-major [P][Mp]
+  float *R;                // [M][4P]
+  int P;
+  // ---- selection (run by the block that completes a tile)
+  SelectArgs sel;
+};
+
+// Main kernel of a step.  Blocks [0, n_chunks * n_jtiles): joint network for a tile of up to 32
+// hypotheses (whole utterances) x 32 output columns,
+//   z[n] = W_out[n] . ReLU(pre_m) + b_out[n],  pre_m = f_proj[b, t_m] + g_m,
+// with the soft-max statistics and the K best keys of the chunk in the epilogue, so that the
+// [M, V + 1] logits never reach memory (LPH = 2 * WAVES lanes share a hypothesis, each holds 32 / LPH
+// columns; the best K are found in K rounds of an LPH-lane arg-max).  The block that completes a
+// tile (counted with one atomic per block) then runs the selection for the tile's utterances, one
+// wave per utterance.  Remaining blocks: R = W_hh h for the current slots; it does not depend on
+// the selection, so it overlaps with it instead of following it.
+template <int WAVES, int ITERS>
+__global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
+  constexpr int kRedFloats = WAVES * 64 * kRedStride;
+  constexpr int kScratchFloats = (int)((sizeof(SelectScratch) * WAVES + 3) / 4);
+  __shared__ __align__(16) float smem[kRedFloats > kScratchFloats ? kRedFloats : kScratchFloats];
+  __shared__ int s_is_last;
+  float *red = smem;
+  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
+  const int n_joint = a.n_chunks * a.n_jtiles;
+  const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
+
+  if ((int)blockIdx.x >= n_joint) {
+    // ---------------------------------------------------------------- R = W_hh h
+    const int idx = blockIdx.x - n_joint, n_tiles = 4 * a.P / 32;
+    const int tile = idx % n_tiles, m0 = (idx / n_tiles) * 32;
+    const int R4 = 4 * a.P, Mp = a.Mp;
+    const float *wp = a.Whh + (size_t)(tile * 32 + col) * 4;
+    const float *hp = a.h_cur + (size_t)(m0 + col) * 4;
+    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R4 * 4); };
+    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
+    auto fb = [](float4 v) { return v; };
+    SplitKOperands<ITERS> op;
+    splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
+    if (done) return;
+    RB_STAMP(2, 1);
+    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
+    RB_STAMP(2, 2);
+    // thread -> (hypothesis j, VPL adjacent rows of the tile)
+    const int j = tid / LPH, i0 = (tid % LPH) * VPL;
+    const int m = m0 + j;
+    if (m < a.M) {
+#pragma unroll
+      for (int q = 0; q < VPL; ++q) a.R[(size_t)m * R4 + tile * 32 + i0 + q] = tile_value<WAVES>(red, i0 + q, j);
+    }
+    RB_STAMP(2, 3);
+    return;
+  }
+
+  // -------------------------------------------------------------------- joint
+  const int chunk = blockIdx.x % a.n_chunks, ty = blockIdx.x / a.n_chunks;
+  const int n0 = chunk * 32, m0 = ty * a.rpt;
+  RB_STAMP(0, 0);
+  {
+    const int Np = a.n_chunks * 32;
+    const float *wp = a.W + (size_t)(n0 + col) * 4;
+    const float *pp = a.pre + (size_t)(m0 + col) * 4;
+    const int Mp = a.Mp, round_ops = a.round_ops;
+    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * Np * 4); };
+    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(pp + (size_t)(k >> 2) * Mp * 4); };
+    auto fb = [&](float4 f) {
+      f.x = fmaxf(f.x, 0.f); f.y = fmaxf(f.y, 0.f); f.z = fmaxf(f.z, 0.f); f.w = fmaxf(f.w, 0.f);
+      if (round_ops) f = bf16_round4(f);
+      return f;
+    };
+    SplitKOperands<ITERS> op;
+    splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
+    if (done) return;
+    RB_STAMP(0, 1);
+    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
+    RB_STAMP(0, 2);
+  }
+
+  // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
+  const int j = tid / LPH, e = tid % LPH, i0 = e * VPL;
+  const int m = m0 + j;
+  const bool mvalid = j < a.rpt && m < a.M;
+  const int nz = 1 + a.ND;
+  uint64_t cand[VPL];
+  float mx = -INFINITY;
+  float zv[VPL];
+#pragma unroll
+  for (int q = 0; q < VPL; ++q) {
+    const int n = n0 + i0 + q;
+    const float z = tile_value<WAVES>(red, i0 + q, j) + a.bias[n];
+    zv[q] = z;
+    cand[q] = no_cand();
+    if (n < a.V) {
+      cand[q] = pack_cand((a.lm && mvalid) ? z + a.lambda * a.lm[(size_t)m * a.V + n] : z, n);
+      mx = fmaxf(mx, z);
+    } else if (n < a.V + nz && mvalid) {
+      a.zs[(size_t)m * nz + (n - a.V)] = z;
+    }
+  }
+  mx = group_max<LPH>(mx);
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < VPL; ++q)
+    if (n0 + i0 + q < a.V) sum += __expf(zv[q] - mx);
+  sum = group_sum<LPH>(sum);
+  RB_STAMP(0, 3);
+  // local order of this lane's candidates (VPL is 2 or 4: a few compare-exchanges)
+#pragma unroll
+  for (int x = 0; x < VPL; ++x)
+#pragma unroll
+    for (int y = 0; y + 1 < VPL - x; ++y)
+      if (cand[y + 1] > cand[y]) {
+        const uint64_t tc = cand[y];
+        cand[y] = cand[y + 1];
+        cand[y + 1] = tc;
+      }
+  // K rounds: the best remaining candidate among the LPH lanes of the hypothesis
+  uint64_t mine[2] = {no_cand(), no_cand()};  // lane e keeps the winners of rounds e and e + LPH
+  for (int r = 0; r < a.K; ++r) {
+    const uint64_t best = group_max_u64<LPH>(cand[0]);
+    if (best == cand[0]) {  // mine was taken: move my list up
+#pragma unroll
+      for (int q = 0; q + 1 < VPL; ++q) cand[q] = cand[q + 1];
+      cand[VPL - 1] = no_cand();
+    }
+    if (e == (r & (LPH - 1))) {
+      if (r < LPH) mine[0] = best; else mine[1] = best;
+    }
+  }
+  RB_STAMP(0, 4);
+  if (mvalid) {
+    const size_t pc = (size_t)m * a.n_chunks + chunk;
+    if (e == 0) {
+      a.p_max[pc] = mx;
+      a.p_sum[pc] = sum;
+    }
+    if (e < a.K) a.p_cand[pc * a.K + e] = mine[0];
+    if (LPH + e < a.K) a.p_cand[pc * a.K + LPH + e] = mine[1];
+  }
+
+  // ---- the block that completes the tile runs the selection for its utterances.
+  // One thread per block does the cache maintenance: the barrier makes the block's stores its own
+  // (workgroup scope), its release makes them visible device-wide before the block is counted, and
+  // only the completing block pays for an acquire (an L2 invalidate is far too dear to issue per thread).
+  __syncthreads();
+  if (tid == 0) {
+    const int old = __hip_atomic_fetch_add(a.tile_ctr + ty, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    const int last = old == a.n_chunks - 1;
+    if (last) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      a.tile_ctr[ty] = 0;  // every other block of the tile has been counted: ready for the next step
+    }
+    s_is_last = last;
+  }
+  __syncthreads();
+  if (!s_is_last) return;
+  RB_STAMP(0, 5);
+  SelectScratch *scratch = reinterpret_cast<SelectScratch *>(smem);
+  const int wave = tid >> 6;
+  for (int u = wave; u < a.upt; u += WAVES) {
+    const int b = ty * a.upt + u;
+    if (b < a.sel.B) select_dispatch(a.sel, b, scratch[wave]);
+  }
+  RB_STAMP(0, 6);
 }
 
 // stand-alone selection kernel: one wave per utterance, four utterances per block
@@ -807,61 +881,35 @@ __device__ __forceinline__ float tanh_f(float x) {
   return x < 0.f ? -r : r;
 }
 
-// W_hh: k4-major [P][4P] with the gate rows re-ordered; h: k4-major [P][Mp]; c: row-major [M][P].
-template <int WAVES, int ITERS>
-__global__ __launch_bounds__(WAVES * 64) void k_lstm(const float *__restrict__ Whh, const float *__restrict__ G,
-                                                     const float *__restrict__ h_cur,
-                                                     const float *__restrict__ c_cur, float *__restrict__ h_nxt,
-                                                     float *__restrict__ c_nxt, const int *__restrict__ src_row,
-                                                     const int *__restrict__ tok, int M, int Mp, int P,
-                                                     const int *done) {
-  __shared__ float red[WAVES * 64 * kRedStride];
-  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int tile = blockIdx.x, m0 = blockIdx.y * 32;
-  RB_STAMP(2, 0);
-  const int m = m0 + col;
-  const int src = m < M ? src_row[m] : 0;
-  const int R = 4 * P;
-  const float *wp = Whh + (size_t)(tile * 32 + col) * 4;
-  const float *hp = h_cur + (size_t)src * 4;
-  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R * 4); };
-  auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
-  auto fb = [](float4 v) { return v; };
+// Pointwise part of the LSTM cell for every new slot: gates = R[parent] + G[token] with
+// R = W_hh h of the parent (computed for every current slot by the main kernel, before the selection
+// was known) and G = W_ih emb + biases per token; slots that did not append a token copy their
+// parent's state.  R, G: [.][4P] with the four gates of a unit adjacent; h: k4-major [P][Mp]; c: [M][P].
+__global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict__ R, const float *__restrict__ G,
+                                                        const float *__restrict__ h_cur,
+                                                        const float *__restrict__ c_cur, float *__restrict__ h_nxt,
+                                                        float *__restrict__ c_nxt, const int *__restrict__ src_row,
+                                                        const int *__restrict__ tok, int M, int Mp, int P,
+                                                        const int *done) {
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  const int m = gid / P, u = gid % P;
+  if (m >= M) return;
   const int done_flag = *reinterpret_cast<const volatile int *>(done);
-  SplitKOperands<ITERS> op;
-  splitk_load<WAVES, ITERS>(op, a_at, b_at, P);
-  if (done_flag) return;
-  // epilogue role of this thread: (hypothesis j, unit ul of the 8 units of the tile); its inputs are
-  // requested now, behind the operand loads, so that they arrive while the contraction runs
-  const int j = tid >> 3, ul = tid & 7, u = tile * 8 + ul;
-  const int me = m0 + j;
-  const bool evalid = tid < 256 && me < M;
-  int e_tok = -1;
-  float c_old = 0.f, h_old = 0.f;
-  float4 g4 = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (evalid) {
-    const int e_src = src_row[me];
-    e_tok = tok[me];
-    c_old = c_cur[(size_t)e_src * P + u];
-    h_old = h_cur[k4_index(u, e_src, Mp)];
-    if (e_tok >= 0) g4 = *reinterpret_cast<const float4 *>(G + (size_t)e_tok * 4 * P + tile * 32 + 4 * ul);
+  const int src = src_row[m], token = tok[m];
+  const float c_old = c_cur[(size_t)src * P + u];
+  float c = c_old, h;
+  if (token >= 0) {
+    const float4 r4 = *reinterpret_cast<const float4 *>(R + (size_t)src * 4 * P + 4 * u);
+    const float4 g4 = *reinterpret_cast<const float4 *>(G + (size_t)token * 4 * P + 4 * u);
+    if (done_flag) return;
+    c = sigmoid_f(r4.y + g4.y) * c_old + sigmoid_f(r4.x + g4.x) * tanh_f(r4.z + g4.z);
+    h = sigmoid_f(r4.w + g4.w) * tanh_f(c);
+  } else {
+    h = h_cur[k4_index(u, src, Mp)];
+    if (done_flag) return;
   }
-  RB_STAMP(2, 1);
-  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, P, red);
-  RB_STAMP(2, 2);
-  if (!evalid) return;
-  float c = c_old, h = h_old;
-  if (e_tok >= 0) {
-    const float gi = tile_value<WAVES>(red, 4 * ul + 0, j) + g4.x;
-    const float gf = tile_value<WAVES>(red, 4 * ul + 1, j) + g4.y;
-    const float gg = tile_value<WAVES>(red, 4 * ul + 2, j) + g4.z;
-    const float go = tile_value<WAVES>(red, 4 * ul + 3, j) + g4.w;
-    c = sigmoid_f(gf) * c_old + sigmoid_f(gi) * tanh_f(gg);
-    h = sigmoid_f(go) * tanh_f(c);
-  }
-  c_nxt[(size_t)me * P + u] = c;
-  h_nxt[k4_index(u, me, Mp)] = h;
-  RB_STAMP(2, 3);
+  c_nxt[(size_t)m * P + u] = c;
+  h_nxt[k4_index(u, m, Mp)] = h;
 }
 
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
@@ -975,6 +1023,10 @@ struct InitArgs {
   int *src_row, *tok;
   float *h0, *c0;  // zeroed state the first LSTM step reads (nullable), n_state floats each
   size_t n_state;
+  float *R;        // recurrent product of the zero state (nullable), n_R floats
+  size_t n_R;
+  int *tile_ctr;   // per-tile block counters of the main kernel
+  int n_tiles;
   int B, K, T, V, lstm;
   int *finished, *utt_steps, *n_finished, *done, *step_base, *bad_arg;
   volatile int *h_done;
@@ -1013,6 +1065,9 @@ __global__ void k_init(InitArgs a) {
     a.src_row[gid] = gid;
     a.tok[gid] = (a.lstm && k == 0) ? a.V : -1;
   }
+  for (int i = gid; i < a.n_tiles; i += gridDim.x * blockDim.x) a.tile_ctr[i] = 0;
+  if (a.R)
+    for (size_t i = gid; i < a.n_R; i += (size_t)gridDim.x * blockDim.x) a.R[i] = 0.f;
   if (a.h0) {
     const size_t n = a.n_state;
     for (size_t i = gid; i < n; i += (size_t)gridDim.x * blockDim.x) {

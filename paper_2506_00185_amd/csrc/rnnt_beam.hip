@@ -38,8 +38,8 @@ struct KernelTimer {
 };
 
 enum { KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_COUNT };
-const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init", "k_joint", "k_select",
-                                      "k_lm_rows",           "k_lstm", "k_pred_proj", "k_backtrace"};
+const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init",           "k_step_main", "k_select",
+                                      "k_lm_rows",           "k_lstm_pointwise", "k_pred_proj", "k_backtrace"};
 
 }  // namespace
 
@@ -53,13 +53,14 @@ struct rnnt_beam {
         *b_out = nullptr, *W_hh = nullptr, *G = nullptr, *tab = nullptr;
   // workspace
   float *f_proj = nullptr, *pre = nullptr, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
-  float *lm_rows = nullptr;
+  float *lm_rows = nullptr, *Rgates = nullptr;
+  int *tile_ctr = nullptr;
   double *score = nullptr;
   int *t = nullptr, *sym = nullptr, *len = nullptr, *last = nullptr, *ctx = nullptr, *lengths = nullptr;
   uint32_t *hash = nullptr;
   int *src_row = nullptr, *tok = nullptr;
-  float *p_max = nullptr, *p_sum = nullptr, *p_key = nullptr, *zs = nullptr;
-  int *p_idx = nullptr;
+  float *p_max = nullptr, *p_sum = nullptr, *zs = nullptr;
+  uint64_t *p_cand = nullptr;
   int *tree_parent = nullptr, *tree_token = nullptr, *tree_merged = nullptr;
   int *finished = nullptr, *utt_steps = nullptr, *ctrl = nullptr;  // ctrl: n_finished, done, step_base, bad_arg, nonfinite
   int *h_done = nullptr, *h_done_dev = nullptr;                    // pinned host word and its device alias
@@ -250,14 +251,9 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
   } else if (c.pred == RNNT_PRED_LSTM) {
     {
       ScopedKernelTime tm(h, s, KT_LSTM);
-      const dim3 grid(4 * c.P / 32, m_tiles);
-#define RB_LSTM(W, I)                                                                                         \
-  hipLaunchKernelGGL((k_lstm<W, I>), grid, dim3(W * 64), 0, s, h->W_hh, h->G, h->h[cur], h->c[cur], h->h[cur ^ 1], \
-                     h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done)
-      if (c.P == 640) RB_LSTM(8, 10);
-      else if (c.P % 64 == 0) RB_LSTM(8, 0);
-      else RB_LSTM(4, 0);
-#undef RB_LSTM
+      const int n = p.M * c.P;
+      hipLaunchKernelGGL(k_lstm_pointwise, dim3((n + 255) / 256), dim3(256), 0, s, h->Rgates, h->G, h->h[cur], h->c[cur],
+                         h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done);
     }
     {
       PredProjArgs a;
@@ -297,12 +293,36 @@ int launch_lm(rnnt_beam *h, hipStream_t s, const StepPlan &p) {
   return RNNT_OK;
 }
 
+void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunks, SelectArgs &a) {
+  const rnnt_config_t &c = h->cfg;
+  a.score = h->score; a.t = h->t; a.sym = h->sym; a.len = h->len; a.last = h->last; a.hash = h->hash;
+  a.ctx = h->ctx;
+  a.lengths = h->lengths;
+  a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
+  a.n_chunks = n_chunks;
+  a.normalized = p.inj_tok ? 1 : 0;
+  a.use_ctx = (c.pred == RNNT_PRED_STATELESS || p.lm) ? 1 : 0;
+  a.B = p.B; a.K = p.K; a.V = c.V; a.ND = c.n_durations;
+  for (int i = 0; i < 8; ++i) a.dur[i] = c.durations[i];
+  a.algo = p.algo;
+  a.max_sym = c.max_symbols;
+  a.gamma = c.prune_margin;
+  a.has_lm = p.lm ? 1 : 0;
+  a.lambda = p.lambda;
+  a.src_row = h->src_row; a.tok = h->tok;
+  a.tree_parent = h->tree_parent; a.tree_token = h->tree_token; a.tree_merged = h->tree_merged;
+  a.S_max = h->S_max;
+  a.step_base = h->ctrl + 2;
+  a.step_off = step_off;
+  a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = h->ctrl; a.done = h->ctrl + 1;
+  a.h_done = h->h_done_dev;
+}
+
 // one beam-search step; cur = parity of the prediction-network state it reads
 int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, int cur, int bump) {
   const rnnt_config_t &c = h->cfg;
-  int *n_finished = h->ctrl, *done = h->ctrl + 1, *step_base = h->ctrl + 2;
+  int *done = h->ctrl + 1;
   const int kt = beam_template(p.K);
-  int n_chunks;
   if (p.inj_tok) {
     InjectArgs a;
     a.tok_logp = p.inj_tok;
@@ -312,17 +332,22 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.hash = h->hash;
     a.lengths = h->lengths;
     a.M = p.M; a.K = p.K; a.T = p.T; a.V = c.V; a.ND = c.n_durations;
-    a.p_key = h->p_key;
-    a.p_idx = h->p_idx;
+    a.p_cand = h->p_cand;
     a.zs = h->zs;
     a.done = done;
-    n_chunks = 64;
-    ScopedKernelTime tm(h, s, KT_JOINT);
-    if (kt == 4) hipLaunchKernelGGL(k_inject<4>, dim3(p.M), dim3(64), 0, s, a);
-    else if (kt == 8) hipLaunchKernelGGL(k_inject<8>, dim3(p.M), dim3(64), 0, s, a);
-    else hipLaunchKernelGGL(k_inject<16>, dim3(p.M), dim3(64), 0, s, a);
+    {
+      ScopedKernelTime tm(h, s, KT_JOINT);
+      if (kt == 4) hipLaunchKernelGGL(k_inject<4>, dim3(p.M), dim3(64), 0, s, a);
+      else if (kt == 8) hipLaunchKernelGGL(k_inject<8>, dim3(p.M), dim3(64), 0, s, a);
+      else hipLaunchKernelGGL(k_inject<16>, dim3(p.M), dim3(64), 0, s, a);
+    }
+    RB_HIP(h, hipGetLastError());
+    SelectArgs sa;
+    fill_select_args(h, p, step_off, 64, sa);
+    ScopedKernelTime tm(h, s, KT_SELECT);
+    hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
   } else {
-    JointArgs a;
+    MainArgs a;
     a.pre = h->pre;
     a.W = h->W_out;
     a.bias = h->b_out;
@@ -331,44 +356,26 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
     a.n_chunks = h->n_chunks;
     a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
-    a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_key = h->p_key; a.p_idx = h->p_idx; a.zs = h->zs;
-    a.done = done;
-    n_chunks = h->n_chunks;
-    dim3 grid(h->n_chunks, (p.M + 31) / 32);
+    a.upt = 32 / p.K;
+    a.rpt = a.upt * p.K;
+    a.n_jtiles = (p.B + a.upt - 1) / a.upt;
+    a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
+    a.tile_ctr = h->tile_ctr;
+    const bool lstm = c.pred == RNNT_PRED_LSTM;
+    a.Whh = lstm ? h->W_hh : nullptr;
+    a.h_cur = h->h[cur];
+    a.R = h->Rgates;
+    a.P = c.P;
+    fill_select_args(h, p, step_off, h->n_chunks, a.sel);
+    const int n_joint = a.n_chunks * a.n_jtiles;
+    const int n_rec = lstm ? (4 * c.P / 32) * ((p.M + 31) / 32) : 0;
+    const dim3 grid(n_joint + n_rec);
     ScopedKernelTime tm(h, s, KT_JOINT);
-#define RB_JOINT(W, I) hipLaunchKernelGGL((k_joint<W, I>), grid, dim3(W * 64), 0, s, a)
-    (void)kt;
-    if (c.H == 640) RB_JOINT(8, 10);
-    else if (c.H % 64 == 0) RB_JOINT(8, 0);
-    else RB_JOINT(4, 0);
-#undef RB_JOINT
-  }
-  RB_HIP(h, hipGetLastError());
-  {
-    SelectArgs a;
-    a.score = h->score; a.t = h->t; a.sym = h->sym; a.len = h->len; a.last = h->last; a.hash = h->hash;
-    a.ctx = h->ctx;
-    a.lengths = h->lengths;
-    a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_key = h->p_key; a.p_idx = h->p_idx; a.zs = h->zs;
-    a.n_chunks = n_chunks;
-    a.normalized = p.inj_tok ? 1 : 0;
-    a.use_ctx = (c.pred == RNNT_PRED_STATELESS || p.lm) ? 1 : 0;
-    a.B = p.B; a.K = p.K; a.V = c.V; a.ND = c.n_durations;
-    for (int i = 0; i < 8; ++i) a.dur[i] = c.durations[i];
-    a.algo = p.algo;
-    a.max_sym = c.max_symbols;
-    a.gamma = c.prune_margin;
-    a.has_lm = p.lm ? 1 : 0;
-    a.lambda = p.lambda;
-    a.src_row = h->src_row; a.tok = h->tok;
-    a.tree_parent = h->tree_parent; a.tree_token = h->tree_token; a.tree_merged = h->tree_merged;
-    a.S_max = h->S_max;
-    a.step_base = step_base;
-    a.step_off = step_off;
-    a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
-    a.h_done = h->h_done_dev;
-    ScopedKernelTime tm(h, s, KT_SELECT);
-    hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, a);
+#define RB_MAIN(W, I) hipLaunchKernelGGL((k_step_main<W, I>), grid, dim3(W * 64), 0, s, a)
+    if (c.H == 640 && (!lstm || c.P == 640)) RB_MAIN(8, 10);
+    else if (c.H % 64 == 0 && (!lstm || c.P % 64 == 0)) RB_MAIN(8, 0);
+    else RB_MAIN(4, 0);
+#undef RB_MAIN
   }
   RB_HIP(h, hipGetLastError());
   int rc = launch_lm(h, s, p);
@@ -398,6 +405,10 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     a.h0 = lstm ? h->h[1] : nullptr;
     a.c0 = lstm ? h->c[1] : nullptr;
     a.n_state = (size_t)c.P * h->Mp;
+    a.R = lstm ? h->Rgates : nullptr;
+    a.n_R = (size_t)p.M * 4 * c.P;
+    a.tile_ctr = h->tile_ctr;
+    a.n_tiles = c.max_B;
     a.B = p.B; a.K = p.K; a.T = p.T; a.V = c.V;
     a.lstm = lstm ? 1 : 0;
     a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
@@ -521,7 +532,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     return RNNT_E_ARG;
   };
   if (c.D < 32 || c.H < 32 || c.P < 32 || c.D % 32 || c.H % 32 || c.P % 32) return bad("D, H, P must be multiples of 32");
-  if (c.V < 1) return bad("V < 1");
+  if (c.V < 1 || c.V >= (1 << kFlatShift) - 1) return bad("V outside 1 .. 2^20 - 2");
   if (c.model != RNNT_MODEL_RNNT && c.model != RNNT_MODEL_TDT) return bad("unknown model");
   if (c.model == RNNT_MODEL_TDT && (c.n_durations < 1 || c.n_durations > 8)) return bad("TDT needs 1..8 durations");
   if (c.model == RNNT_MODEL_RNNT && c.n_durations != 0) return bad("n_durations must be 0 for RNN-T");
@@ -551,7 +562,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   h->n_chunks = (h->N + 31) / 32;
   h->pc_chunks = h->n_chunks > 64 ? h->n_chunks : 64;
   h->M_max = c.max_B * c.max_beam;
-  h->Mp = (h->M_max + 31) / 32 * 32;
+  h->Mp = (h->M_max + 31) / 32 * 32 + 32;  // a joint tile may start at any multiple of K and reads 32 rows
   h->S_max = c.max_T * (c.max_symbols + 1);
   h->cap = c.max_T * c.max_symbols + 1;
   const size_t M = h->M_max;
@@ -567,6 +578,8 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     A(dev_alloc(h, &h->c[i], (size_t)h->Mp * c.P));
   }
   A(dev_alloc(h, &h->lm_rows, M * c.V));
+  A(dev_alloc(h, &h->Rgates, M * 4 * c.P));
+  A(dev_alloc(h, &h->tile_ctr, (size_t)c.max_B));
   A(dev_alloc(h, &h->score, M));
   A(dev_alloc(h, &h->t, M));
   A(dev_alloc(h, &h->sym, M));
@@ -579,8 +592,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   A(dev_alloc(h, &h->tok, M));
   A(dev_alloc(h, &h->p_max, M * h->pc_chunks));
   A(dev_alloc(h, &h->p_sum, M * h->pc_chunks));
-  A(dev_alloc(h, &h->p_key, M * h->pc_chunks * c.max_beam));
-  A(dev_alloc(h, &h->p_idx, M * h->pc_chunks * c.max_beam));
+  A(dev_alloc(h, &h->p_cand, M * h->pc_chunks * c.max_beam));
   A(dev_alloc(h, &h->zs, M * (1 + 8)));
   const size_t tree = (size_t)c.max_B * h->S_max * c.max_beam;
   A(dev_alloc(h, &h->tree_parent, tree));
