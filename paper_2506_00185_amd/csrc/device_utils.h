@@ -41,6 +41,19 @@ __device__ __forceinline__ double logaddexp_d(double a, double b) {
   return m + log(exp(a - m) + exp(b - m));
 }
 
+// Stores and loads that are coherent across the whole device on their own (they bypass the caches
+// that are private to a group of compute units), for the few words that one block hands to another
+// inside a kernel.  A device-wide release / acquire fence would write back and invalidate the whole
+// L2 instead, which costs microseconds.
+template <typename T>
+__device__ __forceinline__ void store_agent(T *p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T load_agent(const T *p) {
+  return __hip_atomic_load(const_cast<T *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Candidate order used everywhere a "best" is chosen: larger value first, then
 // smaller index.  Returns true if (v1, i1) comes before (v2, i2).
 template <typename V, typename I>

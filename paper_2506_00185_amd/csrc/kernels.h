@@ -8,6 +8,8 @@
 // wall clock at a few points of each kernel.  Compiled out otherwise.
 #ifdef RB_TIMING
 __device__ long long rb_stamps[8 * 16];
+__device__ long long rb_block_ts[2 * 1024];
+#define RB_BLOCK_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) rb_block_ts[2 * blockIdx.x + (i)] = wall_clock64(); } while (0)
 #define RB_STAMP(kernel, i)                                                      \
   do {                                                                           \
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rb_stamps[(kernel) * 16 + (i)] = wall_clock64(); \
@@ -15,6 +17,9 @@ __device__ long long rb_stamps[8 * 16];
 #else
 #define RB_STAMP(kernel, i) \
   do {                      \
+  } while (0)
+#define RB_BLOCK_TS(i) \
+  do {                 \
   } while (0)
 #endif
 
@@ -337,14 +342,14 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       const int ch = e + LPR * q;
       const bool ok = row_ok && ch < a.n_chunks;
 #pragma unroll
-      for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? cands[ch * K + j] : no_cand();
-      pm[q] = (ok && !a.normalized) ? pmax[ch] : -INFINITY;
-      ps[q] = (ok && !a.normalized) ? psum[ch] : 0.f;
+      for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+      pm[q] = (ok && !a.normalized) ? load_agent(pmax + ch) : -INFINITY;
+      ps[q] = (ok && !a.normalized) ? load_agent(psum + ch) : 0.f;
     }
   }
-  const float zb = zsr[0];
+  const float zb = load_agent(zsr);
   float dl[8];
-  for (int d = 0; d < a.ND; ++d) dl[d] = zsr[1 + d];
+  for (int d = 0; d < a.ND; ++d) dl[d] = load_agent(zsr + 1 + d);
   if (a.use_ctx)
     for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
   if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
@@ -400,7 +405,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       uint64_t best = no_cand();
       if (row_ok)
         for (int c = e; c < ncand; c += LPR) {
-          const uint64_t v = cands[c];
+          const uint64_t v = load_agent(cands + c);
           if (v < last && v > best) best = v;
         }
       best = group_max_u64<LPR>(best);
@@ -423,12 +428,12 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         if (pm[q] > -INFINITY) st_sum += ps[q] * __expf(pm[q] - st_mx);
     } else {
       if (row_ok)
-        for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, pmax[c]);
+        for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, load_agent(pmax + c));
       st_mx = group_max<LPR>(st_mx);
       if (row_ok)
         for (int c = e; c < a.n_chunks; c += LPR) {
-          const float p = pmax[c];
-          if (p > -INFINITY) st_sum += psum[c] * __expf(p - st_mx);
+          const float p = load_agent(pmax + c);
+          if (p > -INFINITY) st_sum += load_agent(psum + c) * __expf(p - st_mx);
         }
     }
     st_sum = group_sum<LPR>(st_sum);
@@ -678,6 +683,41 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Sele
   }
 }
 
+// R[m] = W_hh h[m] for one tile of 32 gate rows x 32 current slots (it does not depend on the
+// selection, so its blocks ride along in the launches that have idle compute units).
+struct RecurrentArgs {
+  const float *Whh;    // k4-major [P][4P], gate rows re-ordered (NULL: no such blocks)
+  const float *h;      // k4-major [P][Mp]
+  float *R;            // [M][4P]
+  int P, M, Mp;
+  int tile_begin, tile_end;  // gate tiles [begin, end) of 4P / 32 are computed by this launch
+};
+
+template <int WAVES, int ITERS>
+__device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int idx, int done, float *red) {
+  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
+  const int n_tiles = a.tile_end - a.tile_begin;
+  const int tile = a.tile_begin + idx % n_tiles, m0 = (idx / n_tiles) * 32;
+  const int R4 = 4 * a.P, Mp = a.Mp;
+  const float *wp = a.Whh + (size_t)(tile * 32 + col) * 4;
+  const float *hp = a.h + (size_t)(m0 + col) * 4;
+  auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R4 * 4); };
+  auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
+  auto fb = [](float4 v) { return v; };
+  SplitKOperands<ITERS> op;
+  splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
+  if (done) return;
+  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
+  // thread -> (slot j, VPL adjacent rows of the tile)
+  const int j = tid / LPH, i0 = (tid % LPH) * VPL;
+  const int m = m0 + j;
+  if (m < a.M) {
+#pragma unroll
+    for (int q = 0; q < VPL; ++q) a.R[(size_t)m * R4 + tile * 32 + i0 + q] = tile_value<WAVES>(red, i0 + q, j);
+  }
+}
+
 struct MainArgs {
   // ---- joint role
   const float *pre;   // k4-major [H][Mp]: f_proj[b, t_m] + prediction projection of hypothesis m
@@ -691,11 +731,8 @@ struct MainArgs {
   uint64_t *p_cand;        // [M, n_chunks, K] best (key = z + lambda * lm, token) of the chunk, packed
   float *zs;               // [M, 1 + ND] raw blank and duration logits
   int *tile_ctr;           // [n_jtiles] blocks of the tile that have written their lists
-  // ---- recurrent-product role (LSTM): R[m] = W_hh h[m] for every current slot
-  const float *Whh;        // k4-major [P][4P], gate rows re-ordered (NULL: no such blocks)
-  const float *h_cur;      // k4-major [P][Mp]
-  float *R;                // [M][4P]
-  int P;
+  // ---- recurrent-product role (LSTM)
+  RecurrentArgs rec;
   // ---- selection (run by the block that completes a tile)
   SelectArgs sel;
 };
@@ -720,31 +757,11 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int n_joint = a.n_chunks * a.n_jtiles;
   const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
+  if (!done) RB_BLOCK_TS(0);
 
   if ((int)blockIdx.x >= n_joint) {
-    // ---------------------------------------------------------------- R = W_hh h
-    const int idx = blockIdx.x - n_joint, n_tiles = 4 * a.P / 32;
-    const int tile = idx % n_tiles, m0 = (idx / n_tiles) * 32;
-    const int R4 = 4 * a.P, Mp = a.Mp;
-    const float *wp = a.Whh + (size_t)(tile * 32 + col) * 4;
-    const float *hp = a.h_cur + (size_t)(m0 + col) * 4;
-    auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * R4 * 4); };
-    auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
-    auto fb = [](float4 v) { return v; };
-    SplitKOperands<ITERS> op;
-    splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
-    if (done) return;
-    RB_STAMP(2, 1);
-    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
-    RB_STAMP(2, 2);
-    // thread -> (hypothesis j, VPL adjacent rows of the tile)
-    const int j = tid / LPH, i0 = (tid % LPH) * VPL;
-    const int m = m0 + j;
-    if (m < a.M) {
-#pragma unroll
-      for (int q = 0; q < VPL; ++q) a.R[(size_t)m * R4 + tile * 32 + i0 + q] = tile_value<WAVES>(red, i0 + q, j);
-    }
-    RB_STAMP(2, 3);
+    recurrent_tile<WAVES, ITERS>(a.rec, blockIdx.x - n_joint, done, red);
+    RB_BLOCK_TS(1);
     return;
   }
 
@@ -790,7 +807,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
       cand[q] = pack_cand((a.lm && mvalid) ? z + a.lambda * a.lm[(size_t)m * a.V + n] : z, n);
       mx = fmaxf(mx, z);
     } else if (n < a.V + nz && mvalid) {
-      a.zs[(size_t)m * nz + (n - a.V)] = z;
+      store_agent(a.zs + (size_t)m * nz + (n - a.V), z);
     }
   }
   mx = group_max<LPH>(mx);
@@ -827,29 +844,30 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
   if (mvalid) {
     const size_t pc = (size_t)m * a.n_chunks + chunk;
     if (e == 0) {
-      a.p_max[pc] = mx;
-      a.p_sum[pc] = sum;
+      store_agent(a.p_max + pc, mx);
+      store_agent(a.p_sum + pc, sum);
     }
-    if (e < a.K) a.p_cand[pc * a.K + e] = mine[0];
-    if (LPH + e < a.K) a.p_cand[pc * a.K + LPH + e] = mine[1];
+    if (e < a.K) store_agent(a.p_cand + pc * a.K + e, mine[0]);
+    if (LPH + e < a.K) store_agent(a.p_cand + pc * a.K + LPH + e, mine[1]);
   }
 
   // ---- the block that completes the tile runs the selection for its utterances.
-  // One thread per block does the cache maintenance: the barrier makes the block's stores its own
-  // (workgroup scope), its release makes them visible device-wide before the block is counted, and
-  // only the completing block pays for an acquire (an L2 invalidate is far too dear to issue per thread).
+  // The lists were written with device-coherent stores; once every thread's stores have been
+  // acknowledged (workgroup release + barrier) one thread counts the block in.  The completing block
+  // reads the lists with device-coherent loads, so no cache is written back or invalidated.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
-    const int old = __hip_atomic_fetch_add(a.tile_ctr + ty, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    const int old = __hip_atomic_fetch_add(a.tile_ctr + ty, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const int last = old == a.n_chunks - 1;
-    if (last) {
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-      a.tile_ctr[ty] = 0;  // every other block of the tile has been counted: ready for the next step
-    }
+    if (last) store_agent(a.tile_ctr + ty, 0);  // every other block of the tile has been counted
     s_is_last = last;
   }
   __syncthreads();
-  if (!s_is_last) return;
+  if (!s_is_last) {
+    RB_BLOCK_TS(1);
+    return;
+  }
   RB_STAMP(0, 5);
   SelectScratch *scratch = reinterpret_cast<SelectScratch *>(smem);
   const int wave = tid >> 6;
@@ -858,6 +876,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
     if (b < a.sel.B) select_dispatch(a.sel, b, scratch[wave]);
   }
   RB_STAMP(0, 6);
+  RB_BLOCK_TS(1);
 }
 
 // stand-alone selection kernel: one wave per utterance, four utterances per block
@@ -922,6 +941,8 @@ struct PredProjArgs {
   const int *done;
   int *step_base;
   int bump;
+  int n_pred_blocks;   // blocks beyond these compute recurrent tiles of the new state
+  RecurrentArgs rec;
 };
 
 template <int WAVES, int ITERS>
@@ -929,7 +950,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   __shared__ float red[WAVES * 64 * kRedStride];
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int tile = blockIdx.x, m0 = blockIdx.y * 32;
+  if ((int)blockIdx.x >= a.n_pred_blocks) {
+    const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
+    recurrent_tile<WAVES, ITERS>(a.rec, blockIdx.x - a.n_pred_blocks, done_flag, red);
+    return;
+  }
+  const int n_ptiles = a.H / 32;
+  const int tile = blockIdx.x % n_ptiles, m0 = (blockIdx.x / n_ptiles) * 32;
   const float *wp = a.Wp + (size_t)(tile * 32 + col) * 4;
   const float *hp = a.h + (size_t)(m0 + col) * 4;
   const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
@@ -958,7 +985,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
     }
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
-  if (a.bump && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) *a.step_base += a.bump;
+  if (a.bump && blockIdx.x == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)

@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <string>
@@ -119,6 +120,15 @@ int fail(rnnt_beam *h, int code, const std::string &msg) {
 }
 
 int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
+
+// Gate tiles of the recurrent product computed in the prediction-projection launch (the rest ride in the
+// main launch): as many as fit beside the projection's own blocks on the 256 compute units.
+int recurrent_split(const rnnt_config_t &c, int M) {
+  const int m_tiles = (M + 31) / 32, n_tiles = 4 * c.P / 32;
+  const int idle = 256 - (c.H / 32) * m_tiles;
+  int t = idle > 0 ? idle / m_tiles : 0;
+  return t > n_tiles ? n_tiles : t;
+}
 
 int launch_gemm(rnnt_beam *h, hipStream_t s, const float *A, const float *B, const float *bias, float *C, int M, int N,
                 int K, int round_ops, int *nonfinite) {
@@ -263,8 +273,12 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
       a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
       a.done = done; a.step_base = step_base; a.bump = bump;
+      a.n_pred_blocks = (c.H / 32) * m_tiles;
+      a.rec.Whh = h->W_hh; a.rec.h = h->h[cur ^ 1]; a.rec.R = h->Rgates;
+      a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = h->Mp;
+      a.rec.tile_begin = 0; a.rec.tile_end = recurrent_split(c, p.M);
       ScopedKernelTime tm(h, s, KT_PREDPROJ);
-      const dim3 grid(c.H / 32, m_tiles);
+      const dim3 grid(a.n_pred_blocks + a.rec.tile_end * m_tiles);
 #define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), 0, s, a)
       if (c.P == 640) RB_PRED(8, 10);
       else if (c.P % 64 == 0) RB_PRED(8, 0);
@@ -362,13 +376,13 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
     a.tile_ctr = h->tile_ctr;
     const bool lstm = c.pred == RNNT_PRED_LSTM;
-    a.Whh = lstm ? h->W_hh : nullptr;
-    a.h_cur = h->h[cur];
-    a.R = h->Rgates;
-    a.P = c.P;
+    a.rec.Whh = h->W_hh; a.rec.h = h->h[cur]; a.rec.R = h->Rgates;
+    a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = h->Mp;
+    a.rec.tile_begin = lstm ? recurrent_split(c, p.M) : 0;
+    a.rec.tile_end = lstm ? 4 * c.P / 32 : 0;
     fill_select_args(h, p, step_off, h->n_chunks, a.sel);
     const int n_joint = a.n_chunks * a.n_jtiles;
-    const int n_rec = lstm ? (4 * c.P / 32) * ((p.M + 31) / 32) : 0;
+    const int n_rec = (a.rec.tile_end - a.rec.tile_begin) * ((p.M + 31) / 32);
     const dim3 grid(n_joint + n_rec);
     ScopedKernelTime tm(h, s, KT_JOINT);
 #define RB_MAIN(W, I) hipLaunchKernelGGL((k_step_main<W, I>), grid, dim3(W * 64), 0, s, a)
@@ -383,7 +397,17 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
   return launch_pred(h, s, p, cur, bump);
 }
 
-constexpr int kChunkSteps = 8;  // steps per graph launch (even: the state parity flips every step)
+// steps per graph launch (even: the state parity flips every step)
+int chunk_steps() {
+  static int v = [] {
+    const char *e = getenv("RNNT_BEAM_CHUNK");
+    int n = e ? atoi(e) : 16;
+    if (n < 2) n = 2;
+    return n & ~1;
+  }();
+  return v;
+}
+#define kChunkSteps chunk_steps()
 
 int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const StepPlan &p, hipStream_t s) {
   const rnnt_config_t &c = h->cfg;
@@ -737,6 +761,9 @@ int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_
 }
 
 #ifdef RB_TIMING
+int rnnt_beam_debug_block_ts(long long *out) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_block_ts), sizeof(long long) * 2048) == hipSuccess ? 0 : RNNT_E_HIP;
+}
 // tuning builds only: copy the phase stamps out (8 kernels x 16 stamps, 10 ns ticks)
 int rnnt_beam_debug_stamps(long long *out) {
   return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_stamps), sizeof(long long) * 8 * 16) == hipSuccess ? 0 : RNNT_E_HIP;
