@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch the step kernels one by one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-utts", type=int, default=16, help="utterances the oracle decodes for the CPU baseline")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run a plain device copy of this size five times (scale for the FETCH_SIZE / "
+                         "WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (utterances would be sharded "
@@ -64,6 +67,15 @@ def main():
     import paper_2506_00185_amd as A
 
     assert torch.cuda.is_available(), "needs an MI355X"
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.arange(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_MiB": args.copy_calibration, "bytes_read": n * 4, "bytes_written": n * 4}))
+        return
     c = S.config(args.config, prec=args.variant if args.config == 2 else S.CONFIGS[args.config]["prec"])
     w = S.make_weights(c)
     L = S.make_lengths(c)

@@ -683,6 +683,52 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Sele
   }
 }
 
+// Block -> work item, aware of the eight XCDs.  Workgroup i of a launch runs on XCD i % 8, and each
+// XCD has its own L2.  A launch has up to two roles, each a grid of (n-tile, m-tile) items; every
+// item of an n-tile (one 32-row slice of a weight matrix) is given to the XCD  n-tile % 8, so that a
+// slice is only ever read through one L2 and stays there from one step to the next.
+struct XcdMap {
+  int a_tiles, a_m;          // role 0: n-tiles [0, a_tiles) x a_m m-tiles
+  int b_begin, b_end, b_m;   // role 1: n-tiles [b_begin, b_end) x b_m m-tiles
+};
+__host__ __device__ inline int xcd_role_a_tiles(const XcdMap &m, int x) {
+  return m.a_tiles > x ? (m.a_tiles - x + 7) / 8 : 0;
+}
+__host__ __device__ inline int xcd_role_b_first(const XcdMap &m, int x) {
+  return m.b_begin + ((x - m.b_begin) % 8 + 8) % 8;
+}
+__host__ __device__ inline int xcd_role_b_tiles(const XcdMap &m, int x) {
+  const int t0 = xcd_role_b_first(m, x);
+  return m.b_end > t0 ? (m.b_end - t0 + 7) / 8 : 0;
+}
+// number of blocks to launch: eight times the largest per-XCD item count
+__host__ inline int xcd_grid(const XcdMap &m) {
+  int most = 0;
+  for (int x = 0; x < 8; ++x) {
+    const int n = xcd_role_a_tiles(m, x) * m.a_m + xcd_role_b_tiles(m, x) * m.b_m;
+    most = n > most ? n : most;
+  }
+  return 8 * most;
+}
+// role of block `bid` (0, 1, or -1 = nothing to do) and its item
+__device__ __forceinline__ int xcd_item(const XcdMap &m, int bid, int &ntile, int &mtile) {
+  const int x = bid & 7;
+  int s = bid >> 3;
+  const int na = xcd_role_a_tiles(m, x) * m.a_m;
+  if (s < na) {
+    ntile = x + 8 * (s / m.a_m);
+    mtile = s % m.a_m;
+    return 0;
+  }
+  s -= na;
+  if (s < xcd_role_b_tiles(m, x) * m.b_m) {
+    ntile = xcd_role_b_first(m, x) + 8 * (s / m.b_m);
+    mtile = s % m.b_m;
+    return 1;
+  }
+  return -1;
+}
+
 // R[m] = W_hh h[m] for one tile of 32 gate rows x 32 current slots (it does not depend on the
 // selection, so its blocks ride along in the launches that have idle compute units).
 struct RecurrentArgs {
@@ -690,15 +736,13 @@ struct RecurrentArgs {
   const float *h;      // k4-major [P][Mp]
   float *R;            // [M][4P]
   int P, M, Mp;
-  int tile_begin, tile_end;  // gate tiles [begin, end) of 4P / 32 are computed by this launch
 };
 
 template <int WAVES, int ITERS>
-__device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int idx, int done, float *red) {
+__device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int tile, int mtile, int done, float *red) {
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int n_tiles = a.tile_end - a.tile_begin;
-  const int tile = a.tile_begin + idx % n_tiles, m0 = (idx / n_tiles) * 32;
+  const int m0 = mtile * 32;
   const int R4 = 4 * a.P, Mp = a.Mp;
   const float *wp = a.Whh + (size_t)(tile * 32 + col) * 4;
   const float *hp = a.h + (size_t)(m0 + col) * 4;
@@ -733,6 +777,7 @@ struct MainArgs {
   int *tile_ctr;           // [n_jtiles] blocks of the tile that have written their lists
   // ---- recurrent-product role (LSTM)
   RecurrentArgs rec;
+  XcdMap map;              // role 0 = joint (chunk, tile), role 1 = recurrent (gate tile, 32-row tile)
   // ---- selection (run by the block that completes a tile)
   SelectArgs sel;
 };
@@ -755,18 +800,18 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
   float *red = smem;
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int n_joint = a.n_chunks * a.n_jtiles;
   const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
   if (!done) RB_BLOCK_TS(0);
-
-  if ((int)blockIdx.x >= n_joint) {
-    recurrent_tile<WAVES, ITERS>(a.rec, blockIdx.x - n_joint, done, red);
+  int chunk, ty;
+  const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
+  if (role < 0) return;
+  if (role == 1) {
+    recurrent_tile<WAVES, ITERS>(a.rec, chunk, ty, done, red);
     RB_BLOCK_TS(1);
     return;
   }
 
   // -------------------------------------------------------------------- joint
-  const int chunk = blockIdx.x % a.n_chunks, ty = blockIdx.x / a.n_chunks;
   const int n0 = chunk * 32, m0 = ty * a.rpt;
   RB_STAMP(0, 0);
   {
@@ -941,8 +986,8 @@ struct PredProjArgs {
   const int *done;
   int *step_base;
   int bump;
-  int n_pred_blocks;   // blocks beyond these compute recurrent tiles of the new state
-  RecurrentArgs rec;
+  RecurrentArgs rec;   // recurrent tiles of the new state ride along
+  XcdMap map;          // role 0 = projection (tile of H, 32-row tile), role 1 = recurrent
 };
 
 template <int WAVES, int ITERS>
@@ -950,13 +995,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   __shared__ float red[WAVES * 64 * kRedStride];
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  if ((int)blockIdx.x >= a.n_pred_blocks) {
+  int tile, mtile;
+  const int role = xcd_item(a.map, blockIdx.x, tile, mtile);
+  if (role < 0) return;
+  if (role == 1) {
     const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
-    recurrent_tile<WAVES, ITERS>(a.rec, blockIdx.x - a.n_pred_blocks, done_flag, red);
+    recurrent_tile<WAVES, ITERS>(a.rec, tile, mtile, done_flag, red);
     return;
   }
-  const int n_ptiles = a.H / 32;
-  const int tile = blockIdx.x % n_ptiles, m0 = (blockIdx.x / n_ptiles) * 32;
+  const int m0 = mtile * 32;
   const float *wp = a.Wp + (size_t)(tile * 32 + col) * 4;
   const float *hp = a.h + (size_t)(m0 + col) * 4;
   const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
@@ -985,7 +1032,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
     }
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
-  if (a.bump && blockIdx.x == 0 && tid == 0) *a.step_base += a.bump;
+  if (a.bump && tile == 0 && mtile == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)

@@ -72,8 +72,10 @@ struct rnnt_beam {
   int last_B = 0, last_K = 0, last_T = 0;
   hipStream_t last_stream = nullptr;
   hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_chunk[4] = {nullptr, nullptr, nullptr, nullptr};
-  hipEvent_t ev_k0 = nullptr, ev_k1 = nullptr;
   bool profiling = false;
+  std::vector<hipEvent_t> prof_events;              // pool, two per timed launch
+  std::vector<std::pair<int, int>> prof_launches;   // (kernel id, index of its first event)
+  size_t prof_used = 0;
   KernelTimer timers[KT_COUNT];
   // graphs of one chunk of steps, keyed by the launch shape
   typedef std::tuple<int, int, int, int, const void *, uint32_t> GraphKey;
@@ -122,12 +124,16 @@ int fail(rnnt_beam *h, int code, const std::string &msg) {
 int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
 
 // Gate tiles of the recurrent product computed in the prediction-projection launch (the rest ride in the
-// main launch): as many as fit beside the projection's own blocks on the 256 compute units.
+// main launch): as many as fit beside the projection's own blocks, one block per compute unit, on every XCD
+// (32 compute units each).
 int recurrent_split(const rnnt_config_t &c, int M) {
-  const int m_tiles = (M + 31) / 32, n_tiles = 4 * c.P / 32;
-  const int idle = 256 - (c.H / 32) * m_tiles;
-  int t = idle > 0 ? idle / m_tiles : 0;
-  return t > n_tiles ? n_tiles : t;
+  XcdMap m;
+  m.a_tiles = c.H / 32;
+  m.a_m = m.b_m = (M + 31) / 32;
+  m.b_begin = 0;
+  for (m.b_end = 4 * c.P / 32; m.b_end > 0; --m.b_end)
+    if (xcd_grid(m) <= 256) break;
+  return m.b_end;
 }
 
 int launch_gemm(rnnt_beam *h, hipStream_t s, const float *A, const float *B, const float *bias, float *C, int M, int N,
@@ -232,23 +238,29 @@ struct StepPlan {
   int C;
 };
 
-// timing wrapper used in profiling mode: synchronous, one kernel at a time
+// Timing wrapper used in profiling mode: an event before and after the launch, nothing waits.
+// The pairs are read back once the decode has finished, so the kernels run as densely as in an
+// untimed decode (plain launches, no graph).
 struct ScopedKernelTime {
   rnnt_beam *h;
   hipStream_t s;
   int which;
+  size_t first = 0;
+  bool on = false;
   ScopedKernelTime(rnnt_beam *h_, hipStream_t s_, int w) : h(h_), s(s_), which(w) {
-    if (h->profiling) hipEventRecord(h->ev_k0, s);
+    if (!h->profiling) return;
+    while (h->prof_events.size() < h->prof_used + 2) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) return;
+      h->prof_events.push_back(e);
+    }
+    first = h->prof_used;
+    h->prof_used += 2;
+    on = hipEventRecord(h->prof_events[first], s) == hipSuccess;
   }
   ~ScopedKernelTime() {
-    if (h->profiling) {
-      hipEventRecord(h->ev_k1, s);
-      hipEventSynchronize(h->ev_k1);
-      float ms = 0.f;
-      hipEventElapsedTime(&ms, h->ev_k0, h->ev_k1);
-      h->timers[which].ms += ms;
-      h->timers[which].calls += 1;
-    }
+    if (!on) return;
+    if (hipEventRecord(h->prof_events[first + 1], s) == hipSuccess) h->prof_launches.push_back({which, (int)first});
   }
 };
 
@@ -273,12 +285,12 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
       a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
       a.done = done; a.step_base = step_base; a.bump = bump;
-      a.n_pred_blocks = (c.H / 32) * m_tiles;
       a.rec.Whh = h->W_hh; a.rec.h = h->h[cur ^ 1]; a.rec.R = h->Rgates;
       a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = h->Mp;
-      a.rec.tile_begin = 0; a.rec.tile_end = recurrent_split(c, p.M);
+      a.map.a_tiles = c.H / 32; a.map.a_m = m_tiles;
+      a.map.b_begin = 0; a.map.b_end = recurrent_split(c, p.M); a.map.b_m = m_tiles;
       ScopedKernelTime tm(h, s, KT_PREDPROJ);
-      const dim3 grid(a.n_pred_blocks + a.rec.tile_end * m_tiles);
+      const dim3 grid(xcd_grid(a.map));
 #define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), 0, s, a)
       if (c.P == 640) RB_PRED(8, 10);
       else if (c.P % 64 == 0) RB_PRED(8, 0);
@@ -378,12 +390,12 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     const bool lstm = c.pred == RNNT_PRED_LSTM;
     a.rec.Whh = h->W_hh; a.rec.h = h->h[cur]; a.rec.R = h->Rgates;
     a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = h->Mp;
-    a.rec.tile_begin = lstm ? recurrent_split(c, p.M) : 0;
-    a.rec.tile_end = lstm ? 4 * c.P / 32 : 0;
+    a.map.a_tiles = a.n_chunks; a.map.a_m = a.n_jtiles;
+    a.map.b_begin = lstm ? recurrent_split(c, p.M) : 0;
+    a.map.b_end = lstm ? 4 * c.P / 32 : 0;
+    a.map.b_m = (p.M + 31) / 32;
     fill_select_args(h, p, step_off, h->n_chunks, a.sel);
-    const int n_joint = a.n_chunks * a.n_jtiles;
-    const int n_rec = (a.rec.tile_end - a.rec.tile_begin) * ((p.M + 31) / 32);
-    const dim3 grid(n_joint + n_rec);
+    const dim3 grid(xcd_grid(a.map));
     ScopedKernelTime tm(h, s, KT_JOINT);
 #define RB_MAIN(W, I) hipLaunchKernelGGL((k_step_main<W, I>), grid, dim3(W * 64), 0, s, a)
     if (c.H == 640 && (!lstm || c.P == 640)) RB_MAIN(8, 10);
@@ -417,6 +429,8 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   // the previous decode may still be writing the pinned completion word
   if (h->last_stream) RB_HIP(h, hipStreamSynchronize(h->last_stream));
   for (int i = 0; i < KT_COUNT; ++i) h->timers[i] = KernelTimer{kKernelNames[i], 0.f, 0};
+  h->prof_used = 0;
+  h->prof_launches.clear();
   RB_HIP(h, hipEventRecord(h->ev_begin, s));
   {
     InitArgs a;
@@ -634,8 +648,6 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&h->h_done_dev), h->h_done, 0);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
-    if (e == hipSuccess) e = hipEventCreate(&h->ev_k0);
-    if (e == hipSuccess) e = hipEventCreate(&h->ev_k1);
     for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&h->ev_chunk[i]);
     if (e == hipSuccess) e = hipMemset(h->ctrl, 0, 8 * sizeof(int));
     if (e != hipSuccess) {
@@ -750,6 +762,17 @@ int rnnt_beam_set_profiling(rnnt_beam_t *h, int32_t on) {
 
 int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_t *calls, int32_t n_cap) {
   if (!h) return RNNT_E_ARG;
+  if (!h->prof_launches.empty()) {
+    if (h->last_stream || h->have_result) RB_HIP(h, hipStreamSynchronize(h->last_stream));
+    for (const auto &l : h->prof_launches) {
+      float t = 0.f;
+      if (hipEventElapsedTime(&t, h->prof_events[l.second], h->prof_events[l.second + 1]) == hipSuccess) {
+        h->timers[l.first].ms += t;
+        h->timers[l.first].calls += 1;
+      }
+    }
+    h->prof_launches.clear();
+  }
   int n = 0;
   for (int i = 0; i < KT_COUNT && n < n_cap; ++i) {
     if (names) names[n] = h->timers[i].name ? h->timers[i].name : kKernelNames[i];
@@ -778,8 +801,8 @@ void rnnt_beam_destroy(rnnt_beam_t *h) {
   for (auto &kv : h->graphs) hipGraphExecDestroy(kv.second);
   for (void *p : h->allocs) hipFree(p);
   if (h->h_done) hipHostFree(h->h_done);
-  hipEvent_t evs[] = {h->ev_begin, h->ev_end, h->ev_k0, h->ev_k1, h->ev_chunk[0], h->ev_chunk[1], h->ev_chunk[2],
-                      h->ev_chunk[3]};
+  hipEvent_t evs[] = {h->ev_begin, h->ev_end, h->ev_chunk[0], h->ev_chunk[1], h->ev_chunk[2], h->ev_chunk[3]};
+  for (hipEvent_t e : h->prof_events) hipEventDestroy(e);
   for (hipEvent_t e : evs)
     if (e) hipEventDestroy(e);
   delete h;
