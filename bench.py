@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X, dense fp32 matrix
 PEAK_BF16_MFMA_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
 
 
 def kernel_flops(name: str, c: dict, M: int, B: int, T: int) -> float:
@@ -37,8 +38,17 @@ def kernel_flops(name: str, c: dict, M: int, B: int, T: int) -> float:
         return joint
     if name == "k_pred_proj":
         return 2.0 * M * c["P"] * c["H"] if c["pred"] == "lstm" else 0.0
+    if name == "k_joint_big":  # token columns only; blank and duration rows are done by the row kernel
+        return 2.0 * M * c["H"] * c["V"]
     if name.startswith("k_gemm_nt"):
         return 2.0 * B * T * c["D"] * c["H"]
+    return 0.0
+
+
+def kernel_bytes(name: str, c: dict, M: int) -> float:
+    """Algorithmic HBM bytes of one launch of the kernels that are bound by memory traffic."""
+    if name == "k_row_select":  # one read of the float32 logits of every hypothesis
+        return 4.0 * M * c["V"] + (4.0 * M * c["V"] if c["lm"] else 0.0)
     return 0.0
 
 
@@ -122,19 +132,34 @@ def main():
     kt = dec.kernel_times()
     dec.set_profiling(False)
     kernels = {n: dict(total_ms=round(t, 4), launches=k, avg_us=round(t / k * 1e3, 3) if k else None,
-                       tflops=round(kernel_flops(n, c, B * K, B, T) / (t / k * 1e-3) / 1e12, 3) if k and t > 0 else None)
+                       tflops=round(kernel_flops(n, c, B * K, B, T) / (t / k * 1e-3) / 1e12, 3) if k and t > 0 else None,
+                       gbs=round(kernel_bytes(n, c, B * K) / (t / k * 1e-3) / 1e9, 1) if k and t > 0 else None)
                for n, (t, k) in kt.items() if k}
     loop = {n: v for n, v in kernels.items()
-            if n in ("k_step_main", "k_select", "k_lstm_pointwise", "k_pred_proj", "k_lm_rows")}
+            if n in ("k_step_main", "k_select", "k_lstm_pointwise", "k_pred_proj", "k_lm_rows", "k_joint_big",
+                     "k_row_select")}
     dom = max(loop, key=lambda n: loop[n]["total_ms"])
     flops = kernel_flops(dom, c, B * K, B, T)
-    peak = PEAK_FP32_MFMA_TFLOPS  # every contraction runs on the fp32 matrix instructions
-    achieved = flops / (loop[dom]["avg_us"] * 1e-6) / 1e12 if flops else 0.0
-    roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
-                    frac=round(achieved / peak, 5), traffic=None, avg_us=loop[dom]["avg_us"],
-                    flops_per_launch=flops)
-    # the joint shares its launch with the recurrent product: utilisation of the launch as a whole
-    joint_util = kernel_flops("k_step_main", c, B * K, B, T) / (loop["k_step_main"]["avg_us"] * 1e-6) / 1e12 / peak
+    nbytes = kernel_bytes(dom, c, B * K)
+    if nbytes:
+        achieved = nbytes / (loop[dom]["avg_us"] * 1e-6) / 1e9
+        roofline = dict(kernel=dom, bound="hbm", achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=round(achieved / PEAK_HBM_GBS, 5), traffic=None, avg_us=loop[dom]["avg_us"],
+                        bytes_per_launch=nbytes)
+    else:
+        # the fused kernels contract on the fp32 matrix instructions, k_joint_big on the bf16 ones
+        peak = PEAK_BF16_MFMA_TFLOPS if dom == "k_joint_big" else PEAK_FP32_MFMA_TFLOPS
+        achieved = flops / (loop[dom]["avg_us"] * 1e-6) / 1e12 if flops else 0.0
+        roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
+                        frac=round(achieved / peak, 5), traffic=None, avg_us=loop[dom]["avg_us"],
+                        flops_per_launch=flops)
+    # utilisation of the matrix cores by the launch that holds the joint
+    if "k_joint_big" in loop:
+        joint_util = (kernel_flops("k_joint_big", c, B * K, B, T) / (loop["k_joint_big"]["avg_us"] * 1e-6) / 1e12
+                      / PEAK_BF16_MFMA_TFLOPS)
+    else:  # the joint shares its launch with the recurrent product
+        joint_util = (kernel_flops("k_step_main", c, B * K, B, T) / (loop["k_step_main"]["avg_us"] * 1e-6) / 1e12
+                      / PEAK_FP32_MFMA_TFLOPS)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -162,7 +187,7 @@ def main():
                    "graph": not args.no_graph, "audio_s_per_pass": audio_s},
         "beam_search_steps": n_steps, "us_per_beam_step": round(gpu_ms * 1e3 / max(n_steps, 1), 3),
         "gpu_ms_per_pass": round(gpu_ms, 4), "beam1_ms_per_pass": round(ms_beam1, 4),
-        "beam_over_greedy": round(ms / ms_beam1, 4), "main_kernel_mfma_util": round(joint_util, 5),
+        "beam_over_greedy": round(ms / ms_beam1, 4), "joint_launch_mfma_util": round(joint_util, 5),
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))

@@ -36,6 +36,12 @@ typedef enum { RNNT_ALSD = 0, RNNT_AES = 1 } rnnt_algo_t;
 typedef enum { RNNT_MODEL_RNNT = 0, RNNT_MODEL_TDT = 1 } rnnt_model_t;
 typedef enum { RNNT_PRED_LSTM = 0, RNNT_PRED_STATELESS = 1 } rnnt_pred_t;
 typedef enum { RNNT_F32 = 0, RNNT_BF16_JOINT = 1 } rnnt_prec_t;
+/* How a step computes the joint's output layer.  FUSED keeps the [B * beam, V + 1] logits on chip
+ * (per-chunk top-K in the contraction's epilogue); MATERIALIZED writes them to HBM from a bf16
+ * matrix-core contraction and selects row by row, which pays off for large (B * beam) x V.
+ * MATERIALIZED needs RNNT_BF16_JOINT, the stateless prediction network, V <= 8192 and H % 16 == 0;
+ * AUTO takes it for such decoders when B * beam >= 128 and V >= 2048. */
+typedef enum { RNNT_JOINT_AUTO = 0, RNNT_JOINT_FUSED = 1, RNNT_JOINT_MATERIALIZED = 2 } rnnt_joint_path_t;
 
 enum {
   RNNT_OK = 0,
@@ -65,6 +71,8 @@ typedef struct {
                                 the best one of its hypothesis is not expanded; INFINITY = off */
   int32_t use_graph;         /* 1: replay the per-step kernels as a captured HIP graph (Sec. 2.1,
                                 "CUDA Graphs"); 0: launch them one by one */
+  int32_t joint_path;        /* rnnt_joint_path_t; create fails if MATERIALIZED is asked for a decoder
+                                that cannot take it */
 } rnnt_config_t;
 
 /* Device pointers, float32, caller-owned.  Unused ones may be NULL. */

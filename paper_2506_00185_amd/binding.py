@@ -28,7 +28,7 @@ class _Config(C.Structure):
                 ("D", C.c_int32), ("H", C.c_int32), ("P", C.c_int32), ("E", C.c_int32), ("V", C.c_int32),
                 ("n_durations", C.c_int32), ("durations", C.c_int32 * 8), ("stateless_context", C.c_int32),
                 ("max_B", C.c_int32), ("max_T", C.c_int32), ("max_beam", C.c_int32), ("max_symbols", C.c_int32),
-                ("prune_margin", C.c_float), ("use_graph", C.c_int32)]
+                ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -121,7 +121,8 @@ class NGramLM:
 class BeamDecoder:
     """rnnt_beam_create / decode / results / destroy for one model."""
 
-    def __init__(self, c: dict, w: dict, max_B=None, max_T=None, max_beam=None, use_graph=True, device="cuda:0"):
+    def __init__(self, c: dict, w: dict, max_B=None, max_T=None, max_beam=None, use_graph=True, device="cuda:0",
+                 joint_path="auto"):
         lib = load_library()
         torch = _torch()
         self.device = torch.device(device)
@@ -142,6 +143,7 @@ class BeamDecoder:
         cfg.max_symbols = c["s"]
         cfg.prune_margin = c["gamma"] if math.isfinite(c["gamma"]) else float("inf")
         cfg.use_graph = 1 if use_graph else 0
+        cfg.joint_path = {"auto": 0, "fused": 1, "materialized": 2}[joint_path]
         self.cfg = cfg
         self._w = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
                    for k, v in w.items()}

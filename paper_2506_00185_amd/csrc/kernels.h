@@ -679,7 +679,8 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Sele
     if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s);
     else select_utterance<8, 0, 8>(a, b, s);
   } else {
-    select_utterance<4, 0, 16>(a, b, s);
+    if (a.n_chunks <= 4) select_utterance<4, 1, 16>(a, b, s);
+    else select_utterance<4, 0, 16>(a, b, s);
   }
 }
 

@@ -1,0 +1,373 @@
+// Kernels for large (hypotheses x vocabulary) products with a bf16 joint: the joint's output
+// layer as a bf16 matrix-core contraction that writes float32 logits, and a row-wise exact
+// top-K over them.  A step of this mode is
+//   k_joint_big -> k_row_select -> k_select -> k_stateless_pre_big
+// Keeping the per-row top-K in the contraction's epilogue, as the small-shape kernel does, costs
+// more vector instructions at K = 10 and V = 8192 than the trip of the logits through HBM.
+#pragma once
+#include "kernels.h"
+
+#ifndef RB_BIG_STORE
+#define RB_BIG_STORE 2
+#endif
+
+namespace rb {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// bf16 operand layout ("k8-major"): element (row, k) of an R-row matrix at ((k / 8) * R + row) * 8 + k % 8,
+// so that a lane's 8 consecutive k are one 16-byte load and 32 consecutive rows are 512 contiguous bytes.
+__host__ __device__ inline size_t k8_index(int k, int row, int rows) {
+  return ((size_t)(k >> 3) * rows + row) * 8 + (k & 7);
+}
+
+__device__ __forceinline__ uint16_t bf16_bits(float x) {  // round to nearest even
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// acc[i][j] += sum_{k<16} A[i][k] B[k][j] on the bf16 matrix cores.  Lane l supplies
+// A[i = l % 32][k = 8 * (l / 32) .. + 7] and B[k = 8 * (l / 32) .. + 7][j = l % 32] and receives
+// acc[i = 8 * (r / 4) + 4 * (l / 32) + r % 4][j = l % 32] in register r.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ floatx16 mfma32_bf16(u32x4 a, u32x4 b, floatx16 acc) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0,
+                                                 0);
+}
+
+struct BigJointArgs {
+  const uint16_t *Wb;  // bf16 k8-major [H][Npad] output layer (token rows; rows >= V are zero)
+  const uint16_t *Ab;  // bf16 k8-major [H][Mp]: ReLU(pre), rounded
+  const float *bias;   // [Npad]
+  float *Z;            // [M][Npad] logits of the token columns
+  int M, Mp, H, Npad;
+  XcdMap map;          // role 0: (block of 256 columns, block of 32 * MS rows)
+  const int *done;
+};
+
+// Z[m][n] = W_out[n] . a_m + b_out[n] for a block of 256 columns x 160 hypotheses.
+// 8 waves, two per SIMD: a wave issues in order and nothing of its own overlaps with its matrix
+// instructions (measured: 30 vector instructions beside 10 matrix ones cost their full 4 cycles each),
+// so the loads, LDS traffic and barriers of one wave run while the SIMD's other wave multiplies.
+// Wave w owns columns 32 w .. 32 w + 31 x all five hypothesis tiles (80 accumulator registers).  A stage
+// is two k-steps of 16: the wave's own output-layer rows come straight from global memory into a ring
+// of D register sets, requested D stages ahead (26 KB per stage and compute unit in flight); the
+// activation tile (160 x 32, 10 KB) is shared, so it goes registers -> LDS one stage ahead of its use,
+// in a ring of three slots with one barrier per stage.  The stage loop has no branches, so that the
+// compiler's count of outstanding loads stays exact.  Needs H % (32 * D) == 0 (the caller pads the
+// operands with zeros along k).
+// The hypotheses are the rows of the matrix-core product and the vocabulary its columns, so that a
+// lane ends up with four consecutive hypotheses of ONE column and 32 lanes store 128 contiguous bytes.
+template <int D>
+__global__ __launch_bounds__(512) void k_joint_big(BigJointArgs a) {
+  constexpr int MS = 5, NP = 2 * MS;  // pieces (k-step, hypothesis tile) of 1 KB per stage
+  __shared__ u32x4 tile[3][NP][64];
+  const int done = *reinterpret_cast<const volatile int *>(a.done);
+  RB_BLOCK_TS(0);
+  RB_STAMP(3, 0);
+  int nb, mb;
+  if (xcd_item(a.map, blockIdx.x, nb, mb) != 0) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
+  const int n0 = nb * 256 + wave * 32, m0 = mb * 32 * MS;
+  const char *wbase = reinterpret_cast<const char *>(a.Wb), *abase = reinterpret_cast<const char *>(a.Ab);
+  const size_t wks = (size_t)2 * a.Npad * 16, aks = (size_t)2 * a.Mp * 16;  // bytes per k-step (two k8 groups)
+  const uint32_t woff = (uint32_t)(((size_t)kg * a.Npad + n0 + col) * 16);
+  auto act_off = [&](int piece, int l) {  // the 16 bytes that lane l feeds to the matrix cores for a piece
+    int row = m0 + 32 * (piece % MS) + (l & 31);
+    row = row < a.Mp ? row : a.Mp - 1;
+    return (uint32_t)((piece / MS) * aks + ((size_t)(l >> 5) * a.Mp + row) * 16);
+  };
+  // pieces 0 .. 7: one per wave, 16 bytes per lane; pieces 8, 9: 4 bytes per thread of the block
+  const uint32_t aoff = act_off(wave, lane);
+  const uint32_t xoff = act_off(8 + (tid >> 8), (tid & 255) >> 2) + 4 * (tid & 3);
+  const int n_st = a.H / 32;
+  u32x4 wr[D][2], ar[D];
+  uint32_t xr[D];
+  auto request = [&](int set, int st) {
+    const char *wk = wbase + (size_t)st * 2 * wks, *ak = abase + (size_t)st * 2 * aks;
+    wr[set][0] = *reinterpret_cast<const u32x4 *>(wk + woff);
+    wr[set][1] = *reinterpret_cast<const u32x4 *>(wk + wks + woff);
+    ar[set] = *reinterpret_cast<const u32x4 *>(ak + aoff);
+    xr[set] = *reinterpret_cast<const uint32_t *>(ak + xoff);
+  };
+  auto stage = [&](int set, int slot) {  // activation tile of a stage: registers -> LDS
+    tile[slot][wave][lane] = ar[set];
+    reinterpret_cast<uint32_t *>(&tile[slot][8][0])[tid] = xr[set];
+  };
+  floatx16 acc[MS];
+  auto multiply = [&](int set, int slot) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int t = 0; t < MS; ++t) acc[t] = mfma32_bf16(tile[slot][kk * MS + t][lane], wr[set][kk], acc[t]);
+  };
+#pragma unroll
+  for (int j = 0; j < D; ++j) request(j, j);
+  const float bias = a.bias[n0 + col];
+  if (done) return;
+#pragma unroll
+  for (int t = 0; t < MS; ++t) acc[t] = floatx16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  // stage st: operands in register set st % D, activation tile in LDS slot st % 3.  The slot written in
+  // an iteration was last read two iterations (two barriers) earlier.
+  stage(0, 0);
+  __syncthreads();
+  RB_STAMP(3, 1);
+  int s0 = 0, s1 = 1, s2 = 2;  // slots of stages st, st + 1, st + 2
+  for (int st0 = 0; st0 < n_st - D; st0 += D) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+#ifndef RB_PROBE_NOSTAGE
+      stage((j + 1) % D, s1);
+#endif
+#ifndef RB_PROBE_NOMMA
+      multiply(j, s0);
+#endif
+#ifndef RB_PROBE_NOLOAD
+      request(j, st0 + j + D);
+#endif
+#ifndef RB_PROBE_NOBAR
+      __syncthreads();
+#endif
+      const int r = s0;
+      s0 = s1;
+      s1 = s2;
+      s2 = r;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < D; ++j) {  // last D stages: nothing left to request
+    if (j + 1 < D) stage(j + 1, s1);
+    multiply(j, s0);
+    if (j + 1 < D) __syncthreads();
+    const int r = s0;
+    s0 = s1;
+    s1 = s2;
+    s2 = r;
+  }
+  RB_STAMP(3, 2);
+  // epilogue: register r of tile t is hypothesis m0 + 32 t + 8 (r / 4) + 4 kg + r % 4, column n0 + col
+  float *zcol = a.Z + n0 + col;
+#pragma unroll
+  for (int t = 0; t < MS; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + 32 * t + 8 * (r >> 2) + 4 * kg + (r & 3);
+      if (m < a.M) zcol[(size_t)m * a.Npad] = acc[t][r] + bias;
+    }
+  RB_STAMP(3, 3);
+  RB_BLOCK_TS(1);
+}
+
+// Stateless prediction network for the large mode: a_m = bf16(ReLU(f_proj[b, t_m] + sum_i tab_i[token_i]))
+// written k8-major.  One thread per (hypothesis, group of 8 outputs).
+struct StatelessPreBigArgs {
+  const float *f_proj, *tab;
+  const int *ctx_tok, *t, *lengths;
+  uint16_t *Ab;
+  int M, Mp, K, T, H, V, n_ctx;
+  const int *done;
+  int *step_base;
+  int bump;
+};
+
+__global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a) {
+  if (*reinterpret_cast<const volatile int *>(a.done)) return;
+  const int gid = blockIdx.x * 256 + threadIdx.x;
+  if (a.bump && gid == 0) *a.step_base += a.bump;
+  const int H8 = a.H >> 3;
+  const int m = gid / H8, o8 = gid % H8;
+  if (m >= a.M) return;
+  const int b = m / a.K;
+  const int T_b = a.lengths[b];
+  int tt = a.t[m];
+  tt = tt < T_b ? tt : T_b - 1;
+  tt = tt < 0 ? 0 : tt;
+  const float *fp = a.f_proj + ((size_t)b * a.T + tt) * a.H + 8 * o8;
+  float v[8];
+  {
+    const float4 x = *reinterpret_cast<const float4 *>(fp), y = *reinterpret_cast<const float4 *>(fp + 4);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+  }
+  for (int i = 0; i < a.n_ctx; ++i) {
+    int tk = a.ctx_tok[m * kCtxMax + i];
+    tk = tk < 0 ? a.V : tk;
+    const float *gp = a.tab + ((size_t)i * (a.V + 1) + tk) * a.H + 8 * o8;
+    const float4 x = *reinterpret_cast<const float4 *>(gp), y = *reinterpret_cast<const float4 *>(gp + 4);
+    v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w; v[4] += y.x; v[5] += y.y; v[6] += y.z; v[7] += y.w;
+  }
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = (uint32_t)bf16_bits(fmaxf(v[2 * i], 0.f)) | ((uint32_t)bf16_bits(fmaxf(v[2 * i + 1], 0.f)) << 16);
+  *reinterpret_cast<uint4 *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// wave-wide max of packed candidates, in every lane
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+  v = group_max_u64<16>(v);
+  uint64_t best = 0;
+#pragma unroll
+  for (int r = 0; r < 64; r += 16) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, r);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), r);
+    const uint64_t w = ((uint64_t)hi << 32) | lo;
+    best = w > best ? w : best;
+  }
+  return best;
+}
+
+struct RowSelectArgs {
+  const float *Z;        // [M][Npad]
+  int Npad;
+  const uint16_t *Ab;    // bf16 k8-major [H][Mp]
+  int M, Mp, H, K, V, ND;
+  const float *Wspec;    // [1 + ND][H] rows V .. V + ND of the output layer (bf16-rounded values)
+  const float *bias_spec;
+  const float *lm;       // [M][V] or NULL
+  float lambda;
+  float *p_max, *p_sum;  // [M] (one list per row)
+  uint64_t *p_cand;      // [M][K]
+  float *zs;             // [M][1 + ND]
+  const int *finished;   // [B]
+  const int *done;
+};
+
+constexpr int kRowRegs = 32;      // float4 registers per lane: V <= 64 * 4 * kRowRegs = 8192
+constexpr int kSurvivorCap = 256;
+
+// One wave per hypothesis: exact K best of the row's keys (as a one-chunk candidate list for the
+// selection kernel), soft-max statistics, blank / duration logits.  Columns V .. Npad - 1 of Z hold
+// -inf (their bias is -inf), so the row needs no tail masks.
+// The K best are found without sorting the row: the K-th largest of the 64 lane maxima is a lower
+// bound of the K-th largest key, so only keys at or above it (a few dozen) are collected in LDS, and
+// each of those finds its rank by counting the ones ahead of it.
+__global__ __launch_bounds__(256) void k_row_select(RowSelectArgs a) {
+  __shared__ uint64_t surv[4][kSurvivorCap];
+  __shared__ int surv_n[4];
+  const int K = a.K, V = a.V;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (*reinterpret_cast<const volatile int *>(a.done)) return;
+  const int m = blockIdx.x * 4 + wave;
+  if (m >= a.M) return;
+  if (a.finished[m / K]) return;
+  const float *zrow = a.Z + (size_t)m * a.Npad;
+  const float *lmrow = a.lm ? a.lm + (size_t)m * V : nullptr;
+  floatx4 z[kRowRegs];
+#pragma unroll
+  for (int q = 0; q < kRowRegs; ++q) {
+    z[q] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (256 * q < a.Npad) z[q] = *reinterpret_cast<const floatx4 *>(zrow + 4 * (lane + 64 * q));
+  }
+  if (lane == 0) surv_n[wave] = 0;
+  // soft-max statistics of the logits
+  float km = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < kRowRegs; ++q) km = fmaxf(km, fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3])));
+  const float mx = wave_max(km);
+  float sum = 0.f;
+  {
+    const float kLog2e = 1.4426950408889634f, off = -mx * kLog2e;
+#pragma unroll
+    for (int q = 0; q < kRowRegs; ++q)
+      sum += (exp2f(fmaf(z[q][0], kLog2e, off)) + exp2f(fmaf(z[q][1], kLog2e, off))) +
+             (exp2f(fmaf(z[q][2], kLog2e, off)) + exp2f(fmaf(z[q][3], kLog2e, off)));
+  }
+  sum = wave_sum(sum);
+  // keys = logit + lambda * LM score
+  if (lmrow) {
+    km = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < kRowRegs; ++q) {
+      const int n = 4 * (lane + 64 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < V) z[q][e] += a.lambda * lmrow[n + e];
+      km = fmaxf(km, fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3])));
+    }
+  }
+  // tau = a lower bound of the K-th largest key: K rounds of "largest remaining lane maximum"
+  float tau = -INFINITY, cur = km;
+  for (int j = 0; j < K; ++j) {
+    tau = wave_max(cur);
+    if (cur == tau) cur = -INFINITY;
+  }
+  wave_sync();
+  // keys at or above tau (never -inf) are appended to the wave's list
+#pragma unroll
+  for (int q = 0; q < kRowRegs; ++q) {
+    const float m4 = fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3]));
+    if (m4 >= tau && m4 > -INFINITY) {
+      const int n = 4 * (lane + 64 * q);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (z[q][e] >= tau && z[q][e] > -INFINITY) {
+          const int pos = atomicAdd(&surv_n[wave], 1);
+          if (pos < kSurvivorCap) surv[wave][pos] = pack_cand(z[q][e], n + e);
+        }
+    }
+  }
+  wave_sync();
+  const int total = surv_n[wave];
+  uint64_t *out = a.p_cand + (size_t)m * K;
+  if (total <= kSurvivorCap) {
+    // rank of every collected key = number of collected keys ahead of it (packed keys are distinct)
+    if (lane < K && lane >= total) out[lane] = no_cand();
+    for (int i = lane; i < total; i += 64) {
+      const uint64_t mine = surv[wave][i];
+      int rank = 0;
+      for (int j = 0; j < total; ++j) rank += surv[wave][j] > mine;
+      if (rank < K) out[rank] = mine;
+    }
+  } else {
+    // more than kSurvivorCap keys at or above tau (many equal keys): K plain rounds over the row in memory
+    uint64_t last = ~0ull;
+    for (int j = 0; j < K; ++j) {
+      uint64_t best = no_cand();
+      for (int n = lane; n < V; n += 64) {
+        float key = zrow[n];
+        if (lmrow) key += a.lambda * lmrow[n];
+        const uint64_t c = key > -INFINITY ? pack_cand(key, n) : no_cand();
+        if (c < last && c > best) best = c;
+      }
+      best = wave_max_u64(best);
+      if (lane == 0) out[j] = best;
+      last = best > no_cand() ? best : no_cand() + 1;
+    }
+  }
+  if (lane == 0) {
+    a.p_max[m] = mx;
+    a.p_sum[m] = sum;
+  }
+  // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; a lane takes 8 consecutive k
+  const int nz = 1 + a.ND;
+  float acc[9];
+#pragma unroll
+  for (int d = 0; d < 9; ++d) acc[d] = 0.f;
+  for (int g = lane; g < (a.H >> 3); g += 64) {
+    const uint4 u = *reinterpret_cast<const uint4 *>(a.Ab + ((size_t)g * a.Mp + m) * 8);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(w[i] << 16);
+      x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int d = 0; d < 9; ++d)
+      if (d < nz) {
+        const float4 p = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g);
+        const float4 q = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g + 4);
+        acc[d] += (x[0] * p.x + x[1] * p.y) + (x[2] * p.z + x[3] * p.w) + (x[4] * q.x + x[5] * q.y) +
+                  (x[6] * q.z + x[7] * q.w);
+      }
+  }
+#pragma unroll
+  for (int d = 0; d < 9; ++d)
+    if (d < nz) {
+      const float v = wave_sum(acc[d]);
+      if (lane == 0) a.zs[(size_t)m * nz + d] = v + a.bias_spec[d];
+    }
+}
+
+}  // namespace rb

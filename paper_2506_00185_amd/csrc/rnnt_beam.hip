@@ -14,6 +14,7 @@
 #include <vector>
 
 #include "kernels.h"
+#include "kernels_big.h"
 #include "lm.h"
 
 using namespace rb;
@@ -38,9 +39,12 @@ struct KernelTimer {
   int calls;
 };
 
-enum { KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_COUNT };
-const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init",           "k_step_main", "k_select",
-                                      "k_lm_rows",           "k_lstm_pointwise", "k_pred_proj", "k_backtrace"};
+enum {
+  KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_JOINTBIG, KT_ROWSELECT,
+  KT_COUNT
+};
+const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init",      "k_step_main", "k_select",    "k_lm_rows",
+                                      "k_lstm_pointwise",    "k_pred_proj", "k_backtrace", "k_joint_big", "k_row_select"};
 
 }  // namespace
 
@@ -56,6 +60,11 @@ struct rnnt_beam {
   float *f_proj = nullptr, *pre = nullptr, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
   float *lm_rows = nullptr, *Rgates = nullptr;
   int *tile_ctr = nullptr;
+  // materialised-logits path (bf16 joint, large shapes)
+  bool big = false;
+  int Npad_big = 0, Hb = 0;  // padded extents of the bf16 operands: 256 columns, 64 k
+  uint16_t *Wb = nullptr, *Ab = nullptr;
+  float *Zbig = nullptr, *Wspec = nullptr, *bias_spec = nullptr, *b_big = nullptr;
   double *score = nullptr;
   int *t = nullptr, *sym = nullptr, *len = nullptr, *last = nullptr, *ctx = nullptr, *lengths = nullptr;
   uint32_t *hash = nullptr;
@@ -184,6 +193,29 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
   out.assign((size_t)h->n_chunks * 32, 0.f);
   for (int i = 0; i < N; ++i) out[i] = tmp[i];
   if ((rc = upload(h, &h->b_out, out))) return rc;
+  if (h->big) {
+    // token rows as bf16, k8-major, padded to whole blocks of 256 columns; blank / duration rows apart
+    std::vector<float> wout;
+    if ((rc = download(h, wout, w->W_out, (size_t)N * H))) return rc;
+    const int Np = h->Npad_big;
+    std::vector<uint16_t> wb((size_t)h->Hb * Np, 0);  // k beyond H stays zero
+    for (int r = 0; r < V; ++r)
+      for (int k = 0; k < H; ++k) {
+        const float x = host_bf16_round(wout[(size_t)r * H + k]);
+        uint32_t u;
+        memcpy(&u, &x, 4);
+        wb[k8_index(k, r, Np)] = (uint16_t)(u >> 16);
+      }
+    if ((rc = upload(h, &h->Wb, wb))) return rc;
+    std::vector<float> spec((size_t)(N - V) * H), bs(N - V), bb((size_t)Np, -INFINITY);  // padded columns: logit -inf
+    for (int r = V; r < N; ++r)
+      for (int k = 0; k < H; ++k) spec[(size_t)(r - V) * H + k] = host_bf16_round(wout[(size_t)r * H + k]);
+    for (int r = V; r < N; ++r) bs[r - V] = tmp[r];
+    for (int r = 0; r < V; ++r) bb[r] = tmp[r];
+    if ((rc = upload(h, &h->Wspec, spec))) return rc;
+    if ((rc = upload(h, &h->bias_spec, bs))) return rc;
+    if ((rc = upload(h, &h->b_big, bb))) return rc;
+  }
 
   if (c.pred == RNNT_PRED_LSTM) {
     // gate rows re-ordered so that rows 4u..4u+3 of a 32-row tile hold gates (i, f, g, o) of unit 8*tile + u
@@ -236,6 +268,7 @@ struct StepPlan {
   float lambda;
   const float *inj_tok, *inj_dur;
   int C;
+  bool big = false;  // logits through HBM (k_joint_big + k_row_select) instead of the fused main kernel
 };
 
 // Timing wrapper used in profiling mode: an event before and after the launch, nothing waits.
@@ -297,6 +330,15 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       else RB_PRED(4, 0);
 #undef RB_PRED
     }
+  } else if (p.big) {
+    StatelessPreBigArgs a;
+    a.f_proj = h->f_proj; a.tab = h->tab; a.ctx_tok = h->ctx; a.t = h->t; a.lengths = h->lengths;
+    a.Ab = h->Ab;
+    a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
+    a.done = done; a.step_base = step_base; a.bump = bump;
+    ScopedKernelTime tm(h, s, KT_PREDPROJ);
+    const int n = p.M * (c.H / 8);
+    hipLaunchKernelGGL(k_stateless_pre_big, dim3((n + 255) / 256), dim3(256), 0, s, a);
   } else {
     StatelessPreArgs a;
     a.f_proj = h->f_proj; a.tab = h->tab; a.ctx_tok = h->ctx; a.t = h->t; a.lengths = h->lengths;
@@ -372,6 +414,41 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     fill_select_args(h, p, step_off, 64, sa);
     ScopedKernelTime tm(h, s, KT_SELECT);
     hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+  } else if (p.big) {
+    constexpr int MS = 5;  // 160 hypotheses per block
+    {
+      BigJointArgs a;
+      a.Wb = h->Wb; a.Ab = h->Ab; a.bias = h->b_big; a.Z = h->Zbig;
+      a.M = p.M; a.Mp = h->Mp; a.H = h->Hb; a.Npad = h->Npad_big;
+      a.map.a_tiles = h->Npad_big / 256; a.map.a_m = (p.M + 32 * MS - 1) / (32 * MS);
+      a.map.b_begin = a.map.b_end = 0; a.map.b_m = 0;
+      a.done = done;
+      ScopedKernelTime tm(h, s, KT_JOINTBIG);
+      const dim3 grid(xcd_grid(a.map));
+      // the kernel's loop runs in whole groups of D stages of k = 32; the operands are padded to k % 64 == 0
+      if (h->Hb % 128 == 0) hipLaunchKernelGGL((k_joint_big<4>), grid, dim3(512), 0, s, a);
+      else hipLaunchKernelGGL((k_joint_big<2>), grid, dim3(512), 0, s, a);
+    }
+    RB_HIP(h, hipGetLastError());
+    {
+      RowSelectArgs a;
+      a.Z = h->Zbig; a.Npad = h->Npad_big; a.Ab = h->Ab; a.M = p.M; a.Mp = h->Mp; a.H = c.H;
+      a.K = p.K; a.V = c.V; a.ND = c.n_durations;
+      a.Wspec = h->Wspec; a.bias_spec = h->bias_spec;
+      a.lm = p.lm ? h->lm_rows : nullptr;
+      a.lambda = p.lambda;
+      a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
+      a.finished = h->finished; a.done = done;
+      ScopedKernelTime tm(h, s, KT_ROWSELECT);
+      hipLaunchKernelGGL(k_row_select, dim3((p.M + 3) / 4), dim3(256), 0, s, a);
+    }
+    RB_HIP(h, hipGetLastError());
+    {
+      SelectArgs sa;
+      fill_select_args(h, p, step_off, 1, sa);
+      ScopedKernelTime tm(h, s, KT_SELECT);
+      hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+    }
   } else {
     MainArgs a;
     a.pre = h->pre;
@@ -601,6 +678,17 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   h->pc_chunks = h->n_chunks > 64 ? h->n_chunks : 64;
   h->M_max = c.max_B * c.max_beam;
   h->Mp = (h->M_max + 31) / 32 * 32 + 32;  // a joint tile may start at any multiple of K and reads 32 rows
+  {
+    const bool can = c.prec == RNNT_BF16_JOINT && c.pred == RNNT_PRED_STATELESS && c.V <= 64 * 4 * kRowRegs &&
+                     c.H % 16 == 0;
+    if (c.joint_path == RNNT_JOINT_MATERIALIZED && !can)
+      return bad("joint_path MATERIALIZED needs the bf16 joint, a stateless prediction network, V <= 8192, H % 16 == 0");
+    if (c.joint_path < RNNT_JOINT_AUTO || c.joint_path > RNNT_JOINT_MATERIALIZED) return bad("unknown joint_path");
+    h->big = can && (c.joint_path == RNNT_JOINT_MATERIALIZED ||
+                     (c.joint_path == RNNT_JOINT_AUTO && c.V >= 2048 && c.max_B * c.max_beam >= 128));
+    h->Npad_big = (c.V + 255) / 256 * 256;
+    h->Hb = (c.H + 63) / 64 * 64;
+  }
   h->S_max = c.max_T * (c.max_symbols + 1);
   h->cap = c.max_T * c.max_symbols + 1;
   const size_t M = h->M_max;
@@ -614,6 +702,11 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   for (int i = 0; i < 2; ++i) {
     A(dev_alloc(h, &h->h[i], (size_t)h->Mp * c.P));
     A(dev_alloc(h, &h->c[i], (size_t)h->Mp * c.P));
+  }
+  if (h->big) {
+    A(dev_alloc(h, &h->Ab, (size_t)h->Mp * h->Hb));
+    if (!rc && hipMemset(h->Ab, 0, (size_t)h->Mp * h->Hb * sizeof(uint16_t)) != hipSuccess) rc = RNNT_E_HIP;  // k >= H stays zero
+    A(dev_alloc(h, &h->Zbig, M * h->Npad_big));
   }
   A(dev_alloc(h, &h->lm_rows, M * c.V));
   A(dev_alloc(h, &h->Rgates, M * 4 * c.P));
@@ -674,6 +767,7 @@ int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, i
   if (lm && algo == RNNT_AES && std::isfinite(h->cfg.prune_margin))
     return fail(h, RNNT_E_ARG, "an LM together with a finite prune margin is not supported");
   StepPlan p{B, beam, T, algo, B * beam, lm, lm ? lm_weight : 0.f, nullptr, nullptr, 1};
+  p.big = h->big && (h->cfg.joint_path == RNNT_JOINT_MATERIALIZED || B * beam >= 128);
   return run_decode(h, enc, lengths, p, static_cast<hipStream_t>(hip_stream));
 }
 

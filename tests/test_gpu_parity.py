@@ -250,6 +250,43 @@ def test_lm_fusion(amd, oracle):
     assert not np.array_equal(g["scores"], g1["scores"])
 
 
+# ------------------------------------------- logits through HBM (bf16 matrix-core joint)
+
+@pytest.mark.parametrize("name,kw,lm_w", [
+    ("rnnt_aes_k10", dict(model="rnnt", algo="aes", beam=10, V=2501, B=5), 0.0),
+    ("rnnt_alsd_k4", dict(model="rnnt", algo="alsd", beam=4, V=1030, B=9), 0.0),
+    ("tdt_alsd_k6", dict(model="tdt", algo="alsd", beam=6, V=777, B=3, durations=(0, 1, 2, 3, 4)), 0.0),
+    ("rnnt_alsd_k16_lm", dict(model="rnnt", algo="alsd", beam=16, V=300, B=2), 0.3),
+])
+def test_materialized_logits_path(amd, oracle, name, kw, lm_w):
+    """Same bars as the bf16 variant of the fused path; shapes that leave ragged tails in every
+    tile of the contraction (V % 256, V % 4, rows % 160) and in the row scan."""
+    c = S.custom_config(T=14, T_min=5, D=64, H=160, P=96, E=96, s=2, pred="stateless", ctx=2, prec="bf16",
+                        blank_bias=3.0, **kw)
+    w, L, enc = _case(c, 900 + kw["beam"])
+    glm = olm = None
+    if lm_w:
+        lm = S.make_lm(V=c["V"], order=3, n_target=20000, zipf_s=1.1, seed=5)
+        glm, olm = amd.NGramLM(lm), oracle.LM(lm)
+    dec = amd.BeamDecoder(c, w, joint_path="materialized")
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=lm_w)
+    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=lm_w, log=True)
+    full, exempt = compare(g, o, TOL_BF16, TIE_BF16)
+    assert full + exempt == c["B"] and full >= 1
+    # and against the fused path of this library, to the same bar
+    dec_f = amd.BeamDecoder(c, w, joint_path="fused")
+    gf = gpu_decode(dec_f, enc, L, lm=glm, lm_weight=lm_w)
+    same = sum(int(np.array_equal(g["tokens"][b, 0], gf["tokens"][b, 0])) for b in range(c["B"]))
+    assert same >= c["B"] - exempt - 1
+
+
+def test_materialized_path_is_refused_where_it_cannot_run(amd):
+    c = S.custom_config(B=2, T=8, T_min=4, D=64, H=64, P=64, E=64, V=50, beam=2, s=2, algo="alsd")
+    w, L, enc = _case(c, 950)
+    with pytest.raises(RuntimeError, match="MATERIALIZED"):
+        amd.BeamDecoder(c, w, joint_path="materialized")
+
+
 # ------------------------------------------------------------- behaviour of the ABI
 
 def test_graph_replay_equals_plain_launches_and_repeats(amd):
