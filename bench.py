@@ -153,6 +153,13 @@ def main():
         roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=peak, unit="TFLOP/s",
                         frac=round(achieved / peak, 5), traffic=None, avg_us=loop[dom]["avg_us"],
                         flops_per_launch=flops)
+    # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summaries
+    tpath = os.path.join(ROOT, "profiles", "%s_%s_traffic.json" % (c["name"], dom))
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            tj = json.load(f)
+        roofline["traffic"] = round(tj["fetch_bytes"] + tj["write_bytes"])
+        roofline["traffic_source"] = os.path.relpath(tpath, ROOT)
     # utilisation of the matrix cores by the launch that holds the joint
     if "k_joint_big" in loop:
         joint_util = (kernel_flops("k_joint_big", c, B * K, B, T) / (loop["k_joint_big"]["avg_us"] * 1e-6) / 1e12

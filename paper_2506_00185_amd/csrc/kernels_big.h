@@ -7,10 +7,6 @@
 #pragma once
 #include "kernels.h"
 
-#ifndef RB_BIG_STORE
-#define RB_BIG_STORE 2
-#endif
-
 namespace rb {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -46,22 +42,27 @@ struct BigJointArgs {
   const int *done;
 };
 
-// Z[m][n] = W_out[n] . a_m + b_out[n] for a block of 256 columns x 160 hypotheses.
-// 8 waves, two per SIMD: a wave issues in order and nothing of its own overlaps with its matrix
-// instructions (measured: 30 vector instructions beside 10 matrix ones cost their full 4 cycles each),
-// so the loads, LDS traffic and barriers of one wave run while the SIMD's other wave multiplies.
-// Wave w owns columns 32 w .. 32 w + 31 x all five hypothesis tiles (80 accumulator registers).  A stage
-// is two k-steps of 16: the wave's own output-layer rows come straight from global memory into a ring
-// of D register sets, requested D stages ahead (26 KB per stage and compute unit in flight); the
-// activation tile (160 x 32, 10 KB) is shared, so it goes registers -> LDS one stage ahead of its use,
-// in a ring of three slots with one barrier per stage.  The stage loop has no branches, so that the
-// compiler's count of outstanding loads stays exact.  Needs H % (32 * D) == 0 (the caller pads the
-// operands with zeros along k).
+// Z[m][n] = W_out[n] . a_m + b_out[n] for a block of 32 * WAVES columns x 160 hypotheses.
+// Two waves per SIMD (one block of 8 waves or two of 4): a wave issues in order and nothing of its own
+// overlaps with its matrix instructions (measured: 30 vector instructions beside 10 matrix ones cost
+// their full 4 cycles each), so the loads, LDS traffic and barriers of one wave have to run while the
+// SIMD's other wave multiplies.
+// Wave w owns 32 columns x all five hypothesis tiles (80 accumulator registers).  A stage is two k-steps
+// of 16: the wave's own output-layer rows come straight from global memory into a ring of D register
+// sets, requested D stages ahead; the activation tile (160 x 32, 10 KB) is shared, so it goes
+// registers -> LDS one stage ahead of its use, in a ring of three slots with one barrier per stage.
+// The stage loop has no branches, so that the compiler's count of outstanding loads stays exact.
+// Needs H % (32 * D) == 0 (the caller pads the operands with zeros along k).
 // The hypotheses are the rows of the matrix-core product and the vocabulary its columns, so that a
-// lane ends up with four consecutive hypotheses of ONE column and 32 lanes store 128 contiguous bytes.
-template <int D>
-__global__ __launch_bounds__(512) void k_joint_big(BigJointArgs a) {
+// lane ends up with four consecutive hypotheses of ONE column and 32 lanes store 128 contiguous bytes
+// (16-byte stores of four columns scattered over 32 rows took twice as long, non-temporal ones four times).
+template <int WAVES, int D>
+__global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArgs a) {
   constexpr int MS = 5, NP = 2 * MS;  // pieces (k-step, hypothesis tile) of 1 KB per stage
+  constexpr int PW = NP / WAVES;      // pieces a wave loads whole, 16 bytes per lane (pieces wave, wave + WAVES, ..)
+  constexpr int FP = PW * WAVES;      // the other NP - FP pieces are loaded 4 bytes per thread
+  constexpr int XD = (NP - FP) * 256 / (64 * WAVES);
+  static_assert(WAVES == 4 || WAVES == 8, "two waves per SIMD: one block of 8 or two blocks of 4");
   __shared__ u32x4 tile[3][NP][64];
   const int done = *reinterpret_cast<const volatile int *>(a.done);
   RB_BLOCK_TS(0);
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(512) void k_joint_big(BigJointArgs a) {
   int nb, mb;
   if (xcd_item(a.map, blockIdx.x, nb, mb) != 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
-  const int n0 = nb * 256 + wave * 32, m0 = mb * 32 * MS;
+  const int n0 = (nb * WAVES + wave) * 32, m0 = mb * 32 * MS;
   const char *wbase = reinterpret_cast<const char *>(a.Wb), *abase = reinterpret_cast<const char *>(a.Ab);
   const size_t wks = (size_t)2 * a.Npad * 16, aks = (size_t)2 * a.Mp * 16;  // bytes per k-step (two k8 groups)
   const uint32_t woff = (uint32_t)(((size_t)kg * a.Npad + n0 + col) * 16);
@@ -78,29 +79,41 @@ __global__ __launch_bounds__(512) void k_joint_big(BigJointArgs a) {
     row = row < a.Mp ? row : a.Mp - 1;
     return (uint32_t)((piece / MS) * aks + ((size_t)(l >> 5) * a.Mp + row) * 16);
   };
-  // pieces 0 .. 7: one per wave, 16 bytes per lane; pieces 8, 9: 4 bytes per thread of the block
-  const uint32_t aoff = act_off(wave, lane);
-  const uint32_t xoff = act_off(8 + (tid >> 8), (tid & 255) >> 2) + 4 * (tid & 3);
+  uint32_t aoff[PW], xoff[XD];
+#pragma unroll
+  for (int i = 0; i < PW; ++i) aoff[i] = act_off(wave + WAVES * i, lane);
+#pragma unroll
+  for (int d = 0; d < XD; ++d) {
+    const int g = tid + 64 * WAVES * d;  // dword g of the pieces FP .. NP - 1
+    xoff[d] = act_off(FP + (g >> 8), (g & 255) >> 2) + 4 * (g & 3);
+  }
   const int n_st = a.H / 32;
-  u32x4 wr[D][2], ar[D];
-  uint32_t xr[D];
+  u32x4 wr[D][2], ar[D][PW];
+  uint32_t xr[D][XD];
   auto request = [&](int set, int st) {
     const char *wk = wbase + (size_t)st * 2 * wks, *ak = abase + (size_t)st * 2 * aks;
     wr[set][0] = *reinterpret_cast<const u32x4 *>(wk + woff);
     wr[set][1] = *reinterpret_cast<const u32x4 *>(wk + wks + woff);
-    ar[set] = *reinterpret_cast<const u32x4 *>(ak + aoff);
-    xr[set] = *reinterpret_cast<const uint32_t *>(ak + xoff);
+#pragma unroll
+    for (int i = 0; i < PW; ++i) ar[set][i] = *reinterpret_cast<const u32x4 *>(ak + aoff[i]);
+#pragma unroll
+    for (int d = 0; d < XD; ++d) xr[set][d] = *reinterpret_cast<const uint32_t *>(ak + xoff[d]);
   };
   auto stage = [&](int set, int slot) {  // activation tile of a stage: registers -> LDS
-    tile[slot][wave][lane] = ar[set];
-    reinterpret_cast<uint32_t *>(&tile[slot][8][0])[tid] = xr[set];
+#pragma unroll
+    for (int i = 0; i < PW; ++i) tile[slot][wave + WAVES * i][lane] = ar[set][i];
+#pragma unroll
+    for (int d = 0; d < XD; ++d) reinterpret_cast<uint32_t *>(&tile[slot][FP][0])[tid + 64 * WAVES * d] = xr[set][d];
   };
   floatx16 acc[MS];
   auto multiply = [&](int set, int slot) {
+    u32x4 bf[NP];
+#pragma unroll
+    for (int p = 0; p < NP; ++p) bf[p] = tile[slot][p][lane];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-      for (int t = 0; t < MS; ++t) acc[t] = mfma32_bf16(tile[slot][kk * MS + t][lane], wr[set][kk], acc[t]);
+      for (int t = 0; t < MS; ++t) acc[t] = mfma32_bf16(bf[kk * MS + t], wr[set][kk], acc[t]);
   };
 #pragma unroll
   for (int j = 0; j < D; ++j) request(j, j);
@@ -117,18 +130,10 @@ __global__ __launch_bounds__(512) void k_joint_big(BigJointArgs a) {
   for (int st0 = 0; st0 < n_st - D; st0 += D) {
 #pragma unroll
     for (int j = 0; j < D; ++j) {
-#ifndef RB_PROBE_NOSTAGE
       stage((j + 1) % D, s1);
-#endif
-#ifndef RB_PROBE_NOMMA
       multiply(j, s0);
-#endif
-#ifndef RB_PROBE_NOLOAD
       request(j, st0 + j + D);
-#endif
-#ifndef RB_PROBE_NOBAR
       __syncthreads();
-#endif
       const int r = s0;
       s0 = s1;
       s1 = s2;

@@ -420,14 +420,15 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       BigJointArgs a;
       a.Wb = h->Wb; a.Ab = h->Ab; a.bias = h->b_big; a.Z = h->Zbig;
       a.M = p.M; a.Mp = h->Mp; a.H = h->Hb; a.Npad = h->Npad_big;
-      a.map.a_tiles = h->Npad_big / 256; a.map.a_m = (p.M + 32 * MS - 1) / (32 * MS);
+      constexpr int WV = 4;  // waves per block; the block covers 32 * WV columns
+      a.map.a_tiles = h->Npad_big / (32 * WV); a.map.a_m = (p.M + 32 * MS - 1) / (32 * MS);
       a.map.b_begin = a.map.b_end = 0; a.map.b_m = 0;
       a.done = done;
       ScopedKernelTime tm(h, s, KT_JOINTBIG);
       const dim3 grid(xcd_grid(a.map));
       // the kernel's loop runs in whole groups of D stages of k = 32; the operands are padded to k % 64 == 0
-      if (h->Hb % 128 == 0) hipLaunchKernelGGL((k_joint_big<4>), grid, dim3(512), 0, s, a);
-      else hipLaunchKernelGGL((k_joint_big<2>), grid, dim3(512), 0, s, a);
+      if (h->Hb % 128 == 0) hipLaunchKernelGGL((k_joint_big<WV, 4>), grid, dim3(64 * WV), 0, s, a);
+      else hipLaunchKernelGGL((k_joint_big<WV, 2>), grid, dim3(64 * WV), 0, s, a);
     }
     RB_HIP(h, hipGetLastError());
     {
