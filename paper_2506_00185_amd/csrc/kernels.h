@@ -305,7 +305,9 @@ __device__ __forceinline__ uint32_t mod_mersenne31(uint64_t x) {
 // NCH > 0: a lane keeps the lists of NCH chunks in registers (n_chunks <= LPR * NCH, K <= KMAX) and
 // the K best of the hypothesis come out of a K-way merge of list heads; NCH == 0: the lists are
 // scanned in memory at every round instead (any size).
-template <int LPR, int NCH, int KMAX>
+// MULTI: the beam may be wider than the 64 / LPR hypotheses handled at once; the per-hypothesis part then
+// runs in several passes.
+template <int LPR, int NCH, int KMAX, bool MULTI = false>
 __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
@@ -314,14 +316,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   const int fin = a.finished[b];
   const int S = *a.step_base + a.step_off;
   const int T_b = a.lengths[b];
-  const int rk = lane / LPR, e = lane % LPR;  // hypothesis and position inside its lane group
-  const bool row_ok = rk < K;
-  const int krow = row_ok ? rk : 0;
-  const int ncand = a.n_chunks * K;
-  const uint64_t *cands = a.p_cand + (size_t)(m_base + krow) * ncand;
-  const float *pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
-  const float *psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
-  const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
   double my_score = -INFINITY;
   int my_t = 0, my_sym = 0, my_len = 0, my_last = -1;
   uint32_t my_hash = 0;
@@ -334,183 +328,217 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
     my_last = a.last[m];
     my_hash = a.hash[m];
   }
+  // LPR lanes per hypothesis, 64 / LPR hypotheses at once; a beam wider than that takes several passes
+  // over the per-hypothesis part (lists -> K best tokens -> candidate scores in LDS)
+  constexpr int kRowsPerPass = 64 / LPR;
+  const int e = lane % LPR;  // position inside the lane group
+  const int ncand = a.n_chunks * K;
+  int rk = 0;                // hypothesis of this lane in the current pass
+  bool row_ok = false;
+  const uint64_t *cands = nullptr;
+  const float *pmax = nullptr, *psum = nullptr;
   uint64_t list[NCH > 0 ? NCH : 1][KMAX];
   float pm[NCH > 0 ? NCH : 1], ps[NCH > 0 ? NCH : 1];
-  if constexpr (NCH > 0) {
-#pragma unroll
-    for (int q = 0; q < NCH; ++q) {
-      const int ch = e + LPR * q;
-      const bool ok = row_ok && ch < a.n_chunks;
-#pragma unroll
-      for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
-      pm[q] = (ok && !a.normalized) ? load_agent(pmax + ch) : -INFINITY;
-      ps[q] = (ok && !a.normalized) ? load_agent(psum + ch) : 0.f;
-    }
-  }
-  const float zb = load_agent(zsr);
+  float zb = 0.f;
   float dl[8];
-  for (int d = 0; d < a.ND; ++d) dl[d] = load_agent(zsr + 1 + d);
-  if (a.use_ctx)
-    for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
-  if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
-    if (lane < K) {
-      a.src_row[m_base + lane] = m_base + lane;
-      a.tok[m_base + lane] = -1;
-    }
-    return;
-  }
-  if (lane < K) {
-    s.score[lane] = my_score;
-    s.t[lane] = my_t;
-    s.sym[lane] = my_sym;
-    s.len[lane] = my_len;
-    s.last[lane] = my_last;
-    s.hash[lane] = my_hash;
-    s.sel_val[lane] = -INFINITY;
-    s.sel_flat[lane] = -1;
-  }
-  // frame of the earliest unfinished hypothesis (lanes >= K hold neutral values)
-  const bool my_live = my_score > -INFINITY;
-  int t_cur = group_min_i<16>((my_live && my_t < T_b) ? my_t : T_b);
-  t_cur = __builtin_amdgcn_readlane(t_cur, 0);
-  if (lane < K) s.kind[lane] = my_live ? ((my_t < T_b && (a.algo == 0 || my_t == t_cur)) ? 2 : 1) : 0;
-
-  // ---- K rounds of "best remaining candidate" in every lane group at once.
-  // Lane e keeps the winners of rounds e, e + LPR, ... (at most KMAX / LPR + 1 of them).
-  constexpr int kMine = (KMAX + LPR - 1) / LPR;
-  uint64_t mine[kMine];
-#pragma unroll
-  for (int i = 0; i < kMine; ++i) mine[i] = no_cand();
-  if constexpr (NCH > 0) {
-#pragma unroll
-    for (int j = 0; j < KMAX; ++j) {
-      if (j < K) {
-        uint64_t best = list[0][0];
-#pragma unroll
-        for (int q = 1; q < NCH; ++q) best = list[q][0] > best ? list[q][0] : best;
-        best = group_max_u64<LPR>(best);
-#pragma unroll
-        for (int q = 0; q < NCH; ++q)
-          if (list[q][0] == best) {  // the winner's list moves up (real candidates are unique)
-#pragma unroll
-            for (int x = 0; x + 1 < KMAX; ++x) list[q][x] = list[q][x + 1];
-            list[q][KMAX - 1] = no_cand();
-          }
-        if (e == j % LPR) mine[j / LPR] = best;
-      }
-    }
-  } else {
-    uint64_t last = ~0ull;
-    for (int j = 0; j < K; ++j) {
-      uint64_t best = no_cand();
-      if (row_ok)
-        for (int c = e; c < ncand; c += LPR) {
-          const uint64_t v = load_agent(cands + c);
-          if (v < last && v > best) best = v;
-        }
-      best = group_max_u64<LPR>(best);
-#pragma unroll
-      for (int i = 0; i < kMine; ++i)
-        if (e == j % LPR && i == j / LPR) mine[i] = best;
-      last = best > no_cand() ? best : no_cand() + 1;  // nothing below "no candidate" is eligible again
-    }
-  }
-  // ---- soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
-  float lse_all = 0.f, lse_nb = 0.f, max_nb = -INFINITY;
-  if (!a.normalized) {
-    float st_mx = -INFINITY, st_sum = 0.f;
+  auto load_rows = [&](int r0) {
+    rk = r0 + lane / LPR;
+    row_ok = rk < K;
+    const int krow = row_ok ? rk : 0;
+    cands = a.p_cand + (size_t)(m_base + krow) * ncand;
+    pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
+    psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
+    const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
     if constexpr (NCH > 0) {
 #pragma unroll
-      for (int q = 0; q < NCH; ++q) st_mx = fmaxf(st_mx, pm[q]);
-      st_mx = group_max<LPR>(st_mx);
+      for (int q = 0; q < NCH; ++q) {
+        const int ch = e + LPR * q;
+        const bool ok = row_ok && ch < a.n_chunks;
 #pragma unroll
-      for (int q = 0; q < NCH; ++q)
-        if (pm[q] > -INFINITY) st_sum += ps[q] * __expf(pm[q] - st_mx);
+        for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+        pm[q] = (ok && !a.normalized) ? load_agent(pmax + ch) : -INFINITY;
+        ps[q] = (ok && !a.normalized) ? load_agent(psum + ch) : 0.f;
+      }
+    }
+    zb = load_agent(zsr);
+    for (int d = 0; d < a.ND; ++d) dl[d] = load_agent(zsr + 1 + d);
+  };
+  auto process_rows = [&]() {
+    // ---- K rounds of "best remaining candidate" in every lane group at once.
+    // Lane e keeps the winners of rounds e, e + LPR, ... (at most KMAX / LPR + 1 of them).
+    constexpr int kMine = (KMAX + LPR - 1) / LPR;
+    uint64_t mine[kMine];
+  #pragma unroll
+    for (int i = 0; i < kMine; ++i) mine[i] = no_cand();
+    if constexpr (NCH > 0) {
+  #pragma unroll
+      for (int j = 0; j < KMAX; ++j) {
+        if (j < K) {
+          uint64_t best = list[0][0];
+  #pragma unroll
+          for (int q = 1; q < NCH; ++q) best = list[q][0] > best ? list[q][0] : best;
+          best = group_max_u64<LPR>(best);
+  #pragma unroll
+          for (int q = 0; q < NCH; ++q)
+            if (list[q][0] == best) {  // the winner's list moves up (real candidates are unique)
+  #pragma unroll
+              for (int x = 0; x + 1 < KMAX; ++x) list[q][x] = list[q][x + 1];
+              list[q][KMAX - 1] = no_cand();
+            }
+          if (e == j % LPR) mine[j / LPR] = best;
+        }
+      }
     } else {
-      if (row_ok)
-        for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, load_agent(pmax + c));
-      st_mx = group_max<LPR>(st_mx);
-      if (row_ok)
-        for (int c = e; c < a.n_chunks; c += LPR) {
-          const float p = load_agent(pmax + c);
-          if (p > -INFINITY) st_sum += load_agent(psum + c) * __expf(p - st_mx);
-        }
+      uint64_t last = ~0ull;
+      for (int j = 0; j < K; ++j) {
+        uint64_t best = no_cand();
+        if (row_ok)
+          for (int c = e; c < ncand; c += LPR) {
+            const uint64_t v = load_agent(cands + c);
+            if (v < last && v > best) best = v;
+          }
+        best = group_max_u64<LPR>(best);
+  #pragma unroll
+        for (int i = 0; i < kMine; ++i)
+          if (e == j % LPR && i == j / LPR) mine[i] = best;
+        last = best > no_cand() ? best : no_cand() + 1;  // nothing below "no candidate" is eligible again
+      }
     }
-    st_sum = group_sum<LPR>(st_sum);
-    lse_nb = st_mx + __logf(st_sum);
-    const float hi = fmaxf(lse_nb, zb), lo = fminf(lse_nb, zb);
-    lse_all = hi + __logf(1.f + __expf(lo - hi));
-    max_nb = st_mx;
-  } else {
-    // keys are log-probabilities already; the best token of the row is round 0's winner, the largest
-    // of the winners spread over the group's lanes
-    max_nb = cand_key(group_max_u64<LPR>(mine[0]));
-  }
-  const double logp_b = (double)zb - (double)lse_all;
-  const double nb = (double)lse_nb - (double)lse_all;
-  const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
-  // TDT: one duration per candidate
-  double x_tok = 0.0, x_blank = 0.0;
-  int adv_tok = 0, adv_blank = 1;
-  if (a.ND > 0) {
+    // ---- soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
+    float lse_all = 0.f, lse_nb = 0.f, max_nb = -INFINITY;
     if (!a.normalized) {
-      float dmx = -INFINITY, sm = 0.f;
-      for (int d = 0; d < a.ND; ++d) dmx = fmaxf(dmx, dl[d]);
-      for (int d = 0; d < a.ND; ++d) sm += __expf(dl[d] - dmx);
-      const float l = dmx + __logf(sm);
-      for (int d = 0; d < a.ND; ++d) dl[d] -= l;
+      float st_mx = -INFINITY, st_sum = 0.f;
+      if constexpr (NCH > 0) {
+  #pragma unroll
+        for (int q = 0; q < NCH; ++q) st_mx = fmaxf(st_mx, pm[q]);
+        st_mx = group_max<LPR>(st_mx);
+  #pragma unroll
+        for (int q = 0; q < NCH; ++q)
+          if (pm[q] > -INFINITY) st_sum += ps[q] * __expf(pm[q] - st_mx);
+      } else {
+        if (row_ok)
+          for (int c = e; c < a.n_chunks; c += LPR) st_mx = fmaxf(st_mx, load_agent(pmax + c));
+        st_mx = group_max<LPR>(st_mx);
+        if (row_ok)
+          for (int c = e; c < a.n_chunks; c += LPR) {
+            const float p = load_agent(pmax + c);
+            if (p > -INFINITY) st_sum += load_agent(psum + c) * __expf(p - st_mx);
+          }
+      }
+      st_sum = group_sum<LPR>(st_sum);
+      lse_nb = st_mx + __logf(st_sum);
+      const float hi = fmaxf(lse_nb, zb), lo = fminf(lse_nb, zb);
+      lse_all = hi + __logf(1.f + __expf(lo - hi));
+      max_nb = st_mx;
+    } else {
+      // keys are log-probabilities already; the best token of the row is round 0's winner, the largest
+      // of the winners spread over the group's lanes
+      max_nb = cand_key(group_max_u64<LPR>(mine[0]));
     }
-    int best = -1, best_b = -1;
-    for (int d = 0; d < a.ND; ++d) {
-      if (best < 0 || dl[d] > dl[best]) best = d;
-      if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
+    const double logp_b = (double)zb - (double)lse_all;
+    const double nb = (double)lse_nb - (double)lse_all;
+    const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
+    // TDT: one duration per candidate
+    double x_tok = 0.0, x_blank = 0.0;
+    int adv_tok = 0, adv_blank = 1;
+    if (a.ND > 0) {
+      if (!a.normalized) {
+        float dmx = -INFINITY, sm = 0.f;
+        for (int d = 0; d < a.ND; ++d) dmx = fmaxf(dmx, dl[d]);
+        for (int d = 0; d < a.ND; ++d) sm += __expf(dl[d] - dmx);
+        const float l = dmx + __logf(sm);
+        for (int d = 0; d < a.ND; ++d) dl[d] -= l;
+      }
+      int best = -1, best_b = -1;
+      for (int d = 0; d < a.ND; ++d) {
+        if (best < 0 || dl[d] > dl[best]) best = d;
+        if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
+      }
+      x_tok = (double)dl[best];
+      x_blank = (double)dl[best_b];
+      adv_tok = a.dur[best];
+      adv_blank = a.dur[best_b];
     }
-    x_tok = (double)dl[best];
-    x_blank = (double)dl[best_b];
-    adv_tok = a.dur[best];
-    adv_blank = a.dur[best_b];
-  }
-  wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
-  // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
-  if (row_ok) {
-    const int kind = s.kind[rk];
-    const bool forced = s.sym[rk] >= a.max_sym;
-    const bool use_gamma = a.algo == 1 && a.gamma < INFINITY;
-    const double thr = maxlogp - (double)a.gamma;
-    const double sc = s.score[rk];
-    const int flat0 = rk << kFlatShift;
-    const double tok_extra = (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok - (double)lse_all;
-#pragma unroll
-    for (int i = 0; i < kMine; ++i) {
-      const int j = e + LPR * i;
-      if (j < K) {
-        const float wk = cand_key(mine[i]);
-        const int wi = cand_idx(mine[i]);
-        double val = -INFINITY;
-        if (kind == 2 && wk > -INFINITY && !forced) {
-          const double lp = (double)wk - (double)lse_all;  // pre-LM log-probability when no LM is fused
-          if (!(use_gamma && lp < thr)) val = sc + (double)wk + tok_extra;
+    wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
+    // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
+    if (row_ok) {
+      const int kind = s.kind[rk];
+      const bool forced = s.sym[rk] >= a.max_sym;
+      const bool use_gamma = a.algo == 1 && a.gamma < INFINITY;
+      const double thr = maxlogp - (double)a.gamma;
+      const double sc = s.score[rk];
+      const int flat0 = rk << kFlatShift;
+      const double tok_extra = (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok - (double)lse_all;
+  #pragma unroll
+      for (int i = 0; i < kMine; ++i) {
+        const int j = e + LPR * i;
+        if (j < K) {
+          const float wk = cand_key(mine[i]);
+          const int wi = cand_idx(mine[i]);
+          double val = -INFINITY;
+          if (kind == 2 && wk > -INFINITY && !forced) {
+            const double lp = (double)wk - (double)lse_all;  // pre-LM log-probability when no LM is fused
+            if (!(use_gamma && lp < thr)) val = sc + (double)wk + tok_extra;
+          }
+          s.rc_val[rk * (K + 1) + j] = val;
+          s.rc_flat[rk * (K + 1) + j] = flat0 + (wi < V ? wi : V - 1);
         }
-        s.rc_val[rk * (K + 1) + j] = val;
-        s.rc_flat[rk * (K + 1) + j] = flat0 + (wi < V ? wi : V - 1);
+      }
+      if (e == LPR - 1) {  // blank / stay: the group's last lane (least loaded with winners)
+        double val = -INFINITY;
+        if (kind == 2) {
+          double bl = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
+          if (use_gamma && logp_b < thr && !forced) bl = -INFINITY;
+          val = sc + bl + x_blank;
+          s.advt[rk] = adv_tok;
+          s.advb[rk] = adv_blank;
+        } else if (kind == 1) {
+          val = sc;  // a waiting or finished hypothesis stays as it is
+        }
+        s.rc_val[rk * (K + 1) + K] = val;
+        s.rc_flat[rk * (K + 1) + K] = flat0 + V;
       }
     }
-    if (e == LPR - 1) {  // blank / stay: the group's last lane (least loaded with winners)
-      double val = -INFINITY;
-      if (kind == 2) {
-        double bl = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
-        if (use_gamma && logp_b < thr && !forced) bl = -INFINITY;
-        val = sc + bl + x_blank;
-        s.advt[rk] = adv_tok;
-        s.advb[rk] = adv_blank;
-      } else if (kind == 1) {
-        val = sc;  // a waiting or finished hypothesis stays as it is
+    wave_sync();
+  };
+  auto per_utterance = [&]() -> bool {  // false: the utterance had finished before this step
+    if (a.use_ctx)
+      for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
+    if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
+      if (lane < K) {
+        a.src_row[m_base + lane] = m_base + lane;
+        a.tok[m_base + lane] = -1;
       }
-      s.rc_val[rk * (K + 1) + K] = val;
-      s.rc_flat[rk * (K + 1) + K] = flat0 + V;
+      return false;
     }
+    if (lane < K) {
+      s.score[lane] = my_score;
+      s.t[lane] = my_t;
+      s.sym[lane] = my_sym;
+      s.len[lane] = my_len;
+      s.last[lane] = my_last;
+      s.hash[lane] = my_hash;
+      s.sel_val[lane] = -INFINITY;
+      s.sel_flat[lane] = -1;
+    }
+    // frame of the earliest unfinished hypothesis (lanes >= K hold neutral values)
+    const bool my_live = my_score > -INFINITY;
+    int t_cur = group_min_i<16>((my_live && my_t < T_b) ? my_t : T_b);
+    t_cur = __builtin_amdgcn_readlane(t_cur, 0);
+    if (lane < K) s.kind[lane] = my_live ? ((my_t < T_b && (a.algo == 0 || my_t == t_cur)) ? 2 : 1) : 0;
+    return true;
+  };
+  if constexpr (MULTI) {
+    for (int r0 = 0; r0 < K; r0 += kRowsPerPass) {
+      load_rows(r0);
+      if (r0 == 0 && !per_utterance()) return;
+      process_rows();
+    }
+  } else {
+    load_rows(0);
+    if (!per_utterance()) return;
+    process_rows();
   }
-  wave_sync();
 
   // ---- the Beam best of all K * (K + 1) candidates, by (value desc, (k, v) asc)
   const int n = K * (K + 1);
@@ -670,7 +698,10 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   wave_sync();
 }
 
-// picks the lane-group width and register budget for the beam and list sizes at hand
+// picks the lane-group width and register budget for the beam and list sizes at hand.
+// WIDE = false leaves out the forms for beams above 8 (they need many registers; the main kernel of a step,
+// which runs the selection in its tail, is built without them and a separate launch takes such beams).
+template <bool WIDE = true>
 __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, SelectScratch &s) {
   if (a.K <= 4) {
     if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s);
@@ -678,8 +709,9 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Sele
   } else if (a.K <= 8) {
     if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s);
     else select_utterance<8, 0, 8>(a, b, s);
-  } else {
+  } else if constexpr (WIDE) {
     if (a.n_chunks <= 4) select_utterance<4, 1, 16>(a, b, s);
+    else if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s);  // four hypotheses per pass
     else select_utterance<4, 0, 16>(a, b, s);
   }
 }
@@ -897,6 +929,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
     if (LPH + e < a.K) store_agent(a.p_cand + pc * a.K + LPH + e, mine[1]);
   }
 
+  if (a.K > 8) {  // the selection of a wide beam is a launch of its own
+    RB_BLOCK_TS(1);
+    return;
+  }
   // ---- the block that completes the tile runs the selection for its utterances.
   // The lists were written with device-coherent stores; once every thread's stores have been
   // acknowledged (workgroup release + barrier) one thread counts the block in.  The completing block
@@ -919,7 +955,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
   const int wave = tid >> 6;
   for (int u = wave; u < a.upt; u += WAVES) {
     const int b = ty * a.upt + u;
-    if (b < a.sel.B) select_dispatch(a.sel, b, scratch[wave]);
+    if (b < a.sel.B) select_dispatch<false>(a.sel, b, scratch[wave]);
   }
   RB_STAMP(0, 6);
   RB_BLOCK_TS(1);

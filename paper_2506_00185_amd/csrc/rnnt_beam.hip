@@ -460,7 +460,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
     a.n_chunks = h->n_chunks;
     a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
-    a.upt = 32 / p.K;
+    a.upt = 32 / p.K < 8 ? 32 / p.K : 8;  // one wave of the completing block per utterance
     a.rpt = a.upt * p.K;
     a.n_jtiles = (p.B + a.upt - 1) / a.upt;
     a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
@@ -474,12 +474,19 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.map.b_m = (p.M + 31) / 32;
     fill_select_args(h, p, step_off, h->n_chunks, a.sel);
     const dim3 grid(xcd_grid(a.map));
-    ScopedKernelTime tm(h, s, KT_JOINT);
 #define RB_MAIN(W, I) hipLaunchKernelGGL((k_step_main<W, I>), grid, dim3(W * 64), 0, s, a)
-    if (c.H == 640 && (!lstm || c.P == 640)) RB_MAIN(8, 10);
-    else if (c.H % 64 == 0 && (!lstm || c.P % 64 == 0)) RB_MAIN(8, 0);
-    else RB_MAIN(4, 0);
+    {
+      ScopedKernelTime tm(h, s, KT_JOINT);
+      if (c.H == 640 && (!lstm || c.P == 640)) RB_MAIN(8, 10);
+      else if (c.H % 64 == 0 && (!lstm || c.P % 64 == 0)) RB_MAIN(8, 0);
+      else RB_MAIN(4, 0);
+    }
 #undef RB_MAIN
+    if (p.K > 8) {  // beams above 8: the main kernel leaves the selection to a launch of its own
+      RB_HIP(h, hipGetLastError());
+      ScopedKernelTime tm(h, s, KT_SELECT);
+      hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, a.sel);
+    }
   }
   RB_HIP(h, hipGetLastError());
   int rc = launch_lm(h, s, p);
