@@ -31,7 +31,7 @@ class _Config(C.Structure):
     _fields_ = [("model", C.c_int32), ("pred", C.c_int32), ("prec", C.c_int32),
                 ("D", C.c_int32), ("H", C.c_int32), ("P", C.c_int32), ("E", C.c_int32), ("V", C.c_int32),
                 ("n_dur", C.c_int32), ("durations", C.c_int32 * 8), ("ctx", C.c_int32),
-                ("max_symbols", C.c_int32), ("lm_rule", C.c_int32), ("gamma", C.c_double)]
+                ("max_symbols", C.c_int32), ("lm_rule", C.c_int32), ("lm_prune", C.c_int32), ("gamma", C.c_double)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -70,7 +70,7 @@ def _i32(a):
     return np.ascontiguousarray(a, dtype=np.int32)
 
 
-def make_config(c: dict, lm_rule: int = 4) -> _Config:
+def make_config(c: dict, lm_rule: int = 4, lm_prune: str = "late") -> _Config:
     cfg = _Config()
     cfg.model = 1 if c["model"] == "tdt" else 0
     cfg.pred = 1 if c["pred"] == "stateless" else 0
@@ -82,6 +82,7 @@ def make_config(c: dict, lm_rule: int = 4) -> _Config:
     cfg.ctx = c["ctx"]
     cfg.max_symbols = c["s"]
     cfg.lm_rule = lm_rule
+    cfg.lm_prune = {"late": 0, "early": 1}[lm_prune]
     cfg.gamma = c["gamma"]
     return cfg
 
@@ -120,11 +121,11 @@ class LM:
 
 
 def decode(c: dict, w: dict | None, enc, lengths, beam=None, algo=None, lm: LM | None = None,
-           lm_weight: float = 0.0, lm_rule: int = 4, injected=None, log=False, snap_every=0,
+           lm_weight: float = 0.0, lm_rule: int = 4, injected=None, log=False, snap_every=0, lm_prune: str = "late",
            n_threads=0) -> dict:
     """Run the oracle on a batch.  ``injected`` = (tok_logp [B,T,C,V+1], dur_logp or None)."""
     L = lib()
-    cfg = make_config(c, lm_rule)
+    cfg = make_config(c, lm_rule, lm_prune)
     beam = c["beam"] if beam is None else beam
     algo = (AES if c["algo"] == "aes" else ALSD) if algo is None else algo
     lengths = _i32(lengths)

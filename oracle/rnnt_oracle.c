@@ -48,6 +48,9 @@ typedef struct {
   int32_t ctx;         /* stateless context size */
   int32_t max_symbols; /* s */
   int32_t lm_rule;     /* 4 = Eq. (4) blank scoring, 3 = Eq. (3) */
+  int32_t lm_prune;    /* 0 = late pruning: the Beam best are chosen on the fused scores;
+                          1 = early pruning: they are chosen on the Transducer's scores alone and the
+                          chosen ones are then rescored with the LM (Sec. 2.3, "Early/late pruning") */
   double gamma;        /* prune margin on log-probability, INFINITY = off */
 } orc_config;
 
@@ -393,14 +396,15 @@ void orc_score_row(const orc_config *c, const double *z, const double *logp_in, 
 /* --------------------------------------------------------------- selection */
 
 typedef struct {
-  double val;
+  double key; /* what the candidates are ranked by */
+  double val; /* the score the new hypothesis gets; differs from key under early pruning only */
   int64_t idx;
 } cand_t;
 
 static int cand_cmp(const void *a, const void *b) {
   const cand_t *x = (const cand_t *)a, *y = (const cand_t *)b;
-  if (x->val > y->val) return -1;
-  if (x->val < y->val) return 1;
+  if (x->key > y->key) return -1;
+  if (x->key < y->key) return 1;
   return x->idx < y->idx ? -1 : (x->idx > y->idx ? 1 : 0);
 }
 
@@ -409,6 +413,7 @@ static int cand_cmp(const void *a, const void *b) {
 void orc_topk(const double *val, int64_t n, int K, int64_t *out_idx) {
   cand_t *c = (cand_t *)malloc(sizeof(cand_t) * (size_t)n);
   for (int64_t i = 0; i < n; ++i) {
+    c[i].key = val[i];
     c[i].val = val[i];
     c[i].idx = i;
   }
@@ -578,6 +583,7 @@ static void decode_utterance(utt_job *J) {
 
     double step_gap = INFINITY;
     for (int64_t i = 0; i < n_cand; ++i) {
+      cand[i].key = -INFINITY;
       cand[i].val = -INFINITY;
       cand[i].idx = i;
       unpruned[i] = -INFINITY;
@@ -594,6 +600,7 @@ static void decode_utterance(utt_job *J) {
       if (!active) {
         kind[k] = 1;
         cand[(int64_t)k * (V + 1) + V].val = hy->score; /* stay */
+        cand[(int64_t)k * (V + 1) + V].key = hy->score;
         continue;
       }
       kind[k] = 2;
@@ -616,10 +623,25 @@ static void decode_utterance(utt_job *J) {
       }
       for (int v = 0; v <= V; ++v) {
         cand[(int64_t)k * (V + 1) + v].val = hy->score + tot[v];
+        cand[(int64_t)k * (V + 1) + v].key = hy->score + tot[v];
         rowlogp[(int64_t)k * (V + 1) + v] = logp[v];
         if (logp[v] > rowmax[k]) rowmax[k] = logp[v];
         if (logp[v] > J->max_logp) J->max_logp = logp[v];
         if (tot[v] > J->max_logp) J->max_logp = tot[v];
+      }
+      if (J->lm && c->lm_prune == 1) {
+        /* early pruning: rank by the same rule without the LM term (masks and durations included) */
+        int a1, a2;
+        double *tot_asr = (double *)malloc(sizeof(double) * (size_t)(V + 1));
+        double *lp2 = (double *)malloc(sizeof(double) * (size_t)(V + 1));
+        if (injected)
+          orc_score_row(c, NULL, tmp_in, c->model == 1 ? tmp_in + V + 1 : NULL, NULL, 0.0, use_gamma, forced, tot_asr,
+                        lp2, &a1, &a2, NULL);
+        else
+          orc_score_row(c, z, NULL, NULL, NULL, 0.0, use_gamma, forced, tot_asr, lp2, &a1, &a2, NULL);
+        for (int v = 0; v <= V; ++v) cand[(int64_t)k * (V + 1) + v].key = hy->score + tot_asr[v];
+        free(tot_asr);
+        free(lp2);
       }
       if (use_gamma && isfinite(c->gamma) && !forced) {
         /* what the candidates would have been worth without the margin, for the near-tie report */
@@ -640,12 +662,12 @@ static void decode_utterance(utt_job *J) {
     /* pruning: the Beam best by (value descending, flat index ascending) */
     qsort(cand, (size_t)n_cand, sizeof(cand_t), cand_cmp);
     for (int i = 0; i < K && i + 1 < n_cand; ++i)
-      if (isfinite(cand[i].val) && isfinite(cand[i + 1].val)) {
-        double gap = cand[i].val - cand[i + 1].val;
+      if (isfinite(cand[i].key) && isfinite(cand[i + 1].key)) {
+        double gap = cand[i].key - cand[i + 1].key;
         if (gap < step_gap) step_gap = gap;
       }
     for (int64_t i = K; i < n_cand; ++i)
-      if (isfinite(cand[i].val)) J->n_cut++; else break;
+      if (isfinite(cand[i].key)) J->n_cut++; else break;
     if (J->algo == 1 && isfinite(c->gamma)) {
       /* a token close to the margin whose candidate could have entered the beam is a near tie too */
       double thr = (K - 1 < n_cand && isfinite(cand[K - 1].val)) ? cand[K - 1].val : -INFINITY;
@@ -750,6 +772,7 @@ static void decode_utterance(utt_job *J) {
     cand_t *r = (cand_t *)malloc(sizeof(cand_t) * (size_t)K);
     for (int k = 0; k < K; ++k) {
       r[k].val = cur[k].live ? cur[k].score : -INFINITY;
+      r[k].key = r[k].val;
       r[k].idx = k;
     }
     qsort(r, (size_t)K, sizeof(cand_t), cand_cmp);

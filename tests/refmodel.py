@@ -238,3 +238,37 @@ def aes_frame_synchronous(logp_fn, T, V, s, K):
                 else:
                     closed[toks] = logaddexp(closed.get(toks, -math.inf), sc)
     return closed
+
+
+def alsd_two_stage(logp_fn, fused_fn, T, V, s, K):
+    """Alignment-length synchronous search with early pruning, written with dictionaries
+    (Sec. 2.3, "Early/late pruning"): at every step all expansions of the unfinished hypotheses
+    are ranked by the Transducer's score alone, the K best are kept and only those are charged
+    the fused (Transducer + LM) increment.  Hypotheses that have consumed all frames compete with
+    their score as it is.  Equal (transcript, frame, symbols in frame) are merged by log-sum.
+    At most s tokens per frame.  ``fused_fn(t, toks)`` returns the fused increments [V + 1].
+    Returns {transcript: score} of the hypotheses alive at the end."""
+    hyps = {((), 0, 0): 0.0}
+    for _ in range(T * (s + 1)):
+        if all(t >= T for (_, t, _) in hyps):
+            break
+        cands = []
+        for (toks, t, sym), sc in hyps.items():
+            if t >= T:
+                cands.append((sc, sc, (toks, t, sym)))
+                continue
+            logp, _ = logp_fn(t, toks)
+            fused = fused_fn(t, toks)
+            cands.append((sc + logp[V], sc + fused[V], (toks, t + 1, 0)))
+            if sym < s:
+                for v in range(V):
+                    cands.append((sc + logp[v], sc + fused[v], (toks + (v,), t, sym + 1)))
+        cands.sort(key=lambda x: -x[0])
+        hyps = {}
+        for _, val, node in cands[:K]:
+            hyps[node] = logaddexp(hyps.get(node, -math.inf), val)
+    out = {}
+    for (toks, t, sym), sc in hyps.items():
+        assert toks not in out
+        out[toks] = sc
+    return out

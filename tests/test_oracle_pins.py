@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import synth_inputs as S
-from refmodel import (RefModel, aes_frame_synchronous, TableModel, dict_lm, dict_lm_score, enumerate_alignments, forward_dp, greedy,
+from refmodel import (RefModel, aes_frame_synchronous, alsd_two_stage, TableModel, dict_lm, dict_lm_score, enumerate_alignments, forward_dp, greedy,
                       logaddexp, py_hash)
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -487,3 +487,74 @@ def test_fused_beam_one_is_greedy_on_fused_scores(oracle, small_lm):
     r = oracle.decode(c, w, enc, L, lm=oracle.LM(small_lm), lm_weight=lam)
     assert tuple(r["tokens"][0, 0, : r["lens"][0, 0]]) == toks
     assert abs(r["scores"][0, 0] - score) < 1e-9
+
+
+def _fused_fn(base, d, V, lam, rule):
+    """Fused increments of Eq. (3) / Eq. (4) from a dictionary LM (order 4)."""
+    def fused(t, toks):
+        lp, _ = base(t, toks)
+        lmrow = np.array([math.log(10.0) * dict_lm_score(d, toks[-3:], v) for v in range(V)])
+        out = lp.copy()
+        if rule == 4:
+            out[:V] = lp[:V] + lam * (math.log(1 - math.exp(lp[V])) + lmrow)
+            out[V] = (1 + lam) * lp[V]
+        else:
+            out[:V] = lp[:V] + lam * lmrow
+        return out
+    return fused
+
+
+@pytest.mark.parametrize("rule", [3, 4])
+def test_early_pruning_changes_nothing_when_nothing_is_pruned(oracle, rule):
+    lm_small = S.make_lm(V=3, order=3, n_target=30, zipf_s=1.1, seed=78)
+    c, w, L, enc = _small(63, V=3, T=3, s=2, beam=2048, H=16, P=16, E=16, D=16)
+    lm = oracle.LM(lm_small)
+    late = oracle.decode(c, w, enc, L, lm=lm, lm_weight=0.6, lm_rule=rule)
+    early = oracle.decode(c, w, enc, L, lm=lm, lm_weight=0.6, lm_rule=rule, lm_prune="early")
+    assert late["n_cut"][0] == 0 and early["n_cut"][0] == 0
+    a, b = _nbest(late), _nbest(early)
+    assert a.keys() == b.keys() and len(a) > 20
+    for k in a:
+        assert abs(a[k] - b[k]) < 1e-9
+
+
+@pytest.mark.parametrize("rule", [3, 4])
+def test_early_pruning_beam_one_follows_the_transducer_and_pays_the_fused_score(oracle, small_lm, rule):
+    c, w, L, enc = _small(64, V=12, T=10, s=2, beam=1, H=16, P=16, E=16, D=16)
+    d = dict_lm(small_lm)
+    lam = 0.8
+    base = _ref_logp_fn(c, w, enc[0])
+    fused = _fused_fn(base, d, 12, lam, rule)
+    toks, _ = greedy(base, 10, 12, 2)
+    # the same walk again, adding up what the fused rule charges for each of its choices
+    t, cur, sym, score = 0, (), 0, 0.0
+    while t < 10:
+        lp, _ = base(t, cur)
+        v = int(np.argmax(lp)) if sym < 2 else 12
+        score += fused(t, cur)[v]
+        if v == 12:
+            t, sym = t + 1, 0
+        else:
+            cur, sym = cur + (v,), sym + 1
+    assert cur == toks
+    r = oracle.decode(c, w, enc, L, lm=oracle.LM(small_lm), lm_weight=lam, lm_rule=rule, lm_prune="early")
+    assert tuple(r["tokens"][0, 0, : r["lens"][0, 0]]) == toks
+    assert abs(r["scores"][0, 0] - score) < 1e-9
+    # late pruning at this weight takes another path, or the two modes could not be told apart here
+    late = oracle.decode(c, w, enc, L, lm=oracle.LM(small_lm), lm_weight=lam, lm_rule=rule)
+    assert tuple(late["tokens"][0, 0, : late["lens"][0, 0]]) != toks
+
+
+@pytest.mark.parametrize("rule,K", [(4, 3), (3, 5)])
+def test_early_pruning_with_a_real_beam_equals_the_two_stage_loop(oracle, small_lm, rule, K):
+    c, w, L, enc = _small(65, V=12, T=7, s=2, beam=K, H=16, P=16, E=16, D=16)
+    d = dict_lm(small_lm)
+    lam = 0.7
+    base = _ref_logp_fn(c, w, enc[0])
+    want = alsd_two_stage(base, _fused_fn(base, d, 12, lam, rule), 7, 12, 2, K)
+    r = oracle.decode(c, w, enc, L, lm=oracle.LM(small_lm), lm_weight=lam, lm_rule=rule, lm_prune="early")
+    assert r["n_cut"][0] > 0
+    got = _nbest(r)
+    assert got.keys() == want.keys()
+    for k in got:
+        assert abs(got[k] - want[k]) < 1e-9

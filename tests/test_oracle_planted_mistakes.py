@@ -41,6 +41,9 @@ MISTAKES = [
     ("prune margin applied to the fused score's maximum only for tokens", "for (int v = 0; v <= V; ++v)\n      if (logp[v] < mx - c->gamma) tot[v] = -INFINITY;",
      "for (int v = 0; v < V; ++v)\n      if (logp[v] < mx - c->gamma) tot[v] = -INFINITY;"),
     ("bf16 rounding truncates", "u += 0x7fffu + lsb;", "u += 0;"),
+    ("early pruning ranks by the fused score",
+     "for (int v = 0; v <= V; ++v) cand[(int64_t)k * (V + 1) + v].key = hy->score + tot_asr[v];", ""),
+    ("early pruning keeps the Transducer's score as the new score", "nh->score = cand[j].val;", "nh->score = cand[j].key;"),
 ]
 
 
