@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload id (2 = the headline case)")
     ap.add_argument("--variant", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-graph", action="store_true", help="launch the step kernels one by one")
+    ap.add_argument("--lm-rule", type=int, default=4, choices=[3, 4], help="LM fusion rule (workloads with an LM)")
+    ap.add_argument("--lm-prune", default="late", choices=["late", "early"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-utts", type=int, default=16, help="utterances the oracle decodes for the CPU baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -93,7 +95,7 @@ def main():
     lm = None
     if c["lm"]:
         lm = A.NGramLM(S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"], 1000 * c["id"] + 3))
-    dec = A.BeamDecoder(c, w, use_graph=not args.no_graph)
+    dec = A.BeamDecoder(c, w, use_graph=not args.no_graph, lm_rule=args.lm_rule, lm_prune=args.lm_prune)
     d_enc = torch.as_tensor(enc).cuda().contiguous()
     d_len = torch.as_tensor(L).cuda().contiguous()
     audio_s = S.audio_seconds(L)
@@ -175,7 +177,8 @@ def main():
         olm = oracle.LM(S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"],
                                   1000 * c["id"] + 3)) if c["lm"] else None
         t0 = time.perf_counter()
-        o = oracle.decode(dict(c, B=n_utt), w, enc[:n_utt], L[:n_utt], lm=olm, lm_weight=c["lm_weight"])
+        o = oracle.decode(dict(c, B=n_utt), w, enc[:n_utt], L[:n_utt], lm=olm, lm_weight=c["lm_weight"],
+                          lm_rule=args.lm_rule, lm_prune=args.lm_prune)
         cdt = time.perf_counter() - t0
         cpu = dict(value=round(S.audio_seconds(L[:n_utt]) / cdt, 2), unit="audio-s/s", cores=int(o["threads"]),
                    kind="oracle", sample=f"first {n_utt} of {B} utterances of the same workload, {cdt:.1f} s wall")
@@ -191,7 +194,8 @@ def main():
         "dtype": "f32" if c["prec"] == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": c["name"] + ("" if c["prec"] == "f32" or args.config != 2 else "_bf16joint"),
                    "B": B, "T": T, "beam": K, "algo": c["algo"], "V": c["V"], "max_symbols": c["s"],
-                   "graph": not args.no_graph, "audio_s_per_pass": audio_s},
+                   "graph": not args.no_graph, "audio_s_per_pass": audio_s,
+                   **({"lm_rule": args.lm_rule, "lm_prune": args.lm_prune} if c["lm"] else {})},
         "beam_search_steps": n_steps, "us_per_beam_step": round(gpu_ms * 1e3 / max(n_steps, 1), 3),
         "gpu_ms_per_pass": round(gpu_ms, 4), "beam1_ms_per_pass": round(ms_beam1, 4),
         "beam_over_greedy": round(ms / ms_beam1, 4), "joint_launch_mfma_util": round(joint_util, 5),

@@ -73,6 +73,12 @@ typedef struct {
                                 "CUDA Graphs"); 0: launch them one by one */
   int32_t joint_path;        /* rnnt_joint_path_t; create fails if MATERIALIZED is asked for a decoder
                                 that cannot take it */
+  int32_t lm_rule;           /* how the LM enters a candidate's score (Sec. 2.3): 0 or 4 = Eq. (4), tokens get
+                                lambda ln((1 - p_blank) p_LM), blank (1 + lambda) ln p_blank; 3 = Eq. (3), tokens
+                                get lambda ln p_LM, blank is left as it is */
+  int32_t lm_early_pruning;  /* 0 = late pruning: the Beam best are chosen on the fused scores; 1 = early pruning:
+                                they are chosen on the Transducer's scores, the chosen ones then get the LM term
+                                (Sec. 2.3, "Early/late pruning") */
 } rnnt_config_t;
 
 /* Device pointers, float32, caller-owned.  Unused ones may be NULL. */

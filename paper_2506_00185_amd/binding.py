@@ -28,7 +28,8 @@ class _Config(C.Structure):
                 ("D", C.c_int32), ("H", C.c_int32), ("P", C.c_int32), ("E", C.c_int32), ("V", C.c_int32),
                 ("n_durations", C.c_int32), ("durations", C.c_int32 * 8), ("stateless_context", C.c_int32),
                 ("max_B", C.c_int32), ("max_T", C.c_int32), ("max_beam", C.c_int32), ("max_symbols", C.c_int32),
-                ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32)]
+                ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32),
+                ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -122,7 +123,7 @@ class BeamDecoder:
     """rnnt_beam_create / decode / results / destroy for one model."""
 
     def __init__(self, c: dict, w: dict, max_B=None, max_T=None, max_beam=None, use_graph=True, device="cuda:0",
-                 joint_path="auto"):
+                 joint_path="auto", lm_rule=4, lm_prune="late"):
         lib = load_library()
         torch = _torch()
         self.device = torch.device(device)
@@ -144,6 +145,8 @@ class BeamDecoder:
         cfg.prune_margin = c["gamma"] if math.isfinite(c["gamma"]) else float("inf")
         cfg.use_graph = 1 if use_graph else 0
         cfg.joint_path = {"auto": 0, "fused": 1, "materialized": 2}[joint_path]
+        cfg.lm_rule = lm_rule
+        cfg.lm_early_pruning = {"late": 0, "early": 1}[lm_prune]
         self.cfg = cfg
         self._w = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
                    for k, v in w.items()}

@@ -246,6 +246,9 @@ struct SelectArgs {
   int algo, max_sym;
   float gamma;
   int has_lm;
+  int lm_rule3;         // 1: Eq. (3) (LM on tokens only, blank as it is); 0: Eq. (4)
+  int lm_early;         // 1: early pruning: keys carry no LM term; the kept candidates are charged it here
+  const float *lm_rows; // [M, V] natural-log LM scores (read for the kept candidates under early pruning)
   float lambda;
   // what the prediction step has to do for each new slot
   int *src_row, *tok;
@@ -268,6 +271,7 @@ __device__ __forceinline__ float logaddexp_f(float a, float b) {
 struct SelectScratch {
   double score[kMaxBeam];
   double rc_val[kMaxBeam * (kMaxBeam + 1)];
+  double rc_key[kMaxBeam * (kMaxBeam + 1)];  // early pruning only: what the candidates are ranked by
   double sel_val[kMaxBeam];
   double n_score[kMaxBeam];
   uint64_t win[kMaxBeam][kMaxBeam];
@@ -468,34 +472,45 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       const double thr = maxlogp - (double)a.gamma;
       const double sc = s.score[rk];
       const int flat0 = rk << kFlatShift;
-      const double tok_extra = (a.has_lm ? (double)a.lambda * nb : 0.0) + x_tok - (double)lse_all;
-  #pragma unroll
+      // Eq. (4): tokens get lambda (ln(1 - p_blank) + lm), blank (1 + lambda) ln p_blank; Eq. (3): tokens lambda lm,
+      // blank unchanged.  Late pruning: lambda * lm is in the key already; early: added here, after the ranking value.
+      const double lm_const = (a.has_lm && !a.lm_rule3) ? (double)a.lambda * nb : 0.0;
+      const double tok_base = x_tok - (double)lse_all;
+      const bool early = a.lm_early != 0;
+#pragma unroll
       for (int i = 0; i < kMine; ++i) {
         const int j = e + LPR * i;
         if (j < K) {
           const float wk = cand_key(mine[i]);
           const int wi = cand_idx(mine[i]);
-          double val = -INFINITY;
+          double val = -INFINITY, key = -INFINITY;
           if (kind == 2 && wk > -INFINITY && !forced) {
-            const double lp = (double)wk - (double)lse_all;  // pre-LM log-probability when no LM is fused
-            if (!(use_gamma && lp < thr)) val = sc + (double)wk + tok_extra;
+            const double lp = (double)wk - (double)lse_all;  // pre-LM log-probability when no LM is in the key
+            if (!(use_gamma && lp < thr)) {
+              key = sc + (double)wk + tok_base;
+              val = key + lm_const;
+              if (early) val += (double)a.lambda * (double)a.lm_rows[(size_t)(m_base + rk) * V + wi];
+            }
           }
           s.rc_val[rk * (K + 1) + j] = val;
+          if (early) s.rc_key[rk * (K + 1) + j] = key;
           s.rc_flat[rk * (K + 1) + j] = flat0 + (wi < V ? wi : V - 1);
         }
       }
       if (e == LPR - 1) {  // blank / stay: the group's last lane (least loaded with winners)
-        double val = -INFINITY;
+        double val = -INFINITY, key = -INFINITY;
         if (kind == 2) {
-          double bl = a.has_lm ? (1.0 + (double)a.lambda) * logp_b : logp_b;
+          double bl = logp_b;
           if (use_gamma && logp_b < thr && !forced) bl = -INFINITY;
-          val = sc + bl + x_blank;
+          key = sc + bl + x_blank;
+          val = (a.has_lm && !a.lm_rule3 && bl > -INFINITY) ? key + (double)a.lambda * bl : key;
           s.advt[rk] = adv_tok;
           s.advb[rk] = adv_blank;
         } else if (kind == 1) {
-          val = sc;  // a waiting or finished hypothesis stays as it is
+          val = key = sc;  // a waiting or finished hypothesis stays as it is
         }
         s.rc_val[rk * (K + 1) + K] = val;
+        if (early) s.rc_key[rk * (K + 1) + K] = key;
         s.rc_flat[rk * (K + 1) + K] = flat0 + V;
       }
     }
@@ -540,18 +555,20 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
     process_rows();
   }
 
-  // ---- the Beam best of all K * (K + 1) candidates, by (value desc, (k, v) asc)
+  // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
+  // value is the new score itself except under early pruning
   const int n = K * (K + 1);
+  const double *rank_of = a.lm_early ? s.rc_key : s.rc_val;
   if (n <= 64) {
     // few candidates: each lane counts how many come before its own; that count is its new slot
-    const double mv = lane < n ? s.rc_val[lane] : -INFINITY;
+    const double mv = lane < n ? rank_of[lane] : -INFINITY;
     const int mf = lane < n ? s.rc_flat[lane] : 0x7fffffff;
     int rank = 0;
 #pragma unroll 4
     for (int c = 0; c < n; ++c)
       rank += comes_before(readlane_d(mv, c), __builtin_amdgcn_readlane(mf, c), mv, mf) ? 1 : 0;
     if (mv > -INFINITY && rank < K) {
-      s.sel_val[rank] = mv;
+      s.sel_val[rank] = s.rc_val[lane];
       s.sel_flat[rank] = mf;
     }
   } else {
@@ -561,7 +578,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       double bv = -INFINITY;
       int bi = 0x7fffffff;
       for (int c = lane; c < n; c += 64) {
-        const double v = s.rc_val[c];
+        const double v = rank_of[c];
         const int i = s.rc_flat[c];
         const bool eligible = v > -INFINITY && (v < last_v || (v == last_v && i > last_i));
         if (eligible && comes_before(v, i, bv, bi)) {
@@ -570,13 +587,14 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         }
       }
       wave_best(bv, bi);
-      if (lane == 0 && bv > -INFINITY) {
-        s.sel_val[j] = bv;
-        s.sel_flat[j] = bi;
-      }
+      if (!(bv > -INFINITY)) break;
+      for (int c = lane; c < n; c += 64)  // the candidate's own lane hands over its score ((k, v) is unique)
+        if (s.rc_flat[c] == bi && rank_of[c] == bv) {
+          s.sel_val[j] = s.rc_val[c];
+          s.sel_flat[j] = bi;
+        }
       last_v = bv;
       last_i = bi;
-      if (!(bv > -INFINITY)) break;
     }
   }
   wave_sync();

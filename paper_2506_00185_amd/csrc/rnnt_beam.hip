@@ -376,6 +376,9 @@ void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunk
   a.max_sym = c.max_symbols;
   a.gamma = c.prune_margin;
   a.has_lm = p.lm ? 1 : 0;
+  a.lm_rule3 = c.lm_rule == 3 ? 1 : 0;
+  a.lm_early = (p.lm && c.lm_early_pruning) ? 1 : 0;
+  a.lm_rows = h->lm_rows;
   a.lambda = p.lambda;
   a.src_row = h->src_row; a.tok = h->tok;
   a.tree_parent = h->tree_parent; a.tree_token = h->tree_token; a.tree_merged = h->tree_merged;
@@ -436,7 +439,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       a.Z = h->Zbig; a.Npad = h->Npad_big; a.Ab = h->Ab; a.M = p.M; a.Mp = h->Mp; a.H = c.H;
       a.K = p.K; a.V = c.V; a.ND = c.n_durations;
       a.Wspec = h->Wspec; a.bias_spec = h->bias_spec;
-      a.lm = p.lm ? h->lm_rows : nullptr;
+      a.lm = (p.lm && !c.lm_early_pruning) ? h->lm_rows : nullptr;  // early pruning ranks without the LM term
       a.lambda = p.lambda;
       a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
       a.finished = h->finished; a.done = done;
@@ -455,7 +458,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.pre = h->pre;
     a.W = h->W_out;
     a.bias = h->b_out;
-    a.lm = p.lm ? h->lm_rows : nullptr;
+    a.lm = (p.lm && !c.lm_early_pruning) ? h->lm_rows : nullptr;  // early pruning ranks without the LM term
     a.lambda = p.lambda;
     a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
     a.n_chunks = h->n_chunks;
@@ -679,6 +682,8 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   if (!w->W_enc || !w->b_enc || !w->W_pred || !w->b_pred || !w->W_out || !w->b_out) return bad("joint weights missing");
   if (c.max_B < 1 || c.max_T < 1 || c.max_beam < 1 || c.max_beam > kMaxBeam) return bad("max_B/max_T/max_beam");
   if (c.max_symbols < 1) return bad("max_symbols < 1");
+  if (c.lm_rule != 0 && c.lm_rule != 3 && c.lm_rule != 4) return bad("lm_rule must be 0, 3 or 4");
+  if (c.lm_early_pruning != 0 && c.lm_early_pruning != 1) return bad("lm_early_pruning must be 0 or 1");
   if (!(c.prune_margin >= 0.f)) return bad("prune_margin must be >= 0 (INFINITY = off)");
 
   h->N = c.V + 1 + c.n_durations;

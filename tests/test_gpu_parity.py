@@ -250,6 +250,27 @@ def test_lm_fusion(amd, oracle):
     assert not np.array_equal(g["scores"], g1["scores"])
 
 
+@pytest.mark.parametrize("rule,prune,beam,algo", [(3, "late", 4, "alsd"), (4, "early", 4, "alsd"), (3, "early", 8, "alsd"),
+                                                  (4, "early", 10, "aes")])
+def test_lm_fusion_rules_and_early_pruning(amd, oracle, rule, prune, beam, algo):
+    """Eq. (3) and early pruning (Sec. 2.3) against the oracle's versions of them; beam 10 goes through
+    the multi-pass selection of wide beams."""
+    V = 300
+    c = S.custom_config(B=4, T=16, T_min=8, D=128, H=160, P=160, E=160, V=V, beam=beam, s=3, algo=algo,
+                        blank_bias=3.0)
+    w, L, enc = _case(c, 810 + beam)
+    lm = S.make_lm(V=V, order=4, n_target=40000, zipf_s=1.1, seed=3)
+    glm, olm = amd.NGramLM(lm), oracle.LM(lm)
+    dec = amd.BeamDecoder(c, w, lm_rule=rule, lm_prune=prune)
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.5)
+    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.5, lm_rule=rule, lm_prune=prune, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 4 and full >= 2
+    # the mode must matter on this input, or the test could not tell it from the default
+    o_default = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.5)
+    assert not np.allclose(o_default["scores"], o["scores"], atol=1e-6)
+
+
 # ------------------------------------------- logits through HBM (bf16 matrix-core joint)
 
 @pytest.mark.parametrize("name,kw,lm_w", [
@@ -257,6 +278,7 @@ def test_lm_fusion(amd, oracle):
     ("rnnt_alsd_k4", dict(model="rnnt", algo="alsd", beam=4, V=1030, B=9), 0.0),
     ("tdt_alsd_k6", dict(model="tdt", algo="alsd", beam=6, V=777, B=3, durations=(0, 1, 2, 3, 4)), 0.0),
     ("rnnt_alsd_k16_lm", dict(model="rnnt", algo="alsd", beam=16, V=300, B=2), 0.3),
+    ("rnnt_alsd_k5_lm_early", dict(model="rnnt", algo="alsd", beam=5, V=300, B=3), 0.4),
 ])
 def test_materialized_logits_path(amd, oracle, name, kw, lm_w):
     """Same bars as the bf16 variant of the fused path; shapes that leave ragged tails in every
@@ -268,13 +290,14 @@ def test_materialized_logits_path(amd, oracle, name, kw, lm_w):
     if lm_w:
         lm = S.make_lm(V=c["V"], order=3, n_target=20000, zipf_s=1.1, seed=5)
         glm, olm = amd.NGramLM(lm), oracle.LM(lm)
-    dec = amd.BeamDecoder(c, w, joint_path="materialized")
+    prune = "early" if name.endswith("early") else "late"
+    dec = amd.BeamDecoder(c, w, joint_path="materialized", lm_prune=prune)
     g = gpu_decode(dec, enc, L, lm=glm, lm_weight=lm_w)
-    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=lm_w, log=True)
+    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=lm_w, lm_prune=prune, log=True)
     full, exempt = compare(g, o, TOL_BF16, TIE_BF16)
     assert full + exempt == c["B"] and full >= 1
     # and against the fused path of this library, to the same bar
-    dec_f = amd.BeamDecoder(c, w, joint_path="fused")
+    dec_f = amd.BeamDecoder(c, w, joint_path="fused", lm_prune=prune)
     gf = gpu_decode(dec_f, enc, L, lm=glm, lm_weight=lm_w)
     same = sum(int(np.array_equal(g["tokens"][b, 0], gf["tokens"][b, 0])) for b in range(c["B"]))
     assert same >= c["B"] - exempt - 1
