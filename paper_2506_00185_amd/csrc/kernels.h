@@ -345,6 +345,10 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   float pm[NCH > 0 ? NCH : 1], ps[NCH > 0 ? NCH : 1];
   float zb = 0.f;
   float dl[8];
+  // a single chunk's list IS the K best of the hypothesis: lane e takes entries e, e + LPR, .. as they are
+  constexpr int kMine = (KMAX + LPR - 1) / LPR;
+  const bool one_list = NCH == 1 && a.n_chunks == 1;
+  uint64_t direct[kMine];
   auto load_rows = [&](int r0) {
     rk = r0 + lane / LPR;
     row_ok = rk < K;
@@ -358,10 +362,19 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       for (int q = 0; q < NCH; ++q) {
         const int ch = e + LPR * q;
         const bool ok = row_ok && ch < a.n_chunks;
+        if (!one_list) {
 #pragma unroll
-        for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+          for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+        }
         pm[q] = (ok && !a.normalized) ? load_agent(pmax + ch) : -INFINITY;
         ps[q] = (ok && !a.normalized) ? load_agent(psum + ch) : 0.f;
+      }
+      if (one_list) {
+#pragma unroll
+        for (int i = 0; i < kMine; ++i) {
+          const int j = e + LPR * i;
+          direct[i] = (row_ok && j < K) ? load_agent(cands + j) : no_cand();
+        }
       }
     }
     zb = load_agent(zsr);
@@ -370,22 +383,24 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
   auto process_rows = [&]() {
     // ---- K rounds of "best remaining candidate" in every lane group at once.
     // Lane e keeps the winners of rounds e, e + LPR, ... (at most KMAX / LPR + 1 of them).
-    constexpr int kMine = (KMAX + LPR - 1) / LPR;
     uint64_t mine[kMine];
-  #pragma unroll
+#pragma unroll
     for (int i = 0; i < kMine; ++i) mine[i] = no_cand();
-    if constexpr (NCH > 0) {
-  #pragma unroll
+    if (one_list) {
+#pragma unroll
+      for (int i = 0; i < kMine; ++i) mine[i] = direct[i];
+    } else if constexpr (NCH > 0) {
+#pragma unroll
       for (int j = 0; j < KMAX; ++j) {
         if (j < K) {
           uint64_t best = list[0][0];
-  #pragma unroll
+#pragma unroll
           for (int q = 1; q < NCH; ++q) best = list[q][0] > best ? list[q][0] : best;
           best = group_max_u64<LPR>(best);
-  #pragma unroll
+#pragma unroll
           for (int q = 0; q < NCH; ++q)
             if (list[q][0] == best) {  // the winner's list moves up (real candidates are unique)
-  #pragma unroll
+#pragma unroll
               for (int x = 0; x + 1 < KMAX; ++x) list[q][x] = list[q][x + 1];
               list[q][KMAX - 1] = no_cand();
             }
@@ -402,7 +417,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
             if (v < last && v > best) best = v;
           }
         best = group_max_u64<LPR>(best);
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < kMine; ++i)
           if (e == j % LPR && i == j / LPR) mine[i] = best;
         last = best > no_cand() ? best : no_cand() + 1;  // nothing below "no candidate" is eligible again
@@ -413,10 +428,10 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
     if (!a.normalized) {
       float st_mx = -INFINITY, st_sum = 0.f;
       if constexpr (NCH > 0) {
-  #pragma unroll
+#pragma unroll
         for (int q = 0; q < NCH; ++q) st_mx = fmaxf(st_mx, pm[q]);
         st_mx = group_max<LPR>(st_mx);
-  #pragma unroll
+#pragma unroll
         for (int q = 0; q < NCH; ++q)
           if (pm[q] > -INFINITY) st_sum += ps[q] * __expf(pm[q] - st_mx);
       } else {
@@ -717,22 +732,28 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
 }
 
 // picks the lane-group width and register budget for the beam and list sizes at hand.
-// WIDE = false leaves out the forms for beams above 8 (they need many registers; the main kernel of a step,
-// which runs the selection in its tail, is built without them and a separate launch takes such beams).
-template <bool WIDE = true>
+// FORMS: 0 = beams up to 8 (what the main kernel of a step runs in its tail); 1 = those plus wider beams
+// whose hypotheses come with a single list; 2 = wider beams with many lists (several passes, many
+// registers).  The heavy forms are kept out of the kernels that do not need them.
+template <int FORMS>
 __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, SelectScratch &s) {
-  if (a.K <= 4) {
-    if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s);
-    else select_utterance<16, 0, 4>(a, b, s);
-  } else if (a.K <= 8) {
-    if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s);
-    else select_utterance<8, 0, 8>(a, b, s);
-  } else if constexpr (WIDE) {
-    if (a.n_chunks <= 4) select_utterance<4, 1, 16>(a, b, s);
-    else if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s);  // four hypotheses per pass
+  if constexpr (FORMS == 2) {
+    if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s);  // four hypotheses per pass
     else select_utterance<4, 0, 16>(a, b, s);
+  } else {
+    if (a.K <= 4) {
+      if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s);
+      else select_utterance<16, 0, 4>(a, b, s);
+    } else if (a.K <= 8) {
+      if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s);
+      else select_utterance<8, 0, 8>(a, b, s);
+    } else if constexpr (FORMS == 1) {
+      select_utterance<4, 1, 16>(a, b, s);
+    }
   }
 }
+// which stand-alone selection kernel takes a beam of K with n_chunks lists per hypothesis
+__host__ __device__ inline bool select_needs_wide_forms(int K, int n_chunks) { return K > 8 && n_chunks > 4; }
 
 // Block -> work item, aware of the eight XCDs.  Workgroup i of a launch runs on XCD i % 8, and each
 // XCD has its own L2.  A launch has up to two roles, each a grid of (n-tile, m-tile) items; every
@@ -973,19 +994,26 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
   const int wave = tid >> 6;
   for (int u = wave; u < a.upt; u += WAVES) {
     const int b = ty * a.upt + u;
-    if (b < a.sel.B) select_dispatch<false>(a.sel, b, scratch[wave]);
+    if (b < a.sel.B) select_dispatch<0>(a.sel, b, scratch[wave]);
   }
   RB_STAMP(0, 6);
   RB_BLOCK_TS(1);
 }
 
-// stand-alone selection kernel: one wave per utterance, four utterances per block
+// stand-alone selection kernels: one wave per utterance, four utterances per block
 __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   __shared__ SelectScratch scratch[4];
   if (*reinterpret_cast<volatile int *>(a.done)) return;
   const int wave = threadIdx.x >> 6;
   const int b = blockIdx.x * 4 + wave;
-  if (b < a.B) select_dispatch(a, b, scratch[wave]);
+  if (b < a.B) select_dispatch<1>(a, b, scratch[wave]);
+}
+__global__ __launch_bounds__(256) void k_select_wide(SelectArgs a) {
+  __shared__ SelectScratch scratch[4];
+  if (*reinterpret_cast<volatile int *>(a.done)) return;
+  const int wave = threadIdx.x >> 6;
+  const int b = blockIdx.x * 4 + wave;
+  if (b < a.B) select_dispatch<2>(a, b, scratch[wave]);
 }
 
 // ---------------------------------------------------------------------------

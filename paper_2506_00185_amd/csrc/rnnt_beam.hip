@@ -416,7 +416,8 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     SelectArgs sa;
     fill_select_args(h, p, step_off, 64, sa);
     ScopedKernelTime tm(h, s, KT_SELECT);
-    hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+    if (select_needs_wide_forms(p.K, 64)) hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+    else hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
   } else if (p.big) {
     constexpr int MS = 5;  // 160 hypotheses per block
     {
@@ -488,7 +489,10 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     if (p.K > 8) {  // beams above 8: the main kernel leaves the selection to a launch of its own
       RB_HIP(h, hipGetLastError());
       ScopedKernelTime tm(h, s, KT_SELECT);
-      hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, a.sel);
+      if (select_needs_wide_forms(p.K, h->n_chunks))
+        hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, a.sel);
+      else
+        hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, a.sel);
     }
   }
   RB_HIP(h, hipGetLastError());
