@@ -3,6 +3,7 @@
 // and k_gemm_nt / k_init / k_backtrace run once per decode call.
 #pragma once
 #include "device_utils.h"
+#include "lm_device.h"
 
 // Phase stamps for tuning builds (-DRB_TIMING): block (0, 0), thread 0 records the constant-rate
 // wall clock at a few points of each kernel.  Compiled out otherwise.
@@ -1032,12 +1033,29 @@ __device__ __forceinline__ float tanh_f(float x) {
 // R = W_hh h of the parent (computed for every current slot by the main kernel, before the selection
 // was known) and G = W_ih emb + biases per token; slots that did not append a token copy their
 // parent's state.  R, G: [.][4P] with the four gates of a unit adjacent; h: k4-major [P][Mp]; c: [M][P].
+// LM rows riding in another launch as extra blocks: block first_block + m builds the row of hypothesis m
+struct LmRowsArgs {
+  LmView view;
+  const int *ctx, *len;
+  float *out;
+  int M;            // 0: no LM rows in this launch
+  int first_block;
+};
+
 __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict__ R, const float *__restrict__ G,
                                                         const float *__restrict__ h_cur,
                                                         const float *__restrict__ c_cur, float *__restrict__ h_nxt,
                                                         float *__restrict__ c_nxt, const int *__restrict__ src_row,
                                                         const int *__restrict__ tok, int M, int Mp, int P,
-                                                        const int *done) {
+                                                        const int *done, LmRowsArgs lmr) {
+  if (lmr.M > 0 && (int)blockIdx.x >= lmr.first_block) {
+    // the LM scores of the new hypotheses depend on the selection only, like the cell update: same launch
+    extern __shared__ float lm_row[];
+    __shared__ LmRowScratch lm_sc;
+    if (*reinterpret_cast<const volatile int *>(done)) return;
+    lm_row_block(lmr.view, lmr.ctx, lmr.len, lmr.out, (int)blockIdx.x - lmr.first_block, lm_row, lm_sc);
+    return;
+  }
   const int gid = blockIdx.x * 256 + threadIdx.x;
   const int m = gid / P, u = gid % P;
   if (m >= M) return;

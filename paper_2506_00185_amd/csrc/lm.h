@@ -4,10 +4,13 @@
 #include <stdint.h>
 
 #include "../../include/rnnt_beam.h"
+#include "lm_device.h"
 
 namespace rb {
 int lm_vocab(const rnnt_lm_t *lm);
 int lm_order(const rnnt_lm_t *lm);
+// the tables of an LM as kernel arguments (for launches that carry LM rows as extra blocks)
+LmView lm_view(const rnnt_lm_t *lm);
 // LM scores (natural log) of every token after each of M hypotheses.
 // ctx [M][kCtxMax] most recent token first (-1 = none), len [M] transcript lengths (NULL: derive from ctx),
 // out [M][V].  done (nullable): device word; the kernel returns at once when it is non-zero.

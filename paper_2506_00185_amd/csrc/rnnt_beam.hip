@@ -297,7 +297,9 @@ struct ScopedKernelTime {
   }
 };
 
-int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bump) {
+// fuse_lm: the LM rows of the new hypotheses ride in the cell-update launch (LSTM models only; the caller
+// then skips the stand-alone LM launch)
+int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bump, bool fuse_lm = false) {
   const rnnt_config_t &c = h->cfg;
   int *done = h->ctrl + 1, *step_base = h->ctrl + 2;
   const int m_tiles = (p.M + 31) / 32;
@@ -306,9 +308,18 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
   } else if (c.pred == RNNT_PRED_LSTM) {
     {
       ScopedKernelTime tm(h, s, KT_LSTM);
-      const int n = p.M * c.P;
-      hipLaunchKernelGGL(k_lstm_pointwise, dim3((n + 255) / 256), dim3(256), 0, s, h->Rgates, h->G, h->h[cur], h->c[cur],
-                         h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done);
+      const int n = p.M * c.P, n_blocks = (n + 255) / 256;
+      LmRowsArgs lmr{};
+      size_t lds = 0;
+      if (fuse_lm && p.lm) {
+        lmr.view = lm_view(p.lm);
+        lmr.ctx = h->ctx; lmr.len = h->len; lmr.out = h->lm_rows;
+        lmr.M = p.M;
+        lmr.first_block = n_blocks;
+        lds = sizeof(float) * (size_t)c.V;
+      }
+      hipLaunchKernelGGL(k_lstm_pointwise, dim3(n_blocks + lmr.M), dim3(256), lds, s, h->Rgates, h->G, h->h[cur],
+                         h->c[cur], h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done, lmr);
     }
     {
       PredProjArgs a;
@@ -496,9 +507,12 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     }
   }
   RB_HIP(h, hipGetLastError());
-  int rc = launch_lm(h, s, p);
-  if (rc) return rc;
-  return launch_pred(h, s, p, cur, bump);
+  const bool fuse_lm = p.lm && !p.inj_tok && c.pred == RNNT_PRED_LSTM;
+  if (!fuse_lm) {
+    int rc = launch_lm(h, s, p);
+    if (rc) return rc;
+  }
+  return launch_pred(h, s, p, cur, bump, fuse_lm);
 }
 
 // steps per graph launch (even: the state parity flips every step)

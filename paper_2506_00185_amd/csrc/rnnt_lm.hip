@@ -16,8 +16,8 @@
 #include <unordered_map>
 #include <vector>
 
-#include "device_utils.h"
 #include "lm.h"
+#include "lm_device.h"
 
 struct rnnt_lm {
   int order = 0, V = 0, bits = 0;
@@ -35,99 +35,25 @@ struct rnnt_lm {
 
 namespace rb {
 
-__host__ __device__ inline uint64_t lm_mix(uint64_t x) {
-  x ^= x >> 30;
-  x *= 0xbf58476d1ce4e5b9ull;
-  x ^= x >> 27;
-  x *= 0x94d049bb133111ebull;
-  x ^= x >> 31;
-  return x;
-}
-
-// key of a context of j tokens, newest[0] = most recent token
-__host__ __device__ inline uint64_t lm_key(const int *newest, int j, int bits) {
-  uint64_t key = (uint64_t)j;
-  for (int i = 0; i < j; ++i) key |= (uint64_t)(newest[i] + 1) << (4 + bits * i);
-  return key;
-}
-
-struct LmView {
-  const uint64_t *ht_key;
-  const int *ht_val;
-  const float *ctx_bo;
-  const int *ctx_begin, *ctx_count;
-  const int *succ_tok;
-  const float *succ_p;
-  const float *uni;
-  uint32_t ht_mask;
-  int order, V, bits;
-};
-
 __global__ __launch_bounds__(256) void k_lm_rows(LmView lm, const int *__restrict__ ctx, const int *__restrict__ len,
                                                  float *__restrict__ out, int M, const int *done) {
   if (done && *reinterpret_cast<const volatile int *>(done)) return;
   extern __shared__ float row[];
-  __shared__ int s_cid[kCtxMax + 1];
-  __shared__ double s_bo[kCtxMax + 2];
-  const int m = blockIdx.x, tid = threadIdx.x;
-  int toks[kCtxMax];
-  int have = 0;
-#pragma unroll
-  for (int i = 0; i < kCtxMax; ++i) {
-    toks[i] = ctx[m * kCtxMax + i];
-    if (toks[i] >= 0 && have == i) have = i + 1;
-  }
-  int jmax = lm.order - 1 < have ? lm.order - 1 : have;
-  if (len && len[m] < jmax) jmax = len[m];
-  if (tid >= 1 && tid <= jmax) {
-    const uint64_t key = lm_key(toks, tid, lm.bits);
-    uint32_t slot = (uint32_t)lm_mix(key) & lm.ht_mask;
-    int cid = -1;
-    for (;;) {
-      const uint64_t k = lm.ht_key[slot];
-      if (k == key) {
-        cid = lm.ht_val[slot];
-        break;
-      }
-      if (k == 0) break;
-      slot = (slot + 1) & lm.ht_mask;
-    }
-    s_cid[tid] = cid;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    // s_bo[j] = sum of back-off weights of the contexts longer than j
-    double acc = 0.0;
-    s_bo[jmax] = 0.0;
-    for (int j = jmax; j >= 1; --j) {
-      acc += s_cid[j] >= 0 ? (double)lm.ctx_bo[s_cid[j]] : 0.0;
-      s_bo[j - 1] = acc;
-    }
-  }
-  __syncthreads();
-  const float base = (float)s_bo[0];
-  for (int v = tid; v < lm.V; v += 256) row[v] = lm.uni[v] + base;
-  for (int j = 1; j <= jmax; ++j) {
-    __syncthreads();
-    const int cid = s_cid[j];
-    if (cid < 0) continue;
-    const int beg = lm.ctx_begin[cid], cnt = lm.ctx_count[cid];
-    const float add = (float)s_bo[j];
-    for (int i = tid; i < cnt; i += 256) row[lm.succ_tok[beg + i]] = lm.succ_p[beg + i] + add;
-  }
-  __syncthreads();
-  const float ln10 = 2.302585092994046f;
-  for (int v = tid; v < lm.V; v += 256) out[(size_t)m * lm.V + v] = row[v] * ln10;
+  __shared__ LmRowScratch sc;
+  lm_row_block(lm, ctx, len, out, blockIdx.x, row, sc);
 }
 
 int lm_vocab(const rnnt_lm_t *lm) { return lm->V; }
 int lm_order(const rnnt_lm_t *lm) { return lm->order; }
 
+LmView lm_view(const rnnt_lm_t *lm) {
+  return LmView{lm->ht_key, lm->ht_val, lm->ctx_bo, lm->ctx_begin, lm->ctx_count, lm->succ_tok,
+                lm->succ_p, lm->uni,    lm->ht_mask, lm->order,    lm->V,         lm->bits};
+}
+
 void lm_launch_rows(const rnnt_lm_t *lm, const int *ctx, const int *len, float *out, int M, const int *done,
                     hipStream_t s) {
-  LmView v{lm->ht_key, lm->ht_val, lm->ctx_bo, lm->ctx_begin, lm->ctx_count, lm->succ_tok,
-           lm->succ_p, lm->uni,    lm->ht_mask, lm->order,    lm->V,         lm->bits};
-  hipLaunchKernelGGL(k_lm_rows, dim3(M), dim3(256), sizeof(float) * lm->V, s, v, ctx, len, out, M, done);
+  hipLaunchKernelGGL(k_lm_rows, dim3(M), dim3(256), sizeof(float) * lm->V, s, lm_view(lm), ctx, len, out, M, done);
 }
 
 }  // namespace rb
