@@ -864,10 +864,12 @@ struct MainArgs {
 // tile (counted with one atomic per block) then runs the selection for the tile's utterances, one
 // wave per utterance.  Remaining blocks: R = W_hh h for the current slots; it does not depend on
 // the selection, so it overlaps with it instead of following it.
-template <int WAVES, int ITERS>
-__global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
+// TAIL = false: no selection in the kernel (a launch of its own follows): for beams wider than the
+// in-kernel forms take.
+template <int WAVES, int ITERS, bool TAIL = true>
+__global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main(MainArgs a) {
   constexpr int kRedFloats = WAVES * 64 * kRedStride;
-  constexpr int kScratchFloats = (int)((sizeof(SelectScratch) * WAVES + 3) / 4);
+  constexpr int kScratchFloats = TAIL ? (int)((sizeof(SelectScratch) * WAVES + 3) / 4) : 1;
   __shared__ __align__(16) float smem[kRedFloats > kScratchFloats ? kRedFloats : kScratchFloats];
   __shared__ int s_is_last;
   float *red = smem;
@@ -969,10 +971,10 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
     if (LPH + e < a.K) store_agent(a.p_cand + pc * a.K + LPH + e, mine[1]);
   }
 
-  if (a.K > 8) {  // the selection of a wide beam is a launch of its own
+  if constexpr (!TAIL) {
     RB_BLOCK_TS(1);
     return;
-  }
+  } else {
   // ---- the block that completes the tile runs the selection for its utterances.
   // The lists were written with device-coherent stores; once every thread's stores have been
   // acknowledged (workgroup release + barrier) one thread counts the block in.  The completing block
@@ -999,6 +1001,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_step_main(MainArgs a) {
   }
   RB_STAMP(0, 6);
   RB_BLOCK_TS(1);
+  }  // TAIL
 }
 
 // stand-alone selection kernels: one wave per utterance, four utterances per block

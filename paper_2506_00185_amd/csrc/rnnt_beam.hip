@@ -489,7 +489,15 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.map.b_m = (p.M + 31) / 32;
     fill_select_args(h, p, step_off, h->n_chunks, a.sel);
     const dim3 grid(xcd_grid(a.map));
-#define RB_MAIN(W, I) hipLaunchKernelGGL((k_step_main<W, I>), grid, dim3(W * 64), 0, s, a)
+    // The selection runs in the tail of this kernel for the beams its in-kernel forms take.  (Building the kernel
+    // without it lets two blocks share a compute unit, but they also share its operand path: measured slower at
+    // every shape, 11.3 vs 10.6 ms at B * beam = 256, beam 4.)
+    const bool tail = p.K <= 8;
+#define RB_MAIN(W, I)                                                                              \
+  do {                                                                                             \
+    if (tail) hipLaunchKernelGGL((k_step_main<W, I, true>), grid, dim3(W * 64), 0, s, a);         \
+    else hipLaunchKernelGGL((k_step_main<W, I, false>), grid, dim3(W * 64), 0, s, a);             \
+  } while (0)
     {
       ScopedKernelTime tm(h, s, KT_JOINT);
       if (c.H == 640 && (!lstm || c.P == 640)) RB_MAIN(8, 10);
@@ -497,7 +505,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       else RB_MAIN(4, 0);
     }
 #undef RB_MAIN
-    if (p.K > 8) {  // beams above 8: the main kernel leaves the selection to a launch of its own
+    if (!tail) {
       RB_HIP(h, hipGetLastError());
       ScopedKernelTime tm(h, s, KT_SELECT);
       if (select_needs_wide_forms(p.K, h->n_chunks))
