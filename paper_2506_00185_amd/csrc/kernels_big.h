@@ -238,38 +238,47 @@ struct RowSelectArgs {
   const int *done;
 };
 
-constexpr int kRowRegs = 32;      // float4 registers per lane: V <= 64 * 4 * kRowRegs = 8192
+constexpr int kRowWaves = 4;       // waves that share a row
+constexpr int kRowRegs = 8;        // float4 registers per lane: V <= kRowWaves * 64 * 4 * kRowRegs = 8192
 constexpr int kSurvivorCap = 256;
 
-// One wave per hypothesis: exact K best of the row's keys (as a one-chunk candidate list for the
-// selection kernel), soft-max statistics, blank / duration logits.  Columns V .. Npad - 1 of Z hold
-// -inf (their bias is -inf), so the row needs no tail masks.
-// The K best are found without sorting the row: the K-th largest of the 64 lane maxima is a lower
-// bound of the K-th largest key, so only keys at or above it (a few dozen) are collected in LDS, and
-// each of those finds its rank by counting the ones ahead of it.
-__global__ __launch_bounds__(256) void k_row_select(RowSelectArgs a) {
-  __shared__ uint64_t surv[4][kSurvivorCap];
-  __shared__ int surv_n[4];
+// One block of four waves per hypothesis: exact K best of the row's keys (as a one-chunk candidate list
+// for the selection kernel), soft-max statistics, blank / duration logits.  Columns V .. Npad - 1 of Z
+// hold -inf (their bias is -inf), so the row needs no tail masks.
+// The K best are found without sorting the row: in every wave the K-th largest of the 64 lane maxima is a
+// lower bound of the K-th largest key of the row, so is the largest of the four; only keys at or above
+// it (a few dozen) are collected in LDS, and each of those finds its rank by counting the ones ahead of it.
+// Four waves per row rather than one: 32 instead of 128 registers of logits per lane, five waves per SIMD
+// instead of 1.25, so that the arithmetic of one row overlaps with the loads of another.
+__global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) {
+  __shared__ uint64_t surv[kSurvivorCap];
+  __shared__ int surv_n;
+  __shared__ float s_max[kRowWaves], s_sum[kRowWaves], s_tau[kRowWaves];
   const int K = a.K, V = a.V;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (*reinterpret_cast<const volatile int *>(a.done)) return;
-  const int m = blockIdx.x * 4 + wave;
-  if (m >= a.M) return;
+  const int m = blockIdx.x;
   if (a.finished[m / K]) return;
   const float *zrow = a.Z + (size_t)m * a.Npad;
   const float *lmrow = a.lm ? a.lm + (size_t)m * V : nullptr;
+  // thread tid holds columns 4 (tid + 256 q) .. + 3
   floatx4 z[kRowRegs];
 #pragma unroll
   for (int q = 0; q < kRowRegs; ++q) {
     z[q] = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    if (256 * q < a.Npad) z[q] = *reinterpret_cast<const floatx4 *>(zrow + 4 * (lane + 64 * q));
+    if (1024 * q + 4 * tid < a.Npad) z[q] = *reinterpret_cast<const floatx4 *>(zrow + 4 * (tid + 256 * q));
   }
-  if (lane == 0) surv_n[wave] = 0;
-  // soft-max statistics of the logits
+  if (tid == 0) surv_n = 0;
+  // soft-max statistics of the logits: block maximum, then the sum of exponentials against it
   float km = -INFINITY;
 #pragma unroll
   for (int q = 0; q < kRowRegs; ++q) km = fmaxf(km, fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3])));
-  const float mx = wave_max(km);
+  {
+    const float wm = wave_max(km);
+    if (lane == 0) s_max[wave] = wm;
+  }
+  __syncthreads();
+  const float mx = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
   float sum = 0.f;
   {
     const float kLog2e = 1.4426950408889634f, off = -mx * kLog2e;
@@ -284,47 +293,52 @@ __global__ __launch_bounds__(256) void k_row_select(RowSelectArgs a) {
     km = -INFINITY;
 #pragma unroll
     for (int q = 0; q < kRowRegs; ++q) {
-      const int n = 4 * (lane + 64 * q);
+      const int n = 4 * (tid + 256 * q);
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (n + e < V) z[q][e] += a.lambda * lmrow[n + e];
       km = fmaxf(km, fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3])));
     }
   }
-  // tau = a lower bound of the K-th largest key: K rounds of "largest remaining lane maximum"
+  // this wave's lower bound of the row's K-th largest key: K rounds of "largest remaining lane maximum"
   float tau = -INFINITY, cur = km;
   for (int j = 0; j < K; ++j) {
     tau = wave_max(cur);
     if (cur == tau) cur = -INFINITY;
   }
-  wave_sync();
-  // keys at or above tau (never -inf) are appended to the wave's list
+  if (lane == 0) {
+    s_sum[wave] = sum;
+    s_tau[wave] = tau;
+  }
+  __syncthreads();
+  tau = fmaxf(fmaxf(s_tau[0], s_tau[1]), fmaxf(s_tau[2], s_tau[3]));
+  // keys at or above tau (never -inf) are appended to the row's list
 #pragma unroll
   for (int q = 0; q < kRowRegs; ++q) {
     const float m4 = fmaxf(fmaxf(z[q][0], z[q][1]), fmaxf(z[q][2], z[q][3]));
     if (m4 >= tau && m4 > -INFINITY) {
-      const int n = 4 * (lane + 64 * q);
+      const int n = 4 * (tid + 256 * q);
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (z[q][e] >= tau && z[q][e] > -INFINITY) {
-          const int pos = atomicAdd(&surv_n[wave], 1);
-          if (pos < kSurvivorCap) surv[wave][pos] = pack_cand(z[q][e], n + e);
+          const int pos = atomicAdd(&surv_n, 1);
+          if (pos < kSurvivorCap) surv[pos] = pack_cand(z[q][e], n + e);
         }
     }
   }
-  wave_sync();
-  const int total = surv_n[wave];
+  __syncthreads();
+  const int total = surv_n;
   uint64_t *out = a.p_cand + (size_t)m * K;
   if (total <= kSurvivorCap) {
     // rank of every collected key = number of collected keys ahead of it (packed keys are distinct)
-    if (lane < K && lane >= total) out[lane] = no_cand();
-    for (int i = lane; i < total; i += 64) {
-      const uint64_t mine = surv[wave][i];
+    if (tid < K && tid >= total) out[tid] = no_cand();
+    for (int i = tid; i < total; i += 64 * kRowWaves) {
+      const uint64_t mine = surv[i];
       int rank = 0;
-      for (int j = 0; j < total; ++j) rank += surv[wave][j] > mine;
+      for (int j = 0; j < total; ++j) rank += surv[j] > mine;
       if (rank < K) out[rank] = mine;
     }
-  } else {
+  } else if (wave == 0) {
     // more than kSurvivorCap keys at or above tau (many equal keys): K plain rounds over the row in memory
     uint64_t last = ~0ull;
     for (int j = 0; j < K; ++j) {
@@ -340,11 +354,12 @@ __global__ __launch_bounds__(256) void k_row_select(RowSelectArgs a) {
       last = best > no_cand() ? best : no_cand() + 1;
     }
   }
-  if (lane == 0) {
+  if (tid == 0) {
     a.p_max[m] = mx;
-    a.p_sum[m] = sum;
+    a.p_sum[m] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
   }
-  // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; a lane takes 8 consecutive k
+  // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; wave 3, a lane takes 8 k
+  if (wave != kRowWaves - 1) return;
   const int nz = 1 + a.ND;
   float acc[9];
 #pragma unroll

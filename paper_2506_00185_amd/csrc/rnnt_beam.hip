@@ -456,7 +456,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
       a.finished = h->finished; a.done = done;
       ScopedKernelTime tm(h, s, KT_ROWSELECT);
-      hipLaunchKernelGGL(k_row_select, dim3((p.M + 3) / 4), dim3(256), 0, s, a);
+      hipLaunchKernelGGL(k_row_select, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
     }
     RB_HIP(h, hipGetLastError());
     {
@@ -718,7 +718,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   h->M_max = c.max_B * c.max_beam;
   h->Mp = (h->M_max + 31) / 32 * 32 + 32;  // a joint tile may start at any multiple of K and reads 32 rows
   {
-    const bool can = c.prec == RNNT_BF16_JOINT && c.pred == RNNT_PRED_STATELESS && c.V <= 64 * 4 * kRowRegs &&
+    const bool can = c.prec == RNNT_BF16_JOINT && c.pred == RNNT_PRED_STATELESS && c.V <= kRowWaves * 64 * 4 * kRowRegs &&
                      c.H % 16 == 0;
     if (c.joint_path == RNNT_JOINT_MATERIALIZED && !can)
       return bad("joint_path MATERIALIZED needs the bf16 joint, a stateless prediction network, V <= 8192, H % 16 == 0");
