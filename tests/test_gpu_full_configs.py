@@ -60,3 +60,33 @@ def test_workload_at_full_size(oracle, cid, variant, rows, tol, tie):
     print(f"config {cid} {variant}: {full} of {len(rows)} sampled utterances identical end to end, "
           f"{exempt} left the oracle's path after a near tie (< {tie})")
     assert full + exempt == len(rows)
+
+
+@pytest.mark.parametrize("name,over,rows", [
+    ("c2_beam12_wide_selection", dict(beam=12), [0, 13, 31]),
+    ("c2_beam1_greedy", dict(beam=1), list(range(0, 32, 4))),
+    ("c3_tdt_alsd_beam6", dict(algo="alsd", gamma=float("inf"), beam=6), [0, 21, 42, 63]),
+    ("c4_eq3_early_pruning", dict(), [5, 20]),
+])
+def test_variants_of_the_workloads_at_full_size(oracle, name, over, rows):
+    """Shapes the benchmark's sweeps run beside the five workloads: a beam above 8 (selection in several
+    passes, a launch of its own), beam 1, TDT under ALSD++, and LM fusion by Eq. (3) with early pruning."""
+    import paper_2506_00185_amd as A
+    cid = int(name[1])
+    c = S.config(cid, **over)
+    w = S.make_weights(c)
+    L = S.make_lengths(c)
+    enc = S.make_enc(c, L)
+    glm = olm = None
+    kw_g, kw_o = {}, {}
+    if c["lm"]:
+        lm = S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"], 1000 * cid + 3)
+        glm, olm = A.NGramLM(lm), oracle.LM(lm)
+        kw_g, kw_o = dict(lm_rule=3, lm_prune="early"), dict(lm_rule=3, lm_prune="early")
+    dec = A.BeamDecoder(c, w, **kw_g)
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=c["lm_weight"])
+    assert g["rc"] == 0
+    o = oracle.decode(dict(c, B=len(rows)), w, enc[rows], L[rows], lm=olm, lm_weight=c["lm_weight"], log=True, **kw_o)
+    full, exempt = compare(g, o, 1e-3, 1e-4, rows=rows)
+    print(f"{name}: {full} of {len(rows)} sampled utterances identical end to end, {exempt} exempt after a near tie")
+    assert full + exempt == len(rows) and full >= 1
