@@ -882,7 +882,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   if (role < 0) return;
   if (role == 1) {
     recurrent_tile<WAVES, ITERS>(a.rec, chunk, ty, done, red);
-    RB_BLOCK_TS(1);
+    if (!done) RB_BLOCK_TS(1);
     return;
   }
 
