@@ -31,7 +31,7 @@ class _Config(C.Structure):
     _fields_ = [("model", C.c_int32), ("pred", C.c_int32), ("prec", C.c_int32),
                 ("D", C.c_int32), ("H", C.c_int32), ("P", C.c_int32), ("E", C.c_int32), ("V", C.c_int32),
                 ("n_dur", C.c_int32), ("durations", C.c_int32 * 8), ("ctx", C.c_int32),
-                ("max_symbols", C.c_int32), ("lm_rule", C.c_int32), ("lm_prune", C.c_int32), ("gamma", C.c_double)]
+                ("max_symbols", C.c_int32), ("lm_rule", C.c_int32), ("lm_prune", C.c_int32), ("tdt_pairs", C.c_int32), ("gamma", C.c_double)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -83,6 +83,7 @@ def make_config(c: dict, lm_rule: int = 4, lm_prune: str = "late") -> _Config:
     cfg.max_symbols = c["s"]
     cfg.lm_rule = lm_rule
     cfg.lm_prune = {"late": 0, "early": 1}[lm_prune]
+    cfg.tdt_pairs = 1 if c.get("tdt_pairs") else 0
     cfg.gamma = c["gamma"]
     return cfg
 
@@ -230,7 +231,7 @@ def score_row(c, z=None, logp=None, dlogp=None, lm_row=None, lm_weight=0.0, lm_r
     lm_a = _f64(lm_row) if lm_row is not None else None
     lib().orc_score_row(C.byref(cfg), _ptr(z_a), _ptr(lp_in), _ptr(dl_in), _ptr(lm_a), C.c_double(lm_weight),
                         C.c_int(int(apply_gamma)), C.c_int(int(forced_blank)), _ptr(tot), _ptr(lp),
-                        C.byref(a1), C.byref(a2), None)
+                        C.byref(a1), C.byref(a2), None, None)
     return tot, lp, a1.value, a2.value
 
 

@@ -51,6 +51,9 @@ typedef struct {
   int32_t lm_prune;    /* 0 = late pruning: the Beam best are chosen on the fused scores;
                           1 = early pruning: they are chosen on the Transducer's scores alone and the
                           chosen ones are then rescored with the LM (Sec. 2.3, "Early/late pruning") */
+  int32_t tdt_pairs;   /* TDT: 0 = one duration per candidate (the most likely one; for blank the most likely one
+                          that advances); 1 = every (symbol, duration) pair is a candidate of its own, blank only
+                          with durations >= 1 */
   double gamma;        /* prune margin on log-probability, INFINITY = off */
 } orc_config;
 
@@ -328,10 +331,12 @@ void orc_lm_query(const orc_lm *lm, const int32_t *tokens, int len, int V, doubl
  * already normalised log-probabilities (injected mode).
  * gap_out (nullable) is lowered to the smallest margin by which a duration
  * argmax was decided.
+ * dl_out (nullable, TDT): the duration log-probabilities are returned there and NOT
+ * added to tot (every (symbol, duration) pair is then a candidate of the caller's).
  */
 void orc_score_row(const orc_config *c, const double *z, const double *logp_in, const double *dlogp_in,
                    const double *lm, double lambda, int apply_gamma, int forced_blank, double *tot,
-                   double *logp_out, int *adv_tok, int *adv_blank, double *gap_out) {
+                   double *logp_out, int *adv_tok, int *adv_blank, double *gap_out, double *dl_out) {
   const int V = c->V;
   double *logp = logp_out;
   double nb = 0.0;
@@ -374,6 +379,10 @@ void orc_score_row(const orc_config *c, const double *z, const double *logp_in, 
     } else {
       double l = logsumexp(z + V + 1, c->n_dur);
       for (int d = 0; d < c->n_dur; ++d) dl[d] = z[V + 1 + d] - l;
+    }
+    if (dl_out) {
+      for (int d = 0; d < c->n_dur; ++d) dl_out[d] = dl[d];
+      return;
     }
     int best = -1, best_b = -1;
     for (int d = 0; d < c->n_dur; ++d) {
@@ -550,10 +559,15 @@ static void decode_utterance(utt_job *J) {
   }
   if (J->lm) orc_lm_query(J->lm, cur[0].tok, 0, V, cur[0].lm);
 
-  const int64_t n_cand = (int64_t)K * (V + 1);
+  /* candidate (k, v[, d]) has index (k (V+1) + v) [* n_dur + d]: the order in which ties are broken */
+  const int pairs = c->model == 1 && c->tdt_pairs;
+  const int nd = pairs ? c->n_dur : 1;
+  const int64_t n_kv = (int64_t)K * (V + 1);
+  const int64_t n_cand = n_kv * nd;
   cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)n_cand);
-  double *unpruned = (double *)malloc(sizeof(double) * (size_t)n_cand);
-  double *rowlogp = (double *)malloc(sizeof(double) * (size_t)n_cand);
+  double *unpruned = (double *)malloc(sizeof(double) * (size_t)n_kv);
+  double *rowlogp = (double *)malloc(sizeof(double) * (size_t)n_kv);
+  double dl[8], dl2[8];
   double *z = (double *)malloc(sizeof(double) * (size_t)N);
   double *tot = (double *)malloc(sizeof(double) * (size_t)(V + 1));
   double *logp = (double *)malloc(sizeof(double) * (size_t)(V + 1));
@@ -586,6 +600,8 @@ static void decode_utterance(utt_job *J) {
       cand[i].key = -INFINITY;
       cand[i].val = -INFINITY;
       cand[i].idx = i;
+    }
+    for (int64_t i = 0; i < n_kv; ++i) {
       unpruned[i] = -INFINITY;
       rowlogp[i] = -INFINITY;
     }
@@ -599,8 +615,8 @@ static void decode_utterance(utt_job *J) {
       int active = hy->t < T_b && (J->algo == 0 || hy->t == t_cur);
       if (!active) {
         kind[k] = 1;
-        cand[(int64_t)k * (V + 1) + V].val = hy->score; /* stay */
-        cand[(int64_t)k * (V + 1) + V].key = hy->score;
+        cand[((int64_t)k * (V + 1) + V) * nd].val = hy->score; /* stay */
+        cand[((int64_t)k * (V + 1) + V) * nd].key = hy->score;
         continue;
       }
       kind[k] = 2;
@@ -615,15 +631,19 @@ static void decode_utterance(utt_job *J) {
           for (int d = 0; d < c->n_dur; ++d) tmp_in[V + 1 + d] = (double)drow[d];
         }
         orc_score_row(c, NULL, tmp_in, c->model == 1 ? tmp_in + V + 1 : NULL, J->lm ? hy->lm : NULL, J->lambda,
-                      use_gamma, forced, tot, logp, &adv_tok[k], &adv_blank[k], &step_gap);
+                      use_gamma, forced, tot, logp, &adv_tok[k], &adv_blank[k], &step_gap, pairs ? dl : NULL);
       } else {
         joint_impl(c, w, f_proj + (size_t)hy->t * H, hy->g, z, J->w_ready);
         orc_score_row(c, z, NULL, NULL, J->lm ? hy->lm : NULL, J->lambda, use_gamma, forced, tot, logp,
-                      &adv_tok[k], &adv_blank[k], &step_gap);
+                      &adv_tok[k], &adv_blank[k], &step_gap, pairs ? dl : NULL);
       }
       for (int v = 0; v <= V; ++v) {
-        cand[(int64_t)k * (V + 1) + v].val = hy->score + tot[v];
-        cand[(int64_t)k * (V + 1) + v].key = hy->score + tot[v];
+        for (int d = 0; d < nd; ++d) {
+          /* pairs: symbol v with duration d; blank must advance at least one frame */
+          double x = pairs ? ((v == V && c->durations[d] < 1) ? -INFINITY : dl[d]) : 0.0;
+          cand[((int64_t)k * (V + 1) + v) * nd + d].val = hy->score + tot[v] + x;
+          cand[((int64_t)k * (V + 1) + v) * nd + d].key = hy->score + tot[v] + x;
+        }
         rowlogp[(int64_t)k * (V + 1) + v] = logp[v];
         if (logp[v] > rowmax[k]) rowmax[k] = logp[v];
         if (logp[v] > J->max_logp) J->max_logp = logp[v];
@@ -636,23 +656,27 @@ static void decode_utterance(utt_job *J) {
         double *lp2 = (double *)malloc(sizeof(double) * (size_t)(V + 1));
         if (injected)
           orc_score_row(c, NULL, tmp_in, c->model == 1 ? tmp_in + V + 1 : NULL, NULL, 0.0, use_gamma, forced, tot_asr,
-                        lp2, &a1, &a2, NULL);
+                        lp2, &a1, &a2, NULL, pairs ? dl2 : NULL);
         else
-          orc_score_row(c, z, NULL, NULL, NULL, 0.0, use_gamma, forced, tot_asr, lp2, &a1, &a2, NULL);
-        for (int v = 0; v <= V; ++v) cand[(int64_t)k * (V + 1) + v].key = hy->score + tot_asr[v];
+          orc_score_row(c, z, NULL, NULL, NULL, 0.0, use_gamma, forced, tot_asr, lp2, &a1, &a2, NULL, pairs ? dl2 : NULL);
+        for (int v = 0; v <= V; ++v)
+          for (int d = 0; d < nd; ++d) {
+            double x = pairs ? ((v == V && c->durations[d] < 1) ? -INFINITY : dl2[d]) : 0.0;
+            cand[((int64_t)k * (V + 1) + v) * nd + d].key = hy->score + tot_asr[v] + x;
+          }
         free(tot_asr);
         free(lp2);
       }
-      if (use_gamma && isfinite(c->gamma) && !forced) {
+      if (use_gamma && isfinite(c->gamma) && !forced && !pairs) {
         /* what the candidates would have been worth without the margin, for the near-tie report */
         int a1, a2;
         double *tot2 = (double *)malloc(sizeof(double) * (size_t)(V + 1));
         double *lp2 = (double *)malloc(sizeof(double) * (size_t)(V + 1));
         if (injected)
           orc_score_row(c, NULL, tmp_in, c->model == 1 ? tmp_in + V + 1 : NULL, J->lm ? hy->lm : NULL, J->lambda, 0,
-                        forced, tot2, lp2, &a1, &a2, NULL);
+                        forced, tot2, lp2, &a1, &a2, NULL, NULL);
         else
-          orc_score_row(c, z, NULL, NULL, J->lm ? hy->lm : NULL, J->lambda, 0, forced, tot2, lp2, &a1, &a2, NULL);
+          orc_score_row(c, z, NULL, NULL, J->lm ? hy->lm : NULL, J->lambda, 0, forced, tot2, lp2, &a1, &a2, NULL, NULL);
         for (int v = 0; v <= V; ++v) unpruned[(int64_t)k * (V + 1) + v] = hy->score + tot2[v];
         free(tot2);
         free(lp2);
@@ -668,7 +692,7 @@ static void decode_utterance(utt_job *J) {
       }
     for (int64_t i = K; i < n_cand; ++i)
       if (isfinite(cand[i].key)) J->n_cut++; else break;
-    if (J->algo == 1 && isfinite(c->gamma)) {
+    if (J->algo == 1 && isfinite(c->gamma) && !pairs) {
       /* a token close to the margin whose candidate could have entered the beam is a near tie too */
       double thr = (K - 1 < n_cand && isfinite(cand[K - 1].val)) ? cand[K - 1].val : -INFINITY;
       for (int k = 0; k < K; ++k) {
@@ -698,7 +722,10 @@ static void decode_utterance(utt_job *J) {
         nh->sym = 0;
         nh->hash = 0;
       } else {
-        int k = (int)(cand[j].idx / (V + 1)), v = (int)(cand[j].idx % (V + 1));
+        const int64_t kv = cand[j].idx / nd;
+        const int dsel = (int)(cand[j].idx % nd);
+        int k = (int)(kv / (V + 1)), v = (int)(kv % (V + 1));
+        if (pairs) adv_tok[k] = adv_blank[k] = c->durations[dsel]; /* the pair's own duration */
         hyp_copy(nh, &cur[k], c);
         nh->score = cand[j].val;
         lp = k;

@@ -115,8 +115,11 @@ def duration_rule(dlogp, durations):
     return durations[best], dlogp[best], durations[best_b], dlogp[best_b]
 
 
-def enumerate_alignments(logp_fn, T, V, s, durations=()):
+def enumerate_alignments(logp_fn, T, V, s, durations=(), pairs=False):
     """Sum of alignment probabilities per transcript, by depth-first enumeration.
+
+    ``pairs`` (TDT): every (symbol, duration) pair is a step of its own, blank only with
+    durations >= 1, instead of one duration per symbol chosen by ``duration_rule``.
 
     ``logp_fn(t, tokens) -> (logp [V+1], dlogp or None)``.  An alignment ends
     when it has consumed T frames; at most ``s`` tokens are emitted without
@@ -130,6 +133,14 @@ def enumerate_alignments(logp_fn, T, V, s, durations=()):
             totals[toks] = logaddexp(totals.get(toks, -math.inf), lp)
             return
         logp, dlogp = logp_fn(t, toks)
+        if durations and pairs:
+            for i, d in enumerate(durations):
+                if d >= 1:
+                    rec(min(t + d, T), toks, 0, lp + logp[V] + dlogp[i])
+                if sym < s:
+                    for v in range(V):
+                        rec(min(t + d, T), toks + (v,), sym + 1 if d == 0 else 0, lp + logp[v] + dlogp[i])
+            return
         if durations:
             adv_tok, x_tok, adv_blank, x_blank = duration_rule(dlogp, durations)
         else:

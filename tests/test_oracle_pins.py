@@ -558,3 +558,33 @@ def test_early_pruning_with_a_real_beam_equals_the_two_stage_loop(oracle, small_
     assert got.keys() == want.keys()
     for k in got:
         assert abs(got[k] - want[k]) < 1e-9
+
+
+# ------------------------------------------- TDT with every (symbol, duration) pair as a candidate
+
+@pytest.mark.parametrize("algo", ["alsd", "aes"])
+def test_tdt_pairs_unpruned_equals_enumeration_over_pairs(oracle, algo):
+    c, w, L, enc = _small(66, model="tdt", durations=(0, 1, 2), V=2, T=3, s=2, beam=8192, algo=algo, tdt_pairs=True)
+    fn = _ref_logp_fn(c, w, enc[0])
+    want = enumerate_alignments(fn, 3, 2, 2, durations=(0, 1, 2), pairs=True)
+    r = oracle.decode(c, w, enc, L)
+    assert r["n_cut"][0] == 0 and r["collisions"][0] == 0
+    got = _nbest(r)
+    assert set(got) == set(want) and len(want) > 10
+    for y, sc in want.items():
+        assert abs(got[y] - sc) < 1e-9, (y, got[y], sc)
+    # more probability mass than with one duration per symbol, which drops every other pair
+    one = _nbest(oracle.decode(dict(c, tdt_pairs=False), w, enc, L))
+    assert all(got[y] > one[y] - 1e-12 for y in one) and any(got[y] > one[y] + 1e-6 for y in one)
+    assert sum(math.exp(v) for v in got.values()) <= 1.0 + 1e-12
+
+
+def test_tdt_pairs_beam_one_equals_the_one_duration_rule(oracle):
+    """The best pair of a hypothesis is (best symbol, its best duration): at beam 1 the two rules coincide."""
+    c, w, L, enc = _small(67, model="tdt", durations=(0, 1, 2, 3), V=9, T=12, s=2, beam=1)
+    a = oracle.decode(c, w, enc, L)
+    b = oracle.decode(dict(c, tdt_pairs=True), w, enc, L)
+    np.testing.assert_array_equal(a["tokens"], b["tokens"])
+    np.testing.assert_allclose(a["scores"], b["scores"], atol=1e-12)
+    toks, score = greedy(_ref_logp_fn(c, w, enc[0]), 12, 9, 2, durations=(0, 1, 2, 3))
+    assert tuple(b["tokens"][0, 0, : b["lens"][0, 0]]) == toks and abs(b["scores"][0, 0] - score) < 1e-9

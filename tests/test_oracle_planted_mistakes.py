@@ -43,6 +43,10 @@ MISTAKES = [
     ("bf16 rounding truncates", "u += 0x7fffu + lsb;", "u += 0;"),
     ("early pruning ranks by the fused score",
      "for (int v = 0; v <= V; ++v) cand[(int64_t)k * (V + 1) + v].key = hy->score + tot_asr[v];", ""),
+    ("blank may stand still when every pair is a candidate",
+     "double x = pairs ? ((v == V && c->durations[d] < 1) ? -INFINITY : dl[d]) : 0.0;", "double x = pairs ? dl[d] : 0.0;"),
+    ("a pair advances by the best duration instead of its own",
+     "if (pairs) adv_tok[k] = adv_blank[k] = c->durations[dsel]; /* the pair's own duration */", ""),
     ("early pruning keeps the Transducer's score as the new score", "nh->score = cand[j].val;", "nh->score = cand[j].key;"),
 ]
 
