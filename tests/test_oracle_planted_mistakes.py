@@ -42,7 +42,7 @@ MISTAKES = [
      "for (int v = 0; v < V; ++v)\n      if (logp[v] < mx - c->gamma) tot[v] = -INFINITY;"),
     ("bf16 rounding truncates", "u += 0x7fffu + lsb;", "u += 0;"),
     ("early pruning ranks by the fused score",
-     "for (int v = 0; v <= V; ++v) cand[(int64_t)k * (V + 1) + v].key = hy->score + tot_asr[v];", ""),
+     "cand[((int64_t)k * (V + 1) + v) * nd + d].key = hy->score + tot_asr[v] + x;", ""),
     ("blank may stand still when every pair is a candidate",
      "double x = pairs ? ((v == V && c->durations[d] < 1) ? -INFINITY : dl[d]) : 0.0;", "double x = pairs ? dl[d] : 0.0;"),
     ("a pair advances by the best duration instead of its own",
