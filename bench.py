@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch the step kernels one by one")
     ap.add_argument("--lm-rule", type=int, default=4, choices=[3, 4], help="LM fusion rule (workloads with an LM)")
     ap.add_argument("--lm-prune", default="late", choices=["late", "early"])
+    ap.add_argument("--tdt-pairs", action="store_true", help="TDT workloads: every (symbol, duration) pair a candidate")
+    ap.add_argument("--algo", default=None, choices=["alsd", "aes"], help="override the workload's search algorithm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-utts", type=int, default=16, help="utterances the oracle decodes for the CPU baseline")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -89,6 +91,13 @@ def main():
         print(json.dumps({"copy_calibration_MiB": args.copy_calibration, "bytes_read": n * 4, "bytes_written": n * 4}))
         return
     c = S.config(args.config, prec=args.variant if args.config == 2 else S.CONFIGS[args.config]["prec"])
+    if args.tdt_pairs:
+        assert c["model"] == "tdt", "--tdt-pairs needs a TDT workload (config 3)"
+        c["tdt_pairs"] = True
+    if args.algo:
+        c["algo"] = args.algo
+        if args.algo == "alsd":
+            c["gamma"] = float("inf")  # the prune margin belongs to AES++
     w = S.make_weights(c)
     L = S.make_lengths(c)
     enc = S.make_enc(c, L)
@@ -195,7 +204,8 @@ def main():
         "config": {"workload": c["name"] + ("" if c["prec"] == "f32" or args.config != 2 else "_bf16joint"),
                    "B": B, "T": T, "beam": K, "algo": c["algo"], "V": c["V"], "max_symbols": c["s"],
                    "graph": not args.no_graph, "audio_s_per_pass": audio_s,
-                   **({"lm_rule": args.lm_rule, "lm_prune": args.lm_prune} if c["lm"] else {})},
+                   **({"lm_rule": args.lm_rule, "lm_prune": args.lm_prune} if c["lm"] else {}),
+                   **({"tdt_pairs": True} if c.get("tdt_pairs") else {})},
         "beam_search_steps": n_steps, "us_per_beam_step": round(gpu_ms * 1e3 / max(n_steps, 1), 3),
         "gpu_ms_per_pass": round(gpu_ms, 4), "beam1_ms_per_pass": round(ms_beam1, 4),
         "beam_over_greedy": round(ms / ms_beam1, 4), "joint_launch_mfma_util": round(joint_util, 5),

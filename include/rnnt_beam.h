@@ -79,6 +79,10 @@ typedef struct {
   int32_t lm_early_pruning;  /* 0 = late pruning: the Beam best are chosen on the fused scores; 1 = early pruning:
                                 they are chosen on the Transducer's scores, the chosen ones then get the LM term
                                 (Sec. 2.3, "Early/late pruning") */
+  int32_t tdt_all_pairs;     /* TDT only.  0: a candidate is a symbol with ONE duration, the most likely one (for blank
+                                the most likely one that advances).  1: every (symbol, duration) pair is a candidate
+                                of its own, blank only with durations >= 1: Beam x (V + 1) x n_durations candidates
+                                per utterance and step.  Needs max_beam <= 8 */
 } rnnt_config_t;
 
 /* Device pointers, float32, caller-owned.  Unused ones may be NULL. */

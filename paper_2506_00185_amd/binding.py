@@ -29,7 +29,7 @@ class _Config(C.Structure):
                 ("n_durations", C.c_int32), ("durations", C.c_int32 * 8), ("stateless_context", C.c_int32),
                 ("max_B", C.c_int32), ("max_T", C.c_int32), ("max_beam", C.c_int32), ("max_symbols", C.c_int32),
                 ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32),
-                ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32)]
+                ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32), ("tdt_all_pairs", C.c_int32)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -147,6 +147,7 @@ class BeamDecoder:
         cfg.joint_path = {"auto": 0, "fused": 1, "materialized": 2}[joint_path]
         cfg.lm_rule = lm_rule
         cfg.lm_early_pruning = {"late": 0, "early": 1}[lm_prune]
+        cfg.tdt_all_pairs = 1 if c.get("tdt_pairs") else 0
         self.cfg = cfg
         self._w = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
                    for k, v in w.items()}

@@ -269,10 +269,11 @@ __device__ __forceinline__ float logaddexp_f(float a, float b) {
 }
 
 // LDS scratch of one wave while it handles one utterance
-struct SelectScratch {
+template <int CAND>
+struct SelectScratchT {
   double score[kMaxBeam];
-  double rc_val[kMaxBeam * (kMaxBeam + 1)];
-  double rc_key[kMaxBeam * (kMaxBeam + 1)];  // early pruning only: what the candidates are ranked by
+  double rc_val[CAND];
+  double rc_key[CAND];  // early pruning only: what the candidates are ranked by
   double sel_val[kMaxBeam];
   double n_score[kMaxBeam];
   uint64_t win[kMaxBeam][kMaxBeam];
@@ -280,11 +281,16 @@ struct SelectScratch {
   uint32_t hash[kMaxBeam];
   int ctx[kMaxBeam][kCtxMax];
   int advt[kMaxBeam], advb[kMaxBeam];
-  int rc_flat[kMaxBeam * (kMaxBeam + 1)];
+  int rc_flat[CAND];
   int sel_flat[kMaxBeam];
   int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
   uint32_t n_hash[kMaxBeam];
 };
+// K (K + 1) candidates per utterance: K tokens and blank / stay of every hypothesis
+typedef SelectScratchT<kMaxBeam * (kMaxBeam + 1)> SelectScratch;
+// TDT with every (symbol, duration) pair as a candidate: K (K + 1) ND of them, for beams up to 8
+constexpr int kPairsMaxBeam = 8;
+typedef SelectScratchT<kPairsMaxBeam * (kPairsMaxBeam + 1) * 8> SelectScratchPairs;
 
 // the lanes of one wave see each other's LDS writes after this (they run in lockstep; this
 // only stops the compiler and the memory pipeline from re-ordering)
@@ -312,8 +318,10 @@ __device__ __forceinline__ uint32_t mod_mersenne31(uint64_t x) {
 // scanned in memory at every round instead (any size).
 // MULTI: the beam may be wider than the 64 / LPR hypotheses handled at once; the per-hypothesis part then
 // runs in several passes.
-template <int LPR, int NCH, int KMAX, bool MULTI = false>
-__device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
+// PAIRS (TDT): every (symbol, duration) pair of a hypothesis is a candidate of its own (blank only with
+// durations >= 1) instead of one duration per symbol; candidate (k, j, d) sits at ((k (K + 1) + j) ND + d.
+template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch>
+__device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
   const int nz = 1 + a.ND;
@@ -458,7 +466,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
     const double logp_b = (double)zb - (double)lse_all;
     const double nb = (double)lse_nb - (double)lse_all;
     const double maxlogp = (double)fmaxf(max_nb, zb) - (double)lse_all;
-    // TDT: one duration per candidate
+    // TDT durations
     double x_tok = 0.0, x_blank = 0.0;
     int adv_tok = 0, adv_blank = 1;
     if (a.ND > 0) {
@@ -474,10 +482,12 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         if (best < 0 || dl[d] > dl[best]) best = d;
         if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
       }
-      x_tok = (double)dl[best];
-      x_blank = (double)dl[best_b];
-      adv_tok = a.dur[best];
-      adv_blank = a.dur[best_b];
+      if constexpr (!PAIRS) {  // one duration per candidate: the most likely one (for blank: that advances)
+        x_tok = (double)dl[best];
+        x_blank = (double)dl[best_b];
+        adv_tok = a.dur[best];
+        adv_blank = a.dur[best_b];
+      }
     }
     wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
     // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
@@ -493,6 +503,26 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       const double lm_const = (a.has_lm && !a.lm_rule3) ? (double)a.lambda * nb : 0.0;
       const double tok_base = x_tok - (double)lse_all;
       const bool early = a.lm_early != 0;
+      // where candidate (hypothesis rk, j-th symbol[, duration d]) goes and how it is numbered for the tie-break
+      const int nd = PAIRS ? a.ND : 1;
+      auto put = [&](int j, int token, double key, double val) {
+        if constexpr (PAIRS) {
+          for (int d = 0; d < nd; ++d) {
+            // blank must advance by at least one frame; a waiting hypothesis is the single candidate d = 0
+            const bool ok = key > -INFINITY && (kind == 1 ? d == 0 : (token < V || a.dur[d] >= 1));
+            const double x = kind == 1 ? 0.0 : (double)dl[d];
+            const int c = (rk * (K + 1) + j) * nd + d;
+            s.rc_val[c] = ok ? val + x : -INFINITY;
+            if (early) s.rc_key[c] = ok ? key + x : -INFINITY;
+            s.rc_flat[c] = ((flat0 + token) << 3) | d;
+          }
+        } else {
+          const int c = rk * (K + 1) + j;
+          s.rc_val[c] = val;
+          if (early) s.rc_key[c] = key;
+          s.rc_flat[c] = flat0 + token;
+        }
+      };
 #pragma unroll
       for (int i = 0; i < kMine; ++i) {
         const int j = e + LPR * i;
@@ -508,9 +538,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
               if (early) val += (double)a.lambda * (double)a.lm_rows[(size_t)(m_base + rk) * V + wi];
             }
           }
-          s.rc_val[rk * (K + 1) + j] = val;
-          if (early) s.rc_key[rk * (K + 1) + j] = key;
-          s.rc_flat[rk * (K + 1) + j] = flat0 + (wi < V ? wi : V - 1);
+          put(j, wi < V ? wi : V - 1, key, val);
         }
       }
       if (e == LPR - 1) {  // blank / stay: the group's last lane (least loaded with winners)
@@ -525,9 +553,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         } else if (kind == 1) {
           val = key = sc;  // a waiting or finished hypothesis stays as it is
         }
-        s.rc_val[rk * (K + 1) + K] = val;
-        if (early) s.rc_key[rk * (K + 1) + K] = key;
-        s.rc_flat[rk * (K + 1) + K] = flat0 + V;
+        put(K, V, key, val);
       }
     }
     wave_sync();
@@ -573,7 +599,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
 
   // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
   // value is the new score itself except under early pruning
-  const int n = K * (K + 1);
+  const int n = K * (K + 1) * (PAIRS ? a.ND : 1);
   const double *rank_of = a.lm_early ? s.rc_key : s.rc_val;
   if (n <= 64) {
     // few candidates: each lane counts how many come before its own; that count is its new slot
@@ -632,7 +658,10 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
       s.n_last[j] = -1;
       s.n_hash[j] = 0;
     } else {
-      const int k = s.sel_flat[j] >> kFlatShift, v = s.sel_flat[j] & ((1 << kFlatShift) - 1);
+      const int kv = PAIRS ? s.sel_flat[j] >> 3 : s.sel_flat[j];
+      const int k = kv >> kFlatShift, v = kv & ((1 << kFlatShift) - 1);
+      const int adv_b = PAIRS ? a.dur[s.sel_flat[j] & 7] : s.advb[k];  // frames the step advances: the pair's own
+      const int adv_t = PAIRS ? a.dur[s.sel_flat[j] & 7] : s.advt[k];  // duration, or the hypothesis' chosen one
       parent = k;
       int t = s.t[k], sym = s.sym[k], len = s.len[k], last = s.last[k];
       uint32_t hash = s.hash[k];
@@ -644,7 +673,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         code = -2;
       } else if (v == V) {
         code = -1;
-        t += s.advb[k];
+        t += adv_b;
         sym = 0;
       } else {
         code = v;
@@ -652,8 +681,8 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
         len += 1;
         last = v;
         hash = mod_mersenne31((uint64_t)hash * kHashBase + (uint64_t)(v + 1));
-        t += s.advt[k];
-        sym = s.advt[k] == 0 ? sym + 1 : 0;
+        t += adv_t;
+        sym = adv_t == 0 ? sym + 1 : 0;
 #pragma unroll
         for (int i = kCtxMax - 1; i > 0; --i) ctx_new[i] = ctx_new[i - 1];
         ctx_new[0] = v;
@@ -736,9 +765,17 @@ __device__ void select_utterance(const SelectArgs &a, int b, SelectScratch &s) {
 // FORMS: 0 = beams up to 8 (what the main kernel of a step runs in its tail); 1 = those plus wider beams
 // whose hypotheses come with a single list; 2 = wider beams with many lists (several passes, many
 // registers).  The heavy forms are kept out of the kernels that do not need them.
-template <int FORMS>
-__device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, SelectScratch &s) {
-  if constexpr (FORMS == 2) {
+template <int FORMS, class Scratch = SelectScratch>
+__device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s) {
+  if constexpr (FORMS == 3) {  // TDT, every (symbol, duration) pair a candidate, beams up to 8
+    if (a.K <= 4) {
+      if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4, false, true, Scratch>(a, b, s);
+      else select_utterance<16, 0, 4, false, true, Scratch>(a, b, s);
+    } else {
+      if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8, false, true, Scratch>(a, b, s);
+      else select_utterance<8, 0, 8, false, true, Scratch>(a, b, s);
+    }
+  } else if constexpr (FORMS == 2) {
     if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s);  // four hypotheses per pass
     else select_utterance<4, 0, 16>(a, b, s);
   } else {
@@ -1011,6 +1048,14 @@ __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
   const int wave = threadIdx.x >> 6;
   const int b = blockIdx.x * 4 + wave;
   if (b < a.B) select_dispatch<1>(a, b, scratch[wave]);
+}
+// two utterances per block: the candidate arrays of this form are larger
+__global__ __launch_bounds__(128) void k_select_pairs(SelectArgs a) {
+  __shared__ SelectScratchPairs scratch[2];
+  if (*reinterpret_cast<volatile int *>(a.done)) return;
+  const int wave = threadIdx.x >> 6;
+  const int b = blockIdx.x * 2 + wave;
+  if (b < a.B) select_dispatch<3, SelectScratchPairs>(a, b, scratch[wave]);
 }
 __global__ __launch_bounds__(256) void k_select_wide(SelectArgs a) {
   __shared__ SelectScratch scratch[4];

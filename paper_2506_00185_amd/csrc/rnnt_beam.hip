@@ -400,6 +400,13 @@ void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunk
   a.h_done = h->h_done_dev;
 }
 
+// stand-alone selection: which kernel takes this beam, list count and candidate rule
+void launch_select(rnnt_beam *h, hipStream_t s, const StepPlan &p, const SelectArgs &sa, int n_chunks) {
+  if (h->cfg.tdt_all_pairs) hipLaunchKernelGGL(k_select_pairs, dim3((p.B + 1) / 2), dim3(128), 0, s, sa);
+  else if (select_needs_wide_forms(p.K, n_chunks)) hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+  else hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+}
+
 // one beam-search step; cur = parity of the prediction-network state it reads
 int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, int cur, int bump) {
   const rnnt_config_t &c = h->cfg;
@@ -427,8 +434,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     SelectArgs sa;
     fill_select_args(h, p, step_off, 64, sa);
     ScopedKernelTime tm(h, s, KT_SELECT);
-    if (select_needs_wide_forms(p.K, 64)) hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
-    else hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+    launch_select(h, s, p, sa, 64);
   } else if (p.big) {
     constexpr int MS = 5;  // 160 hypotheses per block
     {
@@ -463,7 +469,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       SelectArgs sa;
       fill_select_args(h, p, step_off, 1, sa);
       ScopedKernelTime tm(h, s, KT_SELECT);
-      hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+      launch_select(h, s, p, sa, 1);
     }
   } else {
     MainArgs a;
@@ -492,7 +498,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     // The selection runs in the tail of this kernel for the beams its in-kernel forms take.  (Building the kernel
     // without it lets two blocks share a compute unit, but they also share its operand path: measured slower at
     // every shape, 11.3 vs 10.6 ms at B * beam = 256, beam 4.)
-    const bool tail = p.K <= 8;
+    const bool tail = p.K <= 8 && !c.tdt_all_pairs;
 #define RB_MAIN(W, I)                                                                              \
   do {                                                                                             \
     if (tail) hipLaunchKernelGGL((k_step_main<W, I, true>), grid, dim3(W * 64), 0, s, a);         \
@@ -508,10 +514,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     if (!tail) {
       RB_HIP(h, hipGetLastError());
       ScopedKernelTime tm(h, s, KT_SELECT);
-      if (select_needs_wide_forms(p.K, h->n_chunks))
-        hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, a.sel);
-      else
-        hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, a.sel);
+      launch_select(h, s, p, a.sel, h->n_chunks);
     }
   }
   RB_HIP(h, hipGetLastError());
@@ -709,6 +712,9 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   if (c.max_B < 1 || c.max_T < 1 || c.max_beam < 1 || c.max_beam > kMaxBeam) return bad("max_B/max_T/max_beam");
   if (c.max_symbols < 1) return bad("max_symbols < 1");
   if (c.lm_rule != 0 && c.lm_rule != 3 && c.lm_rule != 4) return bad("lm_rule must be 0, 3 or 4");
+  if (c.tdt_all_pairs != 0 && c.tdt_all_pairs != 1) return bad("tdt_all_pairs must be 0 or 1");
+  if (c.tdt_all_pairs && (c.model != RNNT_MODEL_TDT || c.max_beam > kPairsMaxBeam))
+    return bad("tdt_all_pairs needs a TDT model and max_beam <= 8");
   if (c.lm_early_pruning != 0 && c.lm_early_pruning != 1) return bad("lm_early_pruning must be 0 or 1");
   if (!(c.prune_margin >= 0.f)) return bad("prune_margin must be >= 0 (INFINITY = off)");
 

@@ -271,6 +271,45 @@ def test_lm_fusion_rules_and_early_pruning(amd, oracle, rule, prune, beam, algo)
     assert not np.allclose(o_default["scores"], o["scores"], atol=1e-6)
 
 
+# ------------------------------------------- TDT with every (symbol, duration) pair as a candidate
+
+@pytest.mark.parametrize("algo", ["alsd", "aes"])
+@pytest.mark.parametrize("beam,V", [(4, 37), (6, 9), (8, 3), (1, 20)])
+def test_injected_tdt_pairs_tree_is_bit_exact(amd, oracle, algo, beam, V):
+    durations = (0, 1, 2, 3, 4)
+    B, T, C = 5, 14, 6
+    c = S.custom_config(B=B, T=T, T_min=3, D=32, H=32, P=32, E=32, V=V, beam=beam, s=2, algo=algo, model="tdt",
+                        durations=durations, tdt_pairs=True)
+    L = S.make_lengths(c, 18)
+    L[1] = 0
+    L[2] = T
+    tok, dur = S.make_injected(B, T, C, V, len(durations), seed=beam * 100 + V + 1, levels=96 if V < 10 else 400,
+                               blank_boost=40)
+    dec = amd.BeamDecoder(c, S.make_weights(c, 1))
+    g = gpu_decode_injected(dec, tok, dur, L)
+    o = oracle.decode(c, None, None, L, injected=(tok, dur), log=True)
+    assert np.array_equal(g["n_steps"], o["n_steps"])
+    full, exempt = compare(g, o, tol=1e-9, tie=0.0, exact_tree=True)
+    assert full == B and exempt == 0
+    # the rule matters on this input
+    o1 = oracle.decode(dict(c, tdt_pairs=False), None, None, L, injected=(tok, dur))
+    assert beam == 1 or not np.array_equal(o1["scores"], o["scores"])
+
+
+@pytest.mark.parametrize("algo,beam", [("alsd", 4), ("aes", 8)])
+def test_tdt_pairs_with_the_networks(amd, oracle, algo, beam):
+    c = S.custom_config(B=4, T=20, T_min=8, D=128, H=160, P=160, E=160, V=300, beam=beam, s=2, algo=algo,
+                        model="tdt", durations=(0, 1, 2, 3, 4), blank_bias=3.0, tdt_pairs=True)
+    w, L, enc = _case(c, 1100 + beam)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 4 and full >= 2
+    with pytest.raises(RuntimeError, match="tdt_all_pairs"):
+        amd.BeamDecoder(dict(c, model="rnnt", durations=()), S.make_weights(dict(c, model="rnnt", durations=()), 3))
+
+
 # ------------------------------------------- logits through HBM (bf16 matrix-core joint)
 
 @pytest.mark.parametrize("name,kw,lm_w", [
