@@ -35,10 +35,11 @@ def compare(g, o, tol, tie, exact_tree=False, rows=None):
     """GPU result ``g`` against oracle result ``o`` (decoded with log=True).
 
     Per utterance: the trees (parent, token, merged_into of every live slot) must
-    be identical up to the first step at which the oracle took a decision by a
-    margin below ``tie``.  If they are identical throughout, step counts and
-    token sequences must be identical and scores within ``tol``.  An utterance
-    whose tree leaves the oracle's at or after such a near tie is exempt.
+    be identical up to a step at which the oracle took its decision by a margin
+    below ``tie``: the first step where the two trees differ must itself be such
+    a step.  If they are identical throughout, step counts and token sequences
+    must be identical and scores within ``tol``.  An utterance whose tree leaves
+    the oracle's at a near tie is exempt from there on.
     ``exact_tree``: no exemption at all.  ``rows``: GPU batch rows that the
     oracle rows correspond to.  Returns (n_full_match, n_exempt).
     """
@@ -64,8 +65,10 @@ def compare(g, o, tol, tie, exact_tree=False, rows=None):
         if diverged_at is None and ng != n:
             diverged_at = min(n, ng)
         if diverged_at is not None:
-            assert diverged_at >= first_tie, (
-                f"utterance {gb}: tree differs at step {diverged_at} before any near tie (first at {first_tie}); "
+            at = min(diverged_at, n - 1)
+            assert diverged_at >= first_tie and gaps[at] < tie, (
+                f"utterance {gb}: tree differs at step {diverged_at}, where the oracle's margin was {gaps[at]:.3g} "
+                f"(allowed below {tie}; first near tie at {first_tie}); "
                 f"oracle {o['log_parent'][ob, diverged_at]} {o['log_token'][ob, diverged_at]} "
                 f"gpu {g['parent'][diverged_at, gb]} {g['token'][diverged_at, gb]}")
             exempt += 1
