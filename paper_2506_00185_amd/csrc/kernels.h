@@ -1,6 +1,8 @@
 // Kernels of the per-step beam expansion (gfx950).  One step of the loop is
-//   k_joint (or k_inject) -> k_select -> [k_lm_rows] -> k_lstm -> k_pred_proj
-// and k_gemm_nt / k_init / k_backtrace run once per decode call.
+//   k_step_main (joint + selection in its tail + part of W_hh h) -> k_lstm_pointwise (+ LM rows) -> k_pred_proj
+// for LSTM models (k_stateless_pre instead of the last two for stateless ones; k_inject -> k_select when the
+// log-probabilities are injected; a stand-alone k_select / k_select_wide / k_select_pairs where the tail cannot
+// take the selection), and k_gemm_nt / k_init / k_backtrace run once per decode call.
 #pragma once
 #include "device_utils.h"
 #include "lm_device.h"
@@ -234,7 +236,7 @@ struct SelectArgs {
   uint32_t *hash;
   int *ctx;
   const int *lengths;
-  // candidate lists from k_joint / k_inject
+  // candidate lists from the joint (k_step_main, k_row_select) or k_inject
   const float *p_max, *p_sum;
   const uint64_t *p_cand;  // [M, n_chunks, K] packed (key, token), each chunk's list best first
   const float *zs;
