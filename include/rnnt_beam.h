@@ -125,11 +125,14 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
  * (values outside 0..T are clamped and reported as RNNT_E_ARG by rnnt_beam_results).
  * algo: RNNT_ALSD (length-synchronous, every unfinished hypothesis is expanded at every step) or
  * RNNT_AES (frame-synchronous, hypotheses that left the frame wait for the others).
- * lm may be NULL; with an LM the fused score is Eq. (4) of the paper (blank scored as
+ * lm may be NULL; with an LM the fused score is Eq. (4) of the paper by default (blank scored as
  * (1 + lambda) ln p(blank), tokens as ln p + lambda ln((1 - p(blank)) p_LM)), combined before the
- * beam is cut (late pruning).  An LM together with a finite prune_margin is rejected.
- * Work is enqueued on hip_stream (a hipStream_t, NULL = default stream); the call returns once
- * the data-dependent number of steps has been enqueued.  Results stay valid until the next decode.
+ * beam is cut (late pruning); the config fields lm_rule and lm_early_pruning select Eq. (3) and early
+ * pruning.  An LM together with a finite prune_margin is rejected.
+ * Work is enqueued on hip_stream (a hipStream_t, NULL = default stream) in chunks of 16 steps, at most
+ * two chunks ahead of the device; the call returns once the device has reported (through a pinned word)
+ * that every utterance has finished and the back-trace has been enqueued, i.e. it blocks the calling
+ * thread for most of the decode's duration.  Results stay valid until the next decode.
  */
 int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T,
                      int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream);
