@@ -177,6 +177,16 @@ int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t
 int rnnt_beam_debug_encproj(rnnt_beam_t *h, float *out, int64_t n_floats);
 int rnnt_lm_debug_query(const rnnt_lm_t *lm, const int32_t *ctx_tokens, int32_t n, float *out);
 
+/*
+ * Test hook for host logic, needs no GPU: the block -> work item mapping of the per-step launches.  A launch has
+ * two roles, each a grid of (n-tile, m-tile) items: role 0 with n-tiles [0, a_tiles) x a_m m-tiles, role 1 with
+ * n-tiles [b_begin, b_end) x b_m m-tiles.  Workgroup i runs on XCD i % 8, so every item of n-tile n gets a block
+ * index congruent to n modulo 8.  Returns the number of blocks to launch (a multiple of 8) and, for the first
+ * `cap` blocks, role (-1 = idle), n-tile and m-tile in the host arrays (each may be NULL).
+ */
+int rnnt_beam_debug_block_map(int32_t a_tiles, int32_t a_m, int32_t b_begin, int32_t b_end, int32_t b_m, int32_t *role,
+                              int32_t *ntile, int32_t *mtile, int32_t cap);
+
 /* Time, in milliseconds, between the first and the last kernel of the last decode (HIP events on
  * the decode's stream); negative if unavailable.  Synchronises. */
 float rnnt_beam_last_decode_ms(rnnt_beam_t *h);

@@ -16,11 +16,23 @@ ALSD, AES = 0, 1
 EXPORTS = ["rnnt_beam_create", "rnnt_lm_create", "rnnt_beam_decode", "rnnt_beam_results",
            "rnnt_beam_decode_injected", "rnnt_beam_dump_tree", "rnnt_beam_debug_encproj", "rnnt_lm_debug_query",
            "rnnt_beam_last_decode_ms", "rnnt_beam_set_profiling", "rnnt_beam_kernel_times", "rnnt_beam_last_error",
-           "rnnt_beam_destroy", "rnnt_lm_destroy"]
+           "rnnt_beam_destroy", "rnnt_lm_destroy", "rnnt_beam_debug_block_map"]
 
 
 class RnntBeamError(RuntimeError):
     pass
+
+
+def block_map(a_tiles, a_m, b_begin, b_end, b_m):
+    """Host logic, no GPU: (grid, role[], ntile[], mtile[]) of the per-step launches' block -> item mapping."""
+    lib = load_library()
+    n = lib.rnnt_beam_debug_block_map(a_tiles, a_m, b_begin, b_end, b_m, None, None, None, 0)
+    if n < 0:
+        raise RnntBeamError(f"rnnt_beam_debug_block_map: {n}")
+    role, nt, mt = (np.full(n, -7, np.int32) for _ in range(3))
+    lib.rnnt_beam_debug_block_map(a_tiles, a_m, b_begin, b_end, b_m, role.ctypes.data_as(C.c_void_p),
+                                  nt.ctypes.data_as(C.c_void_p), mt.ctypes.data_as(C.c_void_p), n)
+    return n, role, nt, mt
 
 
 class _Config(C.Structure):

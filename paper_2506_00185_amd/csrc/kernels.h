@@ -823,7 +823,7 @@ __host__ inline int xcd_grid(const XcdMap &m) {
   return 8 * most;
 }
 // role of block `bid` (0, 1, or -1 = nothing to do) and its item
-__device__ __forceinline__ int xcd_item(const XcdMap &m, int bid, int &ntile, int &mtile) {
+__host__ __device__ __forceinline__ int xcd_item(const XcdMap &m, int bid, int &ntile, int &mtile) {
   const int x = bid & 7;
   int s = bid >> 3;
   const int na = xcd_role_a_tiles(m, x) * m.a_m;

@@ -885,6 +885,22 @@ int rnnt_beam_debug_encproj(rnnt_beam_t *h, float *out, int64_t n_floats) {
   return RNNT_OK;
 }
 
+int rnnt_beam_debug_block_map(int32_t a_tiles, int32_t a_m, int32_t b_begin, int32_t b_end, int32_t b_m, int32_t *role,
+                              int32_t *ntile, int32_t *mtile, int32_t cap) {
+  if (a_tiles < 0 || a_m < 0 || b_begin < 0 || b_end < b_begin || b_m < 0) return RNNT_E_ARG;
+  XcdMap m;
+  m.a_tiles = a_tiles; m.a_m = a_m; m.b_begin = b_begin; m.b_end = b_end; m.b_m = b_m;
+  const int grid = xcd_grid(m);
+  for (int bid = 0; bid < grid && bid < cap; ++bid) {
+    int n = -1, mt = -1;
+    const int r = xcd_item(m, bid, n, mt);
+    if (role) role[bid] = r;
+    if (ntile) ntile[bid] = r < 0 ? -1 : n;
+    if (mtile) mtile[bid] = r < 0 ? -1 : mt;
+  }
+  return grid;
+}
+
 float rnnt_beam_last_decode_ms(rnnt_beam_t *h) {
   if (!h || !h->have_result) return -1.f;
   if (hipEventSynchronize(h->ev_end) != hipSuccess) return -1.f;

@@ -1,5 +1,6 @@
 """CPU-side checks of the C-ABI library: it loads and exports every function the
-header declares.  No compute call is made here."""
+header declares, fails loudly without a GPU, and its host logic (the block -> work item
+mapping of the per-step launches) is right.  No GPU call is made here."""
 import ctypes
 import os
 import re
@@ -58,3 +59,28 @@ def test_config_struct_matches_header_field_order():
         for n in names.split(","):
             fields.append(re.sub(r"\[.*\]", "", n).strip())
     assert fields == [f[0] for f in _Config._fields_]
+
+
+@pytest.mark.parametrize("a_tiles,a_m,b_begin,b_end,b_m", [(33, 4, 44, 80, 4), (20, 4, 0, 44, 4), (33, 8, 12, 80, 8),
+                                                           (64, 8, 0, 0, 0), (1, 1, 0, 0, 0), (3, 2, 5, 6, 7),
+                                                           (0, 0, 0, 80, 1), (9, 16, 79, 80, 12)])
+def test_block_map_covers_every_item_once_on_the_xcd_of_its_tile(a_tiles, a_m, b_begin, b_end, b_m):
+    """Host logic of the per-step launches: every (role, n-tile, m-tile) item exactly once, on a block whose index
+    is congruent to the n-tile modulo 8 (one weight slice, one L2), grid a multiple of 8 and no larger than
+    8 x the fullest XCD needs."""
+    from paper_2506_00185_amd.binding import block_map
+    grid, role, nt, mt = block_map(a_tiles, a_m, b_begin, b_end, b_m)
+    assert grid % 8 == 0
+    want = {(0, n, m) for n in range(a_tiles) for m in range(a_m)} | {(1, n, m) for n in range(b_begin, b_end)
+                                                                      for m in range(b_m)}
+    got = [(int(r), int(n), int(m)) for r, n, m in zip(role, nt, mt) if r >= 0]
+    assert len(got) == len(set(got)) == len(want) and set(got) == want
+    for bid, (r, n) in enumerate(zip(role, nt)):
+        if r >= 0:
+            assert n % 8 == bid % 8
+    per_xcd = [sum(1 for (r, n, m) in want if n % 8 == x) for x in range(8)]
+    assert grid == 8 * max(per_xcd)
+    # within an XCD the items of role 0 come before those of role 1 (what the selection tail's producers rely on)
+    for x in range(8):
+        roles = [int(role[b]) for b in range(x, grid, 8) if role[b] >= 0]
+        assert roles == sorted(roles)
