@@ -138,11 +138,16 @@ int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, i
                      int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream);
 
 /*
- * Wait for the last decode and copy its n-best lists to host memory: tokens [B, beam, cap]
+ * Wait for the last decode and copy its n-best lists to host memory.  The transcripts are read off the
+ * hypothesis tree by following the parent pointers back from the final slots (Sec. 2.1, "Efficient
+ * hypothesis storing"); no length normalisation is applied.  Host arrays, caller-owned: tokens [B, beam, cap]
  * (positions beyond the length are left untouched; transcripts longer than cap are truncated),
  * lens [B, beam] (-1 for an empty slot), scores [B, beam] (log-probability, -inf for an empty
  * slot), n_steps [B] (beam-search steps each utterance took).  Hypotheses are ordered by
- * (score descending, slot ascending).  Any pointer may be NULL.
+ * (score descending, slot ascending).  Any pointer may be NULL.  Returns RNNT_E_NORESULT before the first
+ * decode, RNNT_E_ARG if a length was outside 0..T (it was clamped; the results are those of the clamped
+ * lengths), RNNT_E_NONFINITE if the encoder projection held NaN or Inf (results undefined), RNNT_E_HIP on
+ * a failed HIP call.
  */
 int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *lens, double *scores,
                       int32_t *n_steps);
