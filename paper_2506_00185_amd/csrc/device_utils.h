@@ -54,6 +54,15 @@ __device__ __forceinline__ T load_agent(const T *p) {
   return __hip_atomic_load(const_cast<T *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Results that only a LATER launch reads.  A plain store leaves its line dirty in the XCD's L2, and the end of
+// every kernel waits until all dirty lines have been written back (the L2s of the XCDs are not coherent with each
+// other, so that is how one launch's output becomes visible to the next).  Writing through at once takes that
+// wait off the chain of dependent launches: 20.0 -> 19.5 ms per decode at 2 061 launches.
+template <typename T>
+__device__ __forceinline__ void store_through(T *p, T v) {
+  store_agent(p, v);
+}
+
 // Candidate order used everywhere a "best" is chosen: larger value first, then
 // smaller index.  Returns true if (v1, i1) comes before (v2, i2).
 template <typename V, typename I>

@@ -565,8 +565,8 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
     if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
       if (lane < K) {
-        a.src_row[m_base + lane] = m_base + lane;
-        a.tok[m_base + lane] = -1;
+        store_through(a.src_row + m_base + lane, m_base + lane);
+        store_through(a.tok + m_base + lane, -1);
       }
       return false;
     }
@@ -727,23 +727,24 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       }
     }
     const int m = m_base + j;
-    a.score[m] = score;
-    a.t[m] = s.n_t[j];
-    a.sym[m] = s.n_sym[j];
-    a.len[m] = s.n_len[j];
-    a.last[m] = s.n_last[j];
-    a.hash[m] = s.n_hash[j];
+    // written through (see store_through): nothing of a step's results waits in an L2 for the kernel's end
+    store_through(a.score + m, score);
+    store_through(a.t + m, s.n_t[j]);
+    store_through(a.sym + m, s.n_sym[j]);
+    store_through(a.len + m, s.n_len[j]);
+    store_through(a.last + m, s.n_last[j]);
+    store_through(a.hash + m, s.n_hash[j]);
     if (a.use_ctx) {
 #pragma unroll
-      for (int i = 0; i < kCtxMax; ++i) a.ctx[m * kCtxMax + i] = ctx_new[i];
+      for (int i = 0; i < kCtxMax; ++i) store_through(a.ctx + m * kCtxMax + i, ctx_new[i]);
     }
-    a.src_row[m] = parent >= 0 ? m_base + parent : m;
-    a.tok[m] = appended;
+    store_through(a.src_row + m, parent >= 0 ? m_base + parent : m);
+    store_through(a.tok + m, appended);
     if (S < a.S_max) {
       const size_t ti = ((size_t)b * a.S_max + S) * K + j;
-      a.tree_parent[ti] = parent;
-      a.tree_token[ti] = code;
-      a.tree_merged[ti] = merged;
+      store_through(a.tree_parent + ti, parent);
+      store_through(a.tree_token + ti, code);
+      store_through(a.tree_merged + ti, merged);
     }
     // finished when no surviving slot has frames left
     const bool open = live && s.n_t[j] < T_b;
@@ -870,7 +871,7 @@ __device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int tile,
   const int m = m0 + j;
   if (m < a.M) {
 #pragma unroll
-    for (int q = 0; q < VPL; ++q) a.R[(size_t)m * R4 + tile * 32 + i0 + q] = tile_value<WAVES>(red, i0 + q, j);
+    for (int q = 0; q < VPL; ++q) store_through(a.R + (size_t)m * R4 + tile * 32 + i0 + q, tile_value<WAVES>(red, i0 + q, j));
   }
 }
 
@@ -1123,8 +1124,8 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
     h = h_cur[k4_index(u, src, Mp)];
     if (done_flag) return;
   }
-  c_nxt[(size_t)m * P + u] = c;
-  h_nxt[k4_index(u, m, Mp)] = h;
+  store_through(c_nxt + (size_t)m * P + u, c);
+  store_through(h_nxt + k4_index(u, m, Mp), h);
 }
 
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
@@ -1187,7 +1188,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)
-    a.pre[k4_index(o0 + q, me, a.Mp)] = tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + bv[q] + fv[q];
+    store_through(a.pre + k4_index(o0 + q, me, a.Mp), tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + bv[q] + fv[q]);
 }
 
 // Stateless prediction network: pre[m] = f_proj[b, t_m] + sum_i tab_i[token_i of m] (tables folded
@@ -1221,7 +1222,9 @@ __global__ __launch_bounds__(256) void k_stateless_pre(StatelessPreArgs a) {
     const float4 g = *reinterpret_cast<const float4 *>(a.tab + ((size_t)i * (a.V + 1) + tk) * a.H + 4 * o4);
     v.x += g.x; v.y += g.y; v.z += g.z; v.w += g.w;
   }
-  *reinterpret_cast<float4 *>(a.pre + ((size_t)o4 * a.Mp + m) * 4) = v;
+  uint64_t *dst = reinterpret_cast<uint64_t *>(a.pre + ((size_t)o4 * a.Mp + m) * 4);
+  store_through(dst, (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32));
+  store_through(dst + 1, (uint64_t)__float_as_uint(v.z) | ((uint64_t)__float_as_uint(v.w) << 32));
 }
 
 __global__ void k_fill_int(int *p, int value, int n) {

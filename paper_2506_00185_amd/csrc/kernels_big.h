@@ -158,7 +158,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + 32 * t + 8 * (r >> 2) + 4 * kg + (r & 3);
-      if (m < a.M) zcol[(size_t)m * a.Npad] = acc[t][r] + bias;
+      if (m < a.M) store_through(zcol + (size_t)m * a.Npad, acc[t][r] + bias);
     }
   RB_STAMP(3, 3);
   RB_BLOCK_TS(1);
@@ -205,7 +205,9 @@ __global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     w[i] = (uint32_t)bf16_bits(fmaxf(v[2 * i], 0.f)) | ((uint32_t)bf16_bits(fmaxf(v[2 * i + 1], 0.f)) << 16);
-  *reinterpret_cast<uint4 *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  uint64_t *dst = reinterpret_cast<uint64_t *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8);
+  store_through(dst, (uint64_t)w[0] | ((uint64_t)w[1] << 32));
+  store_through(dst + 1, (uint64_t)w[2] | ((uint64_t)w[3] << 32));
 }
 
 // wave-wide max of packed candidates, in every lane
@@ -331,12 +333,12 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
   uint64_t *out = a.p_cand + (size_t)m * K;
   if (total <= kSurvivorCap) {
     // rank of every collected key = number of collected keys ahead of it (packed keys are distinct)
-    if (tid < K && tid >= total) out[tid] = no_cand();
+    if (tid < K && tid >= total) store_through(out + tid, no_cand());
     for (int i = tid; i < total; i += 64 * kRowWaves) {
       const uint64_t mine = surv[i];
       int rank = 0;
       for (int j = 0; j < total; ++j) rank += surv[j] > mine;
-      if (rank < K) out[rank] = mine;
+      if (rank < K) store_through(out + rank, mine);
     }
   } else if (wave == 0) {
     // more than kSurvivorCap keys at or above tau (many equal keys): K plain rounds over the row in memory
@@ -350,13 +352,13 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
         if (c < last && c > best) best = c;
       }
       best = wave_max_u64(best);
-      if (lane == 0) out[j] = best;
+      if (lane == 0) store_through(out + j, best);
       last = best > no_cand() ? best : no_cand() + 1;
     }
   }
   if (tid == 0) {
-    a.p_max[m] = mx;
-    a.p_sum[m] = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+    store_through(a.p_max + m, mx);
+    store_through(a.p_sum + m, (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]));
   }
   // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; wave 3, a lane takes 8 k
   if (wave != kRowWaves - 1) return;
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
   for (int d = 0; d < 9; ++d)
     if (d < nz) {
       const float v = wave_sum(acc[d]);
-      if (lane == 0) a.zs[(size_t)m * nz + d] = v + a.bias_spec[d];
+      if (lane == 0) store_through(a.zs + (size_t)m * nz + d, v + a.bias_spec[d]);
     }
 }
 

@@ -92,7 +92,7 @@ __device__ __forceinline__ void lm_row_block(const LmView &lm, const int *__rest
   }
   __syncthreads();
   const float ln10 = 2.302585092994046f;
-  for (int v = tid; v < lm.V; v += nthreads) out[(size_t)m * lm.V + v] = row[v] * ln10;
+  for (int v = tid; v < lm.V; v += nthreads) store_through(out + (size_t)m * lm.V + v, row[v] * ln10);
 }
 
 }  // namespace rb
