@@ -11,8 +11,13 @@
 // wall clock at a few points of each kernel.  Compiled out otherwise.
 #ifdef RB_TIMING
 __device__ long long rb_stamps[8 * 16];
-__device__ long long rb_block_ts[2 * 1024];
-#define RB_BLOCK_TS(i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) rb_block_ts[2 * blockIdx.x + (i)] = wall_clock64(); } while (0)
+__device__ long long rb_block_ts[3 * 2 * 1024];  // [kernel: main, cell update, projection][block][start, end]
+#define RB_BLOCK_TS_K(k, i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) rb_block_ts[(k) * 2048 + 2 * blockIdx.x + (i)] = wall_clock64(); } while (0)
+// the main kernel's stamps are kept from one step in the middle of a decode (the last steps are not typical:
+// most utterances have finished)
+#define RB_BLOCK_TS(i) do { if (rb_step == 300) RB_BLOCK_TS_K(0, i); } while (0)
+// phases of the selection of utterance 0 at that step
+#define RB_SEL_STAMP(i) do { if (b == 0 && S == 300 && (threadIdx.x & 63) == 0) rb_stamps[16 + (i)] = wall_clock64(); } while (0)
 #define RB_STAMP(kernel, i)                                                      \
   do {                                                                           \
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rb_stamps[(kernel) * 16 + (i)] = wall_clock64(); \
@@ -23,6 +28,12 @@ __device__ long long rb_block_ts[2 * 1024];
   } while (0)
 #define RB_BLOCK_TS(i) \
   do {                 \
+  } while (0)
+#define RB_BLOCK_TS_K(k, i) \
+  do {                      \
+  } while (0)
+#define RB_SEL_STAMP(i) \
+  do {                  \
   } while (0)
 #endif
 
@@ -360,6 +371,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   constexpr int kMine = (KMAX + LPR - 1) / LPR;
   const bool one_list = NCH == 1 && a.n_chunks == 1;
   uint64_t direct[kMine];
+  RB_SEL_STAMP(0);
   auto load_rows = [&](int r0) {
     rk = r0 + lane / LPR;
     row_ok = rk < K;
@@ -392,6 +404,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     for (int d = 0; d < a.ND; ++d) dl[d] = load_agent(zsr + 1 + d);
   };
   auto process_rows = [&]() {
+    RB_SEL_STAMP(2);
     // ---- K rounds of "best remaining candidate" in every lane group at once.
     // Lane e keeps the winners of rounds e, e + LPR, ... (at most KMAX / LPR + 1 of them).
     uint64_t mine[kMine];
@@ -434,6 +447,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         last = best > no_cand() ? best : no_cand() + 1;  // nothing below "no candidate" is eligible again
       }
     }
+    RB_SEL_STAMP(3);
     // ---- soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
     float lse_all = 0.f, lse_nb = 0.f, max_nb = -INFINITY;
     if (!a.normalized) {
@@ -491,6 +505,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         adv_blank = a.dur[best_b];
       }
     }
+    RB_SEL_STAMP(4);
     wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
     // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
     if (row_ok) {
@@ -561,6 +576,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     wave_sync();
   };
   auto per_utterance = [&]() -> bool {  // false: the utterance had finished before this step
+    RB_SEL_STAMP(1);
     if (a.use_ctx)
       for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
     if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
@@ -599,6 +615,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     process_rows();
   }
 
+  RB_SEL_STAMP(5);
   // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
   // value is the new score itself except under early pruning
   const int n = K * (K + 1) * (PAIRS ? a.ND : 1);
@@ -607,10 +624,20 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     // few candidates: each lane counts how many come before its own; that count is its new slot
     const double mv = lane < n ? rank_of[lane] : -INFINITY;
     const int mf = lane < n ? s.rc_flat[lane] : 0x7fffffff;
+    // (every lane reads all n candidates back from LDS, the same address in all lanes: such reads are broadcasts
+    //  and, unlike lane reads into scalar registers, can be requested many at a time)
     int rank = 0;
-#pragma unroll 4
-    for (int c = 0; c < n; ++c)
-      rank += comes_before(readlane_d(mv, c), __builtin_amdgcn_readlane(mf, c), mv, mf) ? 1 : 0;
+    for (int c0 = 0; c0 < n; c0 += 8) {
+      double cv[8];
+      int cf[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {  // eight requests in flight (the arrays have room beyond n)
+        cv[q] = rank_of[c0 + q];
+        cf[q] = s.rc_flat[c0 + q];
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) rank += (c0 + q < n && comes_before(cv[q], cf[q], mv, mf)) ? 1 : 0;
+    }
     if (mv > -INFINITY && rank < K) {
       s.sel_val[rank] = s.rc_val[lane];
       s.sel_flat[rank] = mf;
@@ -643,6 +670,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   }
   wave_sync();
 
+  RB_SEL_STAMP(6);
   // ---- expansion into the new slots
   int code = -3, parent = -1, appended = -1;
   int ctx_new[kCtxMax];
@@ -701,6 +729,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   }
   wave_sync();
 
+  RB_SEL_STAMP(7);
   // ---- recombination: equal (hash, length, last token, frame, symbols in frame)
   if (lane < K) {
     const int j = lane;
@@ -708,20 +737,24 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     double score = s.n_score[j];
     bool live = s.n_live[j] != 0;
     if (live) {
-      merged = j;
-      for (int i = 0; i < j; ++i) {
-        if (s.n_live[i] && s.n_hash[i] == s.n_hash[j] && s.n_len[i] == s.n_len[j] && s.n_last[i] == s.n_last[j] &&
-            s.n_t[i] == s.n_t[j] && s.n_sym[i] == s.n_sym[j]) {
-          merged = i;
-          break;
-        }
+      // which slots hold the same (hash, length, last token, frame, symbols in frame): all keys are read without
+      // branches in between, so that the LDS reads go out together
+      const uint32_t mh = s.n_hash[j];
+      const int ml = s.n_len[j], mla = s.n_last[j], mt = s.n_t[j], ms = s.n_sym[j];
+      uint32_t same = 0;
+#pragma unroll
+      for (int i = 0; i < KMAX; ++i) {
+        const bool e = (i < K) & (s.n_live[i] != 0) & (s.n_hash[i] == mh) & (s.n_len[i] == ml) & (s.n_last[i] == mla) &
+                       (s.n_t[i] == mt) & (s.n_sym[i] == ms);
+        same |= (uint32_t)e << i;
       }
-      if (merged == j) {
-        for (int i = j + 1; i < K; ++i)
-          if (s.n_live[i] && s.n_hash[i] == s.n_hash[j] && s.n_len[i] == s.n_len[j] &&
-              s.n_last[i] == s.n_last[j] && s.n_t[i] == s.n_t[j] && s.n_sym[i] == s.n_sym[j])
-            score = logaddexp_d(score, s.n_score[i]);
+      const uint32_t lower = same & ((1u << j) - 1u);
+      if (lower == 0) {  // the lowest slot of its class keeps the log-sum, added up in slot order
+        merged = j;
+        for (uint32_t higher = same & ~((2u << j) - 1u); higher; higher &= higher - 1u)
+          score = logaddexp_d(score, s.n_score[__builtin_ctz(higher)]);
       } else {
+        merged = __builtin_ctz(lower);
         live = false;
         score = -INFINITY;
       }
@@ -762,6 +795,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     }
   }
   wave_sync();
+  RB_SEL_STAMP(8);
 }
 
 // picks the lane-group width and register budget for the beam and list sizes at hand.
@@ -916,6 +950,9 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
+#ifdef RB_TIMING
+  const int rb_step = *a.sel.step_base + a.sel.step_off;
+#endif
   if (!done) RB_BLOCK_TS(0);
   int chunk, ty;
   const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
@@ -1111,6 +1148,7 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   const int m = gid / P, u = gid % P;
   if (m >= M) return;
   const int done_flag = *reinterpret_cast<const volatile int *>(done);
+  if (!done_flag) RB_BLOCK_TS_K(1, 0);
   const int src = src_row[m], token = tok[m];
   const float c_old = c_cur[(size_t)src * P + u];
   float c = c_old, h;
@@ -1126,6 +1164,7 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   }
   store_through(c_nxt + (size_t)m * P + u, c);
   store_through(h_nxt + k4_index(u, m, Mp), h);
+  RB_BLOCK_TS_K(1, 1);
 }
 
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
@@ -1166,6 +1205,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   SplitKOperands<ITERS> op;
   splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
   if (done_flag) return;
+  RB_BLOCK_TS_K(2, 0);
   // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1); the frame's projection is requested
   // behind the operand loads
   const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
@@ -1185,6 +1225,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
   if (a.bump && tile == 0 && mtile == 0 && tid == 0) *a.step_base += a.bump;
+  RB_BLOCK_TS_K(2, 1);
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
   static_assert(WAVES == 4 || WAVES == 8, "two waves per SIMD: one block of 8 or two blocks of 4");
   __shared__ u32x4 tile[3][NP][64];
   const int done = *reinterpret_cast<const volatile int *>(a.done);
-  RB_BLOCK_TS(0);
+  RB_BLOCK_TS_K(0, 0);
   RB_STAMP(3, 0);
   int nb, mb;
   if (xcd_item(a.map, blockIdx.x, nb, mb) != 0) return;
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
       if (m < a.M) store_through(zcol + (size_t)m * a.Npad, acc[t][r] + bias);
     }
   RB_STAMP(3, 3);
-  RB_BLOCK_TS(1);
+  RB_BLOCK_TS_K(0, 1);
 }
 
 // Stateless prediction network for the large mode: a_m = bf16(ReLU(f_proj[b, t_m] + sum_i tab_i[token_i]))

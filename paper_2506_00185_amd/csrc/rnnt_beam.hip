@@ -498,7 +498,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     // The selection runs in the tail of this kernel for the beams its in-kernel forms take.  (Building the kernel
     // without it lets two blocks share a compute unit, but they also share its operand path: measured slower at
     // every shape, 11.3 vs 10.6 ms at B * beam = 256, beam 4.)
-    const bool tail = p.K <= 8 && !c.tdt_all_pairs;
+    const bool tail = p.K <= 8 && !c.tdt_all_pairs && !getenv("RNNT_NO_TAIL");
 #define RB_MAIN(W, I)                                                                              \
   do {                                                                                             \
     if (tail) hipLaunchKernelGGL((k_step_main<W, I, true>), grid, dim3(W * 64), 0, s, a);         \
@@ -940,7 +940,7 @@ int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_
 
 #ifdef RB_TIMING
 int rnnt_beam_debug_block_ts(long long *out) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_block_ts), sizeof(long long) * 2048) == hipSuccess ? 0 : RNNT_E_HIP;
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_block_ts), sizeof(long long) * 3 * 2048) == hipSuccess ? 0 : RNNT_E_HIP;
 }
 // tuning builds only: copy the phase stamps out (8 kernels x 16 stamps, 10 ns ticks)
 int rnnt_beam_debug_stamps(long long *out) {
