@@ -22,6 +22,8 @@ __device__ long long rb_block_ts[3 * 2 * 1024];  // [kernel: main, cell update, 
   do {                                                                           \
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rb_stamps[(kernel) * 16 + (i)] = wall_clock64(); \
   } while (0)
+// phases of joint block 0 of the main kernel at the stamped step
+#define RB_MAIN_STAMP(i) do { if (rb_step == 300 && blockIdx.x == 0 && threadIdx.x == 0) rb_stamps[32 + (i)] = wall_clock64(); } while (0)
 #else
 #define RB_STAMP(kernel, i) \
   do {                      \
@@ -34,6 +36,9 @@ __device__ long long rb_block_ts[3 * 2 * 1024];  // [kernel: main, cell update, 
   } while (0)
 #define RB_SEL_STAMP(i) \
   do {                  \
+  } while (0)
+#define RB_MAIN_STAMP(i) \
+  do {                   \
   } while (0)
 #endif
 
@@ -965,7 +970,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
 
   // -------------------------------------------------------------------- joint
   const int n0 = chunk * 32, m0 = ty * a.rpt;
-  RB_STAMP(0, 0);
+  RB_MAIN_STAMP(0);
   {
     const int Np = a.n_chunks * 32;
     const float *wp = a.W + (size_t)(n0 + col) * 4;
@@ -981,9 +986,9 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
     SplitKOperands<ITERS> op;
     splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
     if (done) return;
-    RB_STAMP(0, 1);
+    RB_MAIN_STAMP(1);
     splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
-    RB_STAMP(0, 2);
+    RB_MAIN_STAMP(2);
   }
 
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
@@ -1013,7 +1018,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   for (int q = 0; q < VPL; ++q)
     if (n0 + i0 + q < a.V) sum += __expf(zv[q] - mx);
   sum = group_sum<LPH>(sum);
-  RB_STAMP(0, 3);
+  RB_MAIN_STAMP(3);
   // local order of this lane's candidates (VPL is 2 or 4: a few compare-exchanges)
 #pragma unroll
   for (int x = 0; x < VPL; ++x)
@@ -1037,7 +1042,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
       if (r < LPH) mine[0] = best; else mine[1] = best;
     }
   }
-  RB_STAMP(0, 4);
+  RB_MAIN_STAMP(4);
   if (mvalid) {
     const size_t pc = (size_t)m * a.n_chunks + chunk;
     if (e == 0) {
@@ -1069,14 +1074,14 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
     RB_BLOCK_TS(1);
     return;
   }
-  RB_STAMP(0, 5);
+  RB_MAIN_STAMP(5);
   SelectScratch *scratch = reinterpret_cast<SelectScratch *>(smem);
   const int wave = tid >> 6;
   for (int u = wave; u < a.upt; u += WAVES) {
     const int b = ty * a.upt + u;
     if (b < a.sel.B) select_dispatch<0>(a.sel, b, scratch[wave]);
   }
-  RB_STAMP(0, 6);
+  RB_MAIN_STAMP(6);
   RB_BLOCK_TS(1);
   }  // TAIL
 }
