@@ -135,7 +135,12 @@ int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
 // Gate tiles of the recurrent product computed in the prediction-projection launch (the rest ride in the
 // main launch): as many as fit beside the projection's own blocks, one block per compute unit, on every XCD
 // (32 compute units each).
+// the projection of the prediction step split in two along k (k_pred_proj_half): when whole tiles would leave half
+// of the compute units idle, for the kernels that keep their operands in registers
+bool proj_split(const rnnt_config_t &c, int M) { return c.P == 640 && (c.H / 32) * ((M + 31) / 32) * 2 <= 256; }
+
 int recurrent_split(const rnnt_config_t &c, int M) {
+  if (proj_split(c, M)) return 0;  // no recurrent tiles beside the half tiles: they would set that launch's duration
   XcdMap m;
   m.a_tiles = c.H / 32;
   m.a_m = m.b_m = (M + 31) / 32;
@@ -318,8 +323,10 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
         lmr.first_block = n_blocks;
         lds = sizeof(float) * (size_t)c.V;
       }
+      const bool split = proj_split(c, p.M);
       hipLaunchKernelGGL(k_lstm_pointwise, dim3(n_blocks + lmr.M), dim3(256), lds, s, h->Rgates, h->G, h->h[cur],
-                         h->c[cur], h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done, lmr);
+                         h->c[cur], h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done, lmr,
+                         split ? h->pre : nullptr, split ? c.H * h->Mp : 0);
     }
     {
       PredProjArgs a;
@@ -334,9 +341,14 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       a.map.a_tiles = c.H / 32; a.map.a_m = m_tiles;
       a.map.b_begin = 0; a.map.b_end = recurrent_split(c, p.M); a.map.b_m = m_tiles;
       ScopedKernelTime tm(h, s, KT_PREDPROJ);
+      if (proj_split(c, p.M)) {  // items (32-slot tile, half of k) in place of 32-slot tiles
+        a.map.a_m = 2 * m_tiles;
+        a.map.b_end = 0;
+      }
       const dim3 grid(xcd_grid(a.map));
 #define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), 0, s, a)
-      if (c.P == 640) RB_PRED(8, 10);
+      if (proj_split(c, p.M)) hipLaunchKernelGGL((k_pred_proj_half<8, 5>), grid, dim3(512), 0, s, a);
+      else if (c.P == 640) RB_PRED(8, 10);
       else if (c.P % 64 == 0) RB_PRED(8, 0);
       else RB_PRED(4, 0);
 #undef RB_PRED
