@@ -137,7 +137,11 @@ int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
 // (32 compute units each).
 // the projection of the prediction step split in two along k (k_pred_proj_half): when whole tiles would leave half
 // of the compute units idle, for the kernels that keep their operands in registers
-bool proj_split(const rnnt_config_t &c, int M) { return c.P == 640 && (c.H / 32) * ((M + 31) / 32) * 2 <= 256; }
+// (with fewer than 8 hypotheses the main launch is so short that the recurrent tiles moved into it would set its
+// duration: 508 instead of 739 audio-s/s at batch 1, beam 1)
+bool proj_split(const rnnt_config_t &c, int M) {
+  return c.P == 640 && M >= 8 && (c.H / 32) * ((M + 31) / 32) * 2 <= 256;
+}
 
 int recurrent_split(const rnnt_config_t &c, int M) {
   if (proj_split(c, M)) return 0;  // no recurrent tiles beside the half tiles: they would set that launch's duration
