@@ -26,18 +26,32 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
+def gate_tiles_in_projection_launch(c: dict, M: int) -> int:
+    """How many of the 4P / 32 gate tiles of W_hh h ride in the projection launch (the rest are in the main
+    launch): the library's rule, restated here to count each launch's FLOPs."""
+    from paper_2506_00185_amd.binding import block_map
+    m_tiles = (M + 31) // 32
+    if c["P"] == 640 and M >= 8 and (c["H"] // 32) * m_tiles * 2 <= 256:
+        return 0  # projection split in two along k, all gate tiles in the main launch
+    for b_end in range(4 * c["P"] // 32, 0, -1):
+        if block_map(c["H"] // 32, m_tiles, 0, b_end, m_tiles)[0] <= 256:
+            return b_end
+    return 0
+
+
 def kernel_flops(name: str, c: dict, M: int, B: int, T: int) -> float:
     """Algorithmic floating-point operations of one launch (multiply-add = 2)."""
     nd = len(c["durations"])
     joint = 2.0 * M * c["H"] * (c["V"] + 1 + nd)
     # recurrent half of the LSTM gates; the embedding half is a table made at create
     recurrent = 2.0 * M * c["P"] * 4 * c["P"] if c["pred"] == "lstm" else 0.0
+    in_proj = gate_tiles_in_projection_launch(c, M) / (4 * c["P"] / 32) if c["pred"] == "lstm" else 0.0
     if name == "k_step_main":  # joint blocks and recurrent-product blocks share the launch
-        return joint + recurrent
+        return joint + recurrent * (1.0 - in_proj)
     if name == "joint":
         return joint
-    if name == "k_pred_proj":
-        return 2.0 * M * c["P"] * c["H"] if c["pred"] == "lstm" else 0.0
+    if name in ("k_pred_proj", "k_pred_proj_half"):
+        return (2.0 * M * c["P"] * c["H"] + recurrent * in_proj) if c["pred"] == "lstm" else 0.0
     if name == "k_joint_big":  # token columns only; blank and duration rows are done by the row kernel
         return 2.0 * M * c["H"] * c["V"]
     if name.startswith("k_gemm_nt"):
@@ -147,8 +161,8 @@ def main():
                        gbs=round(kernel_bytes(n, c, B * K) / (t / k * 1e-3) / 1e9, 1) if k and t > 0 else None)
                for n, (t, k) in kt.items() if k}
     loop = {n: v for n, v in kernels.items()
-            if n in ("k_step_main", "k_select", "k_lstm_pointwise", "k_pred_proj", "k_lm_rows", "k_joint_big",
-                     "k_row_select")}
+            if n in ("k_step_main", "k_select", "k_lstm_pointwise", "k_pred_proj", "k_pred_proj_half", "k_lm_rows",
+                     "k_joint_big", "k_row_select")}
     dom = max(loop, key=lambda n: loop[n]["total_ms"])
     flops = kernel_flops(dom, c, B * K, B, T)
     nbytes = kernel_bytes(dom, c, B * K)
