@@ -205,9 +205,7 @@ __global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a
 #pragma unroll
   for (int i = 0; i < 4; ++i)
     w[i] = (uint32_t)bf16_bits(fmaxf(v[2 * i], 0.f)) | ((uint32_t)bf16_bits(fmaxf(v[2 * i + 1], 0.f)) << 16);
-  uint64_t *dst = reinterpret_cast<uint64_t *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8);
-  store_through(dst, (uint64_t)w[0] | ((uint64_t)w[1] << 32));
-  store_through(dst + 1, (uint64_t)w[2] | ((uint64_t)w[3] << 32));
+  *reinterpret_cast<uint4 *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 // wave-wide max of packed candidates, in every lane
