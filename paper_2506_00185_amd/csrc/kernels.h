@@ -1319,9 +1319,7 @@ __global__ __launch_bounds__(256) void k_stateless_pre(StatelessPreArgs a) {
     const float4 g = *reinterpret_cast<const float4 *>(a.tab + ((size_t)i * (a.V + 1) + tk) * a.H + 4 * o4);
     v.x += g.x; v.y += g.y; v.z += g.z; v.w += g.w;
   }
-  uint64_t *dst = reinterpret_cast<uint64_t *>(a.pre + ((size_t)o4 * a.Mp + m) * 4);
-  store_through(dst, (uint64_t)__float_as_uint(v.x) | ((uint64_t)__float_as_uint(v.y) << 32));
-  store_through(dst + 1, (uint64_t)__float_as_uint(v.z) | ((uint64_t)__float_as_uint(v.w) << 32));
+  *reinterpret_cast<float4 *>(a.pre + ((size_t)o4 * a.Mp + m) * 4) = v;  // (16-byte store: cheaper than two written through)
 }
 
 __global__ void k_fill_int(int *p, int value, int n) {
