@@ -115,10 +115,13 @@ __device__ __forceinline__ void splitk_load(SplitKOperands<ITERS> &op, AL a_at, 
   if constexpr (ITERS > 0) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
     const int kbeg = wave * (K / WAVES) + 4 * half;
+    // pairwise, in the order the matrix instructions consume them: loads complete in order, so the first
+    // instructions can start after the first pair instead of after all of one operand
 #pragma unroll
-    for (int i = 0; i < ITERS; ++i) op.a[i] = a_at(kbeg + 8 * i);
-#pragma unroll
-    for (int i = 0; i < ITERS; ++i) op.b[i] = b_at(kbeg + 8 * i);
+    for (int i = 0; i < ITERS; ++i) {
+      op.a[i] = a_at(kbeg + 8 * i);
+      op.b[i] = b_at(kbeg + 8 * i);
+    }
   }
 }
 
@@ -1210,19 +1213,23 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
   auto fb = [&](float4 v) { return round_ops ? bf16_round4(v) : v; };
   const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
-  SplitKOperands<ITERS> op;
-  splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
-  if (done_flag) return;
-  RB_BLOCK_TS_K(2, 0);
-  // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1); the frame's projection is requested
-  // behind the operand loads
+  // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1).  Its frame index is loaded BEFORE the operands: the
+  // address of the frame's projection depends on it, and a wait for a load that was issued after the operands would
+  // wait for all of them too (loads complete in order), i.e. hold the first matrix instruction back until the last
+  // operand has arrived.
   const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
   const int me = m0 + j;
+  const int me_ok = me < a.M ? me : 0;  // (unconditional loads: a branch here would end in a wait for them)
+  const int T_b = a.lengths[me_ok / a.K];
+  int tt = a.t[me_ok];
+  SplitKOperands<ITERS> op;
+  splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
+  __builtin_amdgcn_sched_barrier(0);  // nothing below may be scheduled (and waited for) ahead of the operand loads
+  if (done_flag) return;
+  RB_BLOCK_TS_K(2, 0);
   float fv[VPL], bv[VPL];
   if (me < a.M) {
     const int b = me / a.K;
-    const int T_b = a.lengths[b];
-    int tt = a.t[me];
     tt = tt < T_b ? tt : T_b - 1;
     tt = tt < 0 ? 0 : tt;
 #pragma unroll
@@ -1262,30 +1269,36 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)((k + koff) >> 2) * Mp * 4); };
   auto fb = [&](float4 v) { return round_ops ? bf16_round4(v) : v; };
   const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
-  SplitKOperands<ITERS> op;
-  splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P / 2);
-  if (done_flag) return;
   const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
   const int me = m0 + j;
-  float add[VPL];
+  const int me_ok = me < a.M ? me : 0;  // loaded before the operands, without a branch (see k_pred_proj)
+  const int T_b = a.lengths[me_ok / a.K];
+  int tt = a.t[me_ok];
+  SplitKOperands<ITERS> op;
+  splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P / 2);
+  __builtin_amdgcn_sched_barrier(0);  // nothing below may be scheduled (and waited for) ahead of the operand loads
+  if (done_flag) return;
+  float fv[VPL], bv[VPL];
 #pragma unroll
-  for (int q = 0; q < VPL; ++q) add[q] = 0.f;
+  for (int q = 0; q < VPL; ++q) fv[q] = bv[q] = 0.f;
   if (me < a.M && half == 0) {  // the frame's projection and the bias come in with the first half
     const int b = me / a.K;
-    const int T_b = a.lengths[b];
-    int tt = a.t[me];
     tt = tt < T_b ? tt : T_b - 1;
     tt = tt < 0 ? 0 : tt;
 #pragma unroll
-    for (int q = 0; q < VPL; ++q) add[q] = a.f_proj[((size_t)b * a.T + tt) * a.H + o0 + q] + a.bias[o0 + q];
+    for (int q = 0; q < VPL; ++q) {
+      fv[q] = a.f_proj[((size_t)b * a.T + tt) * a.H + o0 + q];
+      bv[q] = a.bias[o0 + q];
+    }
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P / 2, red);
   if (a.bump && tile == 0 && item == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)
-    __hip_atomic_fetch_add(a.pre + k4_index(o0 + q, me, a.Mp), tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + add[q],
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_fetch_add(a.pre + k4_index(o0 + q, me, a.Mp),
+                           tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + bv[q] + fv[q], __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Stateless prediction network: pre[m] = f_proj[b, t_m] + sum_i tab_i[token_i of m] (tables folded
