@@ -18,7 +18,22 @@
  *   - The caller owns every array it passes in.  Weights and LM arrays are
  *     re-packed into library-owned device memory by the create calls and may be
  *     freed afterwards.  The handle owns workspace, hypothesis tree and graphs.
- *   - H, P, D and E must be multiples of 32; beam <= 16.
+ *   - Shape limits: H, P, D and E must be multiples of 32; beam <= 16 (8 with tdt_all_pairs); an LM's vocabulary
+ *     at most 15 360 tokens (one row of scores is built in 60 KB of on-chip memory).  Kernels specialised for
+ *     H = P = 640 exist beside generic ones for any multiple of 32; the prediction projection is split in two
+ *     along k across blocks only when P % 128 == 0.
+ *
+ * Where the signatures differ from the minimal statement of the problem
+ * (create / decode(enc, lengths, weights, beam, algo, lm, lm_weight) / results), and why:
+ *   - rnnt_lm_create takes V: the LM's vocabulary is checked against the model's at decode time and sizes the
+ *     on-chip row; the n-gram arrays alone do not fix it (unseen tokens).
+ *   - rnnt_beam_results returns scores as double: hypothesis scores are accumulated in float64 on the device
+ *     (a sum of several hundred float32 log-probabilities), and the n-best order is defined on those values.
+ *   - rnnt_beam_dump_tree takes s_cap, the number of tree levels the caller's arrays have room for.
+ *   - rnnt_beam_decode by default follows the device (it returns when the data-dependent number of steps is
+ *     over); with the config field async_enqueue it only enqueues and returns (see there).
+ *   - config fields beyond the model's shape select readings the paper leaves open or variants it describes:
+ *     use_graph, joint_path, lm_rule, lm_early_pruning, tdt_all_pairs, async_enqueue.
  */
 #ifndef RNNT_BEAM_H
 #define RNNT_BEAM_H
@@ -83,6 +98,11 @@ typedef struct {
                                 the most likely one that advances).  1: every (symbol, duration) pair is a candidate
                                 of its own, blank only with durations >= 1: Beam x (V + 1) x n_durations candidates
                                 per utterance and step.  Needs max_beam <= 8 */
+  int32_t async_enqueue;     /* 0: rnnt_beam_decode enqueues chunks of 16 steps, at most two ahead of the device, and
+                                returns once the device has reported that every utterance has finished (the calling
+                                thread is blocked for most of the decode).  1: it enqueues the upper bound of
+                                T (max_symbols + 1) steps at once and returns without waiting; steps after the last
+                                utterance has finished return at once on the device (a few microseconds each) */
 } rnnt_config_t;
 
 /* Device pointers, float32, caller-owned.  Unused ones may be NULL. */
@@ -132,7 +152,11 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
  * Work is enqueued on hip_stream (a hipStream_t, NULL = default stream) in chunks of 16 steps, at most
  * two chunks ahead of the device; the call returns once the device has reported (through a pinned word)
  * that every utterance has finished and the back-trace has been enqueued, i.e. it blocks the calling
- * thread for most of the decode's duration.  Results stay valid until the next decode.
+ * thread for most of the decode's duration (config field async_enqueue: enqueue everything and return).
+ * Up to two chunks of steps enqueued after the last utterance finished still run; their kernels return at once.
+ * Results stay valid until the next decode.  Graphs captured for a decode hold the LM's device tables: an LM
+ * must outlive every decode that uses it, and at most 8 graphs (distinct B, T, beam, algo, LM, LM weight) are
+ * kept per handle, the oldest being dropped.
  */
 int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T,
                      int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream);

@@ -41,7 +41,8 @@ class _Config(C.Structure):
                 ("n_durations", C.c_int32), ("durations", C.c_int32 * 8), ("stateless_context", C.c_int32),
                 ("max_B", C.c_int32), ("max_T", C.c_int32), ("max_beam", C.c_int32), ("max_symbols", C.c_int32),
                 ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32),
-                ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32), ("tdt_all_pairs", C.c_int32)]
+                ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32), ("tdt_all_pairs", C.c_int32),
+                ("async_enqueue", C.c_int32)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -135,7 +136,7 @@ class BeamDecoder:
     """rnnt_beam_create / decode / results / destroy for one model."""
 
     def __init__(self, c: dict, w: dict, max_B=None, max_T=None, max_beam=None, use_graph=True, device="cuda:0",
-                 joint_path="auto", lm_rule=4, lm_prune="late"):
+                 joint_path="auto", lm_rule=4, lm_prune="late", async_enqueue=False):
         lib = load_library()
         torch = _torch()
         self.device = torch.device(device)
@@ -160,6 +161,7 @@ class BeamDecoder:
         cfg.lm_rule = lm_rule
         cfg.lm_early_pruning = {"late": 0, "early": 1}[lm_prune]
         cfg.tdt_all_pairs = 1 if c.get("tdt_pairs") else 0
+        cfg.async_enqueue = 1 if async_enqueue else 0
         self.cfg = cfg
         self._w = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
                    for k, v in w.items()}

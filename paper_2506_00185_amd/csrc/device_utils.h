@@ -54,6 +54,10 @@ __device__ __forceinline__ T load_agent(const T *p) {
   return __hip_atomic_load(const_cast<T *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Blocks the calling wave until every global load and store it has issued has completed; a write-through
+// store completes when the memory side has acknowledged it.  (gfx9 counts stores in vmcnt.)
+__device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Results that only a LATER launch reads.  A plain store leaves its line dirty in the XCD's L2, and the end of
 // every kernel waits until all dirty lines have been written back (the L2s of the XCDs are not coherent with each
 // other, so that is how one launch's output becomes visible to the next).  Writing through at once takes that

@@ -7,41 +7,6 @@
 #include "device_utils.h"
 #include "lm_device.h"
 
-// Phase stamps for tuning builds (-DRB_TIMING): block (0, 0), thread 0 records the constant-rate
-// wall clock at a few points of each kernel.  Compiled out otherwise.
-#ifdef RB_TIMING
-__device__ long long rb_stamps[8 * 16];
-__device__ long long rb_block_ts[3 * 2 * 1024];  // [kernel: main, cell update, projection][block][start, end]
-#define RB_BLOCK_TS_K(k, i) do { if (threadIdx.x == 0 && blockIdx.x < 1024) rb_block_ts[(k) * 2048 + 2 * blockIdx.x + (i)] = wall_clock64(); } while (0)
-// the main kernel's stamps are kept from one step in the middle of a decode (the last steps are not typical:
-// most utterances have finished)
-#define RB_BLOCK_TS(i) do { if (rb_step == 300) RB_BLOCK_TS_K(0, i); } while (0)
-// phases of the selection of utterance 0 at that step
-#define RB_SEL_STAMP(i) do { if (b == 0 && S == 300 && (threadIdx.x & 63) == 0) rb_stamps[16 + (i)] = wall_clock64(); } while (0)
-#define RB_STAMP(kernel, i)                                                      \
-  do {                                                                           \
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) rb_stamps[(kernel) * 16 + (i)] = wall_clock64(); \
-  } while (0)
-// phases of joint block 0 of the main kernel at the stamped step
-#define RB_MAIN_STAMP(i) do { if (rb_step == 300 && blockIdx.x == 0 && threadIdx.x == 0) rb_stamps[32 + (i)] = wall_clock64(); } while (0)
-#else
-#define RB_STAMP(kernel, i) \
-  do {                      \
-  } while (0)
-#define RB_BLOCK_TS(i) \
-  do {                 \
-  } while (0)
-#define RB_BLOCK_TS_K(k, i) \
-  do {                      \
-  } while (0)
-#define RB_SEL_STAMP(i) \
-  do {                  \
-  } while (0)
-#define RB_MAIN_STAMP(i) \
-  do {                   \
-  } while (0)
-#endif
-
 namespace rb {
 
 // ---------------------------------------------------------------------------
@@ -379,7 +344,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   constexpr int kMine = (KMAX + LPR - 1) / LPR;
   const bool one_list = NCH == 1 && a.n_chunks == 1;
   uint64_t direct[kMine];
-  RB_SEL_STAMP(0);
   auto load_rows = [&](int r0) {
     rk = r0 + lane / LPR;
     row_ok = rk < K;
@@ -412,7 +376,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     for (int d = 0; d < a.ND; ++d) dl[d] = load_agent(zsr + 1 + d);
   };
   auto process_rows = [&]() {
-    RB_SEL_STAMP(2);
     // ---- K rounds of "best remaining candidate" in every lane group at once.
     // Lane e keeps the winners of rounds e, e + LPR, ... (at most KMAX / LPR + 1 of them).
     uint64_t mine[kMine];
@@ -455,7 +418,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         last = best > no_cand() ? best : no_cand() + 1;  // nothing below "no candidate" is eligible again
       }
     }
-    RB_SEL_STAMP(3);
     // ---- soft-max statistics of the hypothesis (float transcendental math, scores accumulate in double)
     float lse_all = 0.f, lse_nb = 0.f, max_nb = -INFINITY;
     if (!a.normalized) {
@@ -513,7 +475,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         adv_blank = a.dur[best_b];
       }
     }
-    RB_SEL_STAMP(4);
     wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
     // candidate c of the utterance is rc[k * (K + 1) + j]: j < K tokens, j == K blank / stay
     if (row_ok) {
@@ -584,7 +545,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     wave_sync();
   };
   auto per_utterance = [&]() -> bool {  // false: the utterance had finished before this step
-    RB_SEL_STAMP(1);
     if (a.use_ctx)
       for (int i = lane; i < K * kCtxMax; i += 64) s.ctx[i / kCtxMax][i % kCtxMax] = a.ctx[m_base * kCtxMax + i];
     if (fin) {  // a finished utterance is frozen; its slots tell the prediction step to copy
@@ -623,7 +583,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     process_rows();
   }
 
-  RB_SEL_STAMP(5);
   // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
   // value is the new score itself except under early pruning
   const int n = K * (K + 1) * (PAIRS ? a.ND : 1);
@@ -678,7 +637,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   }
   wave_sync();
 
-  RB_SEL_STAMP(6);
   // ---- expansion into the new slots
   int code = -3, parent = -1, appended = -1;
   int ctx_new[kCtxMax];
@@ -737,7 +695,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   }
   wave_sync();
 
-  RB_SEL_STAMP(7);
   // ---- recombination: equal (hash, length, last token, frame, symbols in frame)
   if (lane < K) {
     const int j = lane;
@@ -803,7 +760,6 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     }
   }
   wave_sync();
-  RB_SEL_STAMP(8);
 }
 
 // picks the lane-group width and register budget for the beam and list sizes at hand.
@@ -958,22 +914,16 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
-#ifdef RB_TIMING
-  const int rb_step = *a.sel.step_base + a.sel.step_off;
-#endif
-  if (!done) RB_BLOCK_TS(0);
   int chunk, ty;
   const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
   if (role < 0) return;
   if (role == 1) {
     recurrent_tile<WAVES, ITERS>(a.rec, chunk, ty, done, red);
-    if (!done) RB_BLOCK_TS(1);
     return;
   }
 
   // -------------------------------------------------------------------- joint
   const int n0 = chunk * 32, m0 = ty * a.rpt;
-  RB_MAIN_STAMP(0);
   {
     const int Np = a.n_chunks * 32;
     const float *wp = a.W + (size_t)(n0 + col) * 4;
@@ -989,9 +939,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
     SplitKOperands<ITERS> op;
     splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
     if (done) return;
-    RB_MAIN_STAMP(1);
     splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
-    RB_MAIN_STAMP(2);
   }
 
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
@@ -1021,7 +969,6 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   for (int q = 0; q < VPL; ++q)
     if (n0 + i0 + q < a.V) sum += __expf(zv[q] - mx);
   sum = group_sum<LPH>(sum);
-  RB_MAIN_STAMP(3);
   // local order of this lane's candidates (VPL is 2 or 4: a few compare-exchanges)
 #pragma unroll
   for (int x = 0; x < VPL; ++x)
@@ -1045,7 +992,6 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
       if (r < LPH) mine[0] = best; else mine[1] = best;
     }
   }
-  RB_MAIN_STAMP(4);
   if (mvalid) {
     const size_t pc = (size_t)m * a.n_chunks + chunk;
     if (e == 0) {
@@ -1057,13 +1003,15 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   }
 
   if constexpr (!TAIL) {
-    RB_BLOCK_TS(1);
     return;
   } else {
   // ---- the block that completes the tile runs the selection for its utterances.
-  // The lists were written with device-coherent stores; once every thread's stores have been
-  // acknowledged (workgroup release + barrier) one thread counts the block in.  The completing block
-  // reads the lists with device-coherent loads, so no cache is written back or invalidated.
+  // The lists were written with device-coherent (write-through) stores.  Every thread first waits until its own
+  // stores have been acknowledged by the memory side (a workgroup-scope release alone does not wait for
+  // outstanding global stores), then the barrier, then one thread counts the block in: the count can therefore
+  // not become visible before any list of the block.  The completing block reads the lists with
+  // device-coherent loads issued after it has seen the full count, so no cache is written back or invalidated.
+  wait_stores_acknowledged();
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
@@ -1074,18 +1022,14 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   }
   __syncthreads();
   if (!s_is_last) {
-    RB_BLOCK_TS(1);
     return;
   }
-  RB_MAIN_STAMP(5);
   SelectScratch *scratch = reinterpret_cast<SelectScratch *>(smem);
   const int wave = tid >> 6;
   for (int u = wave; u < a.upt; u += WAVES) {
     const int b = ty * a.upt + u;
     if (b < a.sel.B) select_dispatch<0>(a.sel, b, scratch[wave]);
   }
-  RB_MAIN_STAMP(6);
-  RB_BLOCK_TS(1);
   }  // TAIL
 }
 
@@ -1159,7 +1103,6 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   const int m = gid / P, u = gid % P;
   if (m >= M) return;
   const int done_flag = *reinterpret_cast<const volatile int *>(done);
-  if (!done_flag) RB_BLOCK_TS_K(1, 0);
   const int src = src_row[m], token = tok[m];
   const float c_old = c_cur[(size_t)src * P + u];
   float c = c_old, h;
@@ -1175,7 +1118,6 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   }
   store_through(c_nxt + (size_t)m * P + u, c);
   store_through(h_nxt + k4_index(u, m, Mp), h);
-  RB_BLOCK_TS_K(1, 1);
 }
 
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
@@ -1226,7 +1168,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   splitk_load<WAVES, ITERS>(op, a_at, b_at, a.P);
   __builtin_amdgcn_sched_barrier(0);  // nothing below may be scheduled (and waited for) ahead of the operand loads
   if (done_flag) return;
-  RB_BLOCK_TS_K(2, 0);
   float fv[VPL], bv[VPL];
   if (me < a.M) {
     const int b = me / a.K;
@@ -1240,7 +1181,6 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
   if (a.bump && tile == 0 && mtile == 0 && tid == 0) *a.step_base += a.bump;
-  RB_BLOCK_TS_K(2, 1);
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)

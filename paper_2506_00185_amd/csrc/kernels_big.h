@@ -65,8 +65,6 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
   static_assert(WAVES == 4 || WAVES == 8, "two waves per SIMD: one block of 8 or two blocks of 4");
   __shared__ u32x4 tile[3][NP][64];
   const int done = *reinterpret_cast<const volatile int *>(a.done);
-  RB_BLOCK_TS_K(0, 0);
-  RB_STAMP(3, 0);
   int nb, mb;
   if (xcd_item(a.map, blockIdx.x, nb, mb) != 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
@@ -125,7 +123,6 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
   // an iteration was last read two iterations (two barriers) earlier.
   stage(0, 0);
   __syncthreads();
-  RB_STAMP(3, 1);
   int s0 = 0, s1 = 1, s2 = 2;  // slots of stages st, st + 1, st + 2
   for (int st0 = 0; st0 < n_st - D; st0 += D) {
 #pragma unroll
@@ -150,7 +147,6 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
     s1 = s2;
     s2 = r;
   }
-  RB_STAMP(3, 2);
   // epilogue: register r of tile t is hypothesis m0 + 32 t + 8 (r / 4) + 4 kg + r % 4, column n0 + col
   float *zcol = a.Z + n0 + col;
 #pragma unroll
@@ -160,8 +156,6 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
       const int m = m0 + 32 * t + 8 * (r >> 2) + 4 * kg + (r & 3);
       if (m < a.M) store_through(zcol + (size_t)m * a.Npad, acc[t][r] + bias);
     }
-  RB_STAMP(3, 3);
-  RB_BLOCK_TS_K(0, 1);
 }
 
 // Stateless prediction network for the large mode: a_m = bf16(ReLU(f_proj[b, t_m] + sum_i tab_i[token_i]))

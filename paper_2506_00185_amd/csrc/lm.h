@@ -9,6 +9,8 @@
 namespace rb {
 int lm_vocab(const rnnt_lm_t *lm);
 int lm_order(const rnnt_lm_t *lm);
+// a number no other LM created in this process has had (graphs that captured an LM's tables are keyed by it)
+uint64_t lm_id(const rnnt_lm_t *lm);
 // the tables of an LM as kernel arguments (for launches that carry LM rows as extra blocks)
 LmView lm_view(const rnnt_lm_t *lm);
 // LM scores (natural log) of every token after each of M hypotheses.

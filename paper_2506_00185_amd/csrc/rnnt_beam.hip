@@ -9,8 +9,11 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <mutex>
+#include <new>
 #include <string>
 #include <tuple>
+#include <type_traits>
 #include <vector>
 
 #include "kernels.h"
@@ -46,25 +49,14 @@ enum {
 const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init",      "k_step_main", "k_select",    "k_lm_rows",
                                       "k_lstm_pointwise",    "k_pred_proj", "k_backtrace", "k_joint_big", "k_row_select"};
 
-}  // namespace
-
-struct rnnt_beam {
-  rnnt_config_t cfg;
-  std::string err;
-  int N = 0, n_chunks = 0, M_max = 0, Mp = 0, S_max = 0, cap = 0, pc_chunks = 0;
-  std::vector<void *> allocs;
-  // packed weights
-  float *W_enc = nullptr, *b_enc = nullptr, *W_pred = nullptr, *b_pred = nullptr, *W_out = nullptr,
-        *b_out = nullptr, *W_hh = nullptr, *G = nullptr, *tab = nullptr;
-  // workspace
+// Device memory a decode works in beyond its inputs and outputs, laid out for given maxima.  The handle owns one
+// (a single allocation made at create); the allocation-free entry point lays one out in the static array.
+struct Workspace {
   float *f_proj = nullptr, *pre = nullptr, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
   float *lm_rows = nullptr, *Rgates = nullptr;
   int *tile_ctr = nullptr;
-  // materialised-logits path (bf16 joint, large shapes)
-  bool big = false;
-  int Npad_big = 0, Hb = 0;  // padded extents of the bf16 operands: 256 columns, 64 k
-  uint16_t *Wb = nullptr, *Ab = nullptr;
-  float *Zbig = nullptr, *Wspec = nullptr, *bias_spec = nullptr, *b_big = nullptr;
+  uint16_t *Ab = nullptr;   // materialised-logits path only
+  float *Zbig = nullptr;
   double *score = nullptr;
   int *t = nullptr, *sym = nullptr, *len = nullptr, *last = nullptr, *ctx = nullptr, *lengths = nullptr;
   uint32_t *hash = nullptr;
@@ -73,22 +65,103 @@ struct rnnt_beam {
   uint64_t *p_cand = nullptr;
   int *tree_parent = nullptr, *tree_token = nullptr, *tree_merged = nullptr;
   int *finished = nullptr, *utt_steps = nullptr, *ctrl = nullptr;  // ctrl: n_finished, done, step_base, bad_arg, nonfinite
-  int *h_done = nullptr, *h_done_dev = nullptr;                    // pinned host word and its device alias
-  int *out_tokens = nullptr, *out_lens = nullptr, *out_steps = nullptr;
-  double *out_scores = nullptr;
+  int *out_tokens = nullptr, *out_lens = nullptr, *out_steps = nullptr;  // n-best lists; the allocation-free entry
+  double *out_scores = nullptr;                                          // point points these at the caller's arrays
+  int Mp = 0, S_max = 0, cap = 0, pc_chunks = 0, max_B = 0;
+};
+
+// Assigns the pointers of `w` inside [base, ..) for a model `c` and the maxima given, every array on a 256-byte
+// boundary, and returns the bytes needed.  base == nullptr: only the size is computed.  with_out: room for the
+// n-best lists too.  big: the arrays of the materialised-logits path (Npad_big columns, Hb padded k).
+size_t layout_workspace(Workspace &w, char *base, const rnnt_config_t &c, int n_chunks, int max_B, int max_T,
+                        int max_beam, bool with_out, bool big, int Npad_big, int Hb) {
+  size_t off = 0;
+  auto take = [&](auto **p, size_t n) {
+    typedef typename std::remove_reference<decltype(**p)>::type T;
+    *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+    off += (n * sizeof(T) + 255) / 256 * 256;
+  };
+  const size_t M = (size_t)max_B * max_beam;
+  w.max_B = max_B;
+  w.Mp = (int)((M + 31) / 32 * 32 + 32);  // a joint tile may start at any multiple of the beam and reads 32 rows
+  w.S_max = max_T * (c.max_symbols + 1);
+  w.cap = max_T * c.max_symbols + 1;
+  w.pc_chunks = n_chunks > 64 ? n_chunks : 64;
+  take(&w.f_proj, (size_t)max_B * max_T * c.H);
+  take(&w.pre, (size_t)w.Mp * c.H);
+  for (int i = 0; i < 2; ++i) {
+    take(&w.h[i], (size_t)w.Mp * c.P);
+    take(&w.c[i], (size_t)w.Mp * c.P);
+  }
+  if (big) {
+    take(&w.Ab, (size_t)w.Mp * Hb);
+    take(&w.Zbig, M * Npad_big);
+  }
+  take(&w.lm_rows, M * c.V);
+  take(&w.Rgates, M * 4 * c.P);
+  take(&w.tile_ctr, (size_t)max_B);
+  take(&w.score, M);
+  take(&w.t, M);
+  take(&w.sym, M);
+  take(&w.len, M);
+  take(&w.last, M);
+  take(&w.hash, M);
+  take(&w.ctx, M * kCtxMax);
+  take(&w.lengths, (size_t)max_B);
+  take(&w.src_row, M);
+  take(&w.tok, M);
+  take(&w.p_max, M * w.pc_chunks);
+  take(&w.p_sum, M * w.pc_chunks);
+  take(&w.p_cand, M * w.pc_chunks * max_beam);
+  take(&w.zs, M * (1 + 8));
+  const size_t tree = (size_t)max_B * w.S_max * max_beam;
+  take(&w.tree_parent, tree);
+  take(&w.tree_token, tree);
+  take(&w.tree_merged, tree);
+  take(&w.finished, (size_t)max_B);
+  take(&w.utt_steps, (size_t)max_B);
+  take(&w.ctrl, 8);
+  if (with_out) {
+    take(&w.out_tokens, M * w.cap);
+    take(&w.out_lens, M);
+    take(&w.out_scores, M);
+    take(&w.out_steps, (size_t)max_B);
+  }
+  return off;
+}
+
+}  // namespace
+
+struct rnnt_beam {
+  rnnt_config_t cfg;
+  std::string err;
+  int N = 0, n_chunks = 0, M_max = 0;
+  std::vector<void *> allocs;
+  // packed weights
+  float *W_enc = nullptr, *b_enc = nullptr, *W_pred = nullptr, *b_pred = nullptr, *W_out = nullptr,
+        *b_out = nullptr, *W_hh = nullptr, *G = nullptr, *tab = nullptr;
+  // materialised-logits path (bf16 joint, large shapes)
+  bool big = false;
+  int Npad_big = 0, Hb = 0;  // padded extents of the bf16 operands: 256 columns, 64 k
+  uint16_t *Wb = nullptr;
+  float *Wspec = nullptr, *bias_spec = nullptr, *b_big = nullptr;
+  Workspace ws;         // the handle's own workspace, laid out for max_B / max_T / max_beam in one allocation
+  int *h_done = nullptr, *h_done_dev = nullptr;  // pinned host word and its device alias
   // last decode
   bool have_result = false;
   int last_B = 0, last_K = 0, last_T = 0;
   hipStream_t last_stream = nullptr;
   hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_chunk[4] = {nullptr, nullptr, nullptr, nullptr};
   bool profiling = false;
+  bool events_off = false;  // set while the allocation-free entry point enqueues (no event may be created)
   std::vector<hipEvent_t> prof_events;              // pool, two per timed launch
   std::vector<std::pair<int, int>> prof_launches;   // (kernel id, index of its first event)
   size_t prof_used = 0;
   KernelTimer timers[KT_COUNT];
   // graphs of one chunk of steps, keyed by the launch shape
-  typedef std::tuple<int, int, int, int, const void *, uint32_t> GraphKey;
-  std::map<GraphKey, hipGraphExec_t> graphs;
+  typedef std::tuple<int, int, int, int, uint64_t, uint32_t> GraphKey;  // B, beam, algo, T, LM id, LM weight
+  std::map<GraphKey, std::pair<hipGraphExec_t, uint64_t>> graphs;       // (graph, creation serial)
+  uint64_t graph_serial = 0;
 };
 
 namespace {
@@ -132,17 +205,17 @@ int fail(rnnt_beam *h, int code, const std::string &msg) {
 
 int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
 
+// The projection of the prediction step split in two along k (k_pred_proj_half): taken when whole tiles would leave
+// half of the compute units idle.  Needs P % 128 == 0 (each half of k is divided among 8 waves in steps of 8).
+// (With fewer than 8 hypotheses the main launch is so short that the recurrent tiles moved into it would set its
+// duration: 508 instead of 739 audio-s/s at batch 1, beam 1.)
+bool proj_split(const rnnt_config_t &c, int M) {
+  return c.P % 128 == 0 && M >= 8 && (c.H / 32) * ((M + 31) / 32) * 2 <= 256;
+}
+
 // Gate tiles of the recurrent product computed in the prediction-projection launch (the rest ride in the
 // main launch): as many as fit beside the projection's own blocks, one block per compute unit, on every XCD
 // (32 compute units each).
-// the projection of the prediction step split in two along k (k_pred_proj_half): when whole tiles would leave half
-// of the compute units idle, for the kernels that keep their operands in registers
-// (with fewer than 8 hypotheses the main launch is so short that the recurrent tiles moved into it would set its
-// duration: 508 instead of 739 audio-s/s at batch 1, beam 1)
-bool proj_split(const rnnt_config_t &c, int M) {
-  return c.P == 640 && M >= 8 && (c.H / 32) * ((M + 31) / 32) * 2 <= 256;
-}
-
 int recurrent_split(const rnnt_config_t &c, int M) {
   if (proj_split(c, M)) return 0;  // no recurrent tiles beside the half tiles: they would set that launch's duration
   XcdMap m;
@@ -175,6 +248,7 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
   const int H = c.H, P = c.P, D = c.D, E = c.E, V = c.V, N = h->N;
   const bool bf = c.prec == RNNT_BF16_JOINT;
   std::vector<float> tmp, out;
+  std::vector<void *> staging;  // device buffers needed only until the folded tables have been computed
   int rc;
   // encoder projection
   if ((rc = download(h, tmp, w->W_enc, (size_t)H * D))) return rc;
@@ -190,6 +264,7 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
     for (auto &x : wpred) x = host_bf16_round(x);
   float *d_wpred_rm = nullptr;
   if ((rc = upload(h, &d_wpred_rm, wpred))) return rc;
+  staging.push_back(d_wpred_rm);
   if ((rc = upload(h, &h->W_pred, to_k4(wpred, H, P, H)))) return rc;
   if ((rc = download(h, bpred, w->b_pred, H))) return rc;
   if ((rc = upload(h, &h->b_pred, bpred))) return rc;
@@ -248,9 +323,12 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
     // G[v] = W_ih emb[v] + b_ih + b_hh for every token (and the start symbol): one GEMM at create
     float *d_wih = nullptr, *d_b = nullptr, *d_emb = nullptr;
     if ((rc = upload(h, &d_wih, wih_p))) return rc;
+    staging.push_back(d_wih);
     if ((rc = upload(h, &d_b, b_p))) return rc;
+    staging.push_back(d_b);
     if ((rc = download(h, emb, w->emb, (size_t)(V + 1) * E))) return rc;
     if ((rc = upload(h, &d_emb, emb))) return rc;
+    staging.push_back(d_emb);
     if ((rc = dev_alloc(h, &h->G, (size_t)(V + 1) * 4 * P))) return rc;
     if ((rc = launch_gemm(h, nullptr, d_emb, d_wih, d_b, h->G, V + 1, 4 * P, E, 0, nullptr))) return rc;
   } else {
@@ -261,6 +339,7 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
     if ((rc = download(h, emb, w->emb, (size_t)ctx * (V + 1) * P))) return rc;
     float *d_emb = nullptr;
     if ((rc = upload(h, &d_emb, emb))) return rc;
+    staging.push_back(d_emb);
     if ((rc = dev_alloc(h, &h->tab, (size_t)ctx * (V + 1) * H))) return rc;
     for (int i = 0; i < ctx; ++i)
       if ((rc = launch_gemm(h, nullptr, d_emb + (size_t)i * (V + 1) * P, d_wpred_rm, i == 0 ? h->b_pred : nullptr,
@@ -268,6 +347,15 @@ int pack_weights(rnnt_beam *h, const rnnt_weights_t *w) {
         return rc;
   }
   RB_HIP(h, hipDeviceSynchronize());
+  // the row-major copies were only the operands of the folding products above
+  for (void *q : staging) {
+    hipFree(q);
+    for (size_t i = 0; i < h->allocs.size(); ++i)
+      if (h->allocs[i] == q) {
+        h->allocs.erase(h->allocs.begin() + i);
+        break;
+      }
+  }
   return RNNT_OK;
 }
 
@@ -278,6 +366,10 @@ struct StepPlan {
   const float *inj_tok, *inj_dur;
   int C;
   bool big = false;  // logits through HBM (k_joint_big + k_row_select) instead of the fused main kernel
+  const Workspace *ws = nullptr;  // where the decode works
+  bool ahead = false;             // enqueue the upper bound of steps at once instead of following the device
+  bool plain = false;             // no graph and no profiling events (nothing that could allocate)
+  int out_cap = 0;                // row length of ws->out_tokens
 };
 
 // Timing wrapper used in profiling mode: an event before and after the launch, nothing waits.
@@ -290,7 +382,7 @@ struct ScopedKernelTime {
   size_t first = 0;
   bool on = false;
   ScopedKernelTime(rnnt_beam *h_, hipStream_t s_, int w) : h(h_), s(s_), which(w) {
-    if (!h->profiling) return;
+    if (!h->profiling || h->events_off) return;
     while (h->prof_events.size() < h->prof_used + 2) {
       hipEvent_t e = nullptr;
       if (hipEventCreate(&e) != hipSuccess) return;
@@ -309,8 +401,9 @@ struct ScopedKernelTime {
 // fuse_lm: the LM rows of the new hypotheses ride in the cell-update launch (LSTM models only; the caller
 // then skips the stand-alone LM launch)
 int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bump, bool fuse_lm = false) {
+  const Workspace &w = *p.ws;
   const rnnt_config_t &c = h->cfg;
-  int *done = h->ctrl + 1, *step_base = h->ctrl + 2;
+  int *done = w.ctrl + 1, *step_base = w.ctrl + 2;
   const int m_tiles = (p.M + 31) / 32;
   if (p.inj_tok) {
     if (bump) hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done);
@@ -322,26 +415,26 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       size_t lds = 0;
       if (fuse_lm && p.lm) {
         lmr.view = lm_view(p.lm);
-        lmr.ctx = h->ctx; lmr.len = h->len; lmr.out = h->lm_rows;
+        lmr.ctx = w.ctx; lmr.len = w.len; lmr.out = w.lm_rows;
         lmr.M = p.M;
         lmr.first_block = n_blocks;
         lds = sizeof(float) * (size_t)c.V;
       }
       const bool split = proj_split(c, p.M);
-      hipLaunchKernelGGL(k_lstm_pointwise, dim3(n_blocks + lmr.M), dim3(256), lds, s, h->Rgates, h->G, h->h[cur],
-                         h->c[cur], h->h[cur ^ 1], h->c[cur ^ 1], h->src_row, h->tok, p.M, h->Mp, c.P, done, lmr,
-                         split ? h->pre : nullptr, split ? c.H * h->Mp : 0);
+      hipLaunchKernelGGL(k_lstm_pointwise, dim3(n_blocks + lmr.M), dim3(256), lds, s, w.Rgates, h->G, w.h[cur],
+                         w.c[cur], w.h[cur ^ 1], w.c[cur ^ 1], w.src_row, w.tok, p.M, w.Mp, c.P, done, lmr,
+                         split ? w.pre : nullptr, split ? c.H * w.Mp : 0);
     }
     {
       PredProjArgs a;
-      a.Wp = h->W_pred; a.bias = h->b_pred; a.h = h->h[cur ^ 1]; a.f_proj = h->f_proj;
-      a.t = h->t; a.lengths = h->lengths;
-      a.pre = h->pre;
-      a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
+      a.Wp = h->W_pred; a.bias = h->b_pred; a.h = w.h[cur ^ 1]; a.f_proj = w.f_proj;
+      a.t = w.t; a.lengths = w.lengths;
+      a.pre = w.pre;
+      a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
       a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
       a.done = done; a.step_base = step_base; a.bump = bump;
-      a.rec.Whh = h->W_hh; a.rec.h = h->h[cur ^ 1]; a.rec.R = h->Rgates;
-      a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = h->Mp;
+      a.rec.Whh = h->W_hh; a.rec.h = w.h[cur ^ 1]; a.rec.R = w.Rgates;
+      a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp;
       a.map.a_tiles = c.H / 32; a.map.a_m = m_tiles;
       a.map.b_begin = 0; a.map.b_end = recurrent_split(c, p.M); a.map.b_m = m_tiles;
       ScopedKernelTime tm(h, s, KT_PREDPROJ);
@@ -351,7 +444,10 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       }
       const dim3 grid(xcd_grid(a.map));
 #define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), 0, s, a)
-      if (proj_split(c, p.M)) hipLaunchKernelGGL((k_pred_proj_half<8, 5>), grid, dim3(512), 0, s, a);
+      if (proj_split(c, p.M)) {
+        if (c.P == 640) hipLaunchKernelGGL((k_pred_proj_half<8, 5>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((k_pred_proj_half<8, 0>), grid, dim3(512), 0, s, a);
+      }
       else if (c.P == 640) RB_PRED(8, 10);
       else if (c.P % 64 == 0) RB_PRED(8, 0);
       else RB_PRED(4, 0);
@@ -359,18 +455,18 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
     }
   } else if (p.big) {
     StatelessPreBigArgs a;
-    a.f_proj = h->f_proj; a.tab = h->tab; a.ctx_tok = h->ctx; a.t = h->t; a.lengths = h->lengths;
-    a.Ab = h->Ab;
-    a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
+    a.f_proj = w.f_proj; a.tab = h->tab; a.ctx_tok = w.ctx; a.t = w.t; a.lengths = w.lengths;
+    a.Ab = w.Ab;
+    a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
     a.done = done; a.step_base = step_base; a.bump = bump;
     ScopedKernelTime tm(h, s, KT_PREDPROJ);
     const int n = p.M * (c.H / 8);
     hipLaunchKernelGGL(k_stateless_pre_big, dim3((n + 255) / 256), dim3(256), 0, s, a);
   } else {
     StatelessPreArgs a;
-    a.f_proj = h->f_proj; a.tab = h->tab; a.ctx_tok = h->ctx; a.t = h->t; a.lengths = h->lengths;
-    a.pre = h->pre;
-    a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
+    a.f_proj = w.f_proj; a.tab = h->tab; a.ctx_tok = w.ctx; a.t = w.t; a.lengths = w.lengths;
+    a.pre = w.pre;
+    a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
     a.done = done; a.step_base = step_base; a.bump = bump;
     ScopedKernelTime tm(h, s, KT_PREDPROJ);
     const int n = p.M * (c.H / 4);
@@ -381,19 +477,21 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
 }
 
 int launch_lm(rnnt_beam *h, hipStream_t s, const StepPlan &p) {
+  const Workspace &w = *p.ws;
   if (!p.lm) return RNNT_OK;
   ScopedKernelTime tm(h, s, KT_LM);
-  lm_launch_rows(p.lm, h->ctx, h->len, h->lm_rows, p.M, h->ctrl + 1, s);
+  lm_launch_rows(p.lm, w.ctx, w.len, w.lm_rows, p.M, w.ctrl + 1, s);
   RB_HIP(h, hipGetLastError());
   return RNNT_OK;
 }
 
 void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunks, SelectArgs &a) {
+  const Workspace &w = *p.ws;
   const rnnt_config_t &c = h->cfg;
-  a.score = h->score; a.t = h->t; a.sym = h->sym; a.len = h->len; a.last = h->last; a.hash = h->hash;
-  a.ctx = h->ctx;
-  a.lengths = h->lengths;
-  a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
+  a.score = w.score; a.t = w.t; a.sym = w.sym; a.len = w.len; a.last = w.last; a.hash = w.hash;
+  a.ctx = w.ctx;
+  a.lengths = w.lengths;
+  a.p_max = w.p_max; a.p_sum = w.p_sum; a.p_cand = w.p_cand; a.zs = w.zs;
   a.n_chunks = n_chunks;
   a.normalized = p.inj_tok ? 1 : 0;
   a.use_ctx = (c.pred == RNNT_PRED_STATELESS || p.lm) ? 1 : 0;
@@ -405,14 +503,14 @@ void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunk
   a.has_lm = p.lm ? 1 : 0;
   a.lm_rule3 = c.lm_rule == 3 ? 1 : 0;
   a.lm_early = (p.lm && c.lm_early_pruning) ? 1 : 0;
-  a.lm_rows = h->lm_rows;
+  a.lm_rows = w.lm_rows;
   a.lambda = p.lambda;
-  a.src_row = h->src_row; a.tok = h->tok;
-  a.tree_parent = h->tree_parent; a.tree_token = h->tree_token; a.tree_merged = h->tree_merged;
-  a.S_max = h->S_max;
-  a.step_base = h->ctrl + 2;
+  a.src_row = w.src_row; a.tok = w.tok;
+  a.tree_parent = w.tree_parent; a.tree_token = w.tree_token; a.tree_merged = w.tree_merged;
+  a.S_max = w.S_max;
+  a.step_base = w.ctrl + 2;
   a.step_off = step_off;
-  a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = h->ctrl; a.done = h->ctrl + 1;
+  a.finished = w.finished; a.utt_steps = w.utt_steps; a.n_finished = w.ctrl; a.done = w.ctrl + 1;
   a.h_done = h->h_done_dev;
 }
 
@@ -425,20 +523,21 @@ void launch_select(rnnt_beam *h, hipStream_t s, const StepPlan &p, const SelectA
 
 // one beam-search step; cur = parity of the prediction-network state it reads
 int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, int cur, int bump) {
+  const Workspace &w = *p.ws;
   const rnnt_config_t &c = h->cfg;
-  int *done = h->ctrl + 1;
+  int *done = w.ctrl + 1;
   const int kt = beam_template(p.K);
   if (p.inj_tok) {
     InjectArgs a;
     a.tok_logp = p.inj_tok;
     a.dur_logp = p.inj_dur;
     a.C = p.C;
-    a.t = h->t;
-    a.hash = h->hash;
-    a.lengths = h->lengths;
+    a.t = w.t;
+    a.hash = w.hash;
+    a.lengths = w.lengths;
     a.M = p.M; a.K = p.K; a.T = p.T; a.V = c.V; a.ND = c.n_durations;
-    a.p_cand = h->p_cand;
-    a.zs = h->zs;
+    a.p_cand = w.p_cand;
+    a.zs = w.zs;
     a.done = done;
     {
       ScopedKernelTime tm(h, s, KT_JOINT);
@@ -455,8 +554,8 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     constexpr int MS = 5;  // 160 hypotheses per block
     {
       BigJointArgs a;
-      a.Wb = h->Wb; a.Ab = h->Ab; a.bias = h->b_big; a.Z = h->Zbig;
-      a.M = p.M; a.Mp = h->Mp; a.H = h->Hb; a.Npad = h->Npad_big;
+      a.Wb = h->Wb; a.Ab = w.Ab; a.bias = h->b_big; a.Z = w.Zbig;
+      a.M = p.M; a.Mp = w.Mp; a.H = h->Hb; a.Npad = h->Npad_big;
       constexpr int WV = 4;  // waves per block; the block covers 32 * WV columns
       a.map.a_tiles = h->Npad_big / (32 * WV); a.map.a_m = (p.M + 32 * MS - 1) / (32 * MS);
       a.map.b_begin = a.map.b_end = 0; a.map.b_m = 0;
@@ -470,13 +569,13 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     RB_HIP(h, hipGetLastError());
     {
       RowSelectArgs a;
-      a.Z = h->Zbig; a.Npad = h->Npad_big; a.Ab = h->Ab; a.M = p.M; a.Mp = h->Mp; a.H = c.H;
+      a.Z = w.Zbig; a.Npad = h->Npad_big; a.Ab = w.Ab; a.M = p.M; a.Mp = w.Mp; a.H = c.H;
       a.K = p.K; a.V = c.V; a.ND = c.n_durations;
       a.Wspec = h->Wspec; a.bias_spec = h->bias_spec;
-      a.lm = (p.lm && !c.lm_early_pruning) ? h->lm_rows : nullptr;  // early pruning ranks without the LM term
+      a.lm = (p.lm && !c.lm_early_pruning) ? w.lm_rows : nullptr;  // early pruning ranks without the LM term
       a.lambda = p.lambda;
-      a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
-      a.finished = h->finished; a.done = done;
+      a.p_max = w.p_max; a.p_sum = w.p_sum; a.p_cand = w.p_cand; a.zs = w.zs;
+      a.finished = w.finished; a.done = done;
       ScopedKernelTime tm(h, s, KT_ROWSELECT);
       hipLaunchKernelGGL(k_row_select, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
     }
@@ -489,22 +588,22 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     }
   } else {
     MainArgs a;
-    a.pre = h->pre;
+    a.pre = w.pre;
     a.W = h->W_out;
     a.bias = h->b_out;
-    a.lm = (p.lm && !c.lm_early_pruning) ? h->lm_rows : nullptr;  // early pruning ranks without the LM term
+    a.lm = (p.lm && !c.lm_early_pruning) ? w.lm_rows : nullptr;  // early pruning ranks without the LM term
     a.lambda = p.lambda;
-    a.M = p.M; a.Mp = h->Mp; a.K = p.K; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
+    a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.H = c.H; a.V = c.V; a.ND = c.n_durations;
     a.n_chunks = h->n_chunks;
     a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
     a.upt = 32 / p.K < 8 ? 32 / p.K : 8;  // one wave of the completing block per utterance
     a.rpt = a.upt * p.K;
     a.n_jtiles = (p.B + a.upt - 1) / a.upt;
-    a.p_max = h->p_max; a.p_sum = h->p_sum; a.p_cand = h->p_cand; a.zs = h->zs;
-    a.tile_ctr = h->tile_ctr;
+    a.p_max = w.p_max; a.p_sum = w.p_sum; a.p_cand = w.p_cand; a.zs = w.zs;
+    a.tile_ctr = w.tile_ctr;
     const bool lstm = c.pred == RNNT_PRED_LSTM;
-    a.rec.Whh = h->W_hh; a.rec.h = h->h[cur]; a.rec.R = h->Rgates;
-    a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = h->Mp;
+    a.rec.Whh = h->W_hh; a.rec.h = w.h[cur]; a.rec.R = w.Rgates;
+    a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp;
     a.map.a_tiles = a.n_chunks; a.map.a_m = a.n_jtiles;
     a.map.b_begin = lstm ? recurrent_split(c, p.M) : 0;
     a.map.b_end = lstm ? 4 * c.P / 32 : 0;
@@ -514,7 +613,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     // The selection runs in the tail of this kernel for the beams its in-kernel forms take.  (Building the kernel
     // without it lets two blocks share a compute unit, but they also share its operand path: measured slower at
     // every shape, 11.3 vs 10.6 ms at B * beam = 256, beam 4.)
-    const bool tail = p.K <= 8 && !c.tdt_all_pairs && !getenv("RNNT_NO_TAIL");
+    const bool tail = p.K <= 8 && !c.tdt_all_pairs;
 #define RB_MAIN(W, I)                                                                              \
   do {                                                                                             \
     if (tail) hipLaunchKernelGGL((k_step_main<W, I, true>), grid, dim3(W * 64), 0, s, a);         \
@@ -543,21 +642,15 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
 }
 
 // steps per graph launch (even: the state parity flips every step)
-int chunk_steps() {
-  static int v = [] {
-    const char *e = getenv("RNNT_BEAM_CHUNK");
-    int n = e ? atoi(e) : 16;
-    if (n < 2) n = 2;
-    return n & ~1;
-  }();
-  return v;
-}
-#define kChunkSteps chunk_steps()
+constexpr int kChunkSteps = 16;
+// instantiated graphs kept per handle (one per launch shape, LM and LM weight); the oldest is dropped beyond that
+constexpr size_t kMaxGraphs = 8;
 
 int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const StepPlan &p, hipStream_t s) {
+  const Workspace &w = *p.ws;
   const rnnt_config_t &c = h->cfg;
-  int *n_finished = h->ctrl, *done = h->ctrl + 1, *step_base = h->ctrl + 2, *bad_arg = h->ctrl + 3,
-      *nonfinite = h->ctrl + 4;
+  int *n_finished = w.ctrl, *done = w.ctrl + 1, *step_base = w.ctrl + 2, *bad_arg = w.ctrl + 3,
+      *nonfinite = w.ctrl + 4;
   h->have_result = false;
   // the previous decode may still be writing the pinned completion word
   if (h->last_stream) RB_HIP(h, hipStreamSynchronize(h->last_stream));
@@ -567,22 +660,22 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   RB_HIP(h, hipEventRecord(h->ev_begin, s));
   {
     InitArgs a;
-    a.score = h->score; a.t = h->t; a.sym = h->sym; a.len = h->len; a.last = h->last; a.hash = h->hash;
-    a.ctx = h->ctx;
+    a.score = w.score; a.t = w.t; a.sym = w.sym; a.len = w.len; a.last = w.last; a.hash = w.hash;
+    a.ctx = w.ctx;
     a.lengths_in = lengths;
-    a.lengths = h->lengths;
-    a.src_row = h->src_row; a.tok = h->tok;
+    a.lengths = w.lengths;
+    a.src_row = w.src_row; a.tok = w.tok;
     const bool lstm = c.pred == RNNT_PRED_LSTM && !p.inj_tok;
-    a.h0 = lstm ? h->h[1] : nullptr;
-    a.c0 = lstm ? h->c[1] : nullptr;
-    a.n_state = (size_t)c.P * h->Mp;
-    a.R = lstm ? h->Rgates : nullptr;
+    a.h0 = lstm ? w.h[1] : nullptr;
+    a.c0 = lstm ? w.c[1] : nullptr;
+    a.n_state = (size_t)c.P * w.Mp;
+    a.R = lstm ? w.Rgates : nullptr;
     a.n_R = (size_t)p.M * 4 * c.P;
-    a.tile_ctr = h->tile_ctr;
-    a.n_tiles = c.max_B;
+    a.tile_ctr = w.tile_ctr;
+    a.n_tiles = w.max_B;
     a.B = p.B; a.K = p.K; a.T = p.T; a.V = c.V;
     a.lstm = lstm ? 1 : 0;
-    a.finished = h->finished; a.utt_steps = h->utt_steps; a.n_finished = n_finished; a.done = done;
+    a.finished = w.finished; a.utt_steps = w.utt_steps; a.n_finished = n_finished; a.done = done;
     a.step_base = step_base; a.bad_arg = bad_arg;
     a.h_done = h->h_done_dev;
     *reinterpret_cast<volatile int *>(h->h_done) = 0;
@@ -593,7 +686,7 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   RB_HIP(h, hipGetLastError());
   if (!p.inj_tok) {
     ScopedKernelTime tm(h, s, KT_ENCPROJ);
-    int rc = launch_gemm(h, s, enc, h->W_enc, h->b_enc, h->f_proj, p.B * p.T, c.H, c.D,
+    int rc = launch_gemm(h, s, enc, h->W_enc, h->b_enc, w.f_proj, p.B * p.T, c.H, c.D,
                          c.prec == RNNT_BF16_JOINT ? 1 : 0, nonfinite);
     if (rc) return rc;
   }
@@ -602,40 +695,53 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   if (rc) return rc;
   if ((rc = launch_lm(h, s, p))) return rc;
 
-  const int max_steps = h->S_max;
-  const bool use_graph = c.use_graph && !h->profiling && !p.inj_tok;
+  // every utterance has finished after at most T (s + 1) steps (the selection enforces it)
+  const int max_steps = p.T * (c.max_symbols + 1) < w.S_max ? p.T * (c.max_symbols + 1) : w.S_max;
+  const bool use_graph = c.use_graph && !h->profiling && !p.inj_tok && !p.plain;
   hipGraphExec_t exec = nullptr;
   if (use_graph) {
+    // The captured kernel arguments hold the LM's device tables: the key carries the LM's unique id, not its
+    // address, which a later LM may be given again.
     uint32_t lbits;
     memcpy(&lbits, &p.lambda, 4);
-    rnnt_beam::GraphKey key(p.B, p.K, p.algo, p.T, (const void *)p.lm, lbits);
+    rnnt_beam::GraphKey key(p.B, p.K, p.algo, p.T, p.lm ? lm_id(p.lm) : 0, lbits);
     auto it = h->graphs.find(key);
     if (it == h->graphs.end()) {
       hipStream_t cs;
       RB_HIP(h, hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
-      hipGraph_t graph;
-      RB_HIP(h, hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
-      for (int i = 0; i < kChunkSteps; ++i) {
-        rc = launch_step(h, cs, p, i, i & 1, i == kChunkSteps - 1 ? kChunkSteps : 0);
-        if (rc) break;
+      hipGraph_t graph = nullptr;
+      hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
+      if (e == hipSuccess) {
+        for (int i = 0; i < kChunkSteps; ++i) {
+          rc = launch_step(h, cs, p, i, i & 1, i == kChunkSteps - 1 ? kChunkSteps : 0);
+          if (rc) break;
+        }
+        e = hipStreamEndCapture(cs, &graph);  // always ended, also after a failed launch
       }
-      hipError_t e = hipStreamEndCapture(cs, &graph);
+      if (e == hipSuccess && !rc) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+      if (graph) hipGraphDestroy(graph);
+      hipStreamDestroy(cs);
       if (rc) return rc;
       RB_HIP(h, e);
-      RB_HIP(h, hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0));
-      RB_HIP(h, hipGraphDestroy(graph));
-      RB_HIP(h, hipStreamDestroy(cs));
-      h->graphs[key] = exec;
+      if (h->graphs.size() >= kMaxGraphs) {  // drop the graph that was created first
+        auto oldest = h->graphs.begin();
+        for (auto g = h->graphs.begin(); g != h->graphs.end(); ++g)
+          if (g->second.second < oldest->second.second) oldest = g;
+        hipGraphExecDestroy(oldest->second.first);
+        h->graphs.erase(oldest);
+      }
+      h->graphs[key] = std::make_pair(exec, h->graph_serial++);
     } else {
-      exec = it->second;
+      exec = it->second.first;
     }
   }
-  // The number of steps depends on the data.  Chunks of steps are enqueued ahead of the
-  // device; a pinned word written by the selection kernel tells the host when every
-  // utterance has finished.  Kernels of steps enqueued after that point return at once.
+  // The number of steps depends on the data.  Chunks of steps are enqueued ahead of the device; a pinned word
+  // written by the selection tells the host when every utterance has finished, and kernels of steps enqueued
+  // after that point return at once (at most two chunks of them).  `ahead`: the upper bound of steps is enqueued
+  // without looking at that word, so the call returns without waiting for the device.
   int enq = 0, chunk_i = 0;
   while (enq < max_steps) {
-    if (*reinterpret_cast<volatile int *>(h->h_done)) break;
+    if (!p.ahead && *reinterpret_cast<volatile int *>(h->h_done)) break;
     if (use_graph) {
       RB_HIP(h, hipGraphLaunch(exec, s));
     } else {
@@ -643,24 +749,26 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
         if ((rc = launch_step(h, s, p, i, i & 1, i == kChunkSteps - 1 ? kChunkSteps : 0))) return rc;
     }
     enq += kChunkSteps;
-    RB_HIP(h, hipEventRecord(h->ev_chunk[chunk_i & 3], s));
-    if (chunk_i >= 2) RB_HIP(h, hipEventSynchronize(h->ev_chunk[(chunk_i - 2) & 3]));
+    if (!p.ahead) {
+      RB_HIP(h, hipEventRecord(h->ev_chunk[chunk_i & 3], s));
+      if (chunk_i >= 2) RB_HIP(h, hipEventSynchronize(h->ev_chunk[(chunk_i - 2) & 3]));
+    }
     ++chunk_i;
   }
   {
     BacktraceArgs a;
-    a.score = h->score;
-    a.len = h->len;
-    a.tree_parent = h->tree_parent;
-    a.tree_token = h->tree_token;
-    a.utt_steps = h->utt_steps;
+    a.score = w.score;
+    a.len = w.len;
+    a.tree_parent = w.tree_parent;
+    a.tree_token = w.tree_token;
+    a.utt_steps = w.utt_steps;
     a.step_base = step_base;
     a.K = p.K;
-    a.S_max = h->S_max;
-    a.cap = h->cap;
-    const size_t lds = (size_t)h->S_max * p.K * 2 * sizeof(int);
+    a.S_max = w.S_max;
+    a.cap = p.out_cap ? p.out_cap : w.cap;
+    const size_t lds = (size_t)w.S_max * p.K * 2 * sizeof(int);
     a.use_lds = lds <= 64 * 1024;
-    a.out_tokens = h->out_tokens; a.out_lens = h->out_lens; a.out_scores = h->out_scores; a.out_steps = h->out_steps;
+    a.out_tokens = w.out_tokens; a.out_lens = w.out_lens; a.out_scores = w.out_scores; a.out_steps = w.out_steps;
     ScopedKernelTime tm(h, s, KT_BACKTRACE);
     hipLaunchKernelGGL(k_backtrace, dim3(p.B), dim3(64), a.use_lds ? lds : 0, s, a);
   }
@@ -683,11 +791,18 @@ int check_shapes(rnnt_beam *h, int B, int T, int beam, int algo) {
   return RNNT_OK;
 }
 
+int check_lm(rnnt_beam *h, const rnnt_lm_t *lm, int algo) {
+  if (lm && lm_vocab(lm) != h->cfg.V) return fail(h, RNNT_E_ARG, "LM vocabulary differs from the model's");
+  if (lm && algo == RNNT_AES && std::isfinite(h->cfg.prune_margin))
+    return fail(h, RNNT_E_ARG, "an LM together with a finite prune margin is not supported");
+  return RNNT_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_beam_t **out) {
+int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_beam_t **out) try {
   if (out) *out = nullptr;
   if (!cfg || !w || !out || cfg->struct_size != sizeof(rnnt_config_t)) {
     g_create_error = "NULL argument or struct_size mismatch";
@@ -734,11 +849,11 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   if (c.lm_early_pruning != 0 && c.lm_early_pruning != 1) return bad("lm_early_pruning must be 0 or 1");
   if (!(c.prune_margin >= 0.f)) return bad("prune_margin must be >= 0 (INFINITY = off)");
 
+  if (c.async_enqueue != 0 && c.async_enqueue != 1) return bad("async_enqueue must be 0 or 1");
+
   h->N = c.V + 1 + c.n_durations;
   h->n_chunks = (h->N + 31) / 32;
-  h->pc_chunks = h->n_chunks > 64 ? h->n_chunks : 64;
   h->M_max = c.max_B * c.max_beam;
-  h->Mp = (h->M_max + 31) / 32 * 32 + 32;  // a joint tile may start at any multiple of K and reads 32 rows
   {
     const bool can = c.prec == RNNT_BF16_JOINT && c.pred == RNNT_PRED_STATELESS && c.V <= kRowWaves * 64 * 4 * kRowRegs &&
                      c.H % 16 == 0;
@@ -750,60 +865,33 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     h->Npad_big = (c.V + 255) / 256 * 256;
     h->Hb = (c.H + 63) / 64 * 64;
   }
-  h->S_max = c.max_T * (c.max_symbols + 1);
-  h->cap = c.max_T * c.max_symbols + 1;
-  const size_t M = h->M_max;
   int rc = RNNT_OK;
   auto A = [&](int r) {
     if (!rc) rc = r;
   };
-  A(pack_weights(h, w));
-  A(dev_alloc(h, &h->f_proj, (size_t)c.max_B * c.max_T * c.H));
-  A(dev_alloc(h, &h->pre, (size_t)h->Mp * c.H));
-  for (int i = 0; i < 2; ++i) {
-    A(dev_alloc(h, &h->h[i], (size_t)h->Mp * c.P));
-    A(dev_alloc(h, &h->c[i], (size_t)h->Mp * c.P));
+  try {
+    A(pack_weights(h, w));
+    if (!rc) {
+      const size_t bytes = layout_workspace(h->ws, nullptr, c, h->n_chunks, c.max_B, c.max_T, c.max_beam, true, h->big,
+                                            h->Npad_big, h->Hb);
+      char *base = nullptr;
+      A(dev_alloc(h, &base, bytes));
+      if (!rc) {
+        layout_workspace(h->ws, base, c, h->n_chunks, c.max_B, c.max_T, c.max_beam, true, h->big, h->Npad_big, h->Hb);
+        // (the padded k of the bf16 activations must read as zero; the control words start at zero)
+        if (hipMemset(base, 0, bytes) != hipSuccess) rc = RNNT_E_HIP;
+      }
+    }
+  } catch (const std::bad_alloc &) {
+    h->err = "out of host memory";
+    rc = RNNT_E_NOMEM;
   }
-  if (h->big) {
-    A(dev_alloc(h, &h->Ab, (size_t)h->Mp * h->Hb));
-    if (!rc && hipMemset(h->Ab, 0, (size_t)h->Mp * h->Hb * sizeof(uint16_t)) != hipSuccess) rc = RNNT_E_HIP;  // k >= H stays zero
-    A(dev_alloc(h, &h->Zbig, M * h->Npad_big));
-  }
-  A(dev_alloc(h, &h->lm_rows, M * c.V));
-  A(dev_alloc(h, &h->Rgates, M * 4 * c.P));
-  A(dev_alloc(h, &h->tile_ctr, (size_t)c.max_B));
-  A(dev_alloc(h, &h->score, M));
-  A(dev_alloc(h, &h->t, M));
-  A(dev_alloc(h, &h->sym, M));
-  A(dev_alloc(h, &h->len, M));
-  A(dev_alloc(h, &h->last, M));
-  A(dev_alloc(h, &h->hash, M));
-  A(dev_alloc(h, &h->ctx, M * kCtxMax));
-  A(dev_alloc(h, &h->lengths, (size_t)c.max_B));
-  A(dev_alloc(h, &h->src_row, M));
-  A(dev_alloc(h, &h->tok, M));
-  A(dev_alloc(h, &h->p_max, M * h->pc_chunks));
-  A(dev_alloc(h, &h->p_sum, M * h->pc_chunks));
-  A(dev_alloc(h, &h->p_cand, M * h->pc_chunks * c.max_beam));
-  A(dev_alloc(h, &h->zs, M * (1 + 8)));
-  const size_t tree = (size_t)c.max_B * h->S_max * c.max_beam;
-  A(dev_alloc(h, &h->tree_parent, tree));
-  A(dev_alloc(h, &h->tree_token, tree));
-  A(dev_alloc(h, &h->tree_merged, tree));
-  A(dev_alloc(h, &h->finished, (size_t)c.max_B));
-  A(dev_alloc(h, &h->utt_steps, (size_t)c.max_B));
-  A(dev_alloc(h, &h->ctrl, 8));
-  A(dev_alloc(h, &h->out_tokens, M * h->cap));
-  A(dev_alloc(h, &h->out_lens, M));
-  A(dev_alloc(h, &h->out_scores, M));
-  A(dev_alloc(h, &h->out_steps, (size_t)c.max_B));
   if (!rc) {
     hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&h->h_done), 64, hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&h->h_done_dev), h->h_done, 0);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
     for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&h->ev_chunk[i]);
-    if (e == hipSuccess) e = hipMemset(h->ctrl, 0, 8 * sizeof(int));
     if (e != hipSuccess) {
       h->err = std::string("create: ") + hipGetErrorString(e);
       rc = RNNT_E_HIP;
@@ -816,79 +904,103 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   }
   *out = h;
   return RNNT_OK;
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_HIP;
 }
 
 int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T, int32_t beam,
-                     int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream) {
+                     int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream) try {
   if (!h) return RNNT_E_ARG;
   if (!enc || !lengths) return fail(h, RNNT_E_ARG, "NULL enc or lengths");
   int rc = check_shapes(h, B, T, beam, algo);
   if (rc) return rc;
-  if (lm && lm_vocab(lm) != h->cfg.V) return fail(h, RNNT_E_ARG, "LM vocabulary differs from the model's");
-  if (lm && algo == RNNT_AES && std::isfinite(h->cfg.prune_margin))
-    return fail(h, RNNT_E_ARG, "an LM together with a finite prune margin is not supported");
+  if ((rc = check_lm(h, lm, algo))) return rc;
   StepPlan p{B, beam, T, algo, B * beam, lm, lm ? lm_weight : 0.f, nullptr, nullptr, 1};
   p.big = h->big && (h->cfg.joint_path == RNNT_JOINT_MATERIALIZED || B * beam >= 128);
+  p.ws = &h->ws;
+  p.ahead = h->cfg.async_enqueue != 0;
   return run_decode(h, enc, lengths, p, static_cast<hipStream_t>(hip_stream));
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_HIP;
 }
 
 int rnnt_beam_decode_injected(rnnt_beam_t *h, const float *tok_logp, const float *dur_logp, int32_t C,
                               const int32_t *lengths, int32_t B, int32_t T, int32_t beam, int32_t algo,
-                              void *hip_stream) {
+                              void *hip_stream) try {
   if (!h) return RNNT_E_ARG;
   if (!tok_logp || !lengths || C < 1) return fail(h, RNNT_E_ARG, "NULL table or lengths, or C < 1");
   if (h->cfg.n_durations > 0 && !dur_logp) return fail(h, RNNT_E_ARG, "TDT needs dur_logp");
   int rc = check_shapes(h, B, T, beam, algo);
   if (rc) return rc;
   StepPlan p{B, beam, T, algo, B * beam, nullptr, 0.f, tok_logp, dur_logp, C};
+  p.ws = &h->ws;
   return run_decode(h, nullptr, lengths, p, static_cast<hipStream_t>(hip_stream));
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_HIP;
 }
 
-int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *lens, double *scores, int32_t *n_steps) {
+int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *lens, double *scores,
+                      int32_t *n_steps) try {
   if (!h) return RNNT_E_ARG;
   if (!h->have_result) return fail(h, RNNT_E_NORESULT, "no decode has been run");
   RB_HIP(h, hipStreamSynchronize(h->last_stream));
+  const Workspace &w = h->ws;
   const int B = h->last_B, K = h->last_K;
   int flags[2] = {0, 0};
-  RB_HIP(h, hipMemcpy(flags, h->ctrl + 3, sizeof(flags), hipMemcpyDeviceToHost));
-  if (lens) RB_HIP(h, hipMemcpy(lens, h->out_lens, sizeof(int) * B * K, hipMemcpyDeviceToHost));
-  if (scores) RB_HIP(h, hipMemcpy(scores, h->out_scores, sizeof(double) * B * K, hipMemcpyDeviceToHost));
-  if (n_steps) RB_HIP(h, hipMemcpy(n_steps, h->out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
+  RB_HIP(h, hipMemcpy(flags, w.ctrl + 3, sizeof(flags), hipMemcpyDeviceToHost));
+  if (lens) RB_HIP(h, hipMemcpy(lens, w.out_lens, sizeof(int) * B * K, hipMemcpyDeviceToHost));
+  if (scores) RB_HIP(h, hipMemcpy(scores, w.out_scores, sizeof(double) * B * K, hipMemcpyDeviceToHost));
+  if (n_steps) RB_HIP(h, hipMemcpy(n_steps, w.out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
   if (tokens && cap > 0) {
-    std::vector<int> buf((size_t)B * K * h->cap), ln((size_t)B * K);
-    RB_HIP(h, hipMemcpy(buf.data(), h->out_tokens, sizeof(int) * buf.size(), hipMemcpyDeviceToHost));
-    RB_HIP(h, hipMemcpy(ln.data(), h->out_lens, sizeof(int) * ln.size(), hipMemcpyDeviceToHost));
+    std::vector<int> buf((size_t)B * K * w.cap), ln((size_t)B * K);
+    RB_HIP(h, hipMemcpy(buf.data(), w.out_tokens, sizeof(int) * buf.size(), hipMemcpyDeviceToHost));
+    RB_HIP(h, hipMemcpy(ln.data(), w.out_lens, sizeof(int) * ln.size(), hipMemcpyDeviceToHost));
     for (size_t i = 0; i < ln.size(); ++i) {
       const int n = ln[i] < cap ? ln[i] : cap;
-      for (int u = 0; u < n; ++u) tokens[i * cap + u] = buf[i * h->cap + u];
+      for (int u = 0; u < n; ++u) tokens[i * cap + u] = buf[i * w.cap + u];
     }
   }
   if (flags[1]) return fail(h, RNNT_E_NONFINITE, "NaN or Inf in the encoder projection");
   if (flags[0]) return fail(h, RNNT_E_ARG, "an utterance length was outside 0..T (clamped)");
   return RNNT_OK;
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_HIP;
 }
 
-int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t *merged_into, int32_t s_cap) {
+int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t *merged_into, int32_t s_cap) try {
   if (!h) return RNNT_E_ARG;
   if (!h->have_result) return fail(h, RNNT_E_NORESULT, "no decode has been run");
   RB_HIP(h, hipStreamSynchronize(h->last_stream));
+  const Workspace &w = h->ws;
   const int B = h->last_B, K = h->last_K;
   std::vector<int> steps(B);
-  RB_HIP(h, hipMemcpy(steps.data(), h->out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
-  const int *src[3] = {h->tree_parent, h->tree_token, h->tree_merged};
+  RB_HIP(h, hipMemcpy(steps.data(), w.out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
+  const int *src[3] = {w.tree_parent, w.tree_token, w.tree_merged};
   int32_t *dst[3] = {parent, token, merged_into};
-  std::vector<int> buf((size_t)h->S_max * K);
+  std::vector<int> buf((size_t)w.S_max * K);
   for (int a = 0; a < 3; ++a) {
     if (!dst[a]) continue;
     for (size_t i = 0; i < (size_t)s_cap * B * K; ++i) dst[a][i] = -9;
     for (int b = 0; b < B; ++b) {
-      RB_HIP(h, hipMemcpy(buf.data(), src[a] + (size_t)b * h->S_max * K, sizeof(int) * buf.size(),
+      RB_HIP(h, hipMemcpy(buf.data(), src[a] + (size_t)b * w.S_max * K, sizeof(int) * buf.size(),
                           hipMemcpyDeviceToHost));
       for (int st = 0; st < steps[b] && st < s_cap; ++st)
         for (int k = 0; k < K; ++k) dst[a][((size_t)st * B + b) * K + k] = buf[(size_t)st * K + k];
     }
   }
   return RNNT_OK;
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_HIP;
 }
 
 int rnnt_beam_debug_encproj(rnnt_beam_t *h, float *out, int64_t n_floats) {
@@ -897,7 +1009,7 @@ int rnnt_beam_debug_encproj(rnnt_beam_t *h, float *out, int64_t n_floats) {
   RB_HIP(h, hipStreamSynchronize(h->last_stream));
   const int64_t n = (int64_t)h->last_B * h->last_T * h->cfg.H;
   if (n_floats < n) return fail(h, RNNT_E_ARG, "buffer too small");
-  RB_HIP(h, hipMemcpy(out, h->f_proj, sizeof(float) * n, hipMemcpyDeviceToHost));
+  RB_HIP(h, hipMemcpy(out, h->ws.f_proj, sizeof(float) * n, hipMemcpyDeviceToHost));
   return RNNT_OK;
 }
 
@@ -954,22 +1066,12 @@ int rnnt_beam_kernel_times(rnnt_beam_t *h, const char **names, float *ms, int32_
   return n;
 }
 
-#ifdef RB_TIMING
-int rnnt_beam_debug_block_ts(long long *out) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_block_ts), sizeof(long long) * 3 * 2048) == hipSuccess ? 0 : RNNT_E_HIP;
-}
-// tuning builds only: copy the phase stamps out (8 kernels x 16 stamps, 10 ns ticks)
-int rnnt_beam_debug_stamps(long long *out) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(rb_stamps), sizeof(long long) * 8 * 16) == hipSuccess ? 0 : RNNT_E_HIP;
-}
-#endif
-
 const char *rnnt_beam_last_error(const rnnt_beam_t *h) { return h ? h->err.c_str() : g_create_error.c_str(); }
 
 void rnnt_beam_destroy(rnnt_beam_t *h) {
   if (!h) return;
   hipDeviceSynchronize();
-  for (auto &kv : h->graphs) hipGraphExecDestroy(kv.second);
+  for (auto &kv : h->graphs) hipGraphExecDestroy(kv.second.first);
   for (void *p : h->allocs) hipFree(p);
   if (h->h_done) hipHostFree(h->h_done);
   hipEvent_t evs[] = {h->ev_begin, h->ev_end, h->ev_chunk[0], h->ev_chunk[1], h->ev_chunk[2], h->ev_chunk[3]};

@@ -10,6 +10,7 @@
 //   * a query fills a vocabulary-sized row in LDS with the unigram scores plus
 //     all back-off weights, then overwrites it level by level with the stored
 //     successors of longer and longer contexts.
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -20,6 +21,7 @@
 #include "lm_device.h"
 
 struct rnnt_lm {
+  uint64_t id = 0;  // unique per created LM in this process (a later LM may reuse this one's address)
   int order = 0, V = 0, bits = 0;
   uint32_t ht_mask = 0;
   // device
@@ -45,6 +47,7 @@ __global__ __launch_bounds__(256) void k_lm_rows(LmView lm, const int *__restric
 
 int lm_vocab(const rnnt_lm_t *lm) { return lm->V; }
 int lm_order(const rnnt_lm_t *lm) { return lm->order; }
+uint64_t lm_id(const rnnt_lm_t *lm) { return lm->id; }
 
 LmView lm_view(const rnnt_lm_t *lm) {
   return LmView{lm->ht_key, lm->ht_val, lm->ctx_bo, lm->ctx_begin, lm->ctx_count, lm->succ_tok,
@@ -72,8 +75,9 @@ bool lm_upload(rnnt_lm *lm, T **p, const std::vector<T> &v) {
 
 extern "C" {
 
+// (no exception leaves these functions: host containers that cannot grow report RNNT_E_NOMEM)
 int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const int8_t *ngram_order,
-                   const float *log10_prob, const float *log10_backoff, int32_t V, rnnt_lm_t **out) {
+                   const float *log10_prob, const float *log10_backoff, int32_t V, rnnt_lm_t **out) try {
   if (out) *out = nullptr;
   if (!out || !ngram_tokens || !ngram_order || !log10_prob || !log10_backoff || order < 1 || n < 1 || V < 1)
     return RNNT_E_ARG;
@@ -138,6 +142,8 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
   }
   rnnt_lm *lm = new (std::nothrow) rnnt_lm();
   if (!lm) return RNNT_E_NOMEM;
+  static std::atomic<uint64_t> next_id{1};
+  lm->id = next_id.fetch_add(1);
   lm->order = order;
   lm->V = V;
   lm->bits = bits;
@@ -153,9 +159,13 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
   }
   *out = lm;
   return RNNT_OK;
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_ARG;
 }
 
-int rnnt_lm_debug_query(const rnnt_lm_t *lm, const int32_t *ctx_tokens, int32_t n, float *out) {
+int rnnt_lm_debug_query(const rnnt_lm_t *lm, const int32_t *ctx_tokens, int32_t n, float *out) try {
   if (!lm || !ctx_tokens || !out || n < 1) return RNNT_E_ARG;
   const int w = lm->order - 1;
   std::vector<int> ctx((size_t)n * rb::kCtxMax, -1);
@@ -179,6 +189,10 @@ int rnnt_lm_debug_query(const rnnt_lm_t *lm, const int32_t *ctx_tokens, int32_t 
   hipFree(d_ctx);
   hipFree(d_out);
   return rc;
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_ARG;
 }
 
 void rnnt_lm_destroy(rnnt_lm_t *lm) {

@@ -251,6 +251,57 @@ def aes_frame_synchronous(logp_fn, T, V, s, K):
     return closed
 
 
+def aes_bucketed(logp_fn, T, V, s, K, durations=(), gamma=math.inf):
+    """The two-set loop of ``aes_frame_synchronous`` for models whose symbols carry durations (TDT), and with a
+    prune margin.  A hypothesis that leaves frame t by a blank or by a token of duration d >= 1 is put into the
+    waiting set of the frame it lands on (``bucket[t + d]``, clamped at T = finished); tokens of duration 0 keep it
+    open in the frame for the next round, at most ``s`` of them.  Frames are visited in order; the hypotheses
+    waiting at a frame become its open set; every round expands all open hypotheses by one symbol (one duration
+    per symbol: ``duration_rule``), lets every waiting hypothesis of every later frame compete with its score as
+    it is, keeps the K best, and merges equal transcripts that wait at the same frame.  ``gamma``: a symbol
+    (blank included) whose log-probability is more than gamma below the best one of its hypothesis is not
+    expanded; a blank forced by the frame limit is kept.  Returns {transcript: score} of the finished set."""
+    bucket = {t: {} for t in range(T + 1)}
+    bucket[0][()] = 0.0
+    for t in range(T):
+        open_, bucket[t] = bucket[t], {}
+        rnd = 0
+        while open_:
+            cands = []  # (score, landing frame or None = stays open, transcript)
+            for toks, sc in open_.items():
+                logp, dlogp = logp_fn(t, toks)
+                if durations:
+                    adv_tok, x_tok, adv_blank, x_blank = duration_rule(dlogp, durations)
+                else:
+                    adv_tok, x_tok, adv_blank, x_blank = 0, 0.0, 1, 0.0
+                floor = max(logp) - gamma
+                forced = rnd >= s
+                if forced or logp[V] >= floor:
+                    cands.append((sc + logp[V] + x_blank, min(t + adv_blank, T), toks))
+                if not forced:
+                    for v in range(V):
+                        if logp[v] >= floor:
+                            cands.append((sc + logp[v] + x_tok, None if adv_tok == 0 else min(t + adv_tok, T),
+                                          toks + (v,)))
+            for tw in range(t + 1, T + 1):
+                for toks, sc in bucket[tw].items():
+                    cands.append((sc, tw, toks))
+            cands.sort(key=lambda x: -x[0])
+            if len(cands) > K:
+                assert cands[K - 1][0] != cands[K][0], "exact tie at the cut: the case cannot pin the order"
+            open_ = {}
+            for tw in range(t + 1, T + 1):
+                bucket[tw] = {}
+            for sc, land, toks in cands[:K]:
+                if land is None:
+                    assert toks not in open_
+                    open_[toks] = sc
+                else:
+                    bucket[land][toks] = logaddexp(bucket[land].get(toks, -math.inf), sc)
+            rnd += 1
+    return bucket[T]
+
+
 def alsd_two_stage(logp_fn, fused_fn, T, V, s, K):
     """Alignment-length synchronous search with early pruning, written with dictionaries
     (Sec. 2.3, "Early/late pruning"): at every step all expansions of the unfinished hypotheses

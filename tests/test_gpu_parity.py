@@ -370,6 +370,32 @@ def test_graph_replay_equals_plain_launches_and_repeats(amd):
     np.testing.assert_array_equal(r3["scores"], rb["scores"])
 
 
+def test_async_enqueue_gives_the_same_result(amd):
+    """async_enqueue = 1 enqueues the upper bound of steps without following the device; the result is the
+    same as that of the default loop, bit for bit, with and without graph replay."""
+    c = S.custom_config(B=5, T=20, T_min=6, D=128, H=160, P=160, E=160, V=300, beam=4, s=3, algo="alsd")
+    w, L, enc = _case(c, 900)
+    ref = gpu_decode(amd.BeamDecoder(c, w, use_graph=False), enc, L)
+    for graph in (True, False):
+        dec = amd.BeamDecoder(c, w, use_graph=graph, async_enqueue=True)
+        for _ in range(2):
+            r = gpu_decode(dec, enc, L)
+            for key in ("tokens", "lens", "scores", "n_steps", "parent", "token", "merged"):
+                np.testing.assert_array_equal(r[key], ref[key])
+
+
+def test_split_projection_at_a_generic_width(amd, oracle):
+    """P = 128: the prediction projection is split in two along k across blocks with the generic (any P % 128 == 0)
+    form of the kernel, and all gate tiles ride in the main launch."""
+    c = S.custom_config(B=6, T=18, T_min=7, D=64, H=96, P=128, E=64, V=90, beam=4, s=2, algo="alsd", blank_bias=3.0)
+    w, L, enc = _case(c, 970)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 6 and full >= 4
+
+
 def test_error_paths(amd):
     import torch
     from paper_2506_00185_amd import RnntBeamError
