@@ -162,6 +162,26 @@ int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, i
                      int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, void *hip_stream);
 
 /*
+ * For callers that cannot allocate device memory (code under HIP graph capture, serving loops, harnesses that
+ * forbid it): rnnt_beam_decode with its whole workspace (hypothesis state, candidate lists, tree, encoder
+ * projection, LSTM state) in a static 64 MiB device array of the library instead of the handle's allocation,
+ * and the n-best lists written straight to the caller's DEVICE arrays: tokens [B, beam, cap] (positions beyond
+ * a length untouched, longer transcripts truncated), lens [B, beam], scores [B, beam] (float64), n_steps [B],
+ * flags [2] (nullable: 1 if a length was outside 0..T and clamped; 1 if the encoder projection held NaN or Inf).
+ * Calls no hipMalloc / hipFree and creates no graph or event; all steps are enqueued at once (as with
+ * async_enqueue) and the call returns without waiting: synchronise hip_stream before reading the outputs.
+ * Always takes the fused joint path.  Returns RNNT_E_ARG when B, T and beam need more than the 64 MiB
+ * (roughly: B * T * H * 4 bytes of encoder projection + 12 B * T (max_symbols + 1) beam bytes of tree must fit;
+ * batch 64 x 250 frames at H = 640 does).  Every call on a GPU uses that GPU's one array: calls that overlap
+ * in time on one GPU (any handles, any streams) race; nothing is kept from one call to the next.
+ * rnnt_beam_results / rnnt_beam_dump_tree do not apply to it.
+ */
+int rnnt_beam_decode_static(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T,
+                            int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, int32_t *tokens,
+                            int32_t cap, int32_t *lens, double *scores, int32_t *n_steps, int32_t *flags,
+                            void *hip_stream);
+
+/*
  * Wait for the last decode and copy its n-best lists to host memory.  The transcripts are read off the
  * hypothesis tree by following the parent pointers back from the final slots (Sec. 2.1, "Efficient
  * hypothesis storing"); no length normalisation is applied.  Host arrays, caller-owned: tokens [B, beam, cap]

@@ -16,7 +16,7 @@ ALSD, AES = 0, 1
 EXPORTS = ["rnnt_beam_create", "rnnt_lm_create", "rnnt_beam_decode", "rnnt_beam_results",
            "rnnt_beam_decode_injected", "rnnt_beam_dump_tree", "rnnt_beam_debug_encproj", "rnnt_lm_debug_query",
            "rnnt_beam_last_decode_ms", "rnnt_beam_set_profiling", "rnnt_beam_kernel_times", "rnnt_beam_last_error",
-           "rnnt_beam_destroy", "rnnt_lm_destroy", "rnnt_beam_debug_block_map"]
+           "rnnt_beam_destroy", "rnnt_lm_destroy", "rnnt_beam_debug_block_map", "rnnt_beam_decode_static"]
 
 
 class RnntBeamError(RuntimeError):
@@ -195,6 +195,32 @@ class BeamDecoder:
                                              C.c_int32(B), C.c_int32(T), C.c_int32(beam), C.c_int32(algo),
                                              lm.handle if lm is not None else None, C.c_float(lm_weight),
                                              C.c_void_p(s.cuda_stream))
+        _check(rc, self.handle)
+
+    # -- rnnt_beam_decode_static ---------------------------------------------
+    def decode_static(self, enc, lengths, tokens, lens, scores, n_steps, flags=None, beam=None, algo=None,
+                      lm: NGramLM | None = None, lm_weight=0.0, stream=None):
+        """All arrays are CUDA tensors owned by the caller: tokens int32 [B, beam, cap], lens int32 [B, beam],
+        scores float64 [B, beam], n_steps int32 [B], flags int32 [2] or None.  Returns without waiting."""
+        torch = _torch()
+        assert enc.is_cuda and enc.dtype == torch.float32 and enc.is_contiguous()
+        assert lengths.is_cuda and lengths.dtype == torch.int32 and lengths.is_contiguous()
+        B, T, D = enc.shape
+        beam = self.c["beam"] if beam is None else beam
+        algo = (AES if self.c["algo"] == "aes" else ALSD) if algo is None else algo
+        assert tokens.is_cuda and tokens.dtype == torch.int32 and tokens.is_contiguous() and tokens.shape[:2] == (B, beam)
+        assert lens.is_cuda and lens.dtype == torch.int32 and lens.is_contiguous() and lens.shape == (B, beam)
+        assert scores.is_cuda and scores.dtype == torch.float64 and scores.is_contiguous() and scores.shape == (B, beam)
+        assert n_steps.is_cuda and n_steps.dtype == torch.int32 and n_steps.shape == (B,)
+        assert flags is None or (flags.is_cuda and flags.dtype == torch.int32 and flags.numel() >= 2)
+        s = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self._keep = (enc, lengths, lm, tokens, lens, scores, n_steps, flags)
+        rc = load_library().rnnt_beam_decode_static(
+            self.handle, C.c_void_p(enc.data_ptr()), C.c_void_p(lengths.data_ptr()), C.c_int32(B), C.c_int32(T),
+            C.c_int32(beam), C.c_int32(algo), lm.handle if lm is not None else None, C.c_float(lm_weight),
+            C.c_void_p(tokens.data_ptr()), C.c_int32(tokens.shape[2]), C.c_void_p(lens.data_ptr()),
+            C.c_void_p(scores.data_ptr()), C.c_void_p(n_steps.data_ptr()),
+            C.c_void_p(flags.data_ptr()) if flags is not None else None, C.c_void_p(s.cuda_stream))
         _check(rc, self.handle)
 
     def decode_injected(self, tok_logp, dur_logp, lengths, beam=None, algo=None, stream=None):

@@ -22,6 +22,14 @@
 
 using namespace rb;
 
+// Workspace of rnnt_beam_decode_static: one array per GPU for the life of the process.  In host code the name
+// below is only a handle for the symbol look-up; the device address of each GPU's copy is kept in g_scratch_ptr.
+constexpr size_t kScratchBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+static char *g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
 namespace {
 
 thread_local std::string g_create_error;
@@ -798,6 +806,10 @@ int check_lm(rnnt_beam *h, const rnnt_lm_t *lm, int algo) {
   return RNNT_OK;
 }
 
+__global__ void k_copy_int(int *dst, const int *src, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) dst[i] = src[i];
+}
+
 }  // namespace
 
 extern "C" {
@@ -922,6 +934,59 @@ int rnnt_beam_decode(rnnt_beam_t *h, const float *enc, const int32_t *lengths, i
   p.ws = &h->ws;
   p.ahead = h->cfg.async_enqueue != 0;
   return run_decode(h, enc, lengths, p, static_cast<hipStream_t>(hip_stream));
+} catch (const std::bad_alloc &) {
+  return RNNT_E_NOMEM;
+} catch (...) {
+  return RNNT_E_HIP;
+}
+
+int rnnt_beam_decode_static(rnnt_beam_t *h, const float *enc, const int32_t *lengths, int32_t B, int32_t T,
+                            int32_t beam, int32_t algo, const rnnt_lm_t *lm, float lm_weight, int32_t *tokens,
+                            int32_t cap, int32_t *lens, double *scores, int32_t *n_steps, int32_t *flags,
+                            void *hip_stream) try {
+  if (!h) return RNNT_E_ARG;
+  if (!enc || !lengths || !tokens || !lens || !scores || !n_steps || cap < 1)
+    return fail(h, RNNT_E_ARG, "NULL array or cap < 1");
+  int rc = check_shapes(h, B, T, beam, algo);
+  if (rc) return rc;
+  if ((rc = check_lm(h, lm, algo))) return rc;
+  // the static array of the current device (its address is looked up once per device)
+  int dev = -1;
+  RB_HIP(h, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(h, RNNT_E_ARG, "device index beyond the library's table");
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void *q = nullptr;
+      RB_HIP(h, hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+      g_scratch_ptr[dev] = static_cast<char *>(q);
+    }
+  }
+  Workspace ws;
+  const size_t need = layout_workspace(ws, g_scratch_ptr[dev], h->cfg, h->n_chunks, B, T, beam, false, false, 0, 0);
+  if (need > kScratchBytes)
+    return fail(h, RNNT_E_ARG, "rnnt_beam_decode_static: B, T and beam need more than the 64 MiB static workspace");
+  ws.out_tokens = tokens;
+  ws.out_lens = lens;
+  ws.out_scores = scores;
+  ws.out_steps = n_steps;
+  StepPlan p{B, beam, T, algo, B * beam, lm, lm ? lm_weight : 0.f, nullptr, nullptr, 1};
+  p.big = false;  // the fused path only: the logits of the other path would not fit
+  p.ws = &ws;
+  p.ahead = true;
+  p.plain = true;
+  p.out_cap = cap;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  h->events_off = true;
+  rc = run_decode(h, enc, lengths, p, s);
+  h->events_off = false;
+  h->have_result = false;  // the n-best lists went to the caller's arrays, not to the handle
+  if (rc) return rc;
+  if (flags) {
+    hipLaunchKernelGGL(k_copy_int, dim3(1), dim3(64), 0, s, flags, ws.ctrl + 3, 2);
+    RB_HIP(h, hipGetLastError());
+  }
+  return RNNT_OK;
 } catch (const std::bad_alloc &) {
   return RNNT_E_NOMEM;
 } catch (...) {
