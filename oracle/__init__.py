@@ -181,10 +181,12 @@ def decode(c: dict, w: dict | None, enc, lengths, beam=None, algo=None, lm: LM |
 
 # ---- unit-level entry points (for the pins) ---------------------------------
 
-def enc_proj(c, w, enc_t):
+def enc_proj(c, w, enc_t, rounded=False):
+    """``rounded``: the joint's weight matrices in ``w`` have been rounded to bf16 already (same result, faster)."""
     cfg, W = make_config(c), Weights(w)
     out = np.empty(c["H"], np.float64)
-    lib().orc_enc_proj(C.byref(cfg), C.byref(W.struct), _ptr(_f32(enc_t)), _ptr(out))
+    fn = lib().orc_enc_proj_rounded if rounded else lib().orc_enc_proj
+    fn(C.byref(cfg), C.byref(W.struct), _ptr(_f32(enc_t)), _ptr(out))
     return out
 
 
@@ -196,25 +198,28 @@ def lstm_step(c, w, h, cc, token):
     return h2, c2
 
 
-def pred_proj(c, w, h):
+def pred_proj(c, w, h, rounded=False):
     cfg, W = make_config(c), Weights(w)
     out = np.empty(c["H"], np.float64)
-    lib().orc_pred_proj(C.byref(cfg), C.byref(W.struct), _ptr(_f64(h)), _ptr(out))
+    fn = lib().orc_pred_proj_rounded if rounded else lib().orc_pred_proj
+    fn(C.byref(cfg), C.byref(W.struct), _ptr(_f64(h)), _ptr(out))
     return out
 
 
-def stateless_pred(c, w, tokens):
+def stateless_pred(c, w, tokens, rounded=False):
     cfg, W = make_config(c), Weights(w)
     t = _i32(np.asarray(tokens, dtype=np.int32).reshape(-1))
     out = np.empty(c["H"], np.float64)
-    lib().orc_stateless_pred(C.byref(cfg), C.byref(W.struct), _ptr(t), C.c_int(t.size), _ptr(out))
+    fn = lib().orc_stateless_pred_rounded if rounded else lib().orc_stateless_pred
+    fn(C.byref(cfg), C.byref(W.struct), _ptr(t), C.c_int(t.size), _ptr(out))
     return out
 
 
-def joint(c, w, f, g):
+def joint(c, w, f, g, rounded=False):
     cfg, W = make_config(c), Weights(w)
     out = np.empty(c["V"] + 1 + len(c["durations"]), np.float64)
-    lib().orc_joint(C.byref(cfg), C.byref(W.struct), _ptr(_f64(f)), _ptr(_f64(g)), _ptr(out))
+    fn = lib().orc_joint_rounded if rounded else lib().orc_joint
+    fn(C.byref(cfg), C.byref(W.struct), _ptr(_f64(f)), _ptr(_f64(g)), _ptr(out))
     return out
 
 

@@ -213,6 +213,25 @@ void orc_joint(const orc_config *c, const orc_weights *w, const double *f, const
   joint_impl(c, w, f, g, z, 0);
 }
 
+/* The same three joint-network products for callers that hold the weight matrices already rounded to bf16
+ * (rounding is idempotent, so the results are those of the functions above; the per-call rounding of every
+ * weight is what is saved). */
+void orc_enc_proj_rounded(const orc_config *c, const orc_weights *w, const float *enc_t, double *f) {
+  enc_proj_impl(c, w, enc_t, f, 1);
+}
+void orc_pred_proj_rounded(const orc_config *c, const orc_weights *w, const double *h, double *g) {
+  pred_proj_impl(c, w, h, g, 1, 0);
+}
+void orc_stateless_pred_rounded(const orc_config *c, const orc_weights *w, const int *tokens, int len, double *g) {
+  double *e = (double *)malloc(sizeof(double) * (size_t)c->P);
+  orc_stateless_embed(c, w, tokens, len, e);
+  pred_proj_impl(c, w, e, g, 1, 1);
+  free(e);
+}
+void orc_joint_rounded(const orc_config *c, const orc_weights *w, const double *f, const double *g, double *z) {
+  joint_impl(c, w, f, g, z, 1);
+}
+
 /* ---------------------------------------------------------------- n-gram LM */
 
 typedef struct {
@@ -699,7 +718,7 @@ static void decode_utterance(utt_job *J) {
         if (kind[k] != 2) continue;
         for (int v = 0; v <= V; ++v) {
           int64_t i = (int64_t)k * (V + 1) + v;
-          if (unpruned[i] >= thr - 1e-3) {
+          if (isfinite(unpruned[i]) && unpruned[i] >= thr - 1e-3) {
             double dist = fabs(rowlogp[i] - (rowmax[k] - c->gamma));
             if (dist < step_gap) step_gap = dist;
           }

@@ -31,7 +31,21 @@ def gpu_decode_injected(dec, tok, dur, lengths, **kw):
     return r
 
 
-def compare(g, o, tol, tie, exact_tree=False, rows=None):
+def make_walk(oracle, c, w, enc, L, g, tol, lm=None, lm_weight=0.0, lm_rule=4, lm_prune="late"):
+    """walk(gb): step-by-step validity check of the GPU's own tree of batch row ``gb`` (see tree_check.py)."""
+    from tree_check import check_tree
+
+    def walk(gb):
+        n = int(g["n_steps"][gb])
+        nbest = [(tuple(int(x) for x in g["tokens"][gb, j, :g["lens"][gb, j]]), float(g["scores"][gb, j]))
+                 for j in range(g["lens"].shape[1]) if g["lens"][gb, j] >= 0]
+        return check_tree(oracle, c, w, enc[gb], int(L[gb]), g["parent"][:n, gb], g["token"][:n, gb],
+                          g["merged"][:n, gb], n, nbest, slack=2 * tol, tol=tol, lm=lm, lm_weight=lm_weight,
+                          lm_rule=lm_rule, lm_prune=lm_prune)
+    return walk
+
+
+def compare(g, o, tol, tie, exact_tree=False, rows=None, walk=None):
     """GPU result ``g`` against oracle result ``o`` (decoded with log=True).
 
     Per utterance: the trees (parent, token, merged_into of every live slot) must
@@ -39,13 +53,16 @@ def compare(g, o, tol, tie, exact_tree=False, rows=None):
     below ``tie``: the first step where the two trees differ must itself be such
     a step.  If they are identical throughout, step counts and token sequences
     must be identical and scores within ``tol``.  An utterance whose tree leaves
-    the oracle's at a near tie is exempt from there on.
+    the oracle's at a near tie cannot be compared with the oracle's from there on;
+    ``walk`` (see ``make_walk``) then checks the GPU's own tree step by step,
+    from the first step to the last, and its n-best list.
     ``exact_tree``: no exemption at all.  ``rows``: GPU batch rows that the
-    oracle rows correspond to.  Returns (n_full_match, n_exempt).
+    oracle rows correspond to.  Returns (n_full_match, n_left_the_oracles_tree).
     """
     B = o["lens"].shape[0]
     rows = list(range(B)) if rows is None else rows
     full, exempt = 0, 0
+    left = []
     for ob, gb in enumerate(rows):
         n = int(o["n_steps"][ob])
         gaps = o["log_gap"][ob, :n]
@@ -72,6 +89,7 @@ def compare(g, o, tol, tie, exact_tree=False, rows=None):
                 f"oracle {o['log_parent'][ob, diverged_at]} {o['log_token'][ob, diverged_at]} "
                 f"gpu {g['parent'][diverged_at, gb]} {g['token'][diverged_at, gb]}")
             exempt += 1
+            left.append(gb)
             continue
         np.testing.assert_array_equal(g["lens"][gb], o["lens"][ob])
         for j in range(o["lens"].shape[1]):
@@ -83,4 +101,11 @@ def compare(g, o, tol, tie, exact_tree=False, rows=None):
             assert abs(g["scores"][gb, j] - o["scores"][ob, j]) <= tol, (
                 gb, j, g["scores"][gb, j], o["scores"][ob, j])
         full += 1
+    if walk is not None and left:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, len(left))) as pool:  # the oracle's C routines release the GIL
+            reports = list(pool.map(walk, left))
+        print(f"walked {len(left)} trees that left the oracle's: steps checked {[r['steps_checked'] for r in reports]}, "
+              f"stopped at a duration near tie {sum(r['stopped_at_duration_tie'] for r in reports)}, largest score "
+              f"difference {max([r.get('max_score_diff', 0.0) for r in reports]):.3g}")
     return full, exempt

@@ -334,3 +334,97 @@ def alsd_two_stage(logp_fn, fused_fn, T, V, s, K):
         assert toks not in out
         out[toks] = sc
     return out
+
+
+def replay_step_margins(logp_fn, T, V, s, K, algo, durations, gamma, log_parent, log_token, log_merged, n_steps):
+    """Walks one utterance along a decoder's logged tree (parent slot, token code, merged-into slot per step) and
+    recomputes, from the model alone, the smallest margin by which any decision of each step was taken:
+      * the gaps between consecutive candidates in the ranking, down to the gap between the last kept and the
+        first discarded one (kept candidates' order decides the slot numbers, the last gap decides the cut);
+      * TDT, one duration per symbol: the margins of the two duration arg-maxes of every expanded hypothesis;
+      * AES with a finite prune margin: for every symbol of a hypothesis that is expanded freely (not forced to
+        blank) whose unmasked candidate would rank within 1e-3 of the cut or better, the distance of its
+        log-probability from the margin's threshold.
+    Slots follow the unified step: dead slots have no candidate; a live hypothesis that is finished or (AES) not at
+    the earliest frame has the single candidate "stay"; candidates are ordered by (value desc, k (V + 1) + v asc).
+    Also checks that the logged selection IS the head of that ranking whenever the step's margin is clear.
+    Returns the list of margins, one per step."""
+    slots = [dict(live=(k == 0), toks=(), t=0, sym=0, score=0.0 if k == 0 else -math.inf) for k in range(K)]
+    out = []
+    for st in range(n_steps):
+        open_t = [h["t"] for h in slots if h["live"] and h["t"] < T]
+        assert open_t, "the log goes on after the utterance has finished"
+        t_cur = min(open_t)
+        margin = math.inf
+        cands = []       # (value, flat index)
+        unmasked = {}    # flat index -> (value without the prune margin, distance from the margin's threshold)
+        adv = {}
+        for k, h in enumerate(slots):
+            if not h["live"]:
+                continue
+            if not (h["t"] < T and (algo == "alsd" or h["t"] == t_cur)):
+                cands.append((h["score"], k * (V + 1) + V))
+                continue
+            logp, dlogp = logp_fn(h["t"], h["toks"])
+            x_tok = x_blank = 0.0
+            adv[k] = (0, 1)
+            if durations:
+                best = max(range(len(durations)), key=lambda d: (dlogp[d], -d))
+                adv_ok = [d for d in range(len(durations)) if durations[d] >= 1]
+                best_b = max(adv_ok, key=lambda d: (dlogp[d], -d))
+                for d in range(len(durations)):
+                    if d != best:
+                        margin = min(margin, dlogp[best] - dlogp[d])
+                    if d != best_b and durations[d] >= 1:
+                        margin = min(margin, dlogp[best_b] - dlogp[d])
+                x_tok, x_blank = dlogp[best], dlogp[best_b]
+                adv[k] = (durations[best], durations[best_b])
+            forced = h["sym"] >= s
+            floor = max(logp) - gamma if algo == "aes" else -math.inf
+            for v in range(V + 1):
+                val = h["score"] + logp[v] + (x_blank if v == V else x_tok)
+                masked = (forced and v < V) or (not (forced and v == V) and logp[v] < floor)
+                cands.append((-math.inf if masked else val, k * (V + 1) + v))
+                if algo == "aes" and math.isfinite(gamma) and not forced:
+                    unmasked[k * (V + 1) + v] = (val, abs(logp[v] - floor))
+        cands.sort(key=lambda c: (-c[0], c[1]))
+        finite = [c for c in cands if c[0] > -math.inf]
+        for i in range(min(K, len(finite) - 1)):
+            margin = min(margin, finite[i][0] - finite[i + 1][0])
+        cut = finite[K - 1][0] if len(finite) >= K else -math.inf
+        for val, dist in unmasked.values():
+            if val >= cut - 1e-3:
+                margin = min(margin, dist)
+        out.append(margin)
+        # the logged step
+        new = []
+        for j in range(K):
+            p, code = int(log_parent[st][j]), int(log_token[st][j])
+            if p < 0:
+                new.append(dict(live=False, toks=(), t=0, sym=0, score=-math.inf))
+                continue
+            h = slots[p]
+            v = V if code < 0 else code
+            if margin > 1e-9:
+                assert j < len(finite) and finite[j][1] == p * (V + 1) + v, (st, j, finite[:K], p, code)
+            val = dict((i, x) for x, i in finite)[p * (V + 1) + v]
+            n = dict(h, score=val)
+            if code == -2:
+                pass
+            elif code == -1:
+                n.update(t=min(h["t"] + adv[p][1], T), sym=0)
+            else:
+                n.update(toks=h["toks"] + (code,), t=min(h["t"] + adv[p][0], T),
+                         sym=h["sym"] + 1 if adv[p][0] == 0 else 0)
+            new.append(n)
+        if margin > 1e-9:
+            assert sum(1 for n in new if n["live"]) == min(K, len(finite))
+        for j in range(K):
+            m = int(log_merged[st][j])
+            if new[j]["live"] and m != j:
+                assert 0 <= m < j and (new[m]["toks"], new[m]["t"], new[m]["sym"]) == (
+                    new[j]["toks"], new[j]["t"], new[j]["sym"])
+                new[m]["score"] = logaddexp(new[m]["score"], new[j]["score"])
+                new[j] = dict(live=False, toks=(), t=0, sym=0, score=-math.inf)
+        slots = new
+    return out

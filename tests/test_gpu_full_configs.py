@@ -2,12 +2,21 @@
 times (graph replay).  The whole batch is decoded on the GPU; the oracle decodes
 a sample of the utterances (they are independent of each other) and the
 comparison is the same as in the small cases: trees identical up to the first
-near tie, then identical transcripts and scores within tolerance."""
+near tie, then identical transcripts and scores within tolerance.  A sampled
+utterance whose tree leaves the oracle's at a near tie is not dropped: its own
+tree is walked step by step with the oracle's unit routines (tree_check.py), so
+every sampled utterance is checked from its first step to its n-best list.
+
+bf16 bars: the oracle rounds the same operands, so what is left is float32
+against float64 accumulation around bf16 rounding boundaries: a boundary crossed
+on one side only moves one activation by 2^-8 relative and a logit by about 5e-4.
+Near tie below 5e-3 (every divergence measured on these workloads happened at an
+oracle margin below that), scores within 1e-2 (largest measured 6.2e-3)."""
 import numpy as np
 import pytest
 
 import synth_inputs as S
-from gpu_common import compare, gpu_decode
+from gpu_common import compare, gpu_decode, make_walk
 
 pytestmark = pytest.mark.gpu
 
@@ -15,10 +24,10 @@ CASES = [
     # config, variant, sampled utterances, tol, tie
     (1, "f32", [0], 1e-3, 1e-4),
     (2, "f32", list(range(0, 32, 2)), 1e-3, 1e-4),
-    (2, "bf16", list(range(0, 32, 4)), 5e-2, 2e-2),
+    (2, "bf16", list(range(0, 32, 4)), 1e-2, 5e-3),
     (3, "f32", list(range(0, 64, 3)), 1e-3, 1e-4),
     (4, "f32", [0, 9, 18, 27], 1e-3, 1e-4),
-    (5, "bf16", [0, 63, 127], 5e-2, 2e-2),
+    (5, "bf16", [0, 17, 35, 53, 71, 89, 107, 127], 1e-2, 5e-3),
 ]
 
 
@@ -56,10 +65,16 @@ def test_workload_at_full_size(oracle, cid, variant, rows, tol, tie):
     rows = [r for r in rows if r < c["B"]]
     o = oracle.decode(dict(c, B=len(rows)), w, enc[rows], L[rows], lm=olm, lm_weight=c["lm_weight"], log=True)
     assert o["collisions"].sum() == 0
-    full, exempt = compare(g, o, tol, tie, rows=rows)
+    walk = make_walk(oracle, c, w, enc, L, g, tol, lm=olm, lm_weight=c["lm_weight"])
+    full, exempt = compare(g, o, tol, tie, rows=rows, walk=walk)
     print(f"config {cid} {variant}: {full} of {len(rows)} sampled utterances identical end to end, "
-          f"{exempt} left the oracle's path after a near tie (< {tie})")
+          f"{exempt} left the oracle's tree at a near tie (< {tie}) and were walked step by step")
     assert full + exempt == len(rows)
+    assert full >= (len(rows) - 1 if variant == "f32" else 1)
+    # the walk itself, at full size, on a tree that may well equal the oracle's
+    r = walk(rows[0])
+    print(f"walk of utterance {rows[0]}: {r}")
+    assert r["steps_checked"] == g["n_steps"][rows[0]] or r["stopped_at_duration_tie"]
 
 
 @pytest.mark.parametrize("name,over,rows", [
@@ -87,6 +102,7 @@ def test_variants_of_the_workloads_at_full_size(oracle, name, over, rows):
     g = gpu_decode(dec, enc, L, lm=glm, lm_weight=c["lm_weight"])
     assert g["rc"] == 0
     o = oracle.decode(dict(c, B=len(rows)), w, enc[rows], L[rows], lm=olm, lm_weight=c["lm_weight"], log=True, **kw_o)
-    full, exempt = compare(g, o, 1e-3, 1e-4, rows=rows)
-    print(f"{name}: {full} of {len(rows)} sampled utterances identical end to end, {exempt} exempt after a near tie")
+    walk = make_walk(oracle, c, w, enc, L, g, 1e-3, lm=olm, lm_weight=c["lm_weight"], **kw_o)
+    full, exempt = compare(g, o, 1e-3, 1e-4, rows=rows, walk=walk)
+    print(f"{name}: {full} of {len(rows)} sampled utterances identical end to end, {exempt} walked after a near tie")
     assert full + exempt == len(rows) and full >= 1

@@ -3,9 +3,10 @@
 Bars: tree and recombination indices bit-exact when both sides read the same
 injected log-probabilities; float32 end to end: identical token sequences and
 hypothesis scores within 1e-3, except after a decision the oracle took by less
-than 1e-4; bf16-joint variant: scores within 5e-2, near tie below 2e-2 (this library's own
+than 1e-4; bf16-joint variant: scores within 1e-2, near tie below 5e-3 (this library's own
 choice: a bf16 rounding boundary crossed on one side only moves a logit by about 5e-4, and a
-few hundred such events add up over a decode).
+few hundred such events add up over a decode).  A tree that leaves the oracle's at a near tie
+is walked step by step (tree_check.py) instead of being dropped.
 """
 import math
 
@@ -13,12 +14,12 @@ import numpy as np
 import pytest
 
 import synth_inputs as S
-from gpu_common import compare, gpu_decode, gpu_decode_injected, to_gpu
+from gpu_common import compare, gpu_decode, gpu_decode_injected, make_walk, to_gpu
 
 pytestmark = pytest.mark.gpu
 
 TOL, TIE = 1e-3, 1e-4
-TOL_BF16, TIE_BF16 = 5e-2, 2e-2
+TOL_BF16, TIE_BF16 = 1e-2, 5e-3
 
 
 @pytest.fixture(scope="module")
@@ -164,7 +165,7 @@ def test_config1_tiny(amd, oracle, algo, beam):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL))
     assert full + exempt == 1
 
 
@@ -187,7 +188,7 @@ def test_full_width_model_small_batch(amd, oracle, name, kw):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL))
     assert full + exempt == c["B"]
     assert full >= c["B"] // 2, (full, exempt)
     assert g["lens"][1, 0] == 0 and g["scores"][1, 0] == 0.0 and g["n_steps"][1] == 0  # the empty utterance
@@ -200,7 +201,7 @@ def test_odd_shapes(amd, oracle):
     dec = amd.BeamDecoder(c, w, max_B=12, max_T=15, max_beam=8)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL))
     assert full + exempt == 9 and full >= 5
 
 
@@ -211,7 +212,7 @@ def test_stateless_prediction_network(amd, oracle):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL))
     assert full + exempt == 4 and full >= 2
 
 
@@ -223,7 +224,7 @@ def test_bf16_joint_variant(amd, oracle, pred):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL_BF16, TIE_BF16)
+    full, exempt = compare(g, o, TOL_BF16, TIE_BF16, walk=make_walk(oracle, c, w, enc, L, g, TOL_BF16))
     assert full + exempt == 4
     # the variant must differ from the float32 run, or the rounding is not happening
     o32 = oracle.decode(dict(c, prec="f32"), w, enc, L)
@@ -240,7 +241,7 @@ def test_lm_fusion(amd, oracle):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.3)
     o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.3, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL, lm=olm, lm_weight=0.3))
     assert full + exempt == 4 and full >= 2
     # weight 0 gives the run without LM
     g0 = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.0)
@@ -264,7 +265,8 @@ def test_lm_fusion_rules_and_early_pruning(amd, oracle, rule, prune, beam, algo)
     dec = amd.BeamDecoder(c, w, lm_rule=rule, lm_prune=prune)
     g = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.5)
     o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.5, lm_rule=rule, lm_prune=prune, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL, lm=olm, lm_weight=0.5,
+                                                          lm_rule=rule, lm_prune=prune))
     assert full + exempt == 4 and full >= 2
     # the mode must matter on this input, or the test could not tell it from the default
     o_default = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.5)
@@ -304,7 +306,7 @@ def test_tdt_pairs_with_the_networks(amd, oracle, algo, beam):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE)  # (the step-by-step walk knows the one-duration rule only)
     assert full + exempt == 4 and full >= 2
     with pytest.raises(RuntimeError, match="tdt_all_pairs"):
         amd.BeamDecoder(dict(c, model="rnnt", durations=()), S.make_weights(dict(c, model="rnnt", durations=()), 3))
@@ -333,7 +335,8 @@ def test_materialized_logits_path(amd, oracle, name, kw, lm_w):
     dec = amd.BeamDecoder(c, w, joint_path="materialized", lm_prune=prune)
     g = gpu_decode(dec, enc, L, lm=glm, lm_weight=lm_w)
     o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=lm_w, lm_prune=prune, log=True)
-    full, exempt = compare(g, o, TOL_BF16, TIE_BF16)
+    full, exempt = compare(g, o, TOL_BF16, TIE_BF16, walk=make_walk(oracle, c, w, enc, L, g, TOL_BF16, lm=olm,
+                                                                    lm_weight=lm_w, lm_prune=prune))
     assert full + exempt == c["B"] and full >= 1
     # and against the fused path of this library, to the same bar
     dec_f = amd.BeamDecoder(c, w, joint_path="fused", lm_prune=prune)
@@ -392,7 +395,7 @@ def test_split_projection_at_a_generic_width(amd, oracle):
     dec = amd.BeamDecoder(c, w)
     g = gpu_decode(dec, enc, L)
     o = oracle.decode(c, w, enc, L, log=True)
-    full, exempt = compare(g, o, TOL, TIE)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL))
     assert full + exempt == 6 and full >= 4
 
 

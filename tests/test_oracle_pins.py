@@ -9,7 +9,7 @@ import pytest
 import torch
 
 import synth_inputs as S
-from refmodel import (RefModel, aes_frame_synchronous, alsd_two_stage, TableModel, dict_lm, dict_lm_score, enumerate_alignments, forward_dp, greedy,
+from refmodel import (RefModel, aes_bucketed, aes_frame_synchronous, replay_step_margins, alsd_two_stage, TableModel, dict_lm, dict_lm_score, enumerate_alignments, forward_dp, greedy,
                       logaddexp, py_hash)
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -126,6 +126,117 @@ def test_aes_with_pruning_equals_two_set_frame_loop(oracle, K):
         alsd = _nbest(oracle.decode(c, w, enc, L, algo=oracle.ALSD))
         differs += set(alsd) != set(got) or any(abs(alsd[y] - got[y]) > 1e-6 for y in got)
     assert differs > 0, "the cases do not separate AES from ALSD"
+
+
+
+@pytest.mark.parametrize("gamma", [math.inf, 2.3, 0.7])
+@pytest.mark.parametrize("K", [2, 3, 5])
+def test_tdt_aes_with_a_pruning_beam_and_margin_equals_the_bucketed_two_set_loop(oracle, K, gamma):
+    """The regime of the TDT workload: AES++ on a TDT model (per-hypothesis frame index, one duration per symbol)
+    with a beam that really prunes and a finite prune margin, against the frame-by-frame loop with one waiting
+    set per landing frame."""
+    durations = (0, 1, 2, 3, 4)
+    differs_alsd = differs_margin = cut = 0
+    for seed in range(5):
+        c, w, L, enc = _small(230 + seed, model="tdt", durations=durations, V=4, T=9, s=2, beam=K, algo="aes",
+                              gamma=gamma, H=12, P=12, E=12, D=12)
+        w["b_out"][5:] = 0.0   # durations of every size, token and blank often disagree: hypotheses spread over frames
+        w["W_out"][5:] *= 4.0
+        fn = _ref_logp_fn(c, w, enc[0])
+        want = aes_bucketed(fn, 9, 4, 2, K, durations, gamma)
+        r = oracle.decode(c, w, enc, L)
+        got = _nbest(r)
+        assert set(got) == set(want), (seed, got, want)
+        for y in want:
+            assert abs(got[y] - want[y]) < 1e-9
+        cut += int(r["n_cut"][0])
+        alsd = _nbest(oracle.decode(dict(c, gamma=math.inf), w, enc, L, algo=oracle.ALSD))
+        differs_alsd += set(alsd) != set(got) or any(abs(alsd[y] - got[y]) > 1e-6 for y in got)
+        free = _nbest(oracle.decode(dict(c, gamma=math.inf), w, enc, L))
+        differs_margin += set(free) != set(got) or any(abs(free[y] - got[y]) > 1e-6 for y in got)
+    assert cut > 0 or (gamma < 1.0 and K >= 5), "the beam never pruned"  # (a tight margin leaves fewer than 5 candidates)
+    assert differs_alsd > 0, "the cases do not separate AES from ALSD"
+    assert gamma > 1.0 or differs_margin > 0, "the margin never mattered"  # (2.3 rarely reaches into a narrow beam)
+
+
+@pytest.mark.parametrize("K,gamma", [(3, 1.0), (4, 2.3)])
+def test_rnnt_aes_with_margin_equals_the_bucketed_two_set_loop(oracle, K, gamma):
+    differs = 0
+    for seed in range(5):
+        c, w, L, enc = _small(260 + seed, V=5, T=7, s=2, beam=K, algo="aes", gamma=gamma, H=12, P=12, E=12, D=12)
+        fn = _ref_logp_fn(c, w, enc[0])
+        want = aes_bucketed(fn, 7, 5, 2, K, (), gamma)
+        got = _nbest(oracle.decode(c, w, enc, L))
+        assert set(got) == set(want), seed
+        for y in want:
+            assert abs(got[y] - want[y]) < 1e-9
+        # without a margin the bucketed loop is the classical one
+        a, b = aes_bucketed(fn, 7, 5, 2, K), aes_frame_synchronous(fn, 7, 5, 2, K)
+        assert set(a) == set(b) and all(abs(a[y] - b[y]) < 1e-12 for y in a)
+        differs += set(a) != set(want)
+    assert differs > 0, "the margin never mattered"
+
+
+@pytest.mark.parametrize("model", ["rnnt", "tdt"])
+def test_prune_margin_belongs_to_aes_only(oracle, model):
+    """ALSD++ with a prune margin in its configuration is ALSD++: nothing pruned -> the exhaustive sums."""
+    durations = (0, 1, 2) if model == "tdt" else ()
+    c, w, L, enc = _small(270, model=model, durations=durations, V=2, T=4, s=2, beam=4096, algo="alsd", gamma=0.5)
+    fn = _ref_logp_fn(c, w, enc[0])
+    want = enumerate_alignments(fn, 4, 2, 2, durations)
+    r = oracle.decode(c, w, enc, L)
+    assert r["n_cut"][0] == 0
+    got = _nbest(r)
+    assert set(got) == set(want)
+    for y in want:
+        assert abs(got[y] - want[y]) < 1e-9
+    # while under AES++ the same margin does cut
+    assert set(_nbest(oracle.decode(c, w, enc, L, algo=oracle.AES))) != set(want)
+
+
+# ------------------------------------------------------- near-tie report
+
+def test_step_margin_report_on_a_hand_made_table(oracle):
+    """log_gap of a two-frame, one-token table worked out by hand (beam 2, s = 1, ALSD++):
+    step 0: candidates a = -0.25, blank = -1.75, both kept                        -> 1.5
+    step 1: slot 0 = "a" (forced blank, frame 0): -2.0; slot 1 = "" at frame 1: a -2.25, blank -2.75; kept -2.0,
+            -2.25, first discarded -2.75                                          -> min(0.25, 0.5) = 0.25
+    step 2: slot 0 = "a" at frame 1: a -2.5, blank -3.0; slot 1 = "a" with one symbol in frame 1 (forced blank)
+            -3.25; kept -2.5, -3.0, discarded -3.25                               -> 0.25
+    step 3: slot 0 = "aa" forced blank -3.5; slot 1 = "a" finished, stays -3.0    -> 0.5"""
+    c = S.custom_config(B=1, T=2, V=1, beam=2, s=1, algo="alsd")
+    tok = np.array([[[[-0.25, -1.75]], [[-0.5, -1.0]]]], np.float32)
+    r = oracle.decode(c, None, None, np.array([2], np.int32), injected=(tok, None), log=True)
+    assert r["n_steps"][0] == 4
+    np.testing.assert_allclose(r["log_gap"][0, :4], [1.5, 0.25, 0.25, 0.5], rtol=0, atol=1e-12)
+    assert r["min_gap"][0] == 0.25
+    assert _nbest(r) == {(0,): -3.0, (0, 0): -3.5}
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("rnnt_alsd", dict(V=5, T=8, s=2, beam=3, algo="alsd")),
+    ("rnnt_aes_margin", dict(V=5, T=8, s=2, beam=3, algo="aes", gamma=1.5)),
+    ("tdt_aes_margin", dict(V=4, T=10, s=2, beam=4, algo="aes", gamma=2.3, model="tdt", durations=(0, 1, 2, 3, 4))),
+    ("tdt_alsd", dict(V=4, T=10, s=2, beam=5, algo="alsd", model="tdt", durations=(0, 1, 2, 3, 4))),
+    ("stateless_aes", dict(V=6, T=8, s=3, beam=4, algo="aes", pred="stateless", ctx=2)),
+])
+def test_step_margin_report_equals_an_independent_replay(oracle, name, kw):
+    """The per-step margin the oracle reports (the parity tests forgive a divergence only at a step whose margin
+    was small) against margins recomputed from library layers along the oracle's own logged tree: ranking gaps
+    down to the first discarded candidate, duration arg-max margins, distance from the prune margin."""
+    seen_cut = 0
+    for seed in range(4):
+        c, w, L, enc = _small(300 + 7 * seed, B=2, T_min=kw["T"] - 3, H=12, P=12, E=12, D=12, **kw)
+        r = oracle.decode(c, w, enc, L, log=True)
+        for b in range(2):
+            fn = _ref_logp_fn(c, w, enc[b])
+            n = int(r["n_steps"][b])
+            want = replay_step_margins(fn, int(L[b]), c["V"], c["s"], c["beam"], c["algo"], c["durations"], c["gamma"],
+                                       r["log_parent"][b], r["log_token"][b], r["log_merged"][b], n)
+            np.testing.assert_allclose(r["log_gap"][b, :n], want, rtol=0, atol=1e-9)
+            assert abs(r["min_gap"][b] - min(want)) < 1e-9
+            seen_cut += int(r["n_cut"][b] > 0)
+    assert seen_cut > 0
 
 
 # ------------------------------------------------------------------- TDT

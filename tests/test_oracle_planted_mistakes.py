@@ -48,6 +48,15 @@ MISTAKES = [
     ("a pair advances by the best duration instead of its own",
      "if (pairs) adv_tok[k] = adv_blank[k] = c->durations[dsel]; /* the pair's own duration */", ""),
     ("early pruning keeps the Transducer's score as the new score", "nh->score = cand[j].val;", "nh->score = cand[j].key;"),
+    ("near-tie report looks at the kept candidates only", "for (int i = 0; i < K && i + 1 < n_cand; ++i)",
+     "for (int i = 0; i + 1 < K && i + 1 < n_cand; ++i)"),
+    ("duration margin left out of the near-tie report", "    if (gap_out) {\n      for (int d = 0; d < c->n_dur; ++d) {",
+     "    if (0) {\n      for (int d = 0; d < c->n_dur; ++d) {"),
+    ("distance from the prune margin left out of the near-tie report",
+     "if (J->algo == 1 && isfinite(c->gamma) && !pairs) {\n      /* a token close", "if (0) {\n      /* a token close"),
+    ("prune margin applied under ALSD++ too", "const int use_gamma = J->algo == 1;", "const int use_gamma = 1;"),
+    ("AES++ opens the frame of the first unfinished slot instead of the earliest frame",
+     "        if (cur[k].t < t_cur) t_cur = cur[k].t;", "        if (t_cur == T_b) t_cur = cur[k].t;"),
 ]
 
 
