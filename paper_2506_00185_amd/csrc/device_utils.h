@@ -34,6 +34,31 @@ __device__ __forceinline__ float4 bf16_round4(float4 v) {
   return make_float4(bf16_round(v.x), bf16_round(v.y), bf16_round(v.z), bf16_round(v.w));
 }
 
+// ---- bfloat16 operands of the bf16 matrix instructions
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t uintx4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2_t __attribute__((ext_vector_type(2)));
+
+// two float32 -> two bfloat16 in one word (low half first), round to nearest even: one v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
+  const floatx2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// One 32x32x16 bf16 matrix-core step fed from float32 registers: the lane's 8 k-values are the 4 + 4 floats it holds
+// for two consecutive 8-k rounds of the float32 scheme (see mfma32), rounded to bf16 here.  Both operands use the
+// same lane -> k assignment, so every k of the 16 meets its partner exactly once.
+__device__ __forceinline__ floatx16 mfma32_bf16_from_f32(float4 a0, float4 a1, float4 b0, float4 b1, floatx16 acc) {
+  const uintx4_t pa = {pack_bf16_rne(a0.x, a0.y), pack_bf16_rne(a0.z, a0.w), pack_bf16_rne(a1.x, a1.y),
+                       pack_bf16_rne(a1.z, a1.w)};
+  const uintx4_t pb = {pack_bf16_rne(b0.x, b0.y), pack_bf16_rne(b0.z, b0.w), pack_bf16_rne(b1.x, b1.y),
+                       pack_bf16_rne(b1.z, b1.w)};
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, pa), __builtin_bit_cast(bf16x8_t, pb), acc, 0,
+                                                 0, 0);
+}
+
 __device__ __forceinline__ double logaddexp_d(double a, double b) {
   if (a == -INFINITY) return b;
   if (b == -INFINITY) return a;

@@ -2,57 +2,12 @@
 //   k_step_main (joint + selection in its tail + part of W_hh h) -> k_lstm_pointwise (+ LM rows) -> k_pred_proj
 // for LSTM models (k_stateless_pre instead of the last two for stateless ones; k_inject -> k_select when the
 // log-probabilities are injected; a stand-alone k_select / k_select_wide / k_select_pairs where the tail cannot
-// take the selection), and k_gemm_nt / k_init / k_backtrace run once per decode call.
+// take the selection), and k_gemm_tiled (gemm.h) / k_init / k_backtrace run once per decode call.
 #pragma once
 #include "device_utils.h"
 #include "lm_device.h"
 
 namespace rb {
-
-// ---------------------------------------------------------------------------
-// C[M, N] = A[M, K] B[N, K]^T + bias[N]   (both operands K-contiguous, fp32 matrix cores)
-// 256 threads = 2 x 2 waves, each a 32 x 32 tile; K % 8 == 0.
-// round_ops: both operands are rounded to bf16 before they are multiplied.
-// nonfinite (nullable): set to 1 when an output is NaN or Inf.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_gemm_nt(const float *__restrict__ A, const float *__restrict__ B,
-                                                 const float *__restrict__ bias, float *__restrict__ C, int M,
-                                                 int N, int K, int round_ops, int *nonfinite) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5, col = lane & 31;
-  const int m0 = blockIdx.y * 64 + (wave >> 1) * 32, n0 = blockIdx.x * 64 + (wave & 1) * 32;
-  if (m0 >= M || n0 >= N) return;
-  const int am = min(m0 + col, M - 1), bn = min(n0 + col, N - 1);
-  const float *ap = A + (size_t)am * K + 4 * half, *bp = B + (size_t)bn * K + 4 * half;
-  floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll 4
-  for (int k = 0; k < K; k += 8) {
-    float4 a = *reinterpret_cast<const float4 *>(ap + k);
-    float4 b = *reinterpret_cast<const float4 *>(bp + k);
-    if (round_ops) {
-      a = bf16_round4(a);
-      b = bf16_round4(b);
-    }
-    acc = mfma32(a.x, b.x, acc);
-    acc = mfma32(a.y, b.y, acc);
-    acc = mfma32(a.z, b.z, acc);
-    acc = mfma32(a.w, b.w, acc);
-  }
-  const int n = n0 + col;
-  bool bad = false;
-  if (n < N) {
-    const float bv = bias ? bias[n] : 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + 8 * (r >> 2) + 4 * half + (r & 3);
-      if (m < M) {
-        const float v = acc[r] + bv;
-        C[(size_t)m * N + n] = v;
-        bad |= !isfinite(v);
-      }
-    }
-  }
-  if (nonfinite && bad) *nonfinite = 1;
-}
 
 // ---------------------------------------------------------------------------
 // Split-K 32 x 32 tile shared by the three per-step contractions.  The WAVES
@@ -91,30 +46,53 @@ __device__ __forceinline__ void splitk_load(SplitKOperands<ITERS> &op, AL a_at, 
 }
 
 // matrix instructions of the wave's K slice, partial tile to LDS, block barrier.
-// fb: applied to each hypothesis-side operand just before use (ReLU, rounding).
+// fb: applied to each hypothesis-side operand just before use (ReLU).
+// bf16 (uniform over the block): both operands are rounded to bfloat16 (weights handed in are bf16 values already)
+// and two 8-k rounds at a time go through one bf16 matrix instruction, an eighth of the matrix-core time of the
+// eight float32 ones; the accumulation stays float32.
 template <int WAVES, int ITERS, class AL, class BL, class FB>
-__device__ __forceinline__ void splitk_mma(SplitKOperands<ITERS> &op, AL a_at, BL b_at, FB fb, int K, float *red) {
+__device__ __forceinline__ void splitk_mma(SplitKOperands<ITERS> &op, AL a_at, BL b_at, FB fb, int K, float *red,
+                                           int bf16 = 0) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int kw = K / WAVES;
+  const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
   floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
   if constexpr (ITERS > 0) {
+    if (bf16) {
 #pragma unroll
-    for (int i = 0; i < ITERS; ++i) {
-      const float4 b = fb(op.b[i]);
-      acc = mfma32(op.a[i].x, b.x, acc);
-      acc = mfma32(op.a[i].y, b.y, acc);
-      acc = mfma32(op.a[i].z, b.z, acc);
-      acc = mfma32(op.a[i].w, b.w, acc);
+      for (int i = 0; i < ITERS; i += 2) {
+        const bool two = i + 1 < ITERS;
+        acc = mfma32_bf16_from_f32(op.a[i], two ? op.a[i + 1 < ITERS ? i + 1 : i] : zero4, fb(op.b[i]),
+                                   two ? fb(op.b[i + 1 < ITERS ? i + 1 : i]) : zero4, acc);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < ITERS; ++i) {
+        const float4 b = fb(op.b[i]);
+        acc = mfma32(op.a[i].x, b.x, acc);
+        acc = mfma32(op.a[i].y, b.y, acc);
+        acc = mfma32(op.a[i].z, b.z, acc);
+        acc = mfma32(op.a[i].w, b.w, acc);
+      }
     }
   } else {
     const int kbeg = wave * kw + 4 * half, kend = (wave + 1) * kw;
-    for (int k = kbeg; k < kend; k += 8) {
-      const float4 a = a_at(k);
-      const float4 b = fb(b_at(k));
-      acc = mfma32(a.x, b.x, acc);
-      acc = mfma32(a.y, b.y, acc);
-      acc = mfma32(a.z, b.z, acc);
-      acc = mfma32(a.w, b.w, acc);
+    if (bf16) {
+      for (int k = kbeg; k < kend; k += 16) {
+        const bool two = k + 8 < kend;
+        const int k2 = two ? k + 8 : k;
+        const float4 a0 = a_at(k), a1 = a_at(k2), b0 = fb(b_at(k)), b1 = fb(b_at(k2));
+        acc = mfma32_bf16_from_f32(a0, two ? a1 : zero4, b0, two ? b1 : zero4, acc);
+      }
+    } else {
+      for (int k = kbeg; k < kend; k += 8) {
+        const float4 a = a_at(k);
+        const float4 b = fb(b_at(k));
+        acc = mfma32(a.x, b.x, acc);
+        acc = mfma32(a.y, b.y, acc);
+        acc = mfma32(a.z, b.z, acc);
+        acc = mfma32(a.w, b.w, acc);
+      }
     }
   }
   float *mine = red + (wave * 64 + lane) * kRedStride;
@@ -933,13 +911,12 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
     auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(pp + (size_t)(k >> 2) * Mp * 4); };
     auto fb = [&](float4 f) {
       f.x = fmaxf(f.x, 0.f); f.y = fmaxf(f.y, 0.f); f.z = fmaxf(f.z, 0.f); f.w = fmaxf(f.w, 0.f);
-      if (round_ops) f = bf16_round4(f);
       return f;
     };
     SplitKOperands<ITERS> op;
     splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
     if (done) return;
-    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red);
+    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red, round_ops);
   }
 
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
@@ -1153,7 +1130,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
   auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * H * 4); };
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
-  auto fb = [&](float4 v) { return round_ops ? bf16_round4(v) : v; };
+  auto fb = [](float4 v) { return v; };
   const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
   // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1).  Its frame index is loaded BEFORE the operands: the
   // address of the frame's projection depends on it, and a wait for a load that was issued after the operands would
@@ -1179,7 +1156,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
       bv[q] = a.bias[o0 + q];
     }
   }
-  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red);
+  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red, round_ops);
   if (a.bump && tile == 0 && mtile == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll
@@ -1207,7 +1184,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
   const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
   auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)((k + koff) >> 2) * H * 4); };
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)((k + koff) >> 2) * Mp * 4); };
-  auto fb = [&](float4 v) { return round_ops ? bf16_round4(v) : v; };
+  auto fb = [](float4 v) { return v; };
   const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
   const int j = tid / LPH, o0 = tile * 32 + (tid % LPH) * VPL;
   const int me = m0 + j;
@@ -1231,7 +1208,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
       bv[q] = a.bias[o0 + q];
     }
   }
-  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P / 2, red);
+  splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P / 2, red, round_ops);
   if (a.bump && tile == 0 && item == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll

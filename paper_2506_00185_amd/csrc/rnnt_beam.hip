@@ -16,6 +16,7 @@
 #include <type_traits>
 #include <vector>
 
+#include "gemm.h"
 #include "kernels.h"
 #include "kernels_big.h"
 #include "lm.h"
@@ -54,7 +55,7 @@ enum {
   KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_JOINTBIG, KT_ROWSELECT,
   KT_COUNT
 };
-const char *kKernelNames[KT_COUNT] = {"k_gemm_nt(enc_proj)", "k_init",      "k_step_main", "k_select",    "k_lm_rows",
+const char *kKernelNames[KT_COUNT] = {"k_gemm_tiled(enc_proj)", "k_init",      "k_step_main", "k_select",    "k_lm_rows",
                                       "k_lstm_pointwise",    "k_pred_proj", "k_backtrace", "k_joint_big", "k_row_select"};
 
 // Device memory a decode works in beyond its inputs and outputs, laid out for given maxima.  The handle owns one
@@ -235,10 +236,20 @@ int recurrent_split(const rnnt_config_t &c, int M) {
   return m.b_end;
 }
 
+// C = A B^T + bias through the LDS-tiled kernel; round_ops: bf16 operands on the bf16 matrix instructions
 int launch_gemm(rnnt_beam *h, hipStream_t s, const float *A, const float *B, const float *bias, float *C, int M, int N,
                 int K, int round_ops, int *nonfinite) {
-  dim3 grid((N + 63) / 64, (M + 63) / 64);
-  hipLaunchKernelGGL(k_gemm_nt, grid, dim3(256), 0, s, A, B, bias, C, M, N, K, round_ops, nonfinite);
+  GemmArgs a{A, B, bias, C, M, N, K, 0, 0, nonfinite};
+  auto go = [&](auto kernel, int bm, int bn, size_t lds) {
+    a.n_mt = (M + bm - 1) / bm;
+    a.n_nt = (N + bn - 1) / bn;
+    hipLaunchKernelGGL(kernel, dim3(gemm_grid(a.n_mt, a.n_nt)), dim3(256), lds, s, a);
+  };
+  // float32: 64 x 64 tiles (a chunk is 16 slow matrix instructions per wave; many blocks balance the chip);
+  // bf16: 128 x 128 tiles from 2048 rows up (the traffic from L2 per multiply-add halves), else 64 x 64
+  if (!round_ops) go(k_gemm_tiled<false, 1, 1, true>, 64, 64, GemmTile<false, 1, 1>::kLdsBytes);
+  else if (M >= 2048) go(k_gemm_tiled<true, 2, 2, false>, 128, 128, GemmTile<true, 2, 2>::kLdsBytes);
+  else go(k_gemm_tiled<true, 1, 1, true>, 64, 64, GemmTile<true, 1, 1>::kLdsBytes);
   RB_HIP(h, hipGetLastError());
   return RNNT_OK;
 }
