@@ -284,7 +284,10 @@ __device__ __forceinline__ uint32_t mod_mersenne31(uint64_t x) {
 // runs in several passes.
 // PAIRS (TDT): every (symbol, duration) pair of a hypothesis is a candidate of its own (blank only with
 // durations >= 1) instead of one duration per symbol; candidate (k, j, d) sits at ((k (K + 1) + j) ND + d.
-template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch>
+// ONE: every hypothesis comes with exactly one list (n_chunks == 1, NCH == 1), known at compile time: the merge
+// of list heads and its registers drop out.
+template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch,
+          bool ONE = false>
 __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
@@ -320,7 +323,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   float dl[8];
   // a single chunk's list IS the K best of the hypothesis: lane e takes entries e, e + LPR, .. as they are
   constexpr int kMine = (KMAX + LPR - 1) / LPR;
-  const bool one_list = NCH == 1 && a.n_chunks == 1;
+  const bool one_list = ONE || (NCH == 1 && a.n_chunks == 1);
   uint64_t direct[kMine];
   auto load_rows = [&](int r0) {
     rk = r0 + lane / LPR;
@@ -335,9 +338,11 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       for (int q = 0; q < NCH; ++q) {
         const int ch = e + LPR * q;
         const bool ok = row_ok && ch < a.n_chunks;
-        if (!one_list) {
+        if constexpr (!ONE) {
+          if (!one_list) {
 #pragma unroll
-          for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+            for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+          }
         }
         pm[q] = (ok && !a.normalized) ? load_agent(pmax + ch) : -INFINITY;
         ps[q] = (ok && !a.normalized) ? load_agent(psum + ch) : 0.f;
@@ -362,6 +367,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     if (one_list) {
 #pragma unroll
       for (int i = 0; i < kMine; ++i) mine[i] = direct[i];
+    } else if constexpr (ONE) {
     } else if constexpr (NCH > 0) {
 #pragma unroll
       for (int j = 0; j < KMAX; ++j) {
@@ -565,13 +571,21 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   // value is the new score itself except under early pruning
   const int n = K * (K + 1) * (PAIRS ? a.ND : 1);
   const double *rank_of = a.lm_early ? s.rc_key : s.rc_val;
-  if (n <= 64) {
-    // few candidates: each lane counts how many come before its own; that count is its new slot
-    const double mv = lane < n ? rank_of[lane] : -INFINITY;
-    const int mf = lane < n ? s.rc_flat[lane] : 0x7fffffff;
-    // (every lane reads all n candidates back from LDS, the same address in all lanes: such reads are broadcasts
-    //  and, unlike lane reads into scalar registers, can be requested many at a time)
-    int rank = 0;
+  // candidates a lane may own in the counting form below
+  constexpr int kOwn = 1;  // (measured: from 65 candidates up the rounds below are faster than two owned candidates)
+  if (n <= 64 * kOwn) {
+    // Each lane counts, for each candidate it owns (lane, lane + 64, ..), how many candidates come before it; that
+    // count is the candidate's new slot.  (Every lane reads all n candidates back from LDS, the same address in all
+    // lanes: such reads are broadcasts and, unlike lane reads into scalar registers, can be requested many at a time.)
+    double mv[kOwn];
+    int mf[kOwn], rank[kOwn];
+#pragma unroll
+    for (int q = 0; q < kOwn; ++q) {
+      const int c = lane + 64 * q;
+      mv[q] = c < n ? rank_of[c] : -INFINITY;
+      mf[q] = c < n ? s.rc_flat[c] : 0x7fffffff;
+      rank[q] = 0;
+    }
     for (int c0 = 0; c0 < n; c0 += 8) {
       double cv[8];
       int cf[8];
@@ -581,12 +595,19 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         cf[q] = s.rc_flat[c0 + q];
       }
 #pragma unroll
-      for (int q = 0; q < 8; ++q) rank += (c0 + q < n && comes_before(cv[q], cf[q], mv, mf)) ? 1 : 0;
+      for (int q = 0; q < 8; ++q) {
+        const bool in = c0 + q < n;
+#pragma unroll
+        for (int o = 0; o < kOwn; ++o)
+          if (o == 0 || 64 * o < n) rank[o] += (in && comes_before(cv[q], cf[q], mv[o], mf[o])) ? 1 : 0;
+      }
     }
-    if (mv > -INFINITY && rank < K) {
-      s.sel_val[rank] = s.rc_val[lane];
-      s.sel_flat[rank] = mf;
-    }
+#pragma unroll
+    for (int q = 0; q < kOwn; ++q)
+      if (mv[q] > -INFINITY && rank[q] < K) {
+        s.sel_val[rank[q]] = s.rc_val[lane + 64 * q];
+        s.sel_flat[rank[q]] = mf[q];
+      }
   } else {
     double last_v = INFINITY;
     int last_i = -1;
@@ -712,7 +733,10 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     store_through(a.hash + m, s.n_hash[j]);
     if (a.use_ctx) {
 #pragma unroll
-      for (int i = 0; i < kCtxMax; ++i) store_through(a.ctx + m * kCtxMax + i, ctx_new[i]);
+      for (int i = 0; i < kCtxMax; ++i) {
+        store_through(a.ctx + m * kCtxMax + i, ctx_new[i]);
+        s.ctx[j][i] = ctx_new[i];  // (every read of the parents' histories lies before the last wave_sync)
+      }
     }
     store_through(a.src_row + m, parent >= 0 ? m_base + parent : m);
     store_through(a.tok + m, appended);
@@ -741,12 +765,17 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
 }
 
 // picks the lane-group width and register budget for the beam and list sizes at hand.
-// FORMS: 0 = beams up to 8 (what the main kernel of a step runs in its tail); 1 = those plus wider beams
+// FORMS: 4 = one list per hypothesis, known at compile time (tail of the row kernel of the materialised-logits path);
+// 0 = beams up to 8 (what the main kernel of a step runs in its tail); 1 = those plus wider beams
 // whose hypotheses come with a single list; 2 = wider beams with many lists (several passes, many
 // registers).  The heavy forms are kept out of the kernels that do not need them.
 template <int FORMS, class Scratch = SelectScratch>
 __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s) {
-  if constexpr (FORMS == 3) {  // TDT, every (symbol, duration) pair a candidate, beams up to 8
+  if constexpr (FORMS == 4) {  // one list per hypothesis (the materialised-logits path), any beam
+    if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true>(a, b, s);
+    else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true>(a, b, s);
+    else select_utterance<4, 1, 16, false, false, Scratch, true>(a, b, s);
+  } else if constexpr (FORMS == 3) {  // TDT, every (symbol, duration) pair a candidate, beams up to 8
     if (a.K <= 4) {
       if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4, false, true, Scratch>(a, b, s);
       else select_utterance<16, 0, 4, false, true, Scratch>(a, b, s);
@@ -1281,6 +1310,7 @@ struct InitArgs {
   int *tile_ctr;   // per-tile block counters of the main kernel
   int n_tiles;
   int B, K, T, V, lstm;
+  int step_base_init;  // 0, or minus one chunk of steps when the step counter is advanced at the START of a chunk
   int *finished, *utt_steps, *n_finished, *done, *step_base, *bad_arg;
   volatile int *h_done;
 };
@@ -1289,7 +1319,7 @@ __global__ void k_init(InitArgs a) {
   const int gid = blockIdx.x * blockDim.x + threadIdx.x;
   const int M = a.B * a.K;
   if (gid == 0) {
-    *a.step_base = 0;
+    *a.step_base = a.step_base_init;
     int nfin = 0;
     for (int b = 0; b < a.B; ++b) {
       int L = a.lengths_in[b];

@@ -40,6 +40,8 @@ struct BigJointArgs {
   int M, Mp, H, Npad;
   XcdMap map;          // role 0: (block of 256 columns, block of 32 * MS rows)
   const int *done;
+  int *step_base;      // advanced by `bump` before anything of this step reads it (first step of a chunk of steps,
+  int bump;            // when the selection runs in the tail of the row kernel and no later launch closes the step)
 };
 
 // Z[m][n] = W_out[n] . a_m + b_out[n] for a block of 32 * WAVES columns x 160 hypotheses.
@@ -65,6 +67,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
   static_assert(WAVES == 4 || WAVES == 8, "two waves per SIMD: one block of 8 or two blocks of 4");
   __shared__ u32x4 tile[3][NP][64];
   const int done = *reinterpret_cast<const volatile int *>(a.done);
+  if (a.bump && !done && blockIdx.x == 0 && threadIdx.x == 0) *a.step_base += a.bump;
   int nb, mb;
   if (xcd_item(a.map, blockIdx.x, nb, mb) != 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
@@ -170,6 +173,70 @@ struct StatelessPreBigArgs {
   int bump;
 };
 
+// a_m[8 o8 .. + 7] for hypothesis m of utterance b standing at frame tt with token history toks (most recent first)
+__device__ __forceinline__ void stateless_pre_big_item(const StatelessPreBigArgs &a, int m, int b, int tt, const int *toks,
+                                                       int o8) {
+  const float *fp = a.f_proj + ((size_t)b * a.T + tt) * a.H + 8 * o8;
+  float v[8];
+  {
+    const float4 x = *reinterpret_cast<const float4 *>(fp), y = *reinterpret_cast<const float4 *>(fp + 4);
+    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
+  }
+  for (int i = 0; i < a.n_ctx; ++i) {
+    int tk = toks[i];
+    tk = tk < 0 ? a.V : tk;
+    const float *gp = a.tab + ((size_t)i * (a.V + 1) + tk) * a.H + 8 * o8;
+    const float4 x = *reinterpret_cast<const float4 *>(gp), y = *reinterpret_cast<const float4 *>(gp + 4);
+    v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w; v[4] += y.x; v[5] += y.y; v[6] += y.z; v[7] += y.w;
+  }
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = (uint32_t)bf16_bits(fmaxf(v[2 * i], 0.f)) | ((uint32_t)bf16_bits(fmaxf(v[2 * i + 1], 0.f)) << 16);
+  *reinterpret_cast<uint4 *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// two items at once: every load of both is requested before either is finished (the second may be a repeat of the
+// first, `two` false: it is then not stored)
+__device__ __forceinline__ void stateless_pre_big_pair(const StatelessPreBigArgs &a, int m1, int tt1, const int *toks1, int o81,
+                                                       int m2, int tt2, const int *toks2, int o82, int b, bool two) {
+  const float *fp1 = a.f_proj + ((size_t)b * a.T + tt1) * a.H + 8 * o81;
+  const float *fp2 = a.f_proj + ((size_t)b * a.T + tt2) * a.H + 8 * o82;
+  floatx4 v1[2] = {*reinterpret_cast<const floatx4 *>(fp1), *reinterpret_cast<const floatx4 *>(fp1 + 4)};
+  floatx4 v2[2] = {*reinterpret_cast<const floatx4 *>(fp2), *reinterpret_cast<const floatx4 *>(fp2 + 4)};
+  floatx4 g1[4][2], g2[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (i < a.n_ctx) {
+      int t1 = toks1[i], t2 = toks2[i];
+      t1 = t1 < 0 ? a.V : t1;
+      t2 = t2 < 0 ? a.V : t2;
+      const float *p1 = a.tab + ((size_t)i * (a.V + 1) + t1) * a.H + 8 * o81;
+      const float *p2 = a.tab + ((size_t)i * (a.V + 1) + t2) * a.H + 8 * o82;
+      g1[i][0] = *reinterpret_cast<const floatx4 *>(p1);
+      g1[i][1] = *reinterpret_cast<const floatx4 *>(p1 + 4);
+      g2[i][0] = *reinterpret_cast<const floatx4 *>(p2);
+      g2[i][1] = *reinterpret_cast<const floatx4 *>(p2 + 4);
+    }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (i < a.n_ctx) {
+      v1[0] += g1[i][0]; v1[1] += g1[i][1];
+      v2[0] += g2[i][0]; v2[1] += g2[i][1];
+    }
+  auto put = [&](int m, int o8, const floatx4(&v)[2]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float lo = v[i >> 1][2 * (i & 1)], hi = v[i >> 1][2 * (i & 1) + 1];
+      w[i] = (uint32_t)bf16_bits(fmaxf(lo, 0.f)) | ((uint32_t)bf16_bits(fmaxf(hi, 0.f)) << 16);
+    }
+    *reinterpret_cast<uint4 *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  };
+  put(m1, o81, v1);
+  if (two) put(m2, o82, v2);
+}
+
 __global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a) {
   if (*reinterpret_cast<const volatile int *>(a.done)) return;
   const int gid = blockIdx.x * 256 + threadIdx.x;
@@ -182,24 +249,7 @@ __global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a
   int tt = a.t[m];
   tt = tt < T_b ? tt : T_b - 1;
   tt = tt < 0 ? 0 : tt;
-  const float *fp = a.f_proj + ((size_t)b * a.T + tt) * a.H + 8 * o8;
-  float v[8];
-  {
-    const float4 x = *reinterpret_cast<const float4 *>(fp), y = *reinterpret_cast<const float4 *>(fp + 4);
-    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; v[4] = y.x; v[5] = y.y; v[6] = y.z; v[7] = y.w;
-  }
-  for (int i = 0; i < a.n_ctx; ++i) {
-    int tk = a.ctx_tok[m * kCtxMax + i];
-    tk = tk < 0 ? a.V : tk;
-    const float *gp = a.tab + ((size_t)i * (a.V + 1) + tk) * a.H + 8 * o8;
-    const float4 x = *reinterpret_cast<const float4 *>(gp), y = *reinterpret_cast<const float4 *>(gp + 4);
-    v[0] += x.x; v[1] += x.y; v[2] += x.z; v[3] += x.w; v[4] += y.x; v[5] += y.y; v[6] += y.z; v[7] += y.w;
-  }
-  uint32_t w[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    w[i] = (uint32_t)bf16_bits(fmaxf(v[2 * i], 0.f)) | ((uint32_t)bf16_bits(fmaxf(v[2 * i + 1], 0.f)) << 16);
-  *reinterpret_cast<uint4 *>(a.Ab + ((size_t)o8 * a.Mp + m) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  stateless_pre_big_item(a, m, b, tt, a.ctx_tok + m * kCtxMax, o8);
 }
 
 // wave-wide max of packed candidates, in every lane
@@ -230,6 +280,11 @@ struct RowSelectArgs {
   float *zs;             // [M][1 + ND]
   const int *finished;   // [B]
   const int *done;
+  // TAIL: the block that completes an utterance (counted in utt_ctr) runs its selection and writes the
+  // activations of its new hypotheses, so that the step needs no further launch
+  int *utt_ctr;          // [B], zero between steps
+  SelectArgs sel;
+  StatelessPreBigArgs pre;
 };
 
 constexpr int kRowWaves = 4;       // waves that share a row
@@ -244,6 +299,7 @@ constexpr int kSurvivorCap = 256;
 // it (a few dozen) are collected in LDS, and each of those finds its rank by counting the ones ahead of it.
 // Four waves per row rather than one: 32 instead of 128 registers of logits per lane, five waves per SIMD
 // instead of 1.25, so that the arithmetic of one row overlaps with the loads of another.
+template <bool TAIL>
 __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) {
   __shared__ uint64_t surv[kSurvivorCap];
   __shared__ int surv_n;
@@ -353,35 +409,72 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
     store_through(a.p_sum + m, (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]));
   }
   // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; wave 3, a lane takes 8 k
-  if (wave != kRowWaves - 1) return;
-  const int nz = 1 + a.ND;
-  float acc[9];
+  if (wave == kRowWaves - 1) {
+    const int nz = 1 + a.ND;
+    float acc[9];
 #pragma unroll
-  for (int d = 0; d < 9; ++d) acc[d] = 0.f;
-  for (int g = lane; g < (a.H >> 3); g += 64) {
-    const uint4 u = *reinterpret_cast<const uint4 *>(a.Ab + ((size_t)g * a.Mp + m) * 8);
-    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-    float x[8];
+    for (int d = 0; d < 9; ++d) acc[d] = 0.f;
+    for (int g = lane; g < (a.H >> 3); g += 64) {
+      const uint4 u = *reinterpret_cast<const uint4 *>(a.Ab + ((size_t)g * a.Mp + m) * 8);
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+      float x[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[2 * i] = __uint_as_float(w[i] << 16);
-      x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int d = 0; d < 9; ++d)
+        if (d < nz) {
+          const float4 p = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g);
+          const float4 q = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g + 4);
+          acc[d] += (x[0] * p.x + x[1] * p.y) + (x[2] * p.z + x[3] * p.w) + (x[4] * q.x + x[5] * q.y) +
+                    (x[6] * q.z + x[7] * q.w);
+        }
     }
 #pragma unroll
     for (int d = 0; d < 9; ++d)
       if (d < nz) {
-        const float4 p = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g);
-        const float4 q = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g + 4);
-        acc[d] += (x[0] * p.x + x[1] * p.y) + (x[2] * p.z + x[3] * p.w) + (x[4] * q.x + x[5] * q.y) +
-                  (x[6] * q.z + x[7] * q.w);
+        const float v = wave_sum(acc[d]);
+        if (lane == 0) store_through(a.zs + (size_t)m * nz + d, v + a.bias_spec[d]);
       }
   }
-#pragma unroll
-  for (int d = 0; d < 9; ++d)
-    if (d < nz) {
-      const float v = wave_sum(acc[d]);
-      if (lane == 0) store_through(a.zs + (size_t)m * nz + d, v + a.bias_spec[d]);
+  if constexpr (TAIL) {
+    // Every thread waits until its write-through stores (list, statistics, blank / duration logits) have been
+    // acknowledged, then the barrier, then one thread counts the row in: the count cannot become visible before
+    // anything of the row.  The block that brings the utterance's count to K owns the rest of its step.
+    __shared__ int s_is_last;
+    __shared__ SelectScratch scratch;
+    const int b = m / K;
+    wait_stores_acknowledged();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) {
+      const int old = __hip_atomic_fetch_add(a.utt_ctr + b, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int last = old == K - 1;
+      if (last) store_agent(a.utt_ctr + b, 0);  // every other row of the utterance has been counted
+      s_is_last = last;
     }
+    __syncthreads();
+    if (!s_is_last) return;
+    if (wave == 0) select_dispatch<4>(a.sel, b, scratch);  // (reads the lists with device-coherent loads)
+    __syncthreads();
+    // activations of the utterance's new hypotheses, from the selection's scratch (frame, token history)
+    const int T_b = a.pre.lengths[b];
+    const int H8 = a.pre.H >> 3;
+    // (two items per thread and round, so that the loads of both are in flight together)
+    for (int it = tid; it < K * H8; it += 2 * 64 * kRowWaves) {
+      const int it2 = it + 64 * kRowWaves;
+      const bool two = it2 < K * H8;
+      const int j = it / H8, o8 = it % H8, j2 = two ? it2 / H8 : j, o82 = two ? it2 % H8 : o8;
+      int tt = scratch.n_t[j], tt2 = scratch.n_t[j2];
+      tt = tt < T_b ? tt : T_b - 1;
+      tt = tt < 0 ? 0 : tt;
+      tt2 = tt2 < T_b ? tt2 : T_b - 1;
+      tt2 = tt2 < 0 ? 0 : tt2;
+      stateless_pre_big_pair(a.pre, b * K + j, tt, scratch.ctx[j], o8, b * K + j2, tt2, scratch.ctx[j2], o82, b, two);
+    }
+  }
 }
 
 }  // namespace rb

@@ -53,10 +53,11 @@ struct KernelTimer {
 
 enum {
   KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_JOINTBIG, KT_ROWSELECT,
-  KT_COUNT
+  KT_STATELESS, KT_COUNT
 };
 const char *kKernelNames[KT_COUNT] = {"k_gemm_tiled(enc_proj)", "k_init",      "k_step_main", "k_select",    "k_lm_rows",
-                                      "k_lstm_pointwise",    "k_pred_proj", "k_backtrace", "k_joint_big", "k_row_select"};
+                                      "k_lstm_pointwise",    "k_pred_proj", "k_backtrace", "k_joint_big", "k_row_select",
+                                      "k_stateless_pre"};
 
 // Device memory a decode works in beyond its inputs and outputs, laid out for given maxima.  The handle owns one
 // (a single allocation made at create); the allocation-free entry point lays one out in the static array.
@@ -417,6 +418,26 @@ struct ScopedKernelTime {
   }
 };
 
+// steps per graph launch (even: the state parity flips every step)
+constexpr int kChunkSteps = 16;
+
+// Materialised-logits path: selection and next activations in the tail of the row kernel (two launches per step)
+// unless a candidate rule needs a selection kernel of its own.
+#ifdef RB_BIG_TAIL_OFF
+bool big_tail(const rnnt_beam *, const StepPlan &) { return false; }
+#else
+bool big_tail(const rnnt_beam *h, const StepPlan &p) { return p.big && !h->cfg.tdt_all_pairs; }
+#endif
+
+void fill_stateless_pre_big(rnnt_beam *h, const StepPlan &p, int bump, StatelessPreBigArgs &a) {
+  const Workspace &w = *p.ws;
+  const rnnt_config_t &c = h->cfg;
+  a.f_proj = w.f_proj; a.tab = h->tab; a.ctx_tok = w.ctx; a.t = w.t; a.lengths = w.lengths;
+  a.Ab = w.Ab;
+  a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
+  a.done = w.ctrl + 1; a.step_base = w.ctrl + 2; a.bump = bump;
+}
+
 // fuse_lm: the LM rows of the new hypotheses ride in the cell-update launch (LSTM models only; the caller
 // then skips the stand-alone LM launch)
 int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bump, bool fuse_lm = false) {
@@ -474,11 +495,8 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
     }
   } else if (p.big) {
     StatelessPreBigArgs a;
-    a.f_proj = w.f_proj; a.tab = h->tab; a.ctx_tok = w.ctx; a.t = w.t; a.lengths = w.lengths;
-    a.Ab = w.Ab;
-    a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
-    a.done = done; a.step_base = step_base; a.bump = bump;
-    ScopedKernelTime tm(h, s, KT_PREDPROJ);
+    fill_stateless_pre_big(h, p, bump, a);
+    ScopedKernelTime tm(h, s, KT_STATELESS);
     const int n = p.M * (c.H / 8);
     hipLaunchKernelGGL(k_stateless_pre_big, dim3((n + 255) / 256), dim3(256), 0, s, a);
   } else {
@@ -487,7 +505,7 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
     a.pre = w.pre;
     a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
     a.done = done; a.step_base = step_base; a.bump = bump;
-    ScopedKernelTime tm(h, s, KT_PREDPROJ);
+    ScopedKernelTime tm(h, s, KT_STATELESS);
     const int n = p.M * (c.H / 4);
     hipLaunchKernelGGL(k_stateless_pre, dim3((n + 255) / 256), dim3(256), 0, s, a);
   }
@@ -579,6 +597,8 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       a.map.a_tiles = h->Npad_big / (32 * WV); a.map.a_m = (p.M + 32 * MS - 1) / (32 * MS);
       a.map.b_begin = a.map.b_end = 0; a.map.b_m = 0;
       a.done = done;
+      a.step_base = w.ctrl + 2;
+      a.bump = (big_tail(h, p) && step_off == 0) ? kChunkSteps : 0;
       ScopedKernelTime tm(h, s, KT_JOINTBIG);
       const dim3 grid(xcd_grid(a.map));
       // the kernel's loop runs in whole groups of D stages of k = 32; the operands are padded to k % 64 == 0
@@ -595,10 +615,18 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       a.lambda = p.lambda;
       a.p_max = w.p_max; a.p_sum = w.p_sum; a.p_cand = w.p_cand; a.zs = w.zs;
       a.finished = w.finished; a.done = done;
+      a.utt_ctr = w.tile_ctr;
+      fill_select_args(h, p, step_off, 1, a.sel);
+      fill_stateless_pre_big(h, p, 0, a.pre);
       ScopedKernelTime tm(h, s, KT_ROWSELECT);
-      hipLaunchKernelGGL(k_row_select, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
+      if (big_tail(h, p)) hipLaunchKernelGGL(k_row_select<true>, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
+      else hipLaunchKernelGGL(k_row_select<false>, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
     }
     RB_HIP(h, hipGetLastError());
+    if (big_tail(h, p)) {
+      // selection and next activations ran in the row kernel's tail; only the LM rows of the new hypotheses remain
+      return launch_lm(h, s, p);
+    }
     {
       SelectArgs sa;
       fill_select_args(h, p, step_off, 1, sa);
@@ -660,8 +688,6 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
   return launch_pred(h, s, p, cur, bump, fuse_lm);
 }
 
-// steps per graph launch (even: the state parity flips every step)
-constexpr int kChunkSteps = 16;
 // instantiated graphs kept per handle (one per launch shape, LM and LM weight); the oldest is dropped beyond that
 constexpr size_t kMaxGraphs = 8;
 
@@ -694,6 +720,7 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     a.n_tiles = w.max_B;
     a.B = p.B; a.K = p.K; a.T = p.T; a.V = c.V;
     a.lstm = lstm ? 1 : 0;
+    a.step_base_init = big_tail(h, p) ? -kChunkSteps : 0;
     a.finished = w.finished; a.utt_steps = w.utt_steps; a.n_finished = n_finished; a.done = done;
     a.step_base = step_base; a.bad_arg = bad_arg;
     a.h_done = h->h_done_dev;
