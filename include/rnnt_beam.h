@@ -33,7 +33,7 @@
  *   - rnnt_beam_decode by default follows the device (it returns when the data-dependent number of steps is
  *     over); with the config field async_enqueue it only enqueues and returns (see there).
  *   - config fields beyond the model's shape select readings the paper leaves open or variants it describes:
- *     use_graph, joint_path, lm_rule, lm_early_pruning, tdt_all_pairs, async_enqueue.
+ *     use_graph, joint_path, lm_rule, lm_early_pruning, tdt_all_pairs, async_enqueue, aes_prefix_search.
  */
 #ifndef RNNT_BEAM_H
 #define RNNT_BEAM_H
@@ -103,6 +103,14 @@ typedef struct {
                                 thread is blocked for most of the decode).  1: it enqueues the upper bound of
                                 T (max_symbols + 1) steps at once and returns without waiting; steps after the last
                                 utterance has finished return at once on the device (a few microseconds each) */
+  int32_t aes_prefix_search; /* RNNT_AES only: maximum-length prefix search (Sec. 2.2, "AES": probabilities of hypotheses
+                                with shared prefixes are combined; only the longest proper prefix is looked at).  When
+                                two hypotheses expanded in the same frame hold y and y + v, and the expansion of y by v
+                                is one of y's `beam` best tokens and stays in the frame, the candidates of y + v are
+                                RANKED as if its score also held that expansion's score.  The scores themselves are
+                                unchanged: the expansion competes as a candidate of its own and is merged with y + v by
+                                the recombination, so no alignment is counted twice.  Not with tdt_all_pairs or
+                                lm_early_pruning */
 } rnnt_config_t;
 
 /* Device pointers, float32, caller-owned.  Unused ones may be NULL. */

@@ -31,7 +31,8 @@ class _Config(C.Structure):
     _fields_ = [("model", C.c_int32), ("pred", C.c_int32), ("prec", C.c_int32),
                 ("D", C.c_int32), ("H", C.c_int32), ("P", C.c_int32), ("E", C.c_int32), ("V", C.c_int32),
                 ("n_dur", C.c_int32), ("durations", C.c_int32 * 8), ("ctx", C.c_int32),
-                ("max_symbols", C.c_int32), ("lm_rule", C.c_int32), ("lm_prune", C.c_int32), ("tdt_pairs", C.c_int32), ("gamma", C.c_double)]
+                ("max_symbols", C.c_int32), ("lm_rule", C.c_int32), ("lm_prune", C.c_int32), ("tdt_pairs", C.c_int32), ("aes_prefix", C.c_int32),
+                ("gamma", C.c_double)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -84,6 +85,7 @@ def make_config(c: dict, lm_rule: int = 4, lm_prune: str = "late") -> _Config:
     cfg.lm_rule = lm_rule
     cfg.lm_prune = {"late": 0, "early": 1}[lm_prune]
     cfg.tdt_pairs = 1 if c.get("tdt_pairs") else 0
+    cfg.aes_prefix = 1 if c.get("aes_prefix") else 0
     cfg.gamma = c["gamma"]
     return cfg
 

@@ -54,6 +54,7 @@ typedef struct {
   int32_t tdt_pairs;   /* TDT: 0 = one duration per candidate (the most likely one; for blank the most likely one
                           that advances); 1 = every (symbol, duration) pair is a candidate of its own, blank only
                           with durations >= 1 */
+  int32_t aes_prefix;  /* AES++ only: maximum-length prefix search (Sec. 2.2, "AES"), see decode_utterance */
   double gamma;        /* prune margin on log-probability, INFINITY = off */
 } orc_config;
 
@@ -699,6 +700,41 @@ static void decode_utterance(utt_job *J) {
         for (int v = 0; v <= V; ++v) unpruned[(int64_t)k * (V + 1) + v] = hy->score + tot2[v];
         free(tot2);
         free(lp2);
+      }
+    }
+
+    /* AES++, maximum-length prefix search (Sec. 2.2, "AES": the probabilities of hypotheses with shared prefixes
+     * are combined; only the longest proper prefix is looked at).  For hypotheses i and j expanded at this step
+     * in the same frame with transcript(i) = transcript(j) + v, the step's own expansion (j, v) reaches the
+     * transcript of i.  Its score is credited to i for the RANKING of i's candidates only: the new scores stay
+     * what they are, because the expansion (j, v) competes as a candidate of its own and meets i in the
+     * recombination once both have left the frame; adding it to i's score as well would count that alignment
+     * twice.  The credit exists only if (j, v) is one of j's Beam best token candidates (no other expansion of j
+     * can be kept) and stays in the frame (TDT: duration 0).  Pairs are found through Eq. (1), as recombination
+     * finds equal transcripts. */
+    if (c->aes_prefix && J->algo == 1 && !pairs && !(J->lm && c->lm_prune == 1)) {
+      for (int i = 0; i < K; ++i) {
+        if (kind[i] != 2 || cur[i].len < 1) continue;
+        double add = -INFINITY;
+        const int v = cur[i].last;
+        for (int j = 0; j < K; ++j) {
+          if (j == i || kind[j] != 2 || cur[j].t != cur[i].t || cur[j].len + 1 != cur[i].len) continue;
+          if (adv_tok[j] != 0) continue;
+          if ((uint32_t)(((uint64_t)cur[j].hash * ORC_HASH_BASE + (uint64_t)(v + 1)) % ORC_HASH_MOD) != cur[i].hash) continue;
+          if (memcmp(cur[j].tok, cur[i].tok, sizeof(int32_t) * (size_t)cur[j].len) != 0) J->collisions++;
+          const double credit = cand[((int64_t)j * (V + 1) + v) * nd].val;
+          if (!isfinite(credit)) continue;
+          int better = 0; /* token candidates of j that come before (j, v) */
+          for (int u = 0; u < V; ++u) {
+            const double x = cand[((int64_t)j * (V + 1) + u) * nd].val;
+            if (x > credit || (x == credit && u < v)) ++better;
+          }
+          if (better < K) add = logaddexp(add, credit);
+        }
+        if (add > -INFINITY) {
+          const double delta = logaddexp(cur[i].score, add) - cur[i].score;
+          for (int u = 0; u <= V; ++u) cand[((int64_t)i * (V + 1) + u) * nd].key += delta;
+        }
       }
     }
 

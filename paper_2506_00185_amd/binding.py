@@ -42,7 +42,7 @@ class _Config(C.Structure):
                 ("max_B", C.c_int32), ("max_T", C.c_int32), ("max_beam", C.c_int32), ("max_symbols", C.c_int32),
                 ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32),
                 ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32), ("tdt_all_pairs", C.c_int32),
-                ("async_enqueue", C.c_int32)]
+                ("async_enqueue", C.c_int32), ("aes_prefix_search", C.c_int32)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -162,6 +162,7 @@ class BeamDecoder:
         cfg.lm_early_pruning = {"late": 0, "early": 1}[lm_prune]
         cfg.tdt_all_pairs = 1 if c.get("tdt_pairs") else 0
         cfg.async_enqueue = 1 if async_enqueue else 0
+        cfg.aes_prefix_search = 1 if c.get("aes_prefix") else 0
         self.cfg = cfg
         self._w = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
                    for k, v in w.items()}

@@ -213,6 +213,7 @@ struct SelectArgs {
   int has_lm;
   int lm_rule3;         // 1: Eq. (3) (LM on tokens only, blank as it is); 0: Eq. (4)
   int lm_early;         // 1: early pruning: keys carry no LM term; the kept candidates are charged it here
+  int prefix;           // 1: AES++ maximum-length prefix search (ranking credit, see select_utterance)
   const float *lm_rows; // [M, V] natural-log LM scores (read for the kept candidates under early pruning)
   float lambda;
   // what the prediction step has to do for each new slot
@@ -240,6 +241,7 @@ struct SelectScratchT {
   double rc_key[CAND];  // early pruning only: what the candidates are ranked by
   double sel_val[kMaxBeam];
   double n_score[kMaxBeam];
+  double delta[kMaxBeam];  // prefix search: what the ranking adds to every candidate of the hypothesis
   uint64_t win[kMaxBeam][kMaxBeam];
   int t[kMaxBeam], sym[kMaxBeam], len[kMaxBeam], last[kMaxBeam], kind[kMaxBeam];
   uint32_t hash[kMaxBeam];
@@ -567,10 +569,41 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     process_rows();
   }
 
-  // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
-  // value is the new score itself except under early pruning
   const int n = K * (K + 1) * (PAIRS ? a.ND : 1);
-  const double *rank_of = a.lm_early ? s.rc_key : s.rc_val;
+  // ---- AES++, maximum-length prefix search (Sec. 2.2, "AES").  Hypotheses i and j expanded at this step in the
+  // same frame with transcript(i) = transcript(j) + v: the step's own expansion (j, v), if it is among j's Beam best
+  // tokens and stays in the frame, is credited to i for the RANKING of i's candidates; the new scores stay as they
+  // are (the expansion competes on its own and meets i in the recombination; adding it to i's score too would count
+  // that alignment twice).  Pairs are found through Eq. (1), like equal transcripts in the recombination.
+  const bool prefix = !PAIRS && a.prefix && a.algo == 1 && !a.lm_early;
+  if constexpr (!PAIRS) {
+    if (prefix) {
+      if (lane < K) {
+        const int i = lane;
+        double add = -INFINITY;
+        if (s.kind[i] == 2 && s.len[i] >= 1) {
+          const uint32_t hi = s.hash[i];
+          const int li = s.len[i], la = s.last[i], ti = s.t[i];
+          for (int j = 0; j < K; ++j) {
+            if (j == i || s.kind[j] != 2 || s.t[j] != ti || s.len[j] + 1 != li) continue;
+            if (s.advt[j] != 0) continue;
+            if (mod_mersenne31((uint64_t)s.hash[j] * kHashBase + (uint64_t)(la + 1)) != hi) continue;
+            for (int c = 0; c < K; ++c) {  // j's Beam best tokens: is v among them, with a finite score?
+              const int idx = j * (K + 1) + c;
+              if (s.rc_flat[idx] == (j << kFlatShift) + la && s.rc_val[idx] > -INFINITY) add = logaddexp_d(add, s.rc_val[idx]);
+            }
+          }
+        }
+        s.delta[i] = add > -INFINITY ? logaddexp_d(s.score[i], add) - s.score[i] : 0.0;
+      }
+      wave_sync();
+      for (int c = lane; c < n; c += 64) s.rc_key[c] = s.rc_val[c] + s.delta[c / (K + 1)];
+      wave_sync();
+    }
+  }
+  // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
+  // value is the new score itself except under early pruning and with a prefix credit
+  const double *rank_of = (a.lm_early || prefix) ? s.rc_key : s.rc_val;
   // candidates a lane may own in the counting form below
   constexpr int kOwn = 1;  // (measured: from 65 candidates up the rounds below are faster than two owned candidates)
   if (n <= 64 * kOwn) {

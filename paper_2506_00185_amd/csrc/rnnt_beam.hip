@@ -540,6 +540,7 @@ void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunk
   a.has_lm = p.lm ? 1 : 0;
   a.lm_rule3 = c.lm_rule == 3 ? 1 : 0;
   a.lm_early = (p.lm && c.lm_early_pruning) ? 1 : 0;
+  a.prefix = c.aes_prefix_search;
   a.lm_rows = w.lm_rows;
   a.lambda = p.lambda;
   a.src_row = w.src_row; a.tok = w.tok;
@@ -900,6 +901,9 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   if (!(c.prune_margin >= 0.f)) return bad("prune_margin must be >= 0 (INFINITY = off)");
 
   if (c.async_enqueue != 0 && c.async_enqueue != 1) return bad("async_enqueue must be 0 or 1");
+  if (c.aes_prefix_search != 0 && c.aes_prefix_search != 1) return bad("aes_prefix_search must be 0 or 1");
+  if (c.aes_prefix_search && (c.tdt_all_pairs || c.lm_early_pruning))
+    return bad("aes_prefix_search cannot be combined with tdt_all_pairs or lm_early_pruning");
 
   h->N = c.V + 1 + c.n_durations;
   h->n_chunks = (h->N + 31) / 32;

@@ -251,7 +251,7 @@ def aes_frame_synchronous(logp_fn, T, V, s, K):
     return closed
 
 
-def aes_bucketed(logp_fn, T, V, s, K, durations=(), gamma=math.inf):
+def aes_bucketed(logp_fn, T, V, s, K, durations=(), gamma=math.inf, prefix=False):
     """The two-set loop of ``aes_frame_synchronous`` for models whose symbols carry durations (TDT), and with a
     prune margin.  A hypothesis that leaves frame t by a blank or by a token of duration d >= 1 is put into the
     waiting set of the frame it lands on (``bucket[t + d]``, clamped at T = finished); tokens of duration 0 keep it
@@ -260,14 +260,21 @@ def aes_bucketed(logp_fn, T, V, s, K, durations=(), gamma=math.inf):
     per symbol: ``duration_rule``), lets every waiting hypothesis of every later frame compete with its score as
     it is, keeps the K best, and merges equal transcripts that wait at the same frame.  ``gamma``: a symbol
     (blank included) whose log-probability is more than gamma below the best one of its hypothesis is not
-    expanded; a blank forced by the frame limit is kept.  Returns {transcript: score} of the finished set."""
+    expanded; a blank forced by the frame limit is kept.
+    ``prefix``: maximum-length prefix search.  If the open set of a round holds both y and y + (v,), and the
+    expansion of y by v stays in the frame and is one of the K best token expansions of y, the expansions of
+    y + (v,) are RANKED as if its score also held that expansion's score; the scores themselves are unchanged (the
+    expansion competes on its own and is merged with y + (v,) when both have left the frame).
+    Returns {transcript: score} of the finished set."""
     bucket = {t: {} for t in range(T + 1)}
     bucket[0][()] = 0.0
     for t in range(T):
         open_, bucket[t] = bucket[t], {}
         rnd = 0
         while open_:
-            cands = []  # (score, landing frame or None = stays open, transcript)
+            cands = []  # (ranking key, score, landing frame or None = stays open, transcript)
+            tok_vals, stays = {}, {}
+            rows = {}
             for toks, sc in open_.items():
                 logp, dlogp = logp_fn(t, toks)
                 if durations:
@@ -276,23 +283,33 @@ def aes_bucketed(logp_fn, T, V, s, K, durations=(), gamma=math.inf):
                     adv_tok, x_tok, adv_blank, x_blank = 0, 0.0, 1, 0.0
                 floor = max(logp) - gamma
                 forced = rnd >= s
+                row = []
                 if forced or logp[V] >= floor:
-                    cands.append((sc + logp[V] + x_blank, min(t + adv_blank, T), toks))
+                    row.append((sc + logp[V] + x_blank, min(t + adv_blank, T), toks))
+                vals = {}
                 if not forced:
                     for v in range(V):
                         if logp[v] >= floor:
-                            cands.append((sc + logp[v] + x_tok, None if adv_tok == 0 else min(t + adv_tok, T),
-                                          toks + (v,)))
+                            vals[v] = sc + logp[v] + x_tok
+                            row.append((vals[v], None if adv_tok == 0 else min(t + adv_tok, T), toks + (v,)))
+                rows[toks], tok_vals[toks], stays[toks] = row, vals, adv_tok == 0
+            for toks, sc in open_.items():
+                delta = 0.0
+                if prefix and toks and toks[:-1] in open_ and stays[toks[:-1]]:
+                    vals, v = tok_vals[toks[:-1]], toks[-1]
+                    if v in vals and sum(1 for u, x in vals.items() if x > vals[v] or (x == vals[v] and u < v)) < K:
+                        delta = logaddexp(sc, vals[v]) - sc
+                cands += [(val + delta, val, land, y) for val, land, y in rows[toks]]
             for tw in range(t + 1, T + 1):
                 for toks, sc in bucket[tw].items():
-                    cands.append((sc, tw, toks))
+                    cands.append((sc, sc, tw, toks))
             cands.sort(key=lambda x: -x[0])
             if len(cands) > K:
                 assert cands[K - 1][0] != cands[K][0], "exact tie at the cut: the case cannot pin the order"
             open_ = {}
             for tw in range(t + 1, T + 1):
                 bucket[tw] = {}
-            for sc, land, toks in cands[:K]:
+            for _, sc, land, toks in cands[:K]:
                 if land is None:
                     assert toks not in open_
                     open_[toks] = sc

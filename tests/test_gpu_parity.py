@@ -280,6 +280,46 @@ def test_lm_fusion_rules_and_early_pruning(amd, oracle, rule, prune, beam, algo)
     assert not np.allclose(o_default["scores"], o["scores"], atol=1e-6)
 
 
+# ------------------------------------------- AES++ maximum-length prefix search
+
+@pytest.mark.parametrize("beam,V,model,levels,boost", [(4, 37, "rnnt", 400, 40), (8, 3, "rnnt", 32, 0), (3, 5, "tdt", 96, 10),
+                                                       (16, 4, "rnnt", 64, 0), (6, 2, "rnnt", 16, 0)])
+def test_injected_prefix_search_tree_is_bit_exact(amd, oracle, beam, V, model, levels, boost):
+    """Tiny vocabularies: the beam often holds a transcript together with its one-token extension in one frame,
+    so the prefix credit decides many cuts."""
+    durations = (0, 1, 2) if model == "tdt" else ()
+    B, T, C = 5, 14, 6
+    c = S.custom_config(B=B, T=T, T_min=3, D=32, H=32, P=32, E=32, V=V, beam=beam, s=3, algo="aes", model=model,
+                        durations=durations, aes_prefix=True)
+    L = S.make_lengths(c, 19)
+    L[1] = 0
+    L[2] = T
+    tok, dur = S.make_injected(B, T, C, V, len(durations), seed=beam * 100 + V + 7, levels=levels, blank_boost=boost)
+    dec = amd.BeamDecoder(c, S.make_weights(c, 1))
+    g = gpu_decode_injected(dec, tok, dur, L)
+    o = oracle.decode(c, None, None, L, injected=(tok, dur), log=True)
+    assert np.array_equal(g["n_steps"], o["n_steps"])
+    full, exempt = compare(g, o, tol=1e-9, tie=0.0, exact_tree=True)
+    assert full == B and exempt == 0
+    o_plain = oracle.decode(dict(c, aes_prefix=False), None, None, L, injected=(tok, dur), log=True)
+    assert not (np.array_equal(o_plain["log_parent"], o["log_parent"]) and np.array_equal(o_plain["log_token"], o["log_token"])), \
+        "the prefix search changes nothing on this table"
+
+
+@pytest.mark.parametrize("kw", [dict(beam=4), dict(beam=8, gamma=2.3), dict(beam=4, model="tdt", durations=(0, 1, 2, 3, 4))])
+def test_prefix_search_with_the_networks(amd, oracle, kw):
+    c = S.custom_config(B=5, T=20, T_min=8, D=128, H=160, P=160, E=160, V=300, s=3, algo="aes", blank_bias=3.0,
+                        aes_prefix=True, **kw)
+    w, L, enc = _case(c, 1200 + kw["beam"])
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    full, exempt = compare(g, o, TOL, TIE)
+    assert full + exempt == 5 and full >= 3
+    with pytest.raises(RuntimeError, match="aes_prefix_search"):
+        amd.BeamDecoder(dict(c, model="tdt", durations=(0, 1), tdt_pairs=True), S.make_weights(dict(c, model="tdt", durations=(0, 1)), 3))
+
+
 # ------------------------------------------- TDT with every (symbol, duration) pair as a candidate
 
 @pytest.mark.parametrize("algo", ["alsd", "aes"])

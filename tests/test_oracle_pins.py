@@ -194,6 +194,92 @@ def test_prune_margin_belongs_to_aes_only(oracle, model):
     assert set(_nbest(oracle.decode(c, w, enc, L, algo=oracle.AES))) != set(want)
 
 
+# ------------------------------------------- AES++ maximum-length prefix search
+
+@pytest.mark.parametrize("V,T,s,beam", [(2, 4, 2, 1024), (3, 3, 2, 2048)])
+def test_prefix_search_leaves_the_unpruned_result_exact(oracle, V, T, s, beam):
+    """With nothing pruned the prefix search may not change anything: every score is still the sum over the
+    alignments of its transcript (a reading that moved an expansion's score into the longer hypothesis as well
+    would count those alignments twice and fail here)."""
+    c, w, L, enc = _small(100 + V, V=V, T=T, s=s, beam=beam, algo="aes", aes_prefix=True)
+    fn = _ref_logp_fn(c, w, enc[0])
+    want = enumerate_alignments(fn, T, V, s)
+    r = oracle.decode(c, w, enc, L)
+    assert r["n_cut"][0] == 0 and r["collisions"][0] == 0
+    got = _nbest(r)
+    assert set(got) == set(want)
+    for y, sc in want.items():
+        assert abs(got[y] - sc) < 1e-9, (y, got[y], sc)
+    assert sum(math.exp(v) for v in got.values()) <= 1.0 + 1e-12
+
+
+@pytest.mark.parametrize("model,K,gamma,V", [("rnnt", 2, math.inf, 3), ("rnnt", 3, math.inf, 3), ("rnnt", 5, 2.0, 3),
+                                             ("tdt", 3, math.inf, 3), ("tdt", 3, 4.0, 3), ("rnnt", 2, math.inf, 7),
+                                             ("rnnt", 3, math.inf, 9)])
+def test_prefix_search_with_a_pruning_beam_equals_the_two_set_loop(oracle, model, K, gamma, V):
+    """With a real beam the prefix search changes which candidates are kept; against the frame / round loop with
+    dictionaries of transcripts."""
+    durations = (0, 1, 2) if model == "tdt" else ()
+    changed = 0
+    for seed in range(24 if (V > 3 or model == "tdt") else 8):
+        c, w, L, enc = _small(500 + seed, model=model, durations=durations, V=V, T=8, s=3, beam=K, algo="aes",
+                              gamma=gamma, aes_prefix=True, H=12, P=12, E=12, D=12, blank_bias=0.5)
+        if durations:
+            # even seeds: mostly duration 0 (expansions stay in the frame); odd seeds: all durations occur
+            w["b_out"][V + 1:] = [1.5, 0.0, 0.0] if seed % 2 == 0 else [0.2, 0.4, 0.0]
+            if seed % 2:
+                w["W_out"][V + 1:] *= 4.0
+        fn = _ref_logp_fn(c, w, enc[0])
+        want = aes_bucketed(fn, 8, V, 3, K, durations, gamma, prefix=True)
+        got = _nbest(oracle.decode(c, w, enc, L))
+        assert set(got) == set(want), (seed, got, want)
+        for y in want:
+            assert abs(got[y] - want[y]) < 1e-9
+        plain = _nbest(oracle.decode(dict(c, aes_prefix=False), w, enc, L))
+        changed += set(plain) != set(got) or any(abs(plain[y] - got[y]) > 1e-6 for y in got)
+    assert changed > 0 or model == "tdt", "the prefix search never changed a decision on these cases"
+
+
+def test_prefix_credit_needs_one_of_the_beam_best_expansions(oracle):
+    """A hand-made table (two context classes by hash parity, beam 2) where "" and "a" stand in frame 1 together
+    and "a" is only the THIRD best token after "": no credit, the two best expansions of "" fill the beam.  A
+    credit for that expansion would lift "ab" into the beam instead (key -1.8 + 0.51 against -1.5 and -1.6)."""
+    V, NEG = 3, -8.0
+    tok = np.full((1, 2, 2, V + 1), NEG, np.float32)
+    tok[0, 0, 0] = [-0.3, NEG, NEG, -1.0]      # frame 0 after "":  a, then blank
+    tok[0, 0, 1] = [NEG, NEG, NEG, -1.0]       # frame 0 after "a": blank
+    tok[0, 1, 0] = [-0.7, -0.5, -0.6, -3.0]    # frame 1 after "":  b, c, a
+    tok[0, 1, 1] = [-0.9, -0.5, -0.7, -3.0]    # frame 1 after "a"
+    tok += np.random.default_rng(3).uniform(0, 2e-3, tok.shape).astype(np.float32)  # no exact ties anywhere
+    assert py_hash(()) % 2 == 0 and py_hash((0,)) % 2 == 1
+    c = S.custom_config(B=1, T=2, V=V, beam=2, s=2, algo="aes", aes_prefix=True)
+    L = np.array([2], np.int32)
+    r = oracle.decode(c, None, None, L, injected=(tok, None), log=True)
+    # step 2 is the step in question: "" in slot 0 (-1.0), "a" in slot 1 (-1.3), both open in frame 1
+    np.testing.assert_array_equal(r["log_parent"][0, 2], [0, 0])
+    np.testing.assert_array_equal(r["log_token"][0, 2], [1, 2])
+    tm = TableModel(tok[0], None, V, py_hash)
+    want = aes_bucketed(tm.logp_at, 2, V, 2, 2, prefix=True)
+    got = _nbest(r)
+    assert set(got) == set(want)
+    for y in want:
+        assert abs(got[y] - want[y]) < 1e-12
+    # with "a" as the second best token after "" the credit exists (0.575) and lifts "ab" (-1.225) and "ac" (-1.425)
+    # over the expansions of "" (-1.5, -1.55, -1.6)
+    tok[0, 1, 0] = [-0.55, -0.5, -0.6, -3.0]
+    tok[0, 1, 0] += np.float32(1e-3) * np.arange(4, dtype=np.float32)
+    r2 = oracle.decode(c, None, None, L, injected=(tok, None), log=True)
+    np.testing.assert_array_equal(r2["log_parent"][0, 2], [1, 1])
+    np.testing.assert_array_equal(r2["log_token"][0, 2], [1, 2])
+
+
+def test_prefix_search_is_an_aes_option(oracle):
+    c, w, L, enc = _small(520, V=3, T=8, s=3, beam=3, algo="alsd", aes_prefix=True, H=12, P=12, E=12, D=12)
+    a, b = oracle.decode(c, w, enc, L), oracle.decode(dict(c, aes_prefix=False), w, enc, L)
+    np.testing.assert_array_equal(a["scores"], b["scores"])
+    np.testing.assert_array_equal(a["tokens"], b["tokens"])
+
+
 # ------------------------------------------------------- near-tie report
 
 def test_step_margin_report_on_a_hand_made_table(oracle):

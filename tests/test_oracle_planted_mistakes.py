@@ -55,6 +55,13 @@ MISTAKES = [
     ("distance from the prune margin left out of the near-tie report",
      "if (J->algo == 1 && isfinite(c->gamma) && !pairs) {\n      /* a token close", "if (0) {\n      /* a token close"),
     ("prune margin applied under ALSD++ too", "const int use_gamma = J->algo == 1;", "const int use_gamma = 1;"),
+    ("prefix search adds the expansion's score to the longer hypothesis as well (alignments counted twice)",
+     "for (int u = 0; u <= V; ++u) cand[((int64_t)i * (V + 1) + u) * nd].key += delta;",
+     "for (int u = 0; u <= V; ++u) { cand[((int64_t)i * (V + 1) + u) * nd].key += delta; "
+     "cand[((int64_t)i * (V + 1) + u) * nd].val += delta; }"),
+    ("prefix credit also for an expansion that is not among the Beam best of its hypothesis",
+     "if (better < K) add = logaddexp(add, credit);", "add = logaddexp(add, credit);"),
+    ("prefix credit also for an expansion that leaves the frame", "          if (adv_tok[j] != 0) continue;\n", ""),
     ("AES++ opens the frame of the first unfinished slot instead of the earliest frame",
      "        if (cur[k].t < t_cur) t_cur = cur[k].t;", "        if (t_cur == T_b) t_cur = cur[k].t;"),
 ]
