@@ -33,7 +33,8 @@
  *   - rnnt_beam_decode by default follows the device (it returns when the data-dependent number of steps is
  *     over); with the config field async_enqueue it only enqueues and returns (see there).
  *   - config fields beyond the model's shape select readings the paper leaves open or variants it describes:
- *     use_graph, joint_path, lm_rule, lm_early_pruning, tdt_all_pairs, async_enqueue, aes_prefix_search.
+ *     use_graph, joint_path, lm_rule, lm_early_pruning, tdt_all_pairs, async_enqueue, aes_prefix_search,
+ *     persistent_kernel.
  */
 #ifndef RNNT_BEAM_H
 #define RNNT_BEAM_H
@@ -111,6 +112,14 @@ typedef struct {
                                 unchanged: the expansion competes as a candidate of its own and is merged with y + v by
                                 the recombination, so no alignment is counted twice.  Not with tdt_all_pairs or
                                 lm_early_pruning */
+  int32_t persistent_kernel; /* 1: where it applies, the whole step loop runs as ONE launch instead of a replayed graph of
+                                per-step launches (Sec. 2.1, "CUDA Graphs", is what it replaces): one block per compute
+                                unit, the blocks of each XCD decode their own share of the utterances and synchronise
+                                among themselves.  Applies to LSTM decoders without an LM at beams up to 8 with at most
+                                32 hypotheses per XCD (ceil(B / 8) * beam <= 32) and H, P multiples of 64; other
+                                decodes use the per-step launches.  The GPU must be otherwise idle: every block has to be
+                                resident.  All waits between blocks are bounded; rnnt_beam_results returns RNNT_E_HIP if
+                                one ran into its limit or the blocks were not spread evenly over the XCDs */
 } rnnt_config_t;
 
 /* Device pointers, float32, caller-owned.  Unused ones may be NULL. */
@@ -243,6 +252,11 @@ int rnnt_lm_debug_query(const rnnt_lm_t *lm, const int32_t *ctx_tokens, int32_t 
  */
 int rnnt_beam_debug_block_map(int32_t a_tiles, int32_t a_m, int32_t b_begin, int32_t b_end, int32_t b_m, int32_t *role,
                               int32_t *ntile, int32_t *mtile, int32_t cap);
+
+/* Test hook for the error path of the single-launch step loop: the number of polls after which a wait between its
+ * blocks gives up (default 2^22).  With a limit of a few polls the first wait fails, every block returns, and
+ * rnnt_beam_results reports RNNT_E_HIP; no kernel is left waiting. */
+int rnnt_beam_debug_set_spin_limit(rnnt_beam_t *h, int32_t polls);
 
 /* Time, in milliseconds, between the first and the last kernel of the last decode (HIP events on
  * the decode's stream); negative if unavailable.  Synchronises. */

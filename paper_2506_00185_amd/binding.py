@@ -16,7 +16,7 @@ ALSD, AES = 0, 1
 EXPORTS = ["rnnt_beam_create", "rnnt_lm_create", "rnnt_beam_decode", "rnnt_beam_results",
            "rnnt_beam_decode_injected", "rnnt_beam_dump_tree", "rnnt_beam_debug_encproj", "rnnt_lm_debug_query",
            "rnnt_beam_last_decode_ms", "rnnt_beam_set_profiling", "rnnt_beam_kernel_times", "rnnt_beam_last_error",
-           "rnnt_beam_destroy", "rnnt_lm_destroy", "rnnt_beam_debug_block_map", "rnnt_beam_decode_static"]
+           "rnnt_beam_destroy", "rnnt_lm_destroy", "rnnt_beam_debug_block_map", "rnnt_beam_decode_static", "rnnt_beam_debug_set_spin_limit"]
 
 
 class RnntBeamError(RuntimeError):
@@ -42,7 +42,8 @@ class _Config(C.Structure):
                 ("max_B", C.c_int32), ("max_T", C.c_int32), ("max_beam", C.c_int32), ("max_symbols", C.c_int32),
                 ("prune_margin", C.c_float), ("use_graph", C.c_int32), ("joint_path", C.c_int32),
                 ("lm_rule", C.c_int32), ("lm_early_pruning", C.c_int32), ("tdt_all_pairs", C.c_int32),
-                ("async_enqueue", C.c_int32), ("aes_prefix_search", C.c_int32)]
+                ("async_enqueue", C.c_int32), ("aes_prefix_search", C.c_int32),
+                ("persistent_kernel", C.c_int32)]
 
 
 _WNAMES = ["W_enc", "b_enc", "W_pred", "b_pred", "W_out", "b_out", "emb", "W_ih", "W_hh", "b_ih", "b_hh"]
@@ -136,7 +137,7 @@ class BeamDecoder:
     """rnnt_beam_create / decode / results / destroy for one model."""
 
     def __init__(self, c: dict, w: dict, max_B=None, max_T=None, max_beam=None, use_graph=True, device="cuda:0",
-                 joint_path="auto", lm_rule=4, lm_prune="late", async_enqueue=False):
+                 joint_path="auto", lm_rule=4, lm_prune="late", async_enqueue=False, persistent=False):
         lib = load_library()
         torch = _torch()
         self.device = torch.device(device)
@@ -163,6 +164,7 @@ class BeamDecoder:
         cfg.tdt_all_pairs = 1 if c.get("tdt_pairs") else 0
         cfg.async_enqueue = 1 if async_enqueue else 0
         cfg.aes_prefix_search = 1 if c.get("aes_prefix") else 0
+        cfg.persistent_kernel = 1 if persistent else 0
         self.cfg = cfg
         self._w = {k: torch.as_tensor(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
                    for k, v in w.items()}
@@ -269,6 +271,9 @@ class BeamDecoder:
         rc = load_library().rnnt_beam_debug_encproj(self.handle, out.ctypes.data_as(C.c_void_p), C.c_int64(out.size))
         _check(rc, self.handle)
         return out
+
+    def debug_set_spin_limit(self, polls: int):
+        _check(load_library().rnnt_beam_debug_set_spin_limit(self.handle, C.c_int32(polls)), self.handle)
 
     def last_decode_ms(self) -> float:
         return float(load_library().rnnt_beam_last_decode_ms(self.handle))

@@ -295,7 +295,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   const int m_base = b * K;
   const int nz = 1 + a.ND;
   // ---- every load of the prologue is requested before anything waits on one of them
-  const int fin = a.finished[b];
+  const int fin = load_agent(a.finished + b);  // (a wave-uniform word that changes: never through the scalar cache)
   const int S = *a.step_base + a.step_off;
   const int T_b = a.lengths[b];
   double my_score = -INFINITY;
@@ -783,8 +783,8 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     const bool open = live && s.n_t[j] < T_b;
     const unsigned long long any_open = __ballot(open);
     if (j == 0 && (any_open == 0ull || S + 1 >= T_b * (a.max_sym + 1))) {
-      a.finished[b] = 1;
-      a.utt_steps[b] = S + 1;
+      store_through(a.finished + b, 1);
+      store_through(a.utt_steps + b, S + 1);
       __threadfence();
       const int old = atomicAdd(a.n_finished, 1);
       if (old + 1 == a.B) {
@@ -880,7 +880,7 @@ __host__ __device__ __forceinline__ int xcd_item(const XcdMap &m, int bid, int &
   return -1;
 }
 
-// R[m] = W_hh h[m] for one tile of 32 gate rows x 32 current slots (it does not depend on the
+// R[m] = W_hh h[m] for one tile of 32 gate rows x the 32 current slots from m0 on (it does not depend on the
 // selection, so its blocks ride along in the launches that have idle compute units).
 struct RecurrentArgs {
   const float *Whh;    // k4-major [P][4P], gate rows re-ordered (NULL: no such blocks)
@@ -890,10 +890,9 @@ struct RecurrentArgs {
 };
 
 template <int WAVES, int ITERS>
-__device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int tile, int mtile, int done, float *red) {
+__device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int tile, int m0, int done, float *red) {
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int m0 = mtile * 32;
   const int R4 = 4 * a.P, Mp = a.Mp;
   const float *wp = a.Whh + (size_t)(tile * 32 + col) * 4;
   const float *hp = a.h + (size_t)(m0 + col) * 4;
@@ -933,37 +932,16 @@ struct MainArgs {
   SelectArgs sel;
 };
 
-// Main kernel of a step.  Blocks [0, n_chunks * n_jtiles): joint network for a tile of up to 32
-// hypotheses (whole utterances) x 32 output columns,
-//   z[n] = W_out[n] . ReLU(pre_m) + b_out[n],  pre_m = f_proj[b, t_m] + g_m,
-// with the soft-max statistics and the K best keys of the chunk in the epilogue, so that the
-// [M, V + 1] logits never reach memory (LPH = 2 * WAVES lanes share a hypothesis, each holds 32 / LPH
-// columns; the best K are found in K rounds of an LPH-lane arg-max).  The block that completes a
-// tile (counted with one atomic per block) then runs the selection for the tile's utterances, one
-// wave per utterance.  Remaining blocks: R = W_hh h for the current slots; it does not depend on
-// the selection, so it overlaps with it instead of following it.
-// TAIL = false: no selection in the kernel (a launch of its own follows): for beams wider than the
-// in-kernel forms take.
-template <int WAVES, int ITERS, bool TAIL = true>
-__global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main(MainArgs a) {
-  constexpr int kRedFloats = WAVES * 64 * kRedStride;
-  constexpr int kScratchFloats = TAIL ? (int)((sizeof(SelectScratch) * WAVES + 3) / 4) : 1;
-  __shared__ __align__(16) float smem[kRedFloats > kScratchFloats ? kRedFloats : kScratchFloats];
-  __shared__ int s_is_last;
-  float *red = smem;
+// Joint network for 32 output columns (chunk) x the hypotheses [m0, m0 + rows): z[n] = W_out[n] . ReLU(pre_m) + b_out[n]
+// with pre_m = f_proj[b, t_m] + g_m, then, in the epilogue, the soft-max statistics and the K best keys of the chunk,
+// so that the [M, V + 1] logits never reach memory (LPH = 2 * WAVES lanes share a hypothesis, each holds 32 / LPH
+// columns; the best K are found in K rounds of an LPH-lane arg-max).  Lists and statistics are written with
+// device-coherent stores.  red: the block's reduction buffer (WAVES * 64 * kRedStride floats).
+template <int WAVES, int ITERS>
+__device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0, int rows, int done, float *red) {
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
-  int chunk, ty;
-  const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
-  if (role < 0) return;
-  if (role == 1) {
-    recurrent_tile<WAVES, ITERS>(a.rec, chunk, ty, done, red);
-    return;
-  }
-
-  // -------------------------------------------------------------------- joint
-  const int n0 = chunk * 32, m0 = ty * a.rpt;
+  const int n0 = chunk * 32;
   {
     const int Np = a.n_chunks * 32;
     const float *wp = a.W + (size_t)(n0 + col) * 4;
@@ -984,7 +962,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
   const int j = tid / LPH, e = tid % LPH, i0 = e * VPL;
   const int m = m0 + j;
-  const bool mvalid = j < a.rpt && m < a.M;
+  const bool mvalid = j < rows && m < a.M;
   const int nz = 1 + a.ND;
   uint64_t cand[VPL];
   float mx = -INFINITY;
@@ -1040,6 +1018,36 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
     if (e < a.K) store_agent(a.p_cand + pc * a.K + e, mine[0]);
     if (LPH + e < a.K) store_agent(a.p_cand + pc * a.K + LPH + e, mine[1]);
   }
+
+}
+
+// Main kernel of a step.  Blocks [0, n_chunks * n_jtiles): joint network for a tile of up to 32
+// hypotheses (whole utterances) x 32 output columns (joint_tile).  The block that completes a
+// tile (counted with one atomic per block) then runs the selection for the tile's utterances, one
+// wave per utterance.  Remaining blocks: R = W_hh h for the current slots; it does not depend on
+// the selection, so it overlaps with it instead of following it.
+// TAIL = false: no selection in the kernel (a launch of its own follows): for beams wider than the
+// in-kernel forms take.
+template <int WAVES, int ITERS, bool TAIL = true>
+__global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main(MainArgs a) {
+  constexpr int kRedFloats = WAVES * 64 * kRedStride;
+  constexpr int kScratchFloats = TAIL ? (int)((sizeof(SelectScratch) * WAVES + 3) / 4) : 1;
+  __shared__ __align__(16) float smem[kRedFloats > kScratchFloats ? kRedFloats : kScratchFloats];
+  __shared__ int s_is_last;
+  float *red = smem;
+  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
+  const int done = *reinterpret_cast<const volatile int *>(a.sel.done);
+  int chunk, ty;
+  const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
+  if (role < 0) return;
+  if (role == 1) {
+    recurrent_tile<WAVES, ITERS>(a.rec, chunk, ty * 32, done, red);
+    return;
+  }
+
+  joint_tile<WAVES, ITERS>(a, chunk, ty * a.rpt, a.rpt, done, red);
+  if (done) return;
 
   if constexpr (!TAIL) {
     return;
@@ -1121,6 +1129,27 @@ struct LmRowsArgs {
   int first_block;
 };
 
+// unit u of slot m: gates = R[src] + G[token] (the four gates of a unit adjacent), or a copy of the parent's state
+__device__ __forceinline__ void lstm_cell(const float *__restrict__ R, const float *__restrict__ G,
+                                          const float *__restrict__ h_cur, const float *__restrict__ c_cur,
+                                          float *__restrict__ h_nxt, float *__restrict__ c_nxt, int src, int token, int m,
+                                          int u, int Mp, int P, int done_flag) {
+  const float c_old = c_cur[(size_t)src * P + u];
+  float c = c_old, h;
+  if (token >= 0) {
+    const float4 r4 = *reinterpret_cast<const float4 *>(R + (size_t)src * 4 * P + 4 * u);
+    const float4 g4 = *reinterpret_cast<const float4 *>(G + (size_t)token * 4 * P + 4 * u);
+    if (done_flag) return;
+    c = sigmoid_f(r4.y + g4.y) * c_old + sigmoid_f(r4.x + g4.x) * tanh_f(r4.z + g4.z);
+    h = sigmoid_f(r4.w + g4.w) * tanh_f(c);
+  } else {
+    h = h_cur[k4_index(u, src, Mp)];
+    if (done_flag) return;
+  }
+  store_through(c_nxt + (size_t)m * P + u, c);
+  store_through(h_nxt + k4_index(u, m, Mp), h);
+}
+
 __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict__ R, const float *__restrict__ G,
                                                         const float *__restrict__ h_cur,
                                                         const float *__restrict__ c_cur, float *__restrict__ h_nxt,
@@ -1142,21 +1171,7 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   const int m = gid / P, u = gid % P;
   if (m >= M) return;
   const int done_flag = *reinterpret_cast<const volatile int *>(done);
-  const int src = src_row[m], token = tok[m];
-  const float c_old = c_cur[(size_t)src * P + u];
-  float c = c_old, h;
-  if (token >= 0) {
-    const float4 r4 = *reinterpret_cast<const float4 *>(R + (size_t)src * 4 * P + 4 * u);
-    const float4 g4 = *reinterpret_cast<const float4 *>(G + (size_t)token * 4 * P + 4 * u);
-    if (done_flag) return;
-    c = sigmoid_f(r4.y + g4.y) * c_old + sigmoid_f(r4.x + g4.x) * tanh_f(r4.z + g4.z);
-    h = sigmoid_f(r4.w + g4.w) * tanh_f(c);
-  } else {
-    h = h_cur[k4_index(u, src, Mp)];
-    if (done_flag) return;
-  }
-  store_through(c_nxt + (size_t)m * P + u, c);
-  store_through(h_nxt + k4_index(u, m, Mp), h);
+  lstm_cell(R, G, h_cur, c_cur, h_nxt, c_nxt, src_row[m], tok[m], m, u, Mp, P, done_flag);
 }
 
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
@@ -1173,27 +1188,17 @@ struct PredProjArgs {
   XcdMap map;          // role 0 = projection (tile of H, 32-row tile), role 1 = recurrent
 };
 
+// One tile of the projection: 32 outputs of H (tile) x the slots [m0, m0 + 32).
 template <int WAVES, int ITERS>
-__global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
-  __shared__ float red[WAVES * 64 * kRedStride];
+__device__ __forceinline__ void pred_proj_tile(const PredProjArgs &a, int tile, int m0, int done_flag, float *red) {
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  int tile, mtile;
-  const int role = xcd_item(a.map, blockIdx.x, tile, mtile);
-  if (role < 0) return;
-  if (role == 1) {
-    const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
-    recurrent_tile<WAVES, ITERS>(a.rec, tile, mtile, done_flag, red);
-    return;
-  }
-  const int m0 = mtile * 32;
   const float *wp = a.Wp + (size_t)(tile * 32 + col) * 4;
   const float *hp = a.h + (size_t)(m0 + col) * 4;
   const int H = a.H, Mp = a.Mp, round_ops = a.round_ops;
   auto a_at = [&](int k) { return *reinterpret_cast<const float4 *>(wp + (size_t)(k >> 2) * H * 4); };
   auto b_at = [&](int k) { return *reinterpret_cast<const float4 *>(hp + (size_t)(k >> 2) * Mp * 4); };
   auto fb = [](float4 v) { return v; };
-  const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
   // epilogue role: (hypothesis j, outputs o0 .. o0 + VPL - 1).  Its frame index is loaded BEFORE the operands: the
   // address of the frame's projection depends on it, and a wait for a load that was issued after the operands would
   // wait for all of them too (loads complete in order), i.e. hold the first matrix instruction back until the last
@@ -1219,11 +1224,25 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
     }
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P, red, round_ops);
-  if (a.bump && tile == 0 && mtile == 0 && tid == 0) *a.step_base += a.bump;
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)
     store_through(a.pre + k4_index(o0 + q, me, a.Mp), tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + bv[q] + fv[q]);
+}
+
+template <int WAVES, int ITERS>
+__global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
+  __shared__ float red[WAVES * 64 * kRedStride];
+  int tile, mtile;
+  const int role = xcd_item(a.map, blockIdx.x, tile, mtile);
+  if (role < 0) return;
+  const int done_flag = *reinterpret_cast<const volatile int *>(a.done);
+  if (role == 1) {
+    recurrent_tile<WAVES, ITERS>(a.rec, tile, mtile * 32, done_flag, red);
+    return;
+  }
+  if (!done_flag && a.bump && tile == 0 && mtile == 0 && threadIdx.x == 0) *a.step_base += a.bump;
+  pred_proj_tile<WAVES, ITERS>(a, tile, mtile * 32, done_flag, red);
 }
 
 // The same projection with the contraction split in two across blocks, for launches that would leave half the

@@ -19,6 +19,7 @@
 #include "gemm.h"
 #include "kernels.h"
 #include "kernels_big.h"
+#include "kernels_persistent.h"
 #include "lm.h"
 
 using namespace rb;
@@ -156,6 +157,9 @@ struct rnnt_beam {
   uint16_t *Wb = nullptr;
   float *Wspec = nullptr, *bias_spec = nullptr, *b_big = nullptr;
   Workspace ws;         // the handle's own workspace, laid out for max_B / max_T / max_beam in one allocation
+  PersistCtl *pctl = nullptr;  // counters of the single-launch step loop
+  int n_cus = 0, spin_limit = kSpinLimit;
+  bool last_persistent = false;
   int *h_done = nullptr, *h_done_dev = nullptr;  // pinned host word and its device alias
   // last decode
   bool have_result = false;
@@ -692,6 +696,55 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
 // instantiated graphs kept per handle (one per launch shape, LM and LM weight); the oldest is dropped beyond that
 constexpr size_t kMaxGraphs = 8;
 
+// The single-launch step loop (k_decode_persistent) takes LSTM decoders without an LM at beams up to 8 whose
+// utterances, dealt out over the eight XCDs, leave at most 32 slots per XCD; everything else replays per-step launches.
+bool use_persistent(const rnnt_beam *h, const StepPlan &p) {
+  const rnnt_config_t &c = h->cfg;
+  if (!c.persistent_kernel || p.inj_tok || p.lm || p.plain || p.big || h->profiling) return false;
+  if (c.pred != RNNT_PRED_LSTM || c.tdt_all_pairs || p.K > 8) return false;
+  if (c.H % 64 || c.P % 64) return false;
+  if ((p.B + kXccs - 1) / kXccs * p.K > 32) return false;
+  return h->n_cus >= 2 * kXccs;
+}
+
+int launch_persistent(rnnt_beam *h, hipStream_t s, const StepPlan &p, int max_steps) {
+  const Workspace &w = *p.ws;
+  const rnnt_config_t &c = h->cfg;
+  PersistArgs a{};
+  MainArgs &m = a.main;
+  m.pre = w.pre; m.W = h->W_out; m.bias = h->b_out; m.lm = nullptr; m.lambda = 0.f;
+  m.M = p.M; m.Mp = w.Mp; m.K = p.K; m.H = c.H; m.V = c.V; m.ND = c.n_durations;
+  m.n_chunks = h->n_chunks;
+  m.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
+  m.p_max = w.p_max; m.p_sum = w.p_sum; m.p_cand = w.p_cand; m.zs = w.zs;
+  m.tile_ctr = w.tile_ctr;
+  m.rec.Whh = h->W_hh; m.rec.h = nullptr; m.rec.R = w.Rgates; m.rec.P = c.P; m.rec.M = p.M; m.rec.Mp = w.Mp;
+  fill_select_args(h, p, 0, h->n_chunks, m.sel);  // (the step counter word stays 0: the kernel passes the step itself)
+  PredProjArgs &q = a.pp;
+  q.Wp = h->W_pred; q.bias = h->b_pred; q.h = nullptr; q.f_proj = w.f_proj; q.t = w.t; q.lengths = w.lengths;
+  q.pre = w.pre;
+  q.M = p.M; q.Mp = w.Mp; q.K = p.K; q.T = p.T; q.P = c.P; q.H = c.H; q.round_ops = m.round_ops;
+  q.done = w.ctrl + 1; q.step_base = w.ctrl + 2; q.bump = 0;
+  a.G = h->G;
+  for (int i = 0; i < 2; ++i) {
+    a.h[i] = w.h[i];
+    a.c[i] = w.c[i];
+  }
+  a.R = w.Rgates;
+  a.ctl = h->pctl;
+  a.B = p.B;
+  a.max_steps = max_steps;
+  a.spin_limit = h->spin_limit;
+  hipLaunchKernelGGL(k_fill_int, dim3(1), dim3(256), 0, s, reinterpret_cast<int *>(h->pctl), 0,
+                     (int)(sizeof(PersistCtl) / sizeof(int)));
+  const dim3 grid(h->n_cus / kXccs * kXccs);
+  ScopedKernelTime tm(h, s, KT_JOINT);
+  if (c.H == 640 && c.P == 640) hipLaunchKernelGGL((k_decode_persistent<8, 10>), grid, dim3(512), 0, s, a);
+  else hipLaunchKernelGGL((k_decode_persistent<8, 0>), grid, dim3(512), 0, s, a);
+  RB_HIP(h, hipGetLastError());
+  return RNNT_OK;
+}
+
 int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const StepPlan &p, hipStream_t s) {
   const Workspace &w = *p.ws;
   const rnnt_config_t &c = h->cfg;
@@ -737,13 +790,17 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
                          c.prec == RNNT_BF16_JOINT ? 1 : 0, nonfinite);
     if (rc) return rc;
   }
-  // prediction network on the start symbol (reads parity 1, writes parity 0), LM on the empty context
-  int rc = launch_pred(h, s, p, 1, 0);
-  if (rc) return rc;
-  if ((rc = launch_lm(h, s, p))) return rc;
-
   // every utterance has finished after at most T (s + 1) steps (the selection enforces it)
   const int max_steps = p.T * (c.max_symbols + 1) < w.S_max ? p.T * (c.max_symbols + 1) : w.S_max;
+  int rc = RNNT_OK;
+  h->last_persistent = use_persistent(h, p);
+  if (h->last_persistent) {
+    // one launch walks all steps (it starts with the prediction network on the start symbol itself)
+    if ((rc = launch_persistent(h, s, p, max_steps))) return rc;
+  } else {
+  // prediction network on the start symbol (reads parity 1, writes parity 0), LM on the empty context
+  if ((rc = launch_pred(h, s, p, 1, 0))) return rc;
+  if ((rc = launch_lm(h, s, p))) return rc;
   const bool use_graph = c.use_graph && !h->profiling && !p.inj_tok && !p.plain;
   hipGraphExec_t exec = nullptr;
   if (use_graph) {
@@ -802,6 +859,7 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     }
     ++chunk_i;
   }
+  }  // per-step launches
   {
     BacktraceArgs a;
     a.score = w.score;
@@ -901,6 +959,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   if (!(c.prune_margin >= 0.f)) return bad("prune_margin must be >= 0 (INFINITY = off)");
 
   if (c.async_enqueue != 0 && c.async_enqueue != 1) return bad("async_enqueue must be 0 or 1");
+  if (c.persistent_kernel != 0 && c.persistent_kernel != 1) return bad("persistent_kernel must be 0 or 1");
   if (c.aes_prefix_search != 0 && c.aes_prefix_search != 1) return bad("aes_prefix_search must be 0 or 1");
   if (c.aes_prefix_search && (c.tdt_all_pairs || c.lm_early_pruning))
     return bad("aes_prefix_search cannot be combined with tdt_all_pairs or lm_early_pruning");
@@ -946,6 +1005,23 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
     for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&h->ev_chunk[i]);
+    if (e == hipSuccess && c.persistent_kernel) {
+      // the single-launch loop needs every one of its blocks resident at once: one block per compute unit
+      int dev = 0, n_cu = 0, per_cu = 0;
+      e = hipGetDevice(&dev);
+      if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e == hipSuccess && c.H == 640 && c.P == 640)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decode_persistent<8, 10>, 512, 0);
+      else if (e == hipSuccess)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_decode_persistent<8, 0>, 512, 0);
+      h->n_cus = (e == hipSuccess && per_cu >= 1) ? n_cu : 0;
+      void *q = nullptr;
+      if (e == hipSuccess) e = hipMalloc(&q, sizeof(PersistCtl));
+      if (e == hipSuccess) {
+        h->allocs.push_back(q);
+        h->pctl = static_cast<PersistCtl *>(q);
+      }
+    }
     if (e != hipSuccess) {
       h->err = std::string("create: ") + hipGetErrorString(e);
       rc = RNNT_E_HIP;
@@ -1073,6 +1149,12 @@ int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *len
       for (int u = 0; u < n; ++u) tokens[i * cap + u] = buf[i * w.cap + u];
     }
   }
+  if (h->last_persistent) {
+    int ab = 0;
+    RB_HIP(h, hipMemcpy(&ab, &h->pctl->abort, sizeof(int), hipMemcpyDeviceToHost));
+    if (ab == 1) return fail(h, RNNT_E_HIP, "single-launch step loop: a wait between blocks ran into its limit (results invalid)");
+    if (ab == 2) return fail(h, RNNT_E_HIP, "single-launch step loop: blocks not spread evenly over the XCDs (results invalid)");
+  }
   if (flags[1]) return fail(h, RNNT_E_NONFINITE, "NaN or Inf in the encoder projection");
   if (flags[0]) return fail(h, RNNT_E_ARG, "an utterance length was outside 0..T (clamped)");
   return RNNT_OK;
@@ -1142,6 +1224,12 @@ float rnnt_beam_last_decode_ms(rnnt_beam_t *h) {
   float ms = -1.f;
   if (hipEventElapsedTime(&ms, h->ev_begin, h->ev_end) != hipSuccess) return -1.f;
   return ms;
+}
+
+int rnnt_beam_debug_set_spin_limit(rnnt_beam_t *h, int32_t polls) {
+  if (!h || polls < 1) return RNNT_E_ARG;
+  h->spin_limit = polls;
+  return RNNT_OK;
 }
 
 int rnnt_beam_set_profiling(rnnt_beam_t *h, int32_t on) {

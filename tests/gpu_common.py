@@ -13,10 +13,10 @@ def to_gpu(a, dtype=None):
     return t.cuda().contiguous()
 
 
-def gpu_decode(dec, enc, lengths, want_tree=True, **kw):
+def gpu_decode(dec, enc, lengths, want_tree=True, check=True, **kw):
     import torch
     dec.decode(to_gpu(enc, torch.float32), to_gpu(lengths, torch.int32), **kw)
-    r = dec.results()
+    r = dec.results(check=check)
     if want_tree:
         r.update(dec.dump_tree(int(r["n_steps"].max()) + 1))
     return r

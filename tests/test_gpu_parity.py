@@ -446,6 +446,41 @@ def test_split_projection_at_a_generic_width(amd, oracle):
     assert full + exempt == 6 and full >= 4
 
 
+@pytest.mark.parametrize("kw", [dict(B=11, beam=4, algo="alsd"), dict(B=3, beam=8, algo="aes", gamma=2.3),
+                                dict(B=19, beam=2, algo="aes", model="tdt", durations=(0, 1, 2, 3, 4)),
+                                dict(B=32, beam=4, algo="alsd", prec="bf16"), dict(B=8, beam=1, algo="alsd")])
+def test_single_launch_step_loop_equals_the_per_step_launches(amd, oracle, kw):
+    """persistent_kernel = 1: the whole loop in one launch, the blocks of each XCD decoding their own utterances.
+    At these widths (P = 192) both paths run the same tile routines on the same operands, so trees, transcripts
+    and scores must be identical bit for bit; batches that leave some XCDs without an utterance included."""
+    c = S.custom_config(T=22, T_min=6, D=64, H=192, P=192, E=64, V=150, s=3, blank_bias=3.0, **kw)
+    w, L, enc = _case(c, 1300 + kw["B"], zero_len=True)
+    ref = gpu_decode(amd.BeamDecoder(c, w), enc, L)
+    dec = amd.BeamDecoder(c, w, persistent=True)
+    for _ in range(2):
+        r = gpu_decode(dec, enc, L)
+        assert r["rc"] == 0
+        for key in ("tokens", "lens", "scores", "n_steps", "parent", "token", "merged"):
+            np.testing.assert_array_equal(r[key], ref[key])
+    o = oracle.decode(c, w, enc, L, log=True)
+    tol, tie = (TOL_BF16, TIE_BF16) if c["prec"] == "bf16" else (TOL, TIE)
+    full, exempt = compare(r, o, tol, tie, walk=make_walk(oracle, c, w, enc, L, r, tol))
+    assert full + exempt == c["B"] and full >= c["B"] // 2
+
+
+def test_single_launch_step_loop_gives_up_cleanly(amd):
+    """A wait between blocks that runs into its limit ends the kernel (every block returns) and is reported."""
+    c = S.custom_config(B=4, T=12, T_min=6, D=64, H=192, P=192, E=64, V=50, beam=4, s=2, algo="alsd")
+    w, L, enc = _case(c, 1350)
+    dec = amd.BeamDecoder(c, w, persistent=True)
+    dec.debug_set_spin_limit(1)
+    r = gpu_decode(dec, enc, L, want_tree=False, check=False)
+    assert r["rc"] == -3
+    dec.debug_set_spin_limit(1 << 22)
+    r = gpu_decode(dec, enc, L, want_tree=False)
+    assert r["rc"] == 0 and np.all(r["lens"][:, 0] >= 0)
+
+
 def test_error_paths(amd):
     import torch
     from paper_2506_00185_amd import RnntBeamError
