@@ -137,7 +137,7 @@ def measure(S, A, torch, cid: int, variant: str, steps: int, warmup: int, args, 
         lm_arrays = S.make_lm(c["V"], c["lm"]["order"], c["lm"]["n_target"], c["lm"]["zipf_s"], 1000 * c["id"] + 3)
         lm = A.NGramLM(lm_arrays)
     dec = A.BeamDecoder(c, w, use_graph=not args.no_graph, lm_rule=args.lm_rule, lm_prune=args.lm_prune,
-                        async_enqueue=args.async_enqueue, persistent=not args.per_step_launches)
+                        async_enqueue=args.async_enqueue, persistent=args.single_launch)
     d_enc = torch.as_tensor(enc).cuda().contiguous()
     d_len = torch.as_tensor(L).cuda().contiguous()
     audio_s = S.audio_seconds(L)
@@ -231,7 +231,7 @@ def measure(S, A, torch, cid: int, variant: str, steps: int, warmup: int, args, 
                 **({"lm_rule": args.lm_rule, "lm_prune": args.lm_prune} if c["lm"] else {}),
                 **({"tdt_pairs": True} if c.get("tdt_pairs") else {}),
                 **({"async_enqueue": True} if args.async_enqueue else {}),
-                "step_loop": "single launch where it applies" if not args.per_step_launches else "per-step launches"},
+                **({"step_loop": "single launch"} if args.single_launch else {})},
         beam_search_steps=n_steps, us_per_beam_step=round(gpu_ms * 1e3 / max(n_steps, 1), 3),
         gpu_ms_per_pass=round(gpu_ms, 4), beam1_ms_per_pass=round(ms_beam1, 4), beam_over_greedy=round(ms / ms_beam1, 4),
         roofline=roofline, kernels=kernels)
@@ -265,8 +265,9 @@ def main():
     ap.add_argument("--variant", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-graph", action="store_true", help="launch the step kernels one by one")
     ap.add_argument("--async-enqueue", action="store_true", help="enqueue the upper bound of steps without following the device")
-    ap.add_argument("--per-step-launches", action="store_true",
-                    help="replay the graph of per-step kernels also where the single-launch step loop applies")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="the whole step loop as one launch (persistent_kernel) where it applies, instead of the "
+                         "replayed graph of per-step kernels")
     ap.add_argument("--lm-rule", type=int, default=4, choices=[3, 4], help="LM fusion rule (workloads with an LM)")
     ap.add_argument("--lm-prune", default="late", choices=["late", "early"])
     ap.add_argument("--tdt-pairs", action="store_true", help="TDT workloads: every (symbol, duration) pair a candidate")

@@ -2,10 +2,10 @@
 // (Sec. 2.1, "CUDA Graphs": the per-step launches and their boundaries are the cost being avoided).
 //
 // One block per compute unit.  The blocks that run on one XCD form a group that decodes its own share of the
-// utterances from the first step to the last, independently of the other groups: producers and consumers of a
-// group then share one L2, so that what one block writes with ordinary stores the others read back through that L2
-// (with the L1 invalidated after every hand-over), and a barrier spans 32 blocks instead of 256.  Every group
-// streams all weights itself.  A step of a group:
+// utterances from the first step to the last, independently of the other groups, so that a barrier spans 32 blocks
+// instead of 256 and no group ever waits for another.  Hand-over between blocks is the device-scope protocol of the
+// per-step kernels' tail: write-through stores, then a count; the waiting side polls the count with device-coherent
+// loads and then invalidates its caches.  Every group streams all weights itself.  A step of a group:
 //   C  cell update of the LSTM for the group's slots                                   | group barrier
 //   D  prediction projection (H / 32 tiles), the other blocks start on  R' = W_hh h'   | counter: projection tiles done
 //   A  joint network (n_chunks tiles, candidate lists), then the rest of R'            | counter: joint tiles done
@@ -53,8 +53,11 @@ __device__ __forceinline__ int xcc_id() { return __builtin_amdgcn_s_getreg((3 <<
 
 // every thread: my stores have reached the L2
 __device__ __forceinline__ void publish_stores() { wait_stores_acknowledged(); }
-// every thread: drop what this compute unit's L1 holds (other blocks of the group have written since)
-__device__ __forceinline__ void refresh_l1() { asm volatile("buffer_inv sc0" ::: "memory"); }
+// every thread, after a wait: device-scope acquire.  What other blocks handed over was written through to the memory
+// side (store_through / store_agent) before they counted in; this drops every line of the L1 and every clean line of
+// the XCD's L2 that could be older.  (The workgroup-scope form, "buffer_inv sc0", and loads with only sc0 set were
+// measured to be no-ops on the L1 in this mode: a poll with them never saw another compute unit's count.)
+__device__ __forceinline__ void refresh_caches() { asm volatile("buffer_inv sc1" ::: "memory"); }
 
 // thread 0 of the block polls `word` until it reaches `target` (or the abort word is raised, or the limit is hit);
 // returns false to the whole block if the kernel must end.  Ends with the block in step and a fresh L1.
@@ -75,7 +78,7 @@ __device__ __forceinline__ bool block_wait(const int *word, int target, PersistC
   __syncthreads();
   const int ok = *s_flag;
   __syncthreads();
-  refresh_l1();
+  refresh_caches();
   return ok != 0;
 }
 
