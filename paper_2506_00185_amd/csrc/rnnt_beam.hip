@@ -427,11 +427,7 @@ constexpr int kChunkSteps = 16;
 
 // Materialised-logits path: selection and next activations in the tail of the row kernel (two launches per step)
 // unless a candidate rule needs a selection kernel of its own.
-#ifdef RB_BIG_TAIL_OFF
-bool big_tail(const rnnt_beam *, const StepPlan &) { return false; }
-#else
 bool big_tail(const rnnt_beam *h, const StepPlan &p) { return p.big && !h->cfg.tdt_all_pairs; }
-#endif
 
 void fill_stateless_pre_big(rnnt_beam *h, const StepPlan &p, int bump, StatelessPreBigArgs &a) {
   const Workspace &w = *p.ws;
