@@ -242,13 +242,16 @@ struct SelectScratchT {
   double sel_val[kMaxBeam];
   double n_score[kMaxBeam];
   double delta[kMaxBeam];  // prefix search: what the ranking adds to every candidate of the hypothesis
-  uint64_t win[kMaxBeam][kMaxBeam];
   int t[kMaxBeam], sym[kMaxBeam], len[kMaxBeam], last[kMaxBeam], kind[kMaxBeam];
   uint32_t hash[kMaxBeam];
   int ctx[kMaxBeam][kCtxMax];
   int advt[kMaxBeam], advb[kMaxBeam];
   int rc_flat[CAND];
   int sel_flat[kMaxBeam];
+  // staircase form of the ranking (beams 8 .. 10): per hypothesis the place of blank in its sorted list, its head,
+  // the order of the lists by their heads; then the K (K + 1) / 2 candidates that can still be among the Beam best
+  double head_val[kMaxBeam], st_key[64 + 8];
+  int head_flat[kMaxBeam], pos_blank[kMaxBeam], ord[kMaxBeam], st_flat[64 + 8], st_src[64];
   int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
   uint32_t n_hash[kMaxBeam];
 };
@@ -641,6 +644,64 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         s.sel_val[rank[q]] = s.rc_val[lane + 64 * q];
         s.sel_flat[rank[q]] = mf[q];
       }
+  } else if (!PAIRS && KMAX > 7 && K * (K + 1) / 2 <= 64) {
+    // More than 64 candidates, beams up to 10.  The candidates of one hypothesis are a sorted list: its tokens come
+    // best first (the ranking value grows with the key) and blank / stay has its place among them.  With the lists
+    // ordered by their heads, the entry at place p of the list of order o has at least p + o candidates ahead of it,
+    // so only the K (K + 1) / 2 entries with p + o < K can be among the Beam best, and an entry's rank among those
+    // is its rank among all whenever that is below K.  They fit one per lane, and the counting form applies.
+    if (lane < K) {
+      const int base = lane * (K + 1);
+      const double bv = rank_of[base + K];
+      int pos = 0;
+      for (int j = 0; j < K; ++j) {
+        const double tv = rank_of[base + j];
+        pos += (tv > -INFINITY && tv >= bv) ? 1 : 0;  // (on equal values the token comes first: lower index)
+      }
+      s.pos_blank[lane] = pos;
+      s.head_val[lane] = pos == 0 ? bv : rank_of[base];
+      s.head_flat[lane] = pos == 0 ? s.rc_flat[base + K] : s.rc_flat[base];
+    }
+    wave_sync();
+    if (lane < K) {
+      const double hv = s.head_val[lane];
+      const int hf = s.head_flat[lane];
+      int o = 0;
+      for (int r = 0; r < K; ++r) o += comes_before(s.head_val[r], s.head_flat[r], hv, hf) ? 1 : 0;
+      s.ord[lane] = o;
+    }
+    wave_sync();
+    for (int c = lane; c < n; c += 64) {
+      const int r = c / (K + 1), j = c - r * (K + 1);
+      const int pb = s.pos_blank[r], o = s.ord[r];
+      const int p = j == K ? pb : (j < pb ? j : j + 1);
+      if (p + o < K) {
+        const int slot = o * K - o * (o - 1) / 2 + p;
+        s.st_key[slot] = rank_of[c];
+        s.st_flat[slot] = s.rc_flat[c];
+        s.st_src[slot] = c;
+      }
+    }
+    wave_sync();
+    const int nn = K * (K + 1) / 2;
+    const double mv = lane < nn ? s.st_key[lane] : -INFINITY;
+    const int mf = lane < nn ? s.st_flat[lane] : 0x7fffffff;
+    int rank = 0;
+    for (int c0 = 0; c0 < nn; c0 += 8) {
+      double cv[8];
+      int cf[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {  // (the arrays have room beyond nn)
+        cv[q] = s.st_key[c0 + q];
+        cf[q] = s.st_flat[c0 + q];
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) rank += (c0 + q < nn && comes_before(cv[q], cf[q], mv, mf)) ? 1 : 0;
+    }
+    if (mv > -INFINITY && rank < K) {
+      s.sel_val[rank] = s.rc_val[s.st_src[lane]];
+      s.sel_flat[rank] = mf;
+    }
   } else {
     double last_v = INFINITY;
     int last_i = -1;
