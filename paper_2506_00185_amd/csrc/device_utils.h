@@ -92,11 +92,22 @@ __device__ __forceinline__ void store_through(T *p, T v) {
   store_agent(p, v);
 }
 
+// 16 bytes written through (one instruction; the atomic store above exists for 4 and 8 bytes only)
+__device__ __forceinline__ void store16_through(float *p, floatx4 v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+
 // Candidate order used everywhere a "best" is chosen: larger value first, then
 // smaller index.  Returns true if (v1, i1) comes before (v2, i2).
 template <typename V, typename I>
 __device__ __forceinline__ bool comes_before(V v1, I i1, V v2, I i2) {
   return v1 > v2 || (v1 == v2 && i1 < i2);
+}
+// the same without short circuits, for unrolled runs of comparisons (the compiler turns the form above into a branch
+// per comparison when the values are doubles, which costs more than the compares themselves)
+template <typename V, typename I>
+__device__ __forceinline__ int comes_before_count(V v1, I i1, V v2, I i2) {
+  return (int)(v1 > v2) | ((int)(v1 == v2) & (int)(i1 < i2));
 }
 
 // ---- cross-lane exchange without the LDS crossbar --------------------------

@@ -606,7 +606,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
   }
   // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
   // value is the new score itself except under early pruning and with a prefix credit
-  const double *rank_of = (a.lm_early || prefix) ? s.rc_key : s.rc_val;
+  double *rank_of = (a.lm_early || prefix) ? s.rc_key : s.rc_val;
   // candidates a lane may own in the counting form below
   constexpr int kOwn = 1;  // (measured: from 65 candidates up the rounds below are faster than two owned candidates)
   if (n <= 64 * kOwn) {
@@ -622,20 +622,25 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       mf[q] = c < n ? s.rc_flat[c] : 0x7fffffff;
       rank[q] = 0;
     }
+    // the loop below reads in eights: the (up to seven) places after the last candidate hold one that comes before
+    // nothing, so that no comparison needs a bound check (the arrays have room beyond n; nothing else uses it)
+    if (lane < 8) {
+      rank_of[n + lane] = -INFINITY;
+      s.rc_flat[n + lane] = 0x7fffffff;
+    }
+    wave_sync();
     for (int c0 = 0; c0 < n; c0 += 8) {
       double cv[8];
       int cf[8];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) {  // eight requests in flight (the arrays have room beyond n)
+      for (int q = 0; q < 8; ++q) {  // eight requests in flight
         cv[q] = rank_of[c0 + q];
         cf[q] = s.rc_flat[c0 + q];
       }
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
-        const bool in = c0 + q < n;
 #pragma unroll
-        for (int o = 0; o < kOwn; ++o)
-          if (o == 0 || 64 * o < n) rank[o] += (in && comes_before(cv[q], cf[q], mv[o], mf[o])) ? 1 : 0;
+        for (int o = 0; o < kOwn; ++o) rank[o] += comes_before_count(cv[q], cf[q], mv[o], mf[o]);
       }
     }
 #pragma unroll
@@ -682,8 +687,12 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         s.st_src[slot] = c;
       }
     }
-    wave_sync();
     const int nn = K * (K + 1) / 2;
+    if (lane < 8) {  // (as above: the counting loop reads in eights)
+      s.st_key[nn + lane] = -INFINITY;
+      s.st_flat[nn + lane] = 0x7fffffff;
+    }
+    wave_sync();
     const double mv = lane < nn ? s.st_key[lane] : -INFINITY;
     const int mf = lane < nn ? s.st_flat[lane] : 0x7fffffff;
     int rank = 0;
@@ -696,7 +705,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
         cf[q] = s.st_flat[c0 + q];
       }
 #pragma unroll
-      for (int q = 0; q < 8; ++q) rank += (c0 + q < nn && comes_before(cv[q], cf[q], mv, mf)) ? 1 : 0;
+      for (int q = 0; q < 8; ++q) rank += comes_before_count(cv[q], cf[q], mv, mf);
     }
     if (mv > -INFINITY && rank < K) {
       s.sel_val[rank] = s.rc_val[s.st_src[lane]];

@@ -1,9 +1,11 @@
 // Kernels for large (hypotheses x vocabulary) products with a bf16 joint: the joint's output
 // layer as a bf16 matrix-core contraction that writes float32 logits, and a row-wise exact
 // top-K over them.  A step of this mode is
-//   k_joint_big -> k_row_select -> k_select -> k_stateless_pre_big
+//   k_joint_big -> k_row_select (whose tail runs the selection and writes the next activations).
 // Keeping the per-row top-K in the contraction's epilogue, as the small-shape kernel does, costs
-// more vector instructions at K = 10 and V = 8192 than the trip of the logits through HBM.
+// more vector instructions at K = 10 and V = 8192 than the trip of the logits through HBM.  The epilogue does
+// keep the maximum and the sum of exponentials of every (hypothesis, 32-column chunk), so that the row kernel
+// reads 8 bytes per chunk and then only the few chunks that can hold one of the K best keys.
 #pragma once
 #include "kernels.h"
 
@@ -37,6 +39,7 @@ struct BigJointArgs {
   const uint16_t *Ab;  // bf16 k8-major [H][Mp]: ReLU(pre), rounded
   const float *bias;   // [Npad]
   float *Z;            // [M][Npad] logits of the token columns
+  uint64_t *cstat;     // [M][Npad / 32] (maximum, sum of exp(z - maximum)) of each 32-column chunk, two floats
   int M, Mp, H, Npad;
   XcdMap map;          // role 0: (block of 256 columns, block of 32 * MS rows)
   const int *done;
@@ -55,9 +58,11 @@ struct BigJointArgs {
 // registers -> LDS one stage ahead of its use, in a ring of three slots with one barrier per stage.
 // The stage loop has no branches, so that the compiler's count of outstanding loads stays exact.
 // Needs H % (32 * D) == 0 (the caller pads the operands with zeros along k).
-// The hypotheses are the rows of the matrix-core product and the vocabulary its columns, so that a
-// lane ends up with four consecutive hypotheses of ONE column and 32 lanes store 128 contiguous bytes
-// (16-byte stores of four columns scattered over 32 rows took twice as long, non-temporal ones four times).
+// The vocabulary is the row index of the matrix-core product and the hypotheses its columns: a lane ends up with
+// 16 logits of ONE hypothesis (four runs of four consecutive columns), so the chunk statistics need no reduction
+// across lanes beyond one exchange between the wave's halves.  A tile then goes through LDS (transposed) so that
+// eight lanes store the 128 contiguous bytes of a hypothesis' chunk (16-byte stores scattered over 32 rows took
+// twice as long as stores of whole 128-byte runs, non-temporal ones four times).
 template <int WAVES, int D>
 __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArgs a) {
   constexpr int MS = 5, NP = 2 * MS;  // pieces (k-step, hypothesis tile) of 1 KB per stage
@@ -114,11 +119,10 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-      for (int t = 0; t < MS; ++t) acc[t] = mfma32_bf16(bf[kk * MS + t], wr[set][kk], acc[t]);
+      for (int t = 0; t < MS; ++t) acc[t] = mfma32_bf16(wr[set][kk], bf[kk * MS + t], acc[t]);
   };
 #pragma unroll
   for (int j = 0; j < D; ++j) request(j, j);
-  const float bias = a.bias[n0 + col];
   if (done) return;
 #pragma unroll
   for (int t = 0; t < MS; ++t) acc[t] = floatx16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -150,15 +154,53 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
     s1 = s2;
     s2 = r;
   }
-  // epilogue: register r of tile t is hypothesis m0 + 32 t + 8 (r / 4) + 4 kg + r % 4, column n0 + col
-  float *zcol = a.Z + n0 + col;
+  // epilogue: register r of tile t is column n0 + 8 (r / 4) + 4 kg + r % 4 of hypothesis m0 + 32 t + col
+  constexpr int TS = 36;  // floats per hypothesis in the transposition buffer (32 + 4: 16-byte aligned rows)
+  static_assert(sizeof(tile) >= (size_t)WAVES * 32 * TS * 4 + (size_t)32 * MS * WAVES * 8, "epilogue buffers fit the ring");
+  __syncthreads();  // every wave is through with the activation ring, which the buffers below reuse
+  float *tr = reinterpret_cast<float *>(&tile[0][0][0]) + wave * 32 * TS;
+  uint64_t *stat = reinterpret_cast<uint64_t *>(reinterpret_cast<float *>(&tile[0][0][0]) + WAVES * 32 * TS);
+  floatx4 b4[4];
 #pragma unroll
-  for (int t = 0; t < MS; ++t)
+  for (int g = 0; g < 4; ++g) b4[g] = *reinterpret_cast<const floatx4 *>(a.bias + n0 + 8 * g + 4 * kg);
+  const float kLog2e = 1.4426950408889634f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + 32 * t + 8 * (r >> 2) + 4 * kg + (r & 3);
-      if (m < a.M) store_through(zcol + (size_t)m * a.Npad, acc[t][r] + bias);
+  for (int t = 0; t < MS; ++t) {
+    floatx4 v[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[g][e] = acc[t][4 * g + e] + b4[g][e];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) mx = fmaxf(mx, fmaxf(fmaxf(v[g][0], v[g][1]), fmaxf(v[g][2], v[g][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float off = mx > -INFINITY ? -mx * kLog2e : 0.f;  // (a chunk of padding columns holds -inf only)
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      sum += (exp2f(fmaf(v[g][0], kLog2e, off)) + exp2f(fmaf(v[g][1], kLog2e, off))) +
+             (exp2f(fmaf(v[g][2], kLog2e, off)) + exp2f(fmaf(v[g][3], kLog2e, off)));
+    sum += __shfl_xor(sum, 32);
+    if (kg == 0) stat[(32 * t + col) * WAVES + wave] = ((uint64_t)__float_as_uint(sum) << 32) | __float_as_uint(mx);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) *reinterpret_cast<floatx4 *>(tr + col * TS + 8 * g + 4 * kg) = v[g];
+    wave_sync();  // (the buffer is this wave's own)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int hl = (lane >> 3) + 8 * i, q = lane & 7;
+      const floatx4 x = *reinterpret_cast<const floatx4 *>(tr + hl * TS + 4 * q);
+      const int m = m0 + 32 * t + hl;
+      if (m < a.M) store16_through(a.Z + (size_t)m * a.Npad + n0 + 4 * q, x);
     }
+    wave_sync();
+  }
+  __syncthreads();
+  const int n_stat = a.Npad >> 5;
+  for (int i = tid; i < 32 * MS * WAVES; i += 64 * WAVES) {
+    const int m = m0 + i / WAVES;
+    if (m < a.M) store_through(a.cstat + (size_t)m * n_stat + nb * WAVES + i % WAVES, stat[i]);
+  }
 }
 
 // Stateless prediction network for the large mode: a_m = bf16(ReLU(f_proj[b, t_m] + sum_i tab_i[token_i]))
@@ -268,6 +310,7 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 
 struct RowSelectArgs {
   const float *Z;        // [M][Npad]
+  const uint64_t *cstat; // [M][Npad / 32] chunk statistics written with the logits (see BigJointArgs)
   int Npad;
   const uint16_t *Ab;    // bf16 k8-major [H][Mp]
   int M, Mp, H, K, V, ND;
@@ -292,14 +335,17 @@ constexpr int kRowRegs = 8;        // float4 registers per lane: V <= kRowWaves 
 constexpr int kSurvivorCap = 256;
 
 // One block of four waves per hypothesis: exact K best of the row's keys (as a one-chunk candidate list
-// for the selection kernel), soft-max statistics, blank / duration logits.  Columns V .. Npad - 1 of Z
+// for the selection), soft-max statistics, blank / duration logits.  Columns V .. Npad - 1 of Z
 // hold -inf (their bias is -inf), so the row needs no tail masks.
-// The K best are found without sorting the row: in every wave the K-th largest of the 64 lane maxima is a
-// lower bound of the K-th largest key of the row, so is the largest of the four; only keys at or above
-// it (a few dozen) are collected in LDS, and each of those finds its rank by counting the ones ahead of it.
+// The K best are found without sorting the row.  A lower bound tau of the K-th largest key comes first; only keys
+// at or above it (a few dozen) are collected in LDS, and each of those finds its rank by counting the ones ahead of it.
+// STATS (no LM term in the keys): the contraction has left (maximum, sum of exponentials) of every 32-column chunk.
+// Thread c takes chunk c; in every wave the K-th largest of its 64 chunk maxima bounds the row's K-th largest key
+// from below, so does the largest of the four; only chunks whose maximum reaches tau are read, eight lanes each.
+// Otherwise the whole row is read, 32 values per lane, and the lane maxima play the part of the chunk maxima.
 // Four waves per row rather than one: 32 instead of 128 registers of logits per lane, five waves per SIMD
 // instead of 1.25, so that the arithmetic of one row overlaps with the loads of another.
-template <bool TAIL>
+template <bool TAIL, bool STATS>
 __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) {
   __shared__ uint64_t surv[kSurvivorCap];
   __shared__ int surv_n;
@@ -311,6 +357,51 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
   if (a.finished[m / K]) return;
   const float *zrow = a.Z + (size_t)m * a.Npad;
   const float *lmrow = a.lm ? a.lm + (size_t)m * V : nullptr;
+  float mx;
+  if constexpr (STATS) {
+    __shared__ int s_chunks[64 * kRowWaves];
+    __shared__ int s_nq;
+    const int n_stat = a.Npad >> 5;  // <= 256
+    float cm = -INFINITY, cs = 0.f;
+    if (tid < n_stat) {
+      const uint64_t st = a.cstat[(size_t)m * n_stat + tid];
+      cm = __uint_as_float((uint32_t)st);
+      cs = __uint_as_float((uint32_t)(st >> 32));
+    }
+    if (tid == 0) {
+      surv_n = 0;
+      s_nq = 0;
+    }
+    {
+      const float wm = wave_max(cm);
+      if (lane == 0) s_max[wave] = wm;
+    }
+    float tau = -INFINITY, cur = cm;
+    for (int j = 0; j < K; ++j) {
+      tau = wave_max(cur);
+      if (cur == tau) cur = -INFINITY;
+    }
+    if (lane == 0) s_tau[wave] = tau;
+    __syncthreads();
+    mx = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+    float sum = cm > -INFINITY ? cs * exp2f((cm - mx) * 1.4426950408889634f) : 0.f;
+    sum = wave_sum(sum);
+    if (lane == 0) s_sum[wave] = sum;
+    tau = fmaxf(fmaxf(s_tau[0], s_tau[1]), fmaxf(s_tau[2], s_tau[3]));
+    if (cm >= tau && cm > -INFINITY) s_chunks[atomicAdd(&s_nq, 1)] = tid;
+    __syncthreads();
+    const int nq = s_nq;
+    for (int i = tid >> 3; i < nq; i += 8 * kRowWaves) {
+      const int n = 32 * s_chunks[i] + 4 * (tid & 7);
+      const floatx4 z = *reinterpret_cast<const floatx4 *>(zrow + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (z[e] >= tau && z[e] > -INFINITY) {
+          const int pos = atomicAdd(&surv_n, 1);
+          if (pos < kSurvivorCap) surv[pos] = pack_cand(z[e], n + e);
+        }
+    }
+  } else {
   // thread tid holds columns 4 (tid + 256 q) .. + 3
   floatx4 z[kRowRegs];
 #pragma unroll
@@ -328,7 +419,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
     if (lane == 0) s_max[wave] = wm;
   }
   __syncthreads();
-  const float mx = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  mx = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
   float sum = 0.f;
   {
     const float kLog2e = 1.4426950408889634f, off = -mx * kLog2e;
@@ -376,6 +467,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
         }
     }
   }
+  }  // !STATS
   __syncthreads();
   const int total = surv_n;
   uint64_t *out = a.p_cand + (size_t)m * K;

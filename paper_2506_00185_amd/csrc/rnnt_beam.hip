@@ -68,6 +68,7 @@ struct Workspace {
   int *tile_ctr = nullptr;
   uint16_t *Ab = nullptr;   // materialised-logits path only
   float *Zbig = nullptr;
+  uint64_t *cstat = nullptr;  // chunk statistics of the logits, [M][Npad_big / 32]
   double *score = nullptr;
   int *t = nullptr, *sym = nullptr, *len = nullptr, *last = nullptr, *ctx = nullptr, *lengths = nullptr;
   uint32_t *hash = nullptr;
@@ -107,6 +108,7 @@ size_t layout_workspace(Workspace &w, char *base, const rnnt_config_t &c, int n_
   if (big) {
     take(&w.Ab, (size_t)w.Mp * Hb);
     take(&w.Zbig, M * Npad_big);
+    take(&w.cstat, M * (Npad_big / 32));
   }
   take(&w.lm_rows, M * c.V);
   take(&w.Rgates, M * 4 * c.P);
@@ -592,7 +594,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     constexpr int MS = 5;  // 160 hypotheses per block
     {
       BigJointArgs a;
-      a.Wb = h->Wb; a.Ab = w.Ab; a.bias = h->b_big; a.Z = w.Zbig;
+      a.Wb = h->Wb; a.Ab = w.Ab; a.bias = h->b_big; a.Z = w.Zbig; a.cstat = w.cstat;
       a.M = p.M; a.Mp = w.Mp; a.H = h->Hb; a.Npad = h->Npad_big;
       constexpr int WV = 4;  // waves per block; the block covers 32 * WV columns
       a.map.a_tiles = h->Npad_big / (32 * WV); a.map.a_m = (p.M + 32 * MS - 1) / (32 * MS);
@@ -609,7 +611,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     RB_HIP(h, hipGetLastError());
     {
       RowSelectArgs a;
-      a.Z = w.Zbig; a.Npad = h->Npad_big; a.Ab = w.Ab; a.M = p.M; a.Mp = w.Mp; a.H = c.H;
+      a.Z = w.Zbig; a.cstat = w.cstat; a.Npad = h->Npad_big; a.Ab = w.Ab; a.M = p.M; a.Mp = w.Mp; a.H = c.H;
       a.K = p.K; a.V = c.V; a.ND = c.n_durations;
       a.Wspec = h->Wspec; a.bias_spec = h->bias_spec;
       a.lm = (p.lm && !c.lm_early_pruning) ? w.lm_rows : nullptr;  // early pruning ranks without the LM term
@@ -620,8 +622,15 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       fill_select_args(h, p, step_off, 1, a.sel);
       fill_stateless_pre_big(h, p, 0, a.pre);
       ScopedKernelTime tm(h, s, KT_ROWSELECT);
-      if (big_tail(h, p)) hipLaunchKernelGGL(k_row_select<true>, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
-      else hipLaunchKernelGGL(k_row_select<false>, dim3(p.M), dim3(64 * kRowWaves), 0, s, a);
+      // without an LM term in the keys the chunk statistics of the contraction say which chunks to read
+      const dim3 grid(p.M), block(64 * kRowWaves);
+      if (big_tail(h, p)) {
+        if (a.lm) hipLaunchKernelGGL((k_row_select<true, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_row_select<true, true>), grid, block, 0, s, a);
+      } else {
+        if (a.lm) hipLaunchKernelGGL((k_row_select<false, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_row_select<false, true>), grid, block, 0, s, a);
+      }
     }
     RB_HIP(h, hipGetLastError());
     if (big_tail(h, p)) {
