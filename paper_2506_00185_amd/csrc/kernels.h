@@ -178,10 +178,9 @@ __global__ __launch_bounds__(64) void k_inject(InjectArgs a) {
   TopList<KT> top;
   top.init();
   for (int v = lane; v < a.V; v += 64) top.insert(row[v], v);
-  const size_t pc = (size_t)m * 64 + lane;
 #pragma unroll
   for (int j = 0; j < KT; ++j)
-    if (j < a.K) a.p_cand[pc * a.K + j] = pack_cand(top.v[j], top.i[j]);
+    if (j < a.K) a.p_cand[((size_t)m * a.K + j) * 64 + lane] = pack_cand(top.v[j], top.i[j]);
   const int nz = 1 + a.ND;
   if (lane == 0) a.zs[(size_t)m * nz] = row[a.V];
   if (lane >= 1 && lane <= a.ND)
@@ -200,7 +199,8 @@ struct SelectArgs {
   const int *lengths;
   // candidate lists from the joint (k_step_main, k_row_select) or k_inject
   const float *p_max, *p_sum;
-  const uint64_t *p_cand;  // [M, n_chunks, K] packed (key, token), each chunk's list best first
+  const uint64_t *p_cand;  // [M, K, n_chunks] packed (key, token): entry j of every chunk's list (best first) side by
+                           // side, so that lanes that take neighbouring chunks read neighbouring words
   const float *zs;
   int n_chunks;
   int use_ctx;     // 1: the token history of each hypothesis is kept (stateless prediction network, LM)
@@ -338,30 +338,41 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
     psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
     const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
+    // (every load is unconditional, from a clamped address, and what does not apply is replaced afterwards: a load
+    // under a condition of its own costs a branch each)
     if constexpr (NCH > 0) {
 #pragma unroll
       for (int q = 0; q < NCH; ++q) {
         const int ch = e + LPR * q;
         const bool ok = row_ok && ch < a.n_chunks;
+        const int chs = ok ? ch : 0;
         if constexpr (!ONE) {
           if (!one_list) {
 #pragma unroll
-            for (int j = 0; j < KMAX; ++j) list[q][j] = (ok && j < K) ? load_agent(cands + ch * K + j) : no_cand();
+            for (int j = 0; j < KMAX; ++j) {
+              const uint64_t x = load_agent(cands + (j < K ? j : 0) * a.n_chunks + chs);
+              list[q][j] = (ok && j < K) ? x : no_cand();
+            }
           }
         }
-        pm[q] = (ok && !a.normalized) ? load_agent(pmax + ch) : -INFINITY;
-        ps[q] = (ok && !a.normalized) ? load_agent(psum + ch) : 0.f;
+        const float xm = load_agent(pmax + chs), xs = load_agent(psum + chs);
+        pm[q] = (ok && !a.normalized) ? xm : -INFINITY;
+        ps[q] = (ok && !a.normalized) ? xs : 0.f;
       }
       if (one_list) {
 #pragma unroll
         for (int i = 0; i < kMine; ++i) {
           const int j = e + LPR * i;
-          direct[i] = (row_ok && j < K) ? load_agent(cands + j) : no_cand();
+          const uint64_t x = load_agent(cands + (j < K ? j : 0));
+          direct[i] = (row_ok && j < K) ? x : no_cand();
         }
       }
     }
     zb = load_agent(zsr);
-    for (int d = 0; d < a.ND; ++d) dl[d] = load_agent(zsr + 1 + d);
+    if (a.ND > 0) {
+#pragma unroll
+      for (int d = 0; d < 8; ++d) dl[d] = load_agent(zsr + 1 + (d < a.ND ? d : 0));
+    }
   };
   auto process_rows = [&]() {
     // ---- K rounds of "best remaining candidate" in every lane group at once.
@@ -659,9 +670,10 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       const int base = lane * (K + 1);
       const double bv = rank_of[base + K];
       int pos = 0;
-      for (int j = 0; j < K; ++j) {
+#pragma unroll
+      for (int j = 0; j < KMAX; ++j) {  // (reads past the K tokens stay inside the array and are not counted)
         const double tv = rank_of[base + j];
-        pos += (tv > -INFINITY && tv >= bv) ? 1 : 0;  // (on equal values the token comes first: lower index)
+        pos += (int)(j < K) & (int)(tv > -INFINITY) & (int)(tv >= bv);  // (equal values: the token comes first)
       }
       s.pos_blank[lane] = pos;
       s.head_val[lane] = pos == 0 ? bv : rank_of[base];
@@ -672,12 +684,14 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       const double hv = s.head_val[lane];
       const int hf = s.head_flat[lane];
       int o = 0;
-      for (int r = 0; r < K; ++r) o += comes_before(s.head_val[r], s.head_flat[r], hv, hf) ? 1 : 0;
+#pragma unroll
+      for (int r = 0; r < KMAX; ++r) o += (int)(r < K) & comes_before_count(s.head_val[r], s.head_flat[r], hv, hf);
       s.ord[lane] = o;
     }
     wave_sync();
+    const unsigned inv = 65536u / (unsigned)(K + 1) + 1u;  // c / (K + 1) for c < 272 without a division per lane
     for (int c = lane; c < n; c += 64) {
-      const int r = c / (K + 1), j = c - r * (K + 1);
+      const int r = (int)(((unsigned)c * inv) >> 16), j = c - r * (K + 1);
       const int pb = s.pos_blank[r], o = s.ord[r];
       const int p = j == K ? pb : (j < pb ? j : j + 1);
       if (p + o < K) {
@@ -992,7 +1006,7 @@ struct MainArgs {
   int M, Mp, K, H, V, ND, n_chunks, round_ops;
   int upt, rpt, n_jtiles;  // utterances and rows per joint tile (rpt = upt * K <= 32), number of such tiles
   float *p_max, *p_sum;    // [M, n_chunks] soft-max statistics of the chunk's token logits
-  uint64_t *p_cand;        // [M, n_chunks, K] best (key = z + lambda * lm, token) of the chunk, packed
+  uint64_t *p_cand;        // [M, K, n_chunks] best (key = z + lambda * lm, token) of the chunk, packed
   float *zs;               // [M, 1 + ND] raw blank and duration logits
   int *tile_ctr;           // [n_jtiles] blocks of the tile that have written their lists
   // ---- recurrent-product role (LSTM)
@@ -1085,8 +1099,9 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
       store_agent(a.p_max + pc, mx);
       store_agent(a.p_sum + pc, sum);
     }
-    if (e < a.K) store_agent(a.p_cand + pc * a.K + e, mine[0]);
-    if (LPH + e < a.K) store_agent(a.p_cand + pc * a.K + LPH + e, mine[1]);
+    uint64_t *lists = a.p_cand + (size_t)m * a.K * a.n_chunks + chunk;
+    if (e < a.K) store_agent(lists + (size_t)e * a.n_chunks, mine[0]);
+    if (LPH + e < a.K) store_agent(lists + (size_t)(LPH + e) * a.n_chunks, mine[1]);
   }
 
 }
