@@ -345,7 +345,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
       for (int q = 0; q < NCH; ++q) {
         const int ch = e + LPR * q;
         const bool ok = row_ok && ch < a.n_chunks;
-        const int chs = ok ? ch : 0;
+        const int chs = min(ch, a.n_chunks - 1);  // (lanes without a chunk repeat their group's last address: no extra line)
         if constexpr (!ONE) {
           if (!one_list) {
 #pragma unroll
@@ -891,6 +891,7 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scra
   if constexpr (FORMS == 4) {  // one list per hypothesis (the materialised-logits path), any beam
     if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true>(a, b, s);
     else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true>(a, b, s);
+    else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true>(a, b, s);
     else select_utterance<4, 1, 16, false, false, Scratch, true>(a, b, s);
   } else if constexpr (FORMS == 3) {  // TDT, every (symbol, duration) pair a candidate, beams up to 8
     if (a.K <= 4) {

@@ -70,7 +70,12 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
   constexpr int FP = PW * WAVES;      // the other NP - FP pieces are loaded 4 bytes per thread
   constexpr int XD = (NP - FP) * 256 / (64 * WAVES);
   static_assert(WAVES == 4 || WAVES == 8, "two waves per SIMD: one block of 8 or two blocks of 4");
-  __shared__ u32x4 tile[3][NP][64];
+  // activation ring of three slots; the epilogue reuses the memory (transposition buffers + chunk statistics)
+  constexpr int TS = 36;  // floats per hypothesis in a transposition buffer (32 + 4: 16-byte aligned rows)
+  constexpr size_t kRingBytes = sizeof(u32x4) * 3 * NP * 64;
+  constexpr size_t kEpiBytes = (size_t)WAVES * 32 * TS * 4 + (size_t)32 * MS * WAVES * 8;
+  __shared__ __align__(16) unsigned char lds_raw[kRingBytes > kEpiBytes ? kRingBytes : kEpiBytes];
+  u32x4 (*tile)[NP][64] = reinterpret_cast<u32x4 (*)[NP][64]>(lds_raw);
   const int done = *reinterpret_cast<const volatile int *>(a.done);
   if (a.bump && !done && blockIdx.x == 0 && threadIdx.x == 0) *a.step_base += a.bump;
   int nb, mb;
@@ -155,11 +160,9 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
     s2 = r;
   }
   // epilogue: register r of tile t is column n0 + 8 (r / 4) + 4 kg + r % 4 of hypothesis m0 + 32 t + col
-  constexpr int TS = 36;  // floats per hypothesis in the transposition buffer (32 + 4: 16-byte aligned rows)
-  static_assert(sizeof(tile) >= (size_t)WAVES * 32 * TS * 4 + (size_t)32 * MS * WAVES * 8, "epilogue buffers fit the ring");
   __syncthreads();  // every wave is through with the activation ring, which the buffers below reuse
-  float *tr = reinterpret_cast<float *>(&tile[0][0][0]) + wave * 32 * TS;
-  uint64_t *stat = reinterpret_cast<uint64_t *>(reinterpret_cast<float *>(&tile[0][0][0]) + WAVES * 32 * TS);
+  float *tr = reinterpret_cast<float *>(lds_raw) + wave * 32 * TS;
+  uint64_t *stat = reinterpret_cast<uint64_t *>(reinterpret_cast<float *>(lds_raw) + WAVES * 32 * TS);
   floatx4 b4[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) b4[g] = *reinterpret_cast<const floatx4 *>(a.bias + n0 + 8 * g + 4 * kg);

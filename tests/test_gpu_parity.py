@@ -367,6 +367,10 @@ def test_tdt_pairs_with_the_networks(amd, oracle, algo, beam):
     ("tdt_alsd_k6", dict(model="tdt", algo="alsd", beam=6, V=777, B=3, durations=(0, 1, 2, 3, 4)), 0.0),
     ("rnnt_alsd_k16_lm", dict(model="rnnt", algo="alsd", beam=16, V=300, B=2), 0.3),
     ("rnnt_alsd_k5_lm_early", dict(model="rnnt", algo="alsd", beam=5, V=300, B=3), 0.4),
+    # fewer 32-column chunks than the beam is wide: the chunk statistics give no bound, every key is collected
+    ("rnnt_aes_k16_v200", dict(model="rnnt", algo="aes", beam=16, V=200, B=2), 0.0),
+    # ... and more keys than the row kernel's list holds: its plain rounds over the row in memory
+    ("rnnt_alsd_k12_v300", dict(model="rnnt", algo="alsd", beam=12, V=300, B=2), 0.0),
 ])
 def test_materialized_logits_path(amd, oracle, name, kw, lm_w):
     """Same bars as the bf16 variant of the fused path; shapes that leave ragged tails in every
