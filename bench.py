@@ -92,14 +92,17 @@ def kernel_bytes(name: str, c: dict, M: int, B: int, T: int, K: int, steps: int)
         return 2 * lm
     if name == "k_select":                # stand-alone selection from one list per hypothesis
         return M * (8.0 * K + 8.0 + 4.0 * (1 + nd)) + state + tree
-    if name == "k_row_select":            # one read of the float32 logits; with the tail: selection and activations
+    if name == "k_row_select":
+        # without an LM: the chunk statistics (8 bytes per 32 columns) and about 2 K chunks of 128 bytes per row;
+        # with one: one read of the float32 logits and of the LM rows.  Then the tail: selection and activations
         Npad = (V + 255) // 256 * 256
-        return 4.0 * M * Npad + lm + M * (8.0 * K + 8.0 + 4.0 * (1 + nd)) + state + tree + M * H * (4.0 * (1 + c["ctx"]) + 2.0)
+        scan = 4.0 * M * Npad + lm if c["lm"] else M * (8.0 * Npad / 32 + 2 * K * 128.0)
+        return scan + M * (8.0 * K + 8.0 + 4.0 * (1 + nd)) + state + tree + M * H * (4.0 * (1 + c["ctx"]) + 2.0)
     if name == "k_stateless_pre":
         return M * H * (4.0 * (1 + c["ctx"]) + (2.0 if uses_materialized_path(c, M) else 4.0))
     if name == "k_joint_big":
         Npad, Hb = (V + 255) // 256 * 256, (H + 63) // 64 * 64
-        return 2.0 * Npad * Hb + 2.0 * M * Hb + 4.0 * M * Npad
+        return 2.0 * Npad * Hb + 2.0 * M * Hb + 4.0 * M * Npad + 8.0 * M * Npad / 32  # logits and chunk statistics out
     if name.startswith("k_gemm_tiled"):
         return 4.0 * (B * T * D + H * D + B * T * H)
     if name == "k_backtrace":
