@@ -228,6 +228,15 @@ struct SelectArgs {
   volatile int *h_done;  // pinned host word, set when every utterance has finished
 };
 
+// Where the selection finds the candidate lists of its utterance: the arrays of SelectArgs (rows indexed by
+// hypothesis), or arrays in LDS that hold the rows of this utterance only (row0 = its first hypothesis).
+struct CandView {
+  const uint64_t *cand;
+  const float *pmax, *psum, *zs;
+  int row0;
+};
+__device__ __forceinline__ CandView cand_view(const SelectArgs &a) { return CandView{a.p_cand, a.p_max, a.p_sum, a.zs, 0}; }
+
 __device__ __forceinline__ float logaddexp_f(float a, float b) {
   const float m = fmaxf(a, b), d = fminf(a, b) - m;  // d <= 0
   return d > -INFINITY ? m + log1pf(expf(d)) : m;
@@ -293,7 +302,7 @@ __device__ __forceinline__ uint32_t mod_mersenne31(uint64_t x) {
 // of list heads and its registers drop out.
 template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch,
           bool ONE = false>
-__device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
+__device__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
   const int nz = 1 + a.ND;
@@ -334,10 +343,11 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
     rk = r0 + lane / LPR;
     row_ok = rk < K;
     const int krow = row_ok ? rk : 0;
-    cands = a.p_cand + (size_t)(m_base + krow) * ncand;
-    pmax = a.p_max + (size_t)(m_base + krow) * a.n_chunks;
-    psum = a.p_sum + (size_t)(m_base + krow) * a.n_chunks;
-    const float *zsr = a.zs + (size_t)(m_base + krow) * nz;
+    const int crow = m_base - cv.row0 + krow;
+    cands = cv.cand + (size_t)crow * ncand;
+    pmax = cv.pmax + (size_t)crow * a.n_chunks;
+    psum = cv.psum + (size_t)crow * a.n_chunks;
+    const float *zsr = cv.zs + (size_t)crow * nz;
     // (every load is unconditional, from a clamped address, and what does not apply is replaced afterwards: a load
     // under a condition of its own costs a branch each)
     if constexpr (NCH > 0) {
@@ -887,34 +897,38 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s) {
 // whose hypotheses come with a single list; 2 = wider beams with many lists (several passes, many
 // registers).  The heavy forms are kept out of the kernels that do not need them.
 template <int FORMS, class Scratch = SelectScratch>
-__device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s) {
+__device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
   if constexpr (FORMS == 4) {  // one list per hypothesis (the materialised-logits path), any beam
-    if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true>(a, b, s);
-    else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true>(a, b, s);
-    else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true>(a, b, s);
-    else select_utterance<4, 1, 16, false, false, Scratch, true>(a, b, s);
+    if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true>(a, b, s, cv);
+    else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true>(a, b, s, cv);
+    else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true>(a, b, s, cv);
+    else select_utterance<4, 1, 16, false, false, Scratch, true>(a, b, s, cv);
   } else if constexpr (FORMS == 3) {  // TDT, every (symbol, duration) pair a candidate, beams up to 8
     if (a.K <= 4) {
-      if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4, false, true, Scratch>(a, b, s);
-      else select_utterance<16, 0, 4, false, true, Scratch>(a, b, s);
+      if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4, false, true, Scratch>(a, b, s, cv);
+      else select_utterance<16, 0, 4, false, true, Scratch>(a, b, s, cv);
     } else {
-      if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8, false, true, Scratch>(a, b, s);
-      else select_utterance<8, 0, 8, false, true, Scratch>(a, b, s);
+      if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8, false, true, Scratch>(a, b, s, cv);
+      else select_utterance<8, 0, 8, false, true, Scratch>(a, b, s, cv);
     }
   } else if constexpr (FORMS == 2) {
-    if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s);  // four hypotheses per pass
-    else select_utterance<4, 0, 16>(a, b, s);
+    if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s, cv);  // four hypotheses per pass
+    else select_utterance<4, 0, 16>(a, b, s, cv);
   } else {
     if (a.K <= 4) {
-      if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s);
-      else select_utterance<16, 0, 4>(a, b, s);
+      if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s, cv);
+      else select_utterance<16, 0, 4>(a, b, s, cv);
     } else if (a.K <= 8) {
-      if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s);
-      else select_utterance<8, 0, 8>(a, b, s);
+      if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8>(a, b, s, cv);
+      else select_utterance<8, 0, 8>(a, b, s, cv);
     } else if constexpr (FORMS == 1) {
-      select_utterance<4, 1, 16>(a, b, s);
+      select_utterance<4, 1, 16>(a, b, s, cv);
     }
   }
+}
+template <int FORMS, class Scratch = SelectScratch>
+__device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s) {
+  select_dispatch<FORMS, Scratch>(a, b, s, cand_view(a));
 }
 // which stand-alone selection kernel takes a beam of K with n_chunks lists per hypothesis
 __host__ __device__ inline bool select_needs_wide_forms(int K, int n_chunks) { return K > 8 && n_chunks > 4; }

@@ -572,4 +572,150 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
   }
 }
 
+// The row scan, the selection and the next activations of ONE utterance in one block: wave w takes hypothesis w of
+// the utterance (K <= 16 waves).  For keys without an LM term, from the chunk statistics of the contraction.  Nothing
+// is handed from block to block: the K lists, the soft-max statistics and the blank / duration logits stay in LDS, a
+// barrier replaces the write-through stores, their acknowledgement and the counter of the row-per-block form.
+// A wave finds its row's K best keys like a block of the row-per-block form does (threshold from the chunk maxima,
+// here the K-th largest of the lanes' maxima over four chunks each, which is a lower bound as well; keys at or above
+// it collected and ranked by counting).
+constexpr int kUttSurvivorCap = 128;
+
+__global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
+  __shared__ SelectScratch scratch;
+  __shared__ uint64_t l_cand[kMaxBeam * kMaxBeam];
+  __shared__ float l_max[kMaxBeam], l_sum[kMaxBeam], l_zs[kMaxBeam * 9];
+  __shared__ uint64_t surv[kMaxBeam][kUttSurvivorCap];
+  __shared__ uint16_t qchunk[kMaxBeam][256];
+  __shared__ int surv_n[kMaxBeam], q_n[kMaxBeam];
+  const int K = a.K, V = a.V;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;  // wave < K
+  if (*reinterpret_cast<const volatile int *>(a.done)) return;
+  const int b = blockIdx.x;
+  if (a.finished[b]) return;
+  const int m = b * K + wave;
+  const float *zrow = a.Z + (size_t)m * a.Npad;
+  const int n_stat = a.Npad >> 5;  // <= 256: four chunks per lane
+  const float kLog2e = 1.4426950408889634f;
+  float cm[4], cs[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int c = lane + 64 * q;
+    const uint64_t st = a.cstat[(size_t)m * n_stat + (c < n_stat ? c : 0)];
+    cm[q] = c < n_stat ? __uint_as_float((uint32_t)st) : -INFINITY;
+    cs[q] = c < n_stat ? __uint_as_float((uint32_t)(st >> 32)) : 0.f;
+  }
+  if (lane == 0) {
+    surv_n[wave] = 0;
+    q_n[wave] = 0;
+  }
+  const float lmx = fmaxf(fmaxf(cm[0], cm[1]), fmaxf(cm[2], cm[3]));
+  const float mx = wave_max(lmx);
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) sum += cm[q] > -INFINITY ? cs[q] * exp2f((cm[q] - mx) * kLog2e) : 0.f;
+  sum = wave_sum(sum);
+  float tau = -INFINITY, cur = lmx;
+  for (int j = 0; j < K; ++j) {
+    tau = wave_max(cur);
+    if (cur == tau) cur = -INFINITY;
+  }
+  wave_sync();
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (cm[q] >= tau && cm[q] > -INFINITY) qchunk[wave][atomicAdd(&q_n[wave], 1)] = (uint16_t)(lane + 64 * q);
+  wave_sync();
+  const int nq = q_n[wave];
+  for (int i = lane >> 3; i < nq; i += 8) {  // eight lanes read the 128 bytes of a chunk
+    const int n = 32 * (int)qchunk[wave][i] + 4 * (lane & 7);
+    const floatx4 z = *reinterpret_cast<const floatx4 *>(zrow + n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (z[e] >= tau && z[e] > -INFINITY) {
+        const int pos = atomicAdd(&surv_n[wave], 1);
+        if (pos < kUttSurvivorCap) surv[wave][pos] = pack_cand(z[e], n + e);
+      }
+  }
+  wave_sync();
+  const int total = surv_n[wave];
+  uint64_t *out = l_cand + wave * K;
+  if (total <= kUttSurvivorCap) {
+    if (lane < K && lane >= total) out[lane] = no_cand();
+    for (int i = lane; i < total; i += 64) {
+      const uint64_t mine = surv[wave][i];
+      int rank = 0;
+      for (int j = 0; j < total; ++j) rank += surv[wave][j] > mine;
+      if (rank < K) out[rank] = mine;
+    }
+  } else {
+    // more keys at or above tau than the list holds (many equal keys): K plain rounds over the row in memory
+    uint64_t last = ~0ull;
+    for (int j = 0; j < K; ++j) {
+      uint64_t best = no_cand();
+      for (int n = lane; n < V; n += 64) {
+        const float key = zrow[n];
+        const uint64_t c = key > -INFINITY ? pack_cand(key, n) : no_cand();
+        if (c < last && c > best) best = c;
+      }
+      best = wave_max_u64(best);
+      if (lane == 0) out[j] = best;
+      last = best > no_cand() ? best : no_cand() + 1;
+    }
+  }
+  if (lane == 0) {
+    l_max[wave] = mx;
+    l_sum[wave] = sum;
+  }
+  // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; a lane takes 8 k at a time
+  {
+    const int nz = 1 + a.ND;
+    float acc[9];
+#pragma unroll
+    for (int d = 0; d < 9; ++d) acc[d] = 0.f;
+    for (int g = lane; g < (a.H >> 3); g += 64) {
+      const uint4 u = *reinterpret_cast<const uint4 *>(a.Ab + ((size_t)g * a.Mp + m) * 8);
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+      float x[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int d = 0; d < 9; ++d)
+        if (d < nz) {
+          const float4 p = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g);
+          const float4 q = *reinterpret_cast<const float4 *>(a.Wspec + (size_t)d * a.H + 8 * g + 4);
+          acc[d] += (x[0] * p.x + x[1] * p.y) + (x[2] * p.z + x[3] * p.w) + (x[4] * q.x + x[5] * q.y) +
+                    (x[6] * q.z + x[7] * q.w);
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < 9; ++d)
+      if (d < nz) {
+        const float v = wave_sum(acc[d]);
+        if (lane == 0) l_zs[wave * nz + d] = v + a.bias_spec[d];
+      }
+  }
+  __syncthreads();
+  if (wave == 0) select_dispatch<4>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
+  __syncthreads();
+  // activations of the utterance's new hypotheses, from the selection's scratch (frame, token history)
+  const int T_b = a.pre.lengths[b];
+  const int H8 = a.pre.H >> 3;
+  const int nthr = 64 * K;
+  // (two items per thread and round, so that the loads of both are in flight together)
+  for (int it = tid; it < K * H8; it += 2 * nthr) {
+    const int it2 = it + nthr;
+    const bool two = it2 < K * H8;
+    const int j = it / H8, o8 = it % H8, j2 = two ? it2 / H8 : j, o82 = two ? it2 % H8 : o8;
+    int tt = scratch.n_t[j], tt2 = scratch.n_t[j2];
+    tt = tt < T_b ? tt : T_b - 1;
+    tt = tt < 0 ? 0 : tt;
+    tt2 = tt2 < T_b ? tt2 : T_b - 1;
+    tt2 = tt2 < 0 ? 0 : tt2;
+    stateless_pre_big_pair(a.pre, b * K + j, tt, scratch.ctx[j], o8, b * K + j2, tt2, scratch.ctx[j2], o82, b, two);
+  }
+}
+
 }  // namespace rb

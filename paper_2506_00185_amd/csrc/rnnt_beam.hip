@@ -626,7 +626,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       const dim3 grid(p.M), block(64 * kRowWaves);
       if (big_tail(h, p)) {
         if (a.lm) hipLaunchKernelGGL((k_row_select<true, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_row_select<true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL(k_utt_select, dim3(p.B), dim3(64 * p.K), 0, s, a);  // one block per utterance
       } else {
         if (a.lm) hipLaunchKernelGGL((k_row_select<false, false>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((k_row_select<false, true>), grid, block, 0, s, a);
