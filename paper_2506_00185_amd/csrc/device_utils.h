@@ -235,6 +235,14 @@ __device__ __forceinline__ float wave_sum(float v) {
   v = group_sum<16>(v);
   return (readlane_f(v, 0) + readlane_f(v, 16)) + (readlane_f(v, 32) + readlane_f(v, 48));
 }
+__device__ __forceinline__ int wave_sum_i(int v) {
+  v += dpp_i<kDppXor1>(v);
+  v += dpp_i<kDppXor2>(v);
+  v += dpp_i<kDppHalfMirror>(v);
+  v += dpp_i<kDppMirror>(v);
+  return (__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16)) +
+         (__builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48));
+}
 __device__ __forceinline__ void wave_best(float &v, int &i) {
   group_best<16>(v, i);
   float bv = readlane_f(v, 0);

@@ -288,6 +288,38 @@ __device__ __forceinline__ uint32_t mod_mersenne31(uint64_t x) {
   return (uint32_t)(y >= kHashMod ? y - kHashMod : y);
 }
 
+// Rank of the calling lane's candidate (value mv, index mf) among the cnt candidates in LDS: the number of those that
+// come before it.  Every lane reads all candidates (the same address in all lanes: broadcasts, many in flight), eight
+// at a time; the arrays hold eight entries beyond cnt that come before nothing.  First on the values alone (one
+// comparison per candidate): when no two finite values are equal, which the sum of the counts tells, that is the
+// rank; otherwise once more in the full order (value, then index).
+__device__ __forceinline__ int rank_by_counting(const double *keys, const int *flats, int cnt, double mv, int mf) {
+  int ge = 0;  // candidates not below mine, myself included
+  for (int c0 = 0; c0 < cnt; c0 += 8) {
+    double cv[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) cv[q] = keys[c0 + q];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) ge += (int)(cv[q] >= mv);
+  }
+  const bool finite = mv > -INFINITY;
+  const int F = __popcll(__ballot(finite));
+  if (wave_sum_i(finite ? ge : 0) == F * (F + 1) / 2) return ge - 1;
+  int rank = 0;
+  for (int c0 = 0; c0 < cnt; c0 += 8) {
+    double cv[8];
+    int cf[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      cv[q] = keys[c0 + q];
+      cf[q] = flats[c0 + q];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) rank += comes_before_count(cv[q], cf[q], mv, mf);
+  }
+  return rank;
+}
+
 // One beam-search step of utterance b by one wave: the K best tokens and blank of every
 // hypothesis (LPR lanes per hypothesis, all hypotheses at once), the Beam best of those,
 // expansion, tree write, recombination, end-of-utterance detection.
@@ -650,20 +682,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const C
       s.rc_flat[n + lane] = 0x7fffffff;
     }
     wave_sync();
-    for (int c0 = 0; c0 < n; c0 += 8) {
-      double cv[8];
-      int cf[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {  // eight requests in flight
-        cv[q] = rank_of[c0 + q];
-        cf[q] = s.rc_flat[c0 + q];
-      }
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-#pragma unroll
-        for (int o = 0; o < kOwn; ++o) rank[o] += comes_before_count(cv[q], cf[q], mv[o], mf[o]);
-      }
-    }
+    rank[0] = rank_by_counting(rank_of, s.rc_flat, n, mv[0], mf[0]);
 #pragma unroll
     for (int q = 0; q < kOwn; ++q)
       if (mv[q] > -INFINITY && rank[q] < K) {
@@ -719,18 +738,7 @@ __device__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const C
     wave_sync();
     const double mv = lane < nn ? s.st_key[lane] : -INFINITY;
     const int mf = lane < nn ? s.st_flat[lane] : 0x7fffffff;
-    int rank = 0;
-    for (int c0 = 0; c0 < nn; c0 += 8) {
-      double cv[8];
-      int cf[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {  // (the arrays have room beyond nn)
-        cv[q] = s.st_key[c0 + q];
-        cf[q] = s.st_flat[c0 + q];
-      }
-#pragma unroll
-      for (int q = 0; q < 8; ++q) rank += comes_before_count(cv[q], cf[q], mv, mf);
-    }
+    const int rank = rank_by_counting(s.st_key, s.st_flat, nn, mv, mf);
     if (mv > -INFINITY && rank < K) {
       s.sel_val[rank] = s.rc_val[s.st_src[lane]];
       s.sel_flat[rank] = mf;
