@@ -923,7 +923,9 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scra
     if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s, cv);  // four hypotheses per pass
     else select_utterance<4, 0, 16>(a, b, s, cv);
   } else {
-    if (a.K <= 4) {
+    if (a.K <= 2 && a.n_chunks <= 16 * 3) {  // (a form of its own: the lists are loaded and merged KMAX entries wide)
+      select_utterance<16, 3, 2>(a, b, s, cv);
+    } else if (a.K <= 4) {
       if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 4>(a, b, s, cv);
       else select_utterance<16, 0, 4>(a, b, s, cv);
     } else if (a.K <= 8) {
