@@ -1,7 +1,9 @@
 // Kernels for large (hypotheses x vocabulary) products with a bf16 joint: the joint's output
 // layer as a bf16 matrix-core contraction that writes float32 logits, and a row-wise exact
 // top-K over them.  A step of this mode is
-//   k_joint_big -> k_row_select (whose tail runs the selection and writes the next activations).
+//   k_joint_big -> k_utt_select (one block per utterance: row scan, selection, next activations), or, with an LM
+//   term in the keys, k_joint_big -> k_row_select (one block per hypothesis; the block that completes an utterance
+//   runs the selection and writes the next activations in its tail).
 // Keeping the per-row top-K in the contraction's epilogue, as the small-shape kernel does, costs
 // more vector instructions at K = 10 and V = 8192 than the trip of the logits through HBM.  The epilogue does
 // keep the maximum and the sum of exponentials of every (hypothesis, 32-column chunk), so that the row kernel
