@@ -396,6 +396,27 @@ def test_materialized_logits_path(amd, oracle, name, kw, lm_w):
     assert same >= c["B"] - exempt - 1
 
 
+@pytest.mark.parametrize("lm_w", [0.0, 0.3])
+def test_materialized_logits_path_with_every_duration_pair(amd, oracle, lm_w):
+    """The row kernel without a tail (chunk statistics, or the whole row when an LM term is in the keys), then the
+    selection over (symbol, duration) pairs and the activations in launches of their own."""
+    c = S.custom_config(B=4, T=14, T_min=5, D=64, H=160, P=96, E=96, V=700, beam=4, s=2, algo="alsd", model="tdt",
+                        durations=(0, 1, 2, 3, 4), pred="stateless", ctx=2, prec="bf16", blank_bias=3.0, tdt_pairs=True)
+    w, L, enc = _case(c, 1190)
+    glm = olm = None
+    if lm_w:
+        lm = S.make_lm(V=c["V"], order=3, n_target=20000, zipf_s=1.1, seed=7)
+        glm, olm = amd.NGramLM(lm), oracle.LM(lm)
+    dec = amd.BeamDecoder(c, w, joint_path="materialized")
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=lm_w)
+    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=lm_w, log=True)
+    full, exempt = compare(g, o, TOL_BF16, TIE_BF16)  # (the step-by-step walk knows the one-duration rule only)
+    assert full + exempt == 4 and full >= 2
+    gf = gpu_decode(amd.BeamDecoder(c, w, joint_path="fused"), enc, L, lm=glm, lm_weight=lm_w)
+    same = sum(int(np.array_equal(g["tokens"][b, 0], gf["tokens"][b, 0])) for b in range(4))
+    assert same >= 4 - exempt - 1
+
+
 def test_materialized_path_is_refused_where_it_cannot_run(amd):
     c = S.custom_config(B=2, T=8, T_min=4, D=64, H=64, P=64, E=64, V=50, beam=2, s=2, algo="alsd")
     w, L, enc = _case(c, 950)
