@@ -132,6 +132,8 @@ def measure(S, A, torch, cid: int, variant: str, steps: int, warmup: int, args, 
         c["algo"] = args.algo
         if args.algo == "alsd":
             c["gamma"] = float("inf")  # the prune margin belongs to AES++
+    if args.beam:
+        c["beam"] = args.beam
     w = S.make_weights(c)
     L = S.make_lengths(c)
     enc = S.make_enc(c, L)
@@ -275,6 +277,7 @@ def main():
     ap.add_argument("--lm-prune", default="late", choices=["late", "early"])
     ap.add_argument("--tdt-pairs", action="store_true", help="TDT workloads: every (symbol, duration) pair a candidate")
     ap.add_argument("--algo", default=None, choices=["alsd", "aes"], help="override the workload's search algorithm")
+    ap.add_argument("--beam", type=int, default=0, help="override the workload's beam (the paper's Tab. 2 uses 6)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-workloads", action="store_true", help="only the workload named by --config")
     ap.add_argument("--cpu-utts", type=int, default=16, help="utterances the oracle decodes for the CPU baseline")
