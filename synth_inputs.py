@@ -184,6 +184,8 @@ def make_lm(V: int, order: int, n_target: int, zipf_s: float, seed: int) -> dict
     Returns ``tokens`` [n, order] int32 (-1 padded on the right), ``order``
     [n] int8, ``log10_prob`` and ``log10_backoff`` [n] float32.
     """
+    if order > 1 and n_target > sum(V ** n for n in range(1, order + 1)):
+        raise ValueError(f"a vocabulary of {V} tokens has fewer than {n_target} n-grams of orders up to {order}")
     rng = np.random.default_rng(seed)
     ranks = np.arange(1, V + 1, dtype=np.float64)
     pz = ranks ** (-zipf_s)
@@ -206,6 +208,7 @@ def make_lm(V: int, order: int, n_target: int, zipf_s: float, seed: int) -> dict
     total = V
     batch = max(1024, n_target // 16)
     known = np.empty(0, np.int64)
+    idle = 0
     while total < n_target and order > 1:
         draw = rng.choice(V, size=(batch, order), p=pz).astype(np.int32)
         new_rows, new_keys, new_ords = [], [], []
@@ -227,6 +230,9 @@ def make_lm(V: int, order: int, n_target: int, zipf_s: float, seed: int) -> dict
         keys.append(k[sel])
         ords.append(o[sel])
         total += sel.size
+        idle = idle + 1 if sel.size == 0 else 0
+        if idle >= 200:  # (frequent tokens only: the rare n-grams that are left would take for ever to draw)
+            raise ValueError(f"{n_target} distinct n-grams not reached with {V} tokens (stuck at {total})")
     tokens = np.concatenate(rows)
     order_arr = np.concatenate(ords)
     key = np.concatenate(keys)

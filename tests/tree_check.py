@@ -111,6 +111,7 @@ def check_tree(oracle, c, w, enc_b, T_b, parent, token, merged, n_steps, nbest, 
     nbest: list of (transcript tuple, score) the library reported, best first.  Returns a dict with the number of
     steps verified and whether the walk stopped early at a duration near tie."""
     assert not c.get("tdt_pairs"), "the walk knows the one-duration rule only"
+    assert not c.get("aes_prefix"), "the walk ranks by the new scores: it does not know the prefix credit"
     K, V, s = parent.shape[1], c["V"], c["s"]
     algo, gamma = c["algo"], c["gamma"]
     m = UnitModel(oracle, c, w, enc_b, lm, lm_weight, lm_rule)
