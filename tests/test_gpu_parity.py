@@ -359,6 +359,28 @@ def test_tdt_pairs_with_the_networks(amd, oracle, algo, beam):
         amd.BeamDecoder(dict(c, model="rnnt", durations=()), S.make_weights(dict(c, model="rnnt", durations=()), 3))
 
 
+# ------------------------------------------- vocabularies that fill their last chunk
+
+@pytest.mark.parametrize("kw", [
+    dict(V=64, H=96, beam=4, B=9, algo="alsd"),                                           # 2 token chunks, 32 rows a tile
+    dict(V=128, H=192, beam=8, B=5, algo="aes", model="tdt", durations=(0, 1, 2, 3, 4), gamma=2.3),
+    dict(V=96, H=160, beam=3, B=7, algo="alsd", prec="bf16", model="tdt", durations=(0, 1, 2)),
+    dict(V=32, H=800, beam=2, B=3, algo="aes"),                                           # one token chunk, a wide joint
+    dict(V=160, H=128, beam=12, B=4, algo="alsd"),                                        # selection in a launch of its own
+])
+def test_blank_and_durations_alone_in_the_last_chunk(amd, oracle, kw):
+    """V % 32 == 0: blank and durations get no blocks of their own; the token-chunk blocks of a tile compute them for
+    one hypothesis each (or several, when the tile has more hypotheses than the vocabulary has chunks)."""
+    c = S.custom_config(T=16, T_min=5, D=64, P=96, E=64, s=3, blank_bias=3.0, **kw)
+    w, L, enc = _case(c, 1400 + kw["V"], zero_len=True)
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    tol, tie = (TOL_BF16, TIE_BF16 * 2) if c["prec"] == "bf16" else (TOL, TIE)
+    full, exempt = compare(g, o, tol, tie, walk=make_walk(oracle, c, w, enc, L, g, tol))
+    assert full + exempt == c["B"] and full >= c["B"] // 2
+
+
 # ------------------------------------------- logits through HBM (bf16 matrix-core joint)
 
 @pytest.mark.parametrize("name,kw,lm_w", [
