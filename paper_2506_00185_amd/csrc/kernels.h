@@ -334,7 +334,7 @@ __device__ __forceinline__ int rank_by_counting(const double *keys, const int *f
 // of list heads and its registers drop out.
 template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch,
           bool ONE = false>
-__device__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
+__device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   const int m_base = b * K;
   const int nz = 1 + a.ND;
