@@ -30,7 +30,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 LOOP_KERNELS = ("k_step_main", "k_select", "k_lstm_pointwise", "k_pred_proj", "k_lm_rows", "k_joint_big", "k_row_select",
-                "k_stateless_pre")
+                "k_utt_select", "k_stateless_pre")
 
 
 def gate_tiles_in_projection_launch(c: dict, M: int) -> int:
@@ -92,7 +92,7 @@ def kernel_bytes(name: str, c: dict, M: int, B: int, T: int, K: int, steps: int)
         return 2 * lm
     if name == "k_select":                # stand-alone selection from one list per hypothesis
         return M * (8.0 * K + 8.0 + 4.0 * (1 + nd)) + state + tree
-    if name == "k_row_select":
+    if name in ("k_row_select", "k_utt_select"):
         # without an LM: the chunk statistics (8 bytes per 32 columns) and about 2 K chunks of 128 bytes per row;
         # with one: one read of the float32 logits and of the LM rows.  Then the tail: selection and activations
         Npad = (V + 255) // 256 * 256

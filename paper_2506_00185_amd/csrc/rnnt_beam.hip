@@ -54,11 +54,11 @@ struct KernelTimer {
 
 enum {
   KT_ENCPROJ = 0, KT_INIT, KT_JOINT, KT_SELECT, KT_LM, KT_LSTM, KT_PREDPROJ, KT_BACKTRACE, KT_JOINTBIG, KT_ROWSELECT,
-  KT_STATELESS, KT_COUNT
+  KT_STATELESS, KT_UTTSELECT, KT_COUNT
 };
 const char *kKernelNames[KT_COUNT] = {"k_gemm_tiled(enc_proj)", "k_init",      "k_step_main", "k_select",    "k_lm_rows",
                                       "k_lstm_pointwise",    "k_pred_proj", "k_backtrace", "k_joint_big", "k_row_select",
-                                      "k_stateless_pre"};
+                                      "k_stateless_pre",     "k_utt_select"};
 
 // Device memory a decode works in beyond its inputs and outputs, laid out for given maxima.  The handle owns one
 // (a single allocation made at create); the allocation-free entry point lays one out in the static array.
@@ -621,7 +621,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       a.utt_ctr = w.tile_ctr;
       fill_select_args(h, p, step_off, 1, a.sel);
       fill_stateless_pre_big(h, p, 0, a.pre);
-      ScopedKernelTime tm(h, s, KT_ROWSELECT);
+      ScopedKernelTime tm(h, s, (big_tail(h, p) && !a.lm) ? KT_UTTSELECT : KT_ROWSELECT);
       // without an LM term in the keys the chunk statistics of the contraction say which chunks to read
       const dim3 grid(p.M), block(64 * kRowWaves);
       if (big_tail(h, p)) {
