@@ -19,6 +19,11 @@ from gpu_common import compare, gpu_decode, gpu_decode_injected, make_walk, to_g
 pytestmark = pytest.mark.gpu
 
 TOL, TIE = 1e-3, 1e-4
+# bf16-joint variant (the workloads name the precision, the paper does not): operands rounded to bfloat16 on one side
+# in float32, on the other in float64; a rounding boundary crossed on one side only moves a logit by ~5e-4 at H = 640.
+# Near-tie bar 5e-3 (every divergence measured at full size sat below it).  Score tolerance 2e-2: the bf16 matrix
+# instructions add 16 k per step in an order of their own, and one utterance of workload c2 then ended 1.13e-2 from the
+# oracle after 680 steps (1e-2, the value before those instructions were used, failed on it).
 TOL_BF16, TIE_BF16 = 2e-2, 5e-3
 
 
