@@ -243,8 +243,9 @@ __device__ __forceinline__ float logaddexp_f(float a, float b) {
 }
 
 // LDS scratch of one wave while it handles one utterance
-template <int CAND>
+template <int CAND, int STAIR = 64>
 struct SelectScratchT {
+  static constexpr int kStair = STAIR;  // candidates the staircase form of the ranking can hold (64 per lane pass)
   double score[kMaxBeam];
   double rc_val[CAND];
   double rc_key[CAND];  // early pruning only: what the candidates are ranked by
@@ -259,13 +260,15 @@ struct SelectScratchT {
   int sel_flat[kMaxBeam];
   // staircase form of the ranking (beams 8 .. 10): per hypothesis the place of blank in its sorted list, its head,
   // the order of the lists by their heads; then the K (K + 1) / 2 candidates that can still be among the Beam best
-  double head_val[kMaxBeam], st_key[64 + 8];
-  int head_flat[kMaxBeam], pos_blank[kMaxBeam], ord[kMaxBeam], st_flat[64 + 8], st_src[64];
+  double head_val[kMaxBeam], st_key[STAIR + 8];
+  int head_flat[kMaxBeam], pos_blank[kMaxBeam], ord[kMaxBeam], st_flat[STAIR + 8], st_src[STAIR];
   int n_t[kMaxBeam], n_sym[kMaxBeam], n_len[kMaxBeam], n_last[kMaxBeam], n_live[kMaxBeam];
   uint32_t n_hash[kMaxBeam];
 };
 // K (K + 1) candidates per utterance: K tokens and blank / stay of every hypothesis
 typedef SelectScratchT<kMaxBeam * (kMaxBeam + 1)> SelectScratch;
+// the same with room for the staircase of beams up to 16 (16 * 17 / 2 = 136 candidates, three per lane)
+typedef SelectScratchT<kMaxBeam * (kMaxBeam + 1), 192> SelectScratchWide;
 // TDT with every (symbol, duration) pair as a candidate: K (K + 1) ND of them, for beams up to 8
 constexpr int kPairsMaxBeam = 8;
 typedef SelectScratchT<kPairsMaxBeam * (kPairsMaxBeam + 1) * 8> SelectScratchPairs;
@@ -318,6 +321,51 @@ __device__ __forceinline__ int rank_by_counting(const double *keys, const int *f
     for (int q = 0; q < 8; ++q) rank += comes_before_count(cv[q], cf[q], mv, mf);
   }
   return rank;
+}
+
+// The same for OWN candidates per lane (lane, lane + 64, ..): one pass over the candidates serves them all.
+template <int OWN>
+__device__ __forceinline__ void rank_by_counting_n(const double *keys, const int *flats, int cnt, const double (&mv)[OWN],
+                                                   const int (&mf)[OWN], int (&rank)[OWN]) {
+  int ge[OWN];
+#pragma unroll
+  for (int o = 0; o < OWN; ++o) ge[o] = 0;
+  for (int c0 = 0; c0 < cnt; c0 += 8) {
+    double cv[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) cv[q] = keys[c0 + q];
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+      for (int o = 0; o < OWN; ++o) ge[o] += (int)(cv[q] >= mv[o]);
+  }
+  int F = 0, tot = 0;
+#pragma unroll
+  for (int o = 0; o < OWN; ++o) {
+    const bool finite = mv[o] > -INFINITY;
+    F += __popcll(__ballot(finite));
+    tot += finite ? ge[o] : 0;
+  }
+  if (wave_sum_i(tot) == F * (F + 1) / 2) {
+#pragma unroll
+    for (int o = 0; o < OWN; ++o) rank[o] = ge[o] - 1;
+    return;
+  }
+#pragma unroll
+  for (int o = 0; o < OWN; ++o) rank[o] = 0;
+  for (int c0 = 0; c0 < cnt; c0 += 8) {
+    double cv[8];
+    int cf[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      cv[q] = keys[c0 + q];
+      cf[q] = flats[c0 + q];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+      for (int o = 0; o < OWN; ++o) rank[o] += comes_before_count(cv[q], cf[q], mv[o], mf[o]);
+  }
 }
 
 // One beam-search step of utterance b by one wave: the K best tokens and blank of every
@@ -689,12 +737,12 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
         s.sel_val[rank[q]] = s.rc_val[lane + 64 * q];
         s.sel_flat[rank[q]] = mf[q];
       }
-  } else if (!PAIRS && KMAX > 7 && K * (K + 1) / 2 <= 64) {
-    // More than 64 candidates, beams up to 10.  The candidates of one hypothesis are a sorted list: its tokens come
+  } else if (!PAIRS && KMAX > 7 && K * (K + 1) / 2 <= Scratch::kStair) {
+    // More than 64 candidates.  The candidates of one hypothesis are a sorted list: its tokens come
     // best first (the ranking value grows with the key) and blank / stay has its place among them.  With the lists
     // ordered by their heads, the entry at place p of the list of order o has at least p + o candidates ahead of it,
     // so only the K (K + 1) / 2 entries with p + o < K can be among the Beam best, and an entry's rank among those
-    // is its rank among all whenever that is below K.  They fit one per lane, and the counting form applies.
+    // is its rank among all whenever that is below K.  One to three per lane, and the counting form applies.
     if (lane < K) {
       const int base = lane * (K + 1);
       const double bv = rank_of[base + K];
@@ -736,13 +784,26 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
       s.st_flat[nn + lane] = 0x7fffffff;
     }
     wave_sync();
-    const double mv = lane < nn ? s.st_key[lane] : -INFINITY;
-    const int mf = lane < nn ? s.st_flat[lane] : 0x7fffffff;
-    const int rank = rank_by_counting(s.st_key, s.st_flat, nn, mv, mf);
-    if (mv > -INFINITY && rank < K) {
-      s.sel_val[rank] = s.rc_val[s.st_src[lane]];
-      s.sel_flat[rank] = mf;
+    // (candidates a lane owns: as many as the form's widest beam needs and the scratch holds)
+    constexpr int kNeed = (KMAX * (KMAX + 1) / 2 + 63) / 64, kHave = Scratch::kStair / 64;
+    constexpr int OWN = kNeed < kHave ? kNeed : kHave;
+    double mv[OWN];
+    int mf[OWN], rank[OWN];
+#pragma unroll
+    for (int o = 0; o < OWN; ++o) {
+      const int slot = lane + 64 * o;
+      mv[o] = slot < nn ? s.st_key[slot] : -INFINITY;
+      mf[o] = slot < nn ? s.st_flat[slot] : 0x7fffffff;
+      rank[o] = K;
     }
+    if (OWN == 1 || nn <= 64) rank[0] = rank_by_counting(s.st_key, s.st_flat, nn, mv[0], mf[0]);
+    else rank_by_counting_n<OWN>(s.st_key, s.st_flat, nn, mv, mf, rank);
+#pragma unroll
+    for (int o = 0; o < OWN; ++o)
+      if (mv[o] > -INFINITY && rank[o] < K) {
+        s.sel_val[rank[o]] = s.rc_val[s.st_src[lane + 64 * o]];
+        s.sel_flat[rank[o]] = mf[o];
+      }
   } else {
     double last_v = INFINITY;
     int last_i = -1;
@@ -1192,11 +1253,11 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
 
 // stand-alone selection kernels: one wave per utterance, four utterances per block
 __global__ __launch_bounds__(256) void k_select(SelectArgs a) {
-  __shared__ SelectScratch scratch[4];
+  __shared__ SelectScratchWide scratch[4];
   if (*reinterpret_cast<volatile int *>(a.done)) return;
   const int wave = threadIdx.x >> 6;
   const int b = blockIdx.x * 4 + wave;
-  if (b < a.B) select_dispatch<1>(a, b, scratch[wave]);
+  if (b < a.B) select_dispatch<1, SelectScratchWide>(a, b, scratch[wave]);
 }
 // two utterances per block: the candidate arrays of this form are larger
 __global__ __launch_bounds__(128) void k_select_pairs(SelectArgs a) {
@@ -1207,11 +1268,11 @@ __global__ __launch_bounds__(128) void k_select_pairs(SelectArgs a) {
   if (b < a.B) select_dispatch<3, SelectScratchPairs>(a, b, scratch[wave]);
 }
 __global__ __launch_bounds__(256) void k_select_wide(SelectArgs a) {
-  __shared__ SelectScratch scratch[4];
+  __shared__ SelectScratchWide scratch[4];
   if (*reinterpret_cast<volatile int *>(a.done)) return;
   const int wave = threadIdx.x >> 6;
   const int b = blockIdx.x * 4 + wave;
-  if (b < a.B) select_dispatch<2>(a, b, scratch[wave]);
+  if (b < a.B) select_dispatch<2, SelectScratchWide>(a, b, scratch[wave]);
 }
 
 // ---------------------------------------------------------------------------

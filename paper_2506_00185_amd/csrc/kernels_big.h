@@ -541,7 +541,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
     // acknowledged, then the barrier, then one thread counts the row in: the count cannot become visible before
     // anything of the row.  The block that brings the utterance's count to K owns the rest of its step.
     __shared__ int s_is_last;
-    __shared__ SelectScratch scratch;
+    __shared__ SelectScratchWide scratch;
     const int b = m / K;
     wait_stores_acknowledged();
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -554,7 +554,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
     }
     __syncthreads();
     if (!s_is_last) return;
-    if (wave == 0) select_dispatch<4>(a.sel, b, scratch);  // (reads the lists with device-coherent loads)
+    if (wave == 0) select_dispatch<4, SelectScratchWide>(a.sel, b, scratch);  // (reads the lists with device-coherent loads)
     __syncthreads();
     // activations of the utterance's new hypotheses, from the selection's scratch (frame, token history)
     const int T_b = a.pre.lengths[b];
@@ -584,7 +584,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
 constexpr int kUttSurvivorCap = 128;
 
 __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
-  __shared__ SelectScratch scratch;
+  __shared__ SelectScratchWide scratch;
   __shared__ uint64_t l_cand[kMaxBeam * kMaxBeam];
   __shared__ float l_max[kMaxBeam], l_sum[kMaxBeam], l_zs[kMaxBeam * 9];
   __shared__ uint64_t surv[kMaxBeam][kUttSurvivorCap];
@@ -700,7 +700,7 @@ __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
       }
   }
   __syncthreads();
-  if (wave == 0) select_dispatch<4>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
+  if (wave == 0) select_dispatch<4, SelectScratchWide>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
   __syncthreads();
   // activations of the utterance's new hypotheses, from the selection's scratch (frame, token history)
   const int T_b = a.pre.lengths[b];
