@@ -217,6 +217,20 @@ __device__ __forceinline__ uint64_t group_max_u64(uint64_t v) {
   if constexpr (LANES >= 16) v = max_step<kDppMirror>(v);
   return v;
 }
+// wave-wide max of packed candidates, in every lane
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+  v = group_max_u64<16>(v);
+  uint64_t best = 0;
+#pragma unroll
+  for (int r = 0; r < 64; r += 16) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, r);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), r);
+    const uint64_t w = ((uint64_t)hi << 32) | lo;
+    best = w > best ? w : best;
+  }
+  return best;
+}
+
 template <int LANES>
 __device__ __forceinline__ int group_min_i(int v) {
   v = min(v, dpp_i<kDppXor1>(v));

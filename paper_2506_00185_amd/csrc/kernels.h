@@ -1275,6 +1275,128 @@ __global__ __launch_bounds__(256) void k_select_wide(SelectArgs a) {
   if (b < a.B) select_dispatch<2, SelectScratchWide>(a, b, scratch[wave]);
 }
 
+// Beams too wide for the in-kernel forms (9 to 16) on the fused path, where the selection has a launch of its own:
+// one block per utterance, a wave per hypothesis.  A wave first reduces its hypothesis' n_lists chunk lists to the K
+// best keys: the K-th largest of the lists' heads is a lower bound of the K-th largest key, the entries at or above
+// it (the first few of a few lists) are collected in LDS and ranked by counting; the chunks' soft-max statistics are
+// combined into one pair.  Wave 0 then runs the selection on those one-list rows in LDS (the forms of the
+// materialised-logits path).  Against a single wave that merges K x n_lists entries per hypothesis in registers, in
+// several passes: 27 -> about 10 us at beam 12.
+struct MergeSelectArgs {
+  SelectArgs sel;  // n_chunks = 1: what the selection proper sees
+  int n_lists;     // chunk lists per hypothesis in the global arrays (at most 64 * kMergeHeads)
+};
+constexpr int kMergeHeads = 8, kMergeCap = 128;
+
+__global__ __launch_bounds__(64 * kMaxBeam) void k_utt_merge_select(MergeSelectArgs a) {
+  __shared__ SelectScratchWide scratch;
+  __shared__ uint64_t l_cand[kMaxBeam * kMaxBeam];
+  __shared__ float l_max[kMaxBeam], l_sum[kMaxBeam], l_zs[kMaxBeam * 9];
+  __shared__ uint64_t surv[kMaxBeam][kMergeCap];
+  __shared__ int surv_n[kMaxBeam];
+  if (*reinterpret_cast<volatile int *>(a.sel.done)) return;
+  const int K = a.sel.K, nl = a.n_lists, nz = 1 + a.sel.ND;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, b = blockIdx.x;  // wave < K
+  const int m = b * K + wave;
+  const uint64_t *cands = a.sel.p_cand + (size_t)m * K * nl;  // [K][n_lists]
+  uint64_t head[kMergeHeads];
+  float pm[kMergeHeads], ps[kMergeHeads];
+#pragma unroll
+  for (int q = 0; q < kMergeHeads; ++q) {
+    const int c = lane + 64 * q;
+    const bool ok = c < nl;
+    const uint64_t x = cands[ok ? c : 0];
+    const float xm = a.sel.p_max[(size_t)m * nl + (ok ? c : 0)], xs = a.sel.p_sum[(size_t)m * nl + (ok ? c : 0)];
+    head[q] = ok ? x : no_cand();
+    pm[q] = (ok && !a.sel.normalized) ? xm : -INFINITY;
+    ps[q] = (ok && !a.sel.normalized) ? xs : 0.f;
+  }
+  if (lane == 0) surv_n[wave] = 0;
+  if (lane < nz) l_zs[wave * nz + lane] = a.sel.zs[(size_t)m * nz + lane];
+  // soft-max statistics of the row: the largest chunk maximum, the chunks' sums brought to it
+  float mx = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < kMergeHeads; ++q) mx = fmaxf(mx, pm[q]);
+  mx = wave_max(mx);
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < kMergeHeads; ++q)
+    if (pm[q] > -INFINITY) sum += ps[q] * __expf(pm[q] - mx);
+  sum = wave_sum(sum);
+  if (lane == 0) {
+    l_max[wave] = mx;
+    l_sum[wave] = sum;
+  }
+  // tau: the K-th largest head (packed keys are distinct).  Up to kMergeCap lists: every head counts the heads above
+  // it (the heads wait in the survivors' buffer meanwhile), the one with K - 1 above it is tau; more lists: K rounds
+  // of "largest remaining head"
+  uint64_t tau = no_cand();
+  if (nl <= kMergeCap) {
+    __shared__ uint64_t s_tau[kMaxBeam];
+    if (lane == 0) s_tau[wave] = no_cand();
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      if (lane + 64 * q < nl) surv[wave][lane + 64 * q] = head[q];
+    wave_sync();
+    int above[2] = {0, 0};
+    for (int c = 0; c < nl; ++c) {
+      const uint64_t x = surv[wave][c];
+      above[0] += (int)(x > head[0]);
+      above[1] += (int)(x > head[1]);
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      if (lane + 64 * q < nl && above[q] == K - 1 && head[q] > no_cand()) s_tau[wave] = head[q];
+    wave_sync();
+    tau = s_tau[wave];
+  } else {
+    for (int j = 0; j < K; ++j) {
+      uint64_t best = head[0];
+#pragma unroll
+      for (int q = 1; q < kMergeHeads; ++q) best = head[q] > best ? head[q] : best;
+      tau = wave_max_u64(best);
+#pragma unroll
+      for (int q = 0; q < kMergeHeads; ++q)
+        if (head[q] == tau) head[q] = no_cand();
+    }
+  }
+  wave_sync();
+  // entries at or above tau (never "no candidate"): every list holds them at its front
+  for (int e = lane; e < K * nl; e += 64) {
+    const uint64_t x = cands[e];
+    if (x >= tau && x > no_cand()) {
+      const int pos = atomicAdd(&surv_n[wave], 1);
+      if (pos < kMergeCap) surv[wave][pos] = x;
+    }
+  }
+  wave_sync();
+  const int total = surv_n[wave];
+  uint64_t *out = l_cand + wave * K;
+  if (total <= kMergeCap) {
+    if (lane < K && lane >= total) out[lane] = no_cand();
+    for (int i = lane; i < total; i += 64) {
+      const uint64_t mine = surv[wave][i];
+      int rank = 0;
+      for (int q = 0; q < total; ++q) rank += surv[wave][q] > mine;
+      if (rank < K) out[rank] = mine;
+    }
+  } else {  // (many equal keys) K plain rounds over all entries
+    uint64_t last = ~0ull;
+    for (int j = 0; j < K; ++j) {
+      uint64_t best = no_cand();
+      for (int c = lane; c < K * nl; c += 64) {
+        const uint64_t x = cands[c];
+        if (x < last && x > best) best = x;
+      }
+      best = wave_max_u64(best);
+      if (lane == 0) out[j] = best;
+      last = best > no_cand() ? best : no_cand() + 1;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) select_dispatch<4, SelectScratchWide>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
+}
+
 // ---------------------------------------------------------------------------
 // LSTM cell for every slot: gates = G[token] + W_hh h_parent (G = emb W_ih^T + b_ih + b_hh
 // folded at create), rows packed so that a lane holds the four gates of a unit.

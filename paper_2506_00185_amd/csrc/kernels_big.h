@@ -299,20 +299,6 @@ __global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a
   stateless_pre_big_item(a, m, b, tt, a.ctx_tok + m * kCtxMax, o8);
 }
 
-// wave-wide max of packed candidates, in every lane
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-  v = group_max_u64<16>(v);
-  uint64_t best = 0;
-#pragma unroll
-  for (int r = 0; r < 64; r += 16) {
-    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, r);
-    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), r);
-    const uint64_t w = ((uint64_t)hi << 32) | lo;
-    best = w > best ? w : best;
-  }
-  return best;
-}
-
 struct RowSelectArgs {
   const float *Z;        // [M][Npad]
   const uint64_t *cstat; // [M][Npad / 32] chunk statistics written with the logits (see BigJointArgs)

@@ -557,7 +557,13 @@ void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunk
 // stand-alone selection: which kernel takes this beam, list count and candidate rule
 void launch_select(rnnt_beam *h, hipStream_t s, const StepPlan &p, const SelectArgs &sa, int n_chunks) {
   if (h->cfg.tdt_all_pairs) hipLaunchKernelGGL(k_select_pairs, dim3((p.B + 1) / 2), dim3(128), 0, s, sa);
-  else if (select_needs_wide_forms(p.K, n_chunks)) hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
+  else if (select_needs_wide_forms(p.K, n_chunks) && n_chunks <= 64 * kMergeHeads) {
+    MergeSelectArgs ma;  // a block per utterance, a wave per hypothesis: lists merged first, then the one-list selection
+    ma.sel = sa;
+    ma.sel.n_chunks = 1;
+    ma.n_lists = n_chunks;
+    hipLaunchKernelGGL(k_utt_merge_select, dim3(p.B), dim3(64 * p.K), 0, s, ma);
+  } else if (select_needs_wide_forms(p.K, n_chunks)) hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
   else hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
 }
 
