@@ -38,7 +38,7 @@ def gate_tiles_in_projection_launch(c: dict, M: int) -> int:
     launch): the library's rule, restated here to count each launch's FLOPs."""
     from paper_2506_00185_amd.binding import block_map
     m_tiles = (M + 31) // 32
-    if c["P"] % 128 == 0 and M >= 8 and (c["H"] // 32) * m_tiles * 2 <= 256:
+    if c["P"] % 128 == 0 and M >= 8 and (c["H"] // 32) * m_tiles * 2 <= 200:
         return 0  # projection split in two along k, all gate tiles in the main launch
     for b_end in range(4 * c["P"] // 32, 0, -1):
         if block_map(c["H"] // 32, m_tiles, 0, b_end, m_tiles)[0] <= 256:

@@ -224,9 +224,10 @@ int beam_template(int K) { return K <= 4 ? 4 : (K <= 8 ? 8 : 16); }
 // The projection of the prediction step split in two along k (k_pred_proj_half): taken when whole tiles would leave
 // half of the compute units idle.  Needs P % 128 == 0 (each half of k is divided among 8 waves in steps of 8).
 // (With fewer than 8 hypotheses the main launch is so short that the recurrent tiles moved into it would set its
-// duration: 508 instead of 739 audio-s/s at batch 1, beam 1.)
+// duration: 508 instead of 739 audio-s/s at batch 1, beam 1.  Up to 200 half tiles: at 240 (B * beam = 192) whole tiles
+// with gate tiles beside them are as fast or faster: 22.1 vs 23.2 ms at batch 48, beam 4.)
 bool proj_split(const rnnt_config_t &c, int M) {
-  return c.P % 128 == 0 && M >= 8 && (c.H / 32) * ((M + 31) / 32) * 2 <= 256;
+  return c.P % 128 == 0 && M >= 8 && (c.H / 32) * ((M + 31) / 32) * 2 <= 200;
 }
 
 // Gate tiles of the recurrent product computed in the prediction-projection launch (the rest ride in the
