@@ -83,11 +83,14 @@ def kernel_bytes(name: str, c: dict, M: int, B: int, T: int, K: int, steps: int)
         lists = M * n_chunks * (8.0 * K + 8.0)
         rec = (4.0 * 4 * P * P + 4.0 * M * P + 4.0 * M * 4 * P) * (1.0 - in_proj) if lstm else 0.0
         return 4.0 * n_chunks * 32 * H + 4.0 * M * H + 2 * lists + rec + lm + state + tree
-    if name == "k_lstm_pointwise":        # R, G rows, c in / out, h out; LM rows: unigram row read, row written
-        return M * P * (16.0 + 16.0 + 4.0 + 4.0 + 4.0) + 2 * lm
+    # LM rows (unigram row read, row written) ride in the projection launch while a row is at most 16 KiB, else in the
+    # cell-update launch
+    lm_in_proj = 4.0 * V <= 16 * 1024
+    if name == "k_lstm_pointwise":        # R, G rows, c in / out, h out
+        return M * P * (16.0 + 16.0 + 4.0 + 4.0 + 4.0) + (0.0 if lm_in_proj else 2 * lm)
     if name == "k_pred_proj":
         rec = (4.0 * 4 * P * P + 4.0 * M * P + 4.0 * M * 4 * P) * in_proj if lstm else 0.0
-        return 4.0 * H * P + 4.0 * M * P + 4.0 * M * H + 4.0 * M * H + rec
+        return 4.0 * H * P + 4.0 * M * P + 4.0 * M * H + 4.0 * M * H + rec + (2 * lm if lm_in_proj else 0.0)
     if name == "k_lm_rows":
         return 2 * lm
     if name == "k_select":                # stand-alone selection from one list per hypothesis

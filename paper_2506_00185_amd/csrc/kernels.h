@@ -1451,7 +1451,7 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
                                                         const int *done, LmRowsArgs lmr, float *pre_clear,
                                                         int n_pre_clear) {
   if (lmr.M > 0 && (int)blockIdx.x >= lmr.first_block) {
-    // the LM scores of the new hypotheses depend on the selection only, like the cell update: same launch
+    // (vocabularies whose row would take the projection launch's LDS: the rows ride here instead)
     extern __shared__ float lm_row[];
     __shared__ LmRowScratch lm_sc;
     if (*reinterpret_cast<const volatile int *>(done)) return;
@@ -1479,7 +1479,20 @@ struct PredProjArgs {
   int bump;
   RecurrentArgs rec;   // recurrent tiles of the new state ride along
   XcdMap map;          // role 0 = projection (tile of H, 32-row tile), role 1 = recurrent
+  LmRowsArgs lmr;      // blocks from lmr.first_block on build LM rows (lmr.M = 0: none)
 };
+
+// The LM rows of the new hypotheses depend on the selection only, and the next selection is the first to read them:
+// their blocks (a chain of memory round trips with next to no arithmetic) share the compute units with the tiles of
+// the projection.  Dynamic LDS of the launch: V floats.
+__device__ __forceinline__ bool pred_proj_lm_block(const PredProjArgs &a) {
+  if (a.lmr.M == 0 || (int)blockIdx.x < a.lmr.first_block) return false;
+  extern __shared__ float lm_row[];
+  __shared__ LmRowScratch lm_sc;
+  if (!*reinterpret_cast<const volatile int *>(a.done))
+    lm_row_block(a.lmr.view, a.lmr.ctx, a.lmr.len, a.lmr.out, (int)blockIdx.x - a.lmr.first_block, lm_row, lm_sc);
+  return true;
+}
 
 // One tile of the projection: 32 outputs of H (tile) x the slots [m0, m0 + 32).
 template <int WAVES, int ITERS>
@@ -1526,6 +1539,7 @@ __device__ __forceinline__ void pred_proj_tile(const PredProjArgs &a, int tile, 
 template <int WAVES, int ITERS>
 __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   __shared__ float red[WAVES * 64 * kRedStride];
+  if (pred_proj_lm_block(a)) return;
   int tile, mtile;
   const int role = xcd_item(a.map, blockIdx.x, tile, mtile);
   if (role < 0) return;
@@ -1549,6 +1563,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
   __shared__ float red[WAVES * 64 * kRedStride];
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
+  if (pred_proj_lm_block(a)) return;
   int tile, item;
   if (xcd_item(a.map, blockIdx.x, tile, item) != 0) return;
   const int mtile = item >> 1, half = item & 1;

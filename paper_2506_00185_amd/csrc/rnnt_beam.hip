@@ -441,8 +441,10 @@ void fill_stateless_pre_big(rnnt_beam *h, const StepPlan &p, int bump, Stateless
   a.done = w.ctrl + 1; a.step_base = w.ctrl + 2; a.bump = bump;
 }
 
-// fuse_lm: the LM rows of the new hypotheses ride in the cell-update launch (LSTM models only; the caller
-// then skips the stand-alone LM launch)
+// fuse_lm: the LM rows of the new hypotheses ride in the projection launch, or in the cell-update launch when
+// the row is too large to sit in LDS beside the projection's tiles (LSTM models only; the caller then skips the
+// stand-alone LM launch)
+constexpr size_t kLmRowBesideTiles = 16 * 1024;
 int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bump, bool fuse_lm = false) {
   const Workspace &w = *p.ws;
   const rnnt_config_t &c = h->cfg;
@@ -451,17 +453,22 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
   if (p.inj_tok) {
     if (bump) hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done);
   } else if (c.pred == RNNT_PRED_LSTM) {
+    LmRowsArgs lm_rows{};
+    const size_t lm_row_bytes = sizeof(float) * (size_t)c.V;
+    if (fuse_lm && p.lm) {
+      lm_rows.view = lm_view(p.lm);
+      lm_rows.ctx = w.ctx; lm_rows.len = w.len; lm_rows.out = w.lm_rows;
+      lm_rows.M = p.M;
+    }
     {
       ScopedKernelTime tm(h, s, KT_LSTM);
       const int n = p.M * c.P, n_blocks = (n + 255) / 256;
       LmRowsArgs lmr{};
       size_t lds = 0;
-      if (fuse_lm && p.lm) {
-        lmr.view = lm_view(p.lm);
-        lmr.ctx = w.ctx; lmr.len = w.len; lmr.out = w.lm_rows;
-        lmr.M = p.M;
+      if (lm_rows.M && lm_row_bytes > kLmRowBesideTiles) {
+        lmr = lm_rows;
         lmr.first_block = n_blocks;
-        lds = sizeof(float) * (size_t)c.V;
+        lds = lm_row_bytes;
       }
       const bool split = proj_split(c, p.M);
       hipLaunchKernelGGL(k_lstm_pointwise, dim3(n_blocks + lmr.M), dim3(256), lds, s, w.Rgates, h->G, w.h[cur],
@@ -485,11 +492,19 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
         a.map.a_m = 2 * m_tiles;
         a.map.b_end = 0;
       }
-      const dim3 grid(xcd_grid(a.map));
-#define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), 0, s, a)
+      const int n_tiles = xcd_grid(a.map);
+      a.lmr = LmRowsArgs{};
+      size_t lds = 0;
+      if (lm_rows.M && lm_row_bytes <= kLmRowBesideTiles) {
+        a.lmr = lm_rows;
+        a.lmr.first_block = n_tiles;
+        lds = lm_row_bytes;
+      }
+      const dim3 grid(n_tiles + a.lmr.M);
+#define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), lds, s, a)
       if (proj_split(c, p.M)) {
-        if (c.P == 640) hipLaunchKernelGGL((k_pred_proj_half<8, 5>), grid, dim3(512), 0, s, a);
-        else hipLaunchKernelGGL((k_pred_proj_half<8, 0>), grid, dim3(512), 0, s, a);
+        if (c.P == 640) hipLaunchKernelGGL((k_pred_proj_half<8, 5>), grid, dim3(512), lds, s, a);
+        else hipLaunchKernelGGL((k_pred_proj_half<8, 0>), grid, dim3(512), lds, s, a);
       }
       else if (c.P == 640) RB_PRED(8, 10);
       else if (c.P % 64 == 0) RB_PRED(8, 0);

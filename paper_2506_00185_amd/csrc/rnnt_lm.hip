@@ -6,7 +6,8 @@
 //     a stored n-gram of order < max order, is a "context" with a back-off
 //     weight and a list of successors (token, log10 p);
 //   * contexts are found through an open-addressing hash table keyed by the
-//     exact packed token sequence (no false positives);
+//     exact packed token sequence (no false positives), whose 32-byte slots
+//     hold the context's back-off weight and successor range beside the key;
 //   * a query fills a vocabulary-sized row in LDS with the unigram scores plus
 //     all back-off weights, then overwrites it level by level with the stored
 //     successors of longer and longer contexts.
@@ -25,10 +26,7 @@ struct rnnt_lm {
   int order = 0, V = 0, bits = 0;
   uint32_t ht_mask = 0;
   // device
-  uint64_t *ht_key = nullptr;
-  int *ht_val = nullptr;
-  float *ctx_bo = nullptr;
-  int *ctx_begin = nullptr, *ctx_count = nullptr;
+  rb::LmSlot *slots = nullptr;
   int *succ_tok = nullptr;
   float *succ_p = nullptr;
   float *uni = nullptr;
@@ -50,8 +48,7 @@ int lm_order(const rnnt_lm_t *lm) { return lm->order; }
 uint64_t lm_id(const rnnt_lm_t *lm) { return lm->id; }
 
 LmView lm_view(const rnnt_lm_t *lm) {
-  return LmView{lm->ht_key, lm->ht_val, lm->ctx_bo, lm->ctx_begin, lm->ctx_count, lm->succ_tok,
-                lm->succ_p, lm->uni,    lm->ht_mask, lm->order,    lm->V,         lm->bits};
+  return LmView{lm->slots, lm->succ_tok, lm->succ_p, lm->uni, lm->ht_mask, lm->order, lm->V, lm->bits};
 }
 
 void lm_launch_rows(const rnnt_lm_t *lm, const int *ctx, const int *len, float *out, int M, const int *done,
@@ -131,14 +128,16 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
       succ_p[pos] = log10_prob[i];
     }
   uint32_t size = 64;
-  while (size < 2u * (uint32_t)(n_ctx + 1)) size <<= 1;
-  std::vector<uint64_t> ht_key(size, 0);
-  std::vector<int> ht_val(size, -1);
+  while (size < 4u * (uint32_t)(n_ctx + 1)) size <<= 1;  // at most a quarter full: short probe sequences
+  std::vector<rb::LmSlot> slots(size);
+  std::memset(slots.data(), 0, slots.size() * sizeof(rb::LmSlot));
   for (auto &kv : ctx_id) {
     uint32_t slot = (uint32_t)rb::lm_mix(kv.first) & (size - 1);
-    while (ht_key[slot] != 0) slot = (slot + 1) & (size - 1);
-    ht_key[slot] = kv.first;
-    ht_val[slot] = kv.second;
+    while (slots[slot].key != 0) slot = (slot + 1) & (size - 1);
+    slots[slot].key = kv.first;
+    slots[slot].begin = ctx_begin[kv.second];
+    slots[slot].count = ctx_count[kv.second];
+    slots[slot].backoff = ctx_bo[kv.second];
   }
   rnnt_lm *lm = new (std::nothrow) rnnt_lm();
   if (!lm) return RNNT_E_NOMEM;
@@ -148,10 +147,7 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
   lm->V = V;
   lm->bits = bits;
   lm->ht_mask = size - 1;
-  ctx_begin.pop_back();
-  bool ok = lm_upload(lm, &lm->ht_key, ht_key) && lm_upload(lm, &lm->ht_val, ht_val) &&
-            lm_upload(lm, &lm->ctx_bo, ctx_bo) && lm_upload(lm, &lm->ctx_begin, ctx_begin) &&
-            lm_upload(lm, &lm->ctx_count, ctx_count) && lm_upload(lm, &lm->succ_tok, succ_tok) &&
+  bool ok = lm_upload(lm, &lm->slots, slots) && lm_upload(lm, &lm->succ_tok, succ_tok) &&
             lm_upload(lm, &lm->succ_p, succ_p) && lm_upload(lm, &lm->uni, uni);
   if (!ok) {
     rnnt_lm_destroy(lm);

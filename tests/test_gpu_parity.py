@@ -65,8 +65,10 @@ def test_encoder_projection_matches_oracle(amd, oracle, prec, B, T, D, H):
         np.testing.assert_allclose(f[b * c["T"] + t], oracle.enc_proj(c, w, enc[b, t]), atol=2e-5, rtol=0)
 
 
-@pytest.mark.parametrize("n_target,order,V", [(1000, 4, 12), (60000, 4, 300), (30000, 6, 64), (200, 1, 50)])
+@pytest.mark.parametrize("n_target,order,V", [(1000, 4, 12), (60000, 4, 300), (30000, 6, 64), (200, 1, 50),
+                                              (80000, 3, 1500)])
 def test_lm_rows_match_oracle_lm(amd, oracle, n_target, order, V):
+    """(V = 1500: more tokens than a block holds in registers, and successor lists longer than a block.)"""
     lm = S.make_lm(V=V, order=order, n_target=n_target, zipf_s=1.1, seed=n_target + order)
     g, o = amd.NGramLM(lm), oracle.LM(lm)
     rng = np.random.default_rng(1)
@@ -81,6 +83,9 @@ def test_lm_rows_match_oracle_lm(amd, oracle, n_target, order, V):
             ctx[i, :n] = hist[:n]
         else:
             ctx[i, :n] = rng.integers(0, V, n)
+    if order > 1:
+        ctx[1] = -1
+        ctx[1, 0] = 0  # the most frequent token alone: the longest successor list of the model
     got = g.debug_query(ctx)
     for i in range(64):
         hist = [int(x) for x in ctx[i] if x >= 0][::-1]  # oldest first
@@ -261,6 +266,21 @@ def test_lm_fusion(amd, oracle):
     np.testing.assert_array_equal(g0["tokens"], g1["tokens"])
     np.testing.assert_allclose(g0["scores"], g1["scores"], atol=1e-9)
     assert not np.array_equal(g["scores"], g1["scores"])
+
+
+def test_lm_fusion_with_a_row_too_large_for_the_projection_launch(amd, oracle):
+    """LM rows of more than 16 KiB (V > 4096) are built beside the cell update, not beside the projection's tiles."""
+    V = 4200
+    c = S.custom_config(B=3, T=10, T_min=6, D=64, H=96, P=96, E=96, V=V, beam=3, s=2, algo="alsd", blank_bias=3.0)
+    w, L, enc = _case(c, 830)
+    lm = S.make_lm(V=V, order=3, n_target=30000, zipf_s=1.1, seed=9)
+    glm, olm = amd.NGramLM(lm), oracle.LM(lm)
+    dec = amd.BeamDecoder(c, w, joint_path="fused")
+    g = gpu_decode(dec, enc, L, lm=glm, lm_weight=0.4)
+    o = oracle.decode(c, w, enc, L, lm=olm, lm_weight=0.4, log=True)
+    full, exempt = compare(g, o, TOL, TIE, walk=make_walk(oracle, c, w, enc, L, g, TOL, lm=olm, lm_weight=0.4))
+    assert full + exempt == 3 and full >= 2
+    assert not np.array_equal(g["scores"], gpu_decode(dec, enc, L)["scores"])
 
 
 @pytest.mark.parametrize("rule,prune,beam,algo", [(3, "late", 4, "alsd"), (4, "early", 4, "alsd"), (3, "early", 8, "alsd"),
