@@ -152,7 +152,9 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *weights, rn
  * log10 probability and log10 back-off weight of each.  Every unigram must be present.
  * Score of token v after a transcript: p(ctx v) if stored, else backoff(ctx) + score with the
  * oldest context token dropped; ctx = the last order-1 tokens.  The table is stored on the
- * device as a hash of contexts with successor lists.
+ * device as a hash of contexts with successor lists: 128 to 256 bytes per distinct context
+ * (32-byte slots, the table at most a quarter full), 8 bytes per n-gram of order 2 and up,
+ * 4 V bytes of unigrams; allocated here, freed by rnnt_lm_destroy.
  */
 int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const int8_t *ngram_order,
                    const float *log10_prob, const float *log10_backoff, int32_t V, rnnt_lm_t **out);
