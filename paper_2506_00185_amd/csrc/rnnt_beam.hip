@@ -899,10 +899,10 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     a.S_max = w.S_max;
     a.cap = p.out_cap ? p.out_cap : w.cap;
     const size_t lds = (size_t)w.S_max * p.K * 2 * sizeof(int);
-    a.use_lds = lds <= 64 * 1024;
     a.out_tokens = w.out_tokens; a.out_lens = w.out_lens; a.out_scores = w.out_scores; a.out_steps = w.out_steps;
     ScopedKernelTime tm(h, s, KT_BACKTRACE);
-    hipLaunchKernelGGL(k_backtrace, dim3(p.B), dim3(64), a.use_lds ? lds : 0, s, a);
+    if (lds <= 64 * 1024) hipLaunchKernelGGL(k_backtrace<true>, dim3(p.B), dim3(kBacktraceThreads), lds, s, a);
+    else hipLaunchKernelGGL(k_backtrace<false>, dim3(p.B), dim3(kBacktraceThreads), 0, s, a);
   }
   RB_HIP(h, hipGetLastError());
   RB_HIP(h, hipEventRecord(h->ev_end, s));

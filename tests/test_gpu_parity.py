@@ -145,6 +145,22 @@ def test_injected_merge_heavy_tables_are_bit_exact(amd, oracle, algo, beam, V, m
     assert np.sum((m >= 0) & (m != slots)) >= 3, "the table does not exercise recombination"
 
 
+def test_injected_long_utterances_walk_the_tree_in_memory(amd, oracle):
+    """A tree of more than 64 KiB per utterance (steps x beam x 8 bytes) is walked back where it lies, not from an
+    on-chip copy; a shorter one beside it in the same batch ends earlier."""
+    B, T, C, V, beam, s = 2, 130, 3, 6, 8, 7
+    assert T * (s + 1) * beam * 8 > 64 * 1024
+    c = S.custom_config(B=B, T=T, T_min=3, D=32, H=32, P=32, E=32, V=V, beam=beam, s=s, algo="alsd")
+    L = np.array([T, 41], np.int32)
+    tok, _ = S.make_injected(B, T, C, V, 0, seed=77, levels=200, blank_boost=10)
+    dec = amd.BeamDecoder(c, S.make_weights(c, 1))
+    g = gpu_decode_injected(dec, tok, None, L)
+    o = oracle.decode(c, None, None, L, injected=(tok, None), log=True)
+    assert np.array_equal(g["n_steps"], o["n_steps"]) and g["n_steps"].max() > 300
+    full, exempt = compare(g, o, tol=1e-9, tie=0.0, exact_tree=True)
+    assert full == B and exempt == 0
+
+
 def test_injected_tree_walk_gives_the_transcripts(amd, oracle):
     """Back-trace through (parent, token) on the host reproduces what the library reports."""
     B, T, C, V, beam = 3, 10, 4, 20, 5
