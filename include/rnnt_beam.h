@@ -168,11 +168,11 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
  * (1 + lambda) ln p(blank), tokens as ln p + lambda ln((1 - p(blank)) p_LM)), combined before the
  * beam is cut (late pruning); the config fields lm_rule and lm_early_pruning select Eq. (3) and early
  * pruning.  An LM together with a finite prune_margin is rejected.
- * Work is enqueued on hip_stream (a hipStream_t, NULL = default stream) in chunks of 16 steps, at most
- * two chunks ahead of the device; the call returns once the device has reported (through a pinned word)
+ * Work is enqueued on hip_stream (a hipStream_t, NULL = default stream) in chunks of 16 steps, one
+ * chunk ahead of the device; the call returns once the device has reported (through a pinned word)
  * that every utterance has finished and the back-trace has been enqueued, i.e. it blocks the calling
  * thread for most of the decode's duration (config field async_enqueue: enqueue everything and return).
- * Up to two chunks of steps enqueued after the last utterance finished still run; their kernels return at once.
+ * Steps enqueued after the last utterance finished (under two chunks of them) still run; their kernels return at once.
  * Results stay valid until the next decode.  Graphs captured for a decode hold the LM's device tables: an LM
  * must outlive every decode that uses it, and at most 8 graphs (distinct B, T, beam, algo, LM, LM weight) are
  * kept per handle, the oldest being dropped.
