@@ -50,9 +50,11 @@ __device__ __forceinline__ void splitk_load(SplitKOperands<ITERS> &op, AL a_at, 
 // bf16 (uniform over the block): both operands are rounded to bfloat16 (weights handed in are bf16 values already)
 // and two 8-k rounds at a time go through one bf16 matrix instruction, an eighth of the matrix-core time of the
 // eight float32 ones; the accumulation stays float32.
+// xw (ITERS > 0 only): this lane's k values of one more output row; the lane's part of that row's product with its
+// hypothesis goes into the spare float of its slot in red (extra_value() sums the parts).
 template <int WAVES, int ITERS, class AL, class BL, class FB>
 __device__ __forceinline__ void splitk_mma(SplitKOperands<ITERS> &op, AL a_at, BL b_at, FB fb, int K, float *red,
-                                           int bf16 = 0) {
+                                           int bf16 = 0, const float4 *xw = nullptr) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
   const int kw = K / WAVES;
   const float4 zero4 = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -98,7 +100,36 @@ __device__ __forceinline__ void splitk_mma(SplitKOperands<ITERS> &op, AL a_at, B
   float *mine = red + (wave * 64 + lane) * kRedStride;
 #pragma unroll
   for (int r = 0; r < 16; ++r) mine[r] = acc[r];
+  if constexpr (ITERS > 0) {
+    if (xw) {
+      float part = 0.f;
+#pragma unroll
+      for (int i = 0; i < ITERS; ++i) {
+        float4 b = fb(op.b[i]);
+        if (bf16) {  // (the weights are bf16 values already)
+          b.x = __uint_as_float(pack_bf16_rne(b.x, 0.f) << 16);
+          b.y = __uint_as_float(pack_bf16_rne(b.y, 0.f) << 16);
+          b.z = __uint_as_float(pack_bf16_rne(b.z, 0.f) << 16);
+          b.w = __uint_as_float(pack_bf16_rne(b.w, 0.f) << 16);
+        }
+        part = fmaf(xw[i].x, b.x, part);
+        part = fmaf(xw[i].y, b.y, part);
+        part = fmaf(xw[i].z, b.z, part);
+        part = fmaf(xw[i].w, b.w, part);
+      }
+      mine[16] = part;
+    }
+  }
   __syncthreads();
+}
+
+// the extra row's product with hypothesis j (see splitk_mma)
+template <int WAVES>
+__device__ __forceinline__ float extra_value(const float *red, int j) {
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < WAVES; ++w) s += red[(w * 64 + j) * kRedStride + 16] + red[(w * 64 + 32 + j) * kRedStride + 16];
+  return s;
 }
 
 // element (output row i, hypothesis j) of the finished 32 x 32 tile
@@ -1057,7 +1088,9 @@ struct RecurrentArgs {
   const float *h;      // k4-major [P][Mp]
   float *R;            // [M][4P]
   int P, M, Mp;
+  int group;           // slot tiles per block (1, or kRecGroup: the map's items are then groups of slot tiles)
 };
+constexpr int kRecGroup = 4;
 
 template <int WAVES, int ITERS>
 __device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int tile, int m0, int done, float *red) {
@@ -1082,6 +1115,60 @@ __device__ __forceinline__ void recurrent_tile(const RecurrentArgs &a, int tile,
   }
 }
 
+// The same for up to G slot tiles in a row (item `grp` of the tile's row: slot tiles grp * G ...): the 32 gate rows
+// stay in registers, and the slots of the next tile are requested before the matrix instructions of the current one
+// start, so that a block streams half as much per tile and streams while it multiplies.
+template <int WAVES, int ITERS, int G>
+__device__ __forceinline__ void recurrent_tiles(const RecurrentArgs &a, int tile, int grp, int done, float *red) {
+  static_assert(ITERS > 0, "every load of a slice in flight at once");
+  constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
+  const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, wave = tid >> 6, half = lane >> 5;
+  const int R4 = 4 * a.P, Mp = a.Mp;
+  const int m_tiles = (a.M + 31) / 32;
+  const int t0 = grp * a.group, n_mt = m_tiles - t0 < a.group ? m_tiles - t0 : a.group;
+  const int kbeg = wave * (a.P / WAVES) + 4 * half;
+  const float *wp = a.Whh + (size_t)(tile * 32 + col) * 4 + (size_t)(kbeg >> 2) * R4 * 4;
+  const float *hp = a.h + (size_t)(t0 * 32 + col) * 4 + (size_t)(kbeg >> 2) * Mp * 4;
+  float4 wa[ITERS], hb[2][ITERS];
+#pragma unroll
+  for (int i = 0; i < ITERS; ++i) {
+    wa[i] = *reinterpret_cast<const float4 *>(wp + (size_t)(2 * i) * R4 * 4);
+    hb[0][i] = *reinterpret_cast<const float4 *>(hp + (size_t)(2 * i) * Mp * 4);
+  }
+  if (done) return;
+  const int j = tid / LPH, i0 = (tid % LPH) * VPL;
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    if (g >= n_mt) break;
+    if (g + 1 < G && g + 1 < n_mt) {
+#pragma unroll
+      for (int i = 0; i < ITERS; ++i)
+        hb[(g + 1) & 1][i] = *reinterpret_cast<const float4 *>(hp + (size_t)(g + 1) * 32 * 4 + (size_t)(2 * i) * Mp * 4);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // the next tile's loads are under way before the first matrix instruction
+    floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < ITERS; ++i) {
+      const float4 b = hb[g & 1][i];
+      acc = mfma32(wa[i].x, b.x, acc);
+      acc = mfma32(wa[i].y, b.y, acc);
+      acc = mfma32(wa[i].z, b.z, acc);
+      acc = mfma32(wa[i].w, b.w, acc);
+    }
+    if (g > 0) __syncthreads();  // the previous tile's partial sums have been read
+    float *mine = red + (wave * 64 + lane) * kRedStride;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mine[r] = acc[r];
+    __syncthreads();
+    const int m = (t0 + g) * 32 + j;
+    if (m < a.M) {
+#pragma unroll
+      for (int q = 0; q < VPL; ++q)
+        store_through(a.R + (size_t)m * R4 + tile * 32 + i0 + q, tile_value<WAVES>(red, i0 + q, j));
+    }
+  }
+}
+
 struct MainArgs {
   // ---- joint role
   const float *pre;   // k4-major [H][Mp]: f_proj[b, t_m] + prediction projection of hypothesis m
@@ -1090,6 +1177,9 @@ struct MainArgs {
   const float *lm;    // [M, V] natural-log LM scores or NULL
   float lambda;
   int M, Mp, K, H, V, ND, n_chunks, round_ops;
+  int n_jchunks;           // chunks that have joint blocks.  n_chunks - 1: the blank and duration columns, alone in the
+                           // last chunk, are folded into the token chunks' blocks (column V + c of tile ty into chunk
+                           // (n_jchunks - 1 - c + ty) mod n_jchunks)
   int upt, rpt, n_jtiles;  // utterances and rows per joint tile (rpt = upt * K <= 32), number of such tiles
   float *p_max, *p_sum;    // [M, n_chunks] soft-max statistics of the chunk's token logits
   uint64_t *p_cand;        // [M, K, n_chunks] best (key = z + lambda * lm, token) of the chunk, packed
@@ -1112,6 +1202,10 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
   const int n0 = chunk * 32;
+  // (shifted by the tile's index: the blocks with a folded column finish last, and the one that completes a tile
+  // keeps its compute unit for the selection: on a different XCD for every tile this way)
+  const int fold_c = (a.n_jchunks - 1 - chunk + m0 / rows) % a.n_jchunks;
+  const bool folds = ITERS > 0 && a.n_jchunks < a.n_chunks && fold_c <= a.ND;
   {
     const int Np = a.n_chunks * 32;
     const float *wp = a.W + (size_t)(n0 + col) * 4;
@@ -1125,8 +1219,23 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
     };
     SplitKOperands<ITERS> op;
     splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
-    if (done) return;
-    splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red, round_ops);
+    if constexpr (ITERS > 0) {
+      if (folds) {  // (uniform over the block) the folded column's weights, requested behind the operands
+        float4 xw[ITERS];
+        const int kbeg = (tid >> 6) * (a.H / WAVES) + 4 * (lane >> 5);
+        const float *xp = a.W + (size_t)(a.V + fold_c) * 4;
+#pragma unroll
+        for (int i = 0; i < ITERS; ++i) xw[i] = *reinterpret_cast<const float4 *>(xp + (size_t)((kbeg + 8 * i) >> 2) * Np * 4);
+        if (done) return;
+        splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red, round_ops, xw);
+      } else {
+        if (done) return;
+        splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red, round_ops);
+      }
+    } else {
+      if (done) return;
+      splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.H, red, round_ops);
+    }
   }
 
   // epilogue: thread -> (hypothesis j, columns i0 .. i0 + VPL - 1)
@@ -1134,6 +1243,19 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
   const int m = m0 + j;
   const bool mvalid = j < rows && m < a.M;
   const int nz = 1 + a.ND;
+  if (folds && mvalid) {
+    if (e == 0) store_agent(a.zs + (size_t)m * nz + fold_c, extra_value<WAVES>(red, j) + a.bias[a.V + fold_c]);
+    if (fold_c == 0) {  // ... and the empty lists of the chunk that has no block now
+      const size_t pl = (size_t)m * a.n_chunks + a.n_chunks - 1;
+      if (e == 0) {
+        store_agent(a.p_max + pl, -INFINITY);
+        store_agent(a.p_sum + pl, 0.f);
+      }
+      uint64_t *ll = a.p_cand + (size_t)m * a.K * a.n_chunks + a.n_chunks - 1;
+      if (e < a.K) store_agent(ll + (size_t)e * a.n_chunks, no_cand());
+      if (LPH + e < a.K) store_agent(ll + (size_t)(LPH + e) * a.n_chunks, no_cand());
+    }
+  }
   uint64_t cand[VPL];
   float mx = -INFINITY;
   float zv[VPL];
@@ -1213,6 +1335,12 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
   if (role < 0) return;
   if (role == 1) {
+    if constexpr (ITERS > 0) {
+      if (a.rec.group > 1) {
+        recurrent_tiles<WAVES, ITERS, kRecGroup>(a.rec, chunk, ty, done, red);
+        return;
+      }
+    }
     recurrent_tile<WAVES, ITERS>(a.rec, chunk, ty * 32, done, red);
     return;
   }
@@ -1234,7 +1362,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   __syncthreads();
   if (tid == 0) {
     const int old = __hip_atomic_fetch_add(a.tile_ctr + ty, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int last = old == a.n_chunks - 1;
+    const int last = old == a.n_jchunks - 1;
     if (last) store_agent(a.tile_ctr + ty, 0);  // every other block of the tile has been counted
     s_is_last = last;
   }

@@ -233,6 +233,23 @@ bool proj_split(const rnnt_config_t &c, int M) {
 // Gate tiles of the recurrent product computed in the prediction-projection launch (the rest ride in the
 // main launch): as many as fit beside the projection's own blocks, one block per compute unit, on every XCD
 // (32 compute units each).
+// Slot tiles per block of the recurrent product in the main launch.  From 256 slots up that launch has several
+// rounds of blocks per compute unit, and a block that keeps its 32 gate rows in registers for 2 or 4 slot tiles and
+// requests the next tile's slots while it multiplies takes 3.3 us per further tile instead of 5 to 7 us for a tile
+// of its own.  Measured per shape (us per step, blocks of 1 / 2 / 4 tiles): 224 slots 36.6 / 38.7 / 38.2, 256 slots
+// 41.4 / 41.7 / 40.6 (4 tiles: two blocks per gate tile, all resident at once), 288 slots 44.3 / 41.2 / 44.6, 320 slots
+// 46.6 / 44.3 / 48.3, 512 slots 73.3 / 66.8 / 69.7; at 128 slots single tiles are better (26.0 / 27.0 / 26.9): the
+// recurrent blocks run beside the joint blocks there, off the critical path.  (The kernels' fully unrolled form only.)
+int recurrent_group(const rnnt_config_t &c, int M) {
+  const int m_tiles = (M + 31) / 32;
+  if (c.P != 640 || m_tiles < 8) return 1;
+  return m_tiles == 8 ? 4 : 2;
+}
+int recurrent_items(const rnnt_config_t &c, int M) {
+  const int g = recurrent_group(c, M);
+  return ((M + 31) / 32 + g - 1) / g;
+}
+
 int recurrent_split(const rnnt_config_t &c, int M) {
   if (proj_split(c, M)) return 0;  // no recurrent tiles beside the half tiles: they would set that launch's duration
   XcdMap m;
@@ -484,7 +501,7 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
       a.done = done; a.step_base = step_base; a.bump = bump;
       a.rec.Whh = h->W_hh; a.rec.h = w.h[cur ^ 1]; a.rec.R = w.Rgates;
-      a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp;
+      a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp; a.rec.group = 1;
       a.map.a_tiles = c.H / 32; a.map.a_m = m_tiles;
       a.map.b_begin = 0; a.map.b_end = recurrent_split(c, p.M); a.map.b_m = m_tiles;
       ScopedKernelTime tm(h, s, KT_PREDPROJ);
@@ -682,11 +699,17 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.tile_ctr = w.tile_ctr;
     const bool lstm = c.pred == RNNT_PRED_LSTM;
     a.rec.Whh = h->W_hh; a.rec.h = w.h[cur]; a.rec.R = w.Rgates;
-    a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp;
-    a.map.a_tiles = a.n_chunks; a.map.a_m = a.n_jtiles;
+    a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp; a.rec.group = recurrent_group(c, p.M);
+    // More joint blocks than compute units, and the blank / duration columns alone in the last chunk: its blocks
+    // would start when the first ones end, and the selection would wait for them.  The token chunks' blocks take
+    // those columns instead (one each), as dot products on the operands that they hold in registers.
+    const bool fold = c.V % 32 == 0 && c.H == 640 && (!lstm || c.P == 640) && a.n_chunks - 1 >= 1 + c.n_durations &&
+                      a.n_chunks * a.n_jtiles > 256;
+    a.n_jchunks = fold ? a.n_chunks - 1 : a.n_chunks;
+    a.map.a_tiles = a.n_jchunks; a.map.a_m = a.n_jtiles;
     a.map.b_begin = lstm ? recurrent_split(c, p.M) : 0;
     a.map.b_end = lstm ? 4 * c.P / 32 : 0;
-    a.map.b_m = (p.M + 31) / 32;
+    a.map.b_m = recurrent_items(c, p.M);
     fill_select_args(h, p, step_off, h->n_chunks, a.sel);
     const dim3 grid(xcd_grid(a.map));
     // The selection runs in the tail of this kernel for the beams its in-kernel forms take.  (Building the kernel
@@ -741,11 +764,11 @@ int launch_persistent(rnnt_beam *h, hipStream_t s, const StepPlan &p, int max_st
   MainArgs &m = a.main;
   m.pre = w.pre; m.W = h->W_out; m.bias = h->b_out; m.lm = nullptr; m.lambda = 0.f;
   m.M = p.M; m.Mp = w.Mp; m.K = p.K; m.H = c.H; m.V = c.V; m.ND = c.n_durations;
-  m.n_chunks = h->n_chunks;
+  m.n_chunks = m.n_jchunks = h->n_chunks;
   m.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
   m.p_max = w.p_max; m.p_sum = w.p_sum; m.p_cand = w.p_cand; m.zs = w.zs;
   m.tile_ctr = w.tile_ctr;
-  m.rec.Whh = h->W_hh; m.rec.h = nullptr; m.rec.R = w.Rgates; m.rec.P = c.P; m.rec.M = p.M; m.rec.Mp = w.Mp;
+  m.rec.Whh = h->W_hh; m.rec.h = nullptr; m.rec.R = w.Rgates; m.rec.P = c.P; m.rec.M = p.M; m.rec.Mp = w.Mp; m.rec.group = 1;
   fill_select_args(h, p, 0, h->n_chunks, m.sel);  // (the step counter word stays 0: the kernel passes the step itself)
   PredProjArgs &q = a.pp;
   q.Wp = h->W_pred; q.bias = h->b_pred; q.h = nullptr; q.f_proj = w.f_proj; q.t = w.t; q.lengths = w.lengths;

@@ -227,6 +227,29 @@ def test_full_width_model_small_batch(amd, oracle, name, kw):
     assert g["lens"][1, 0] == 0 and g["scores"][1, 0] == 0.0 and g["n_steps"][1] == 0  # the empty utterance
 
 
+@pytest.mark.parametrize("name,kw,prec", [
+    ("rnnt_alsd_256_slots", dict(B=32, T=6, T_min=2, beam=8, s=2, algo="alsd"), "f32"),
+    ("tdt_aes_288_slots", dict(B=36, T=16, T_min=5, beam=8, s=2, algo="aes", model="tdt", durations=(0, 1, 2, 3, 4)), "f32"),
+    ("tdt_alsd_256_slots_bf16", dict(B=64, T=14, T_min=4, beam=4, s=2, algo="alsd", model="tdt",
+                                     durations=(0, 1, 2, 3, 4)), "bf16"),
+])
+def test_full_width_model_wide_batch(amd, oracle, name, kw, prec):
+    """From 256 slots up at the real layer widths: more joint blocks than compute units, so the blank and duration
+    columns (alone in the last column chunk, V % 32 == 0) are computed by the token chunks' blocks, and the blocks of
+    the recurrent product take four slot tiles each (256 slots) or two (288: the last block of a gate tile has one)."""
+    c = S.custom_config(D=256, H=640, P=640, E=640, V=1024, blank_bias=3.0, prec=prec, **kw)
+    w, L, enc = _case(c, 450 + len(name))
+    if c["model"] == "tdt":
+        w["b_out"][c["V"] + 2] += 2.0
+    dec = amd.BeamDecoder(c, w)
+    g = gpu_decode(dec, enc, L)
+    o = oracle.decode(c, w, enc, L, log=True)
+    tol, tie = (TOL_BF16, TIE_BF16) if prec == "bf16" else (TOL, TIE)
+    full, exempt = compare(g, o, tol, tie, walk=make_walk(oracle, c, w, enc, L, g, tol))
+    assert full + exempt == c["B"]
+    assert full >= c["B"] // 2, (full, exempt)
+
+
 def test_odd_shapes(amd, oracle):
     """Vocabulary, batch and frame counts that are not multiples of any tile size."""
     c = S.custom_config(B=9, T=11, T_min=1, D=96, H=160, P=96, E=64, V=77, beam=5, s=2, algo="alsd")
