@@ -412,11 +412,18 @@ __device__ __forceinline__ void rank_by_counting_n(const double *keys, const int
 // ONE: every hypothesis comes with exactly one list (n_chunks == 1, NCH == 1), known at compile time: the merge
 // of list heads and its registers drop out.
 template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch,
-          bool ONE = false>
+          bool ONE = false, int PLAIN = 0>
 __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
+  // PLAIN (the caller has checked): 1 = ALSD++, 2 = AES++ without prune margin and prefix search, both without
+  // durations and LM: the code of the other cases drops out
+  const int a_ND = PLAIN ? 0 : a.ND;
+  const int a_has_lm = PLAIN ? 0 : a.has_lm, a_lm_early = PLAIN ? 0 : a.lm_early, a_lm_rule3 = PLAIN ? 0 : a.lm_rule3;
+  const int a_prefix = PLAIN ? 0 : a.prefix;
+  const float a_gamma = PLAIN ? INFINITY : a.gamma;
+  const int a_algo = PLAIN ? PLAIN - 1 : a.algo;
   const int m_base = b * K;
-  const int nz = 1 + a.ND;
+  const int nz = 1 + a_ND;
   // ---- every load of the prologue is requested before anything waits on one of them
   const int fin = load_agent(a.finished + b);  // (a wave-uniform word that changes: never through the scalar cache)
   const int S = *a.step_base + a.step_off;
@@ -490,9 +497,9 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
       }
     }
     zb = load_agent(zsr);
-    if (a.ND > 0) {
+    if (a_ND > 0) {
 #pragma unroll
-      for (int d = 0; d < 8; ++d) dl[d] = load_agent(zsr + 1 + (d < a.ND ? d : 0));
+      for (int d = 0; d < 8; ++d) dl[d] = load_agent(zsr + 1 + (d < a_ND ? d : 0));
     }
   };
   auto process_rows = [&]() {
@@ -576,16 +583,16 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
     // TDT durations
     double x_tok = 0.0, x_blank = 0.0;
     int adv_tok = 0, adv_blank = 1;
-    if (a.ND > 0) {
+    if (a_ND > 0) {
       if (!a.normalized) {
         float dmx = -INFINITY, sm = 0.f;
-        for (int d = 0; d < a.ND; ++d) dmx = fmaxf(dmx, dl[d]);
-        for (int d = 0; d < a.ND; ++d) sm += __expf(dl[d] - dmx);
+        for (int d = 0; d < a_ND; ++d) dmx = fmaxf(dmx, dl[d]);
+        for (int d = 0; d < a_ND; ++d) sm += __expf(dl[d] - dmx);
         const float l = dmx + __logf(sm);
-        for (int d = 0; d < a.ND; ++d) dl[d] -= l;
+        for (int d = 0; d < a_ND; ++d) dl[d] -= l;
       }
       int best = -1, best_b = -1;
-      for (int d = 0; d < a.ND; ++d) {
+      for (int d = 0; d < a_ND; ++d) {
         if (best < 0 || dl[d] > dl[best]) best = d;
         if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
       }
@@ -601,17 +608,17 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
     if (row_ok) {
       const int kind = s.kind[rk];
       const bool forced = s.sym[rk] >= a.max_sym;
-      const bool use_gamma = a.algo == 1 && a.gamma < INFINITY;
-      const double thr = maxlogp - (double)a.gamma;
+      const bool use_gamma = a_algo == 1 && a_gamma < INFINITY;
+      const double thr = maxlogp - (double)a_gamma;
       const double sc = s.score[rk];
       const int flat0 = rk << kFlatShift;
       // Eq. (4): tokens get lambda (ln(1 - p_blank) + lm), blank (1 + lambda) ln p_blank; Eq. (3): tokens lambda lm,
       // blank unchanged.  Late pruning: lambda * lm is in the key already; early: added here, after the ranking value.
-      const double lm_const = (a.has_lm && !a.lm_rule3) ? (double)a.lambda * nb : 0.0;
+      const double lm_const = (a_has_lm && !a_lm_rule3) ? (double)a.lambda * nb : 0.0;
       const double tok_base = x_tok - (double)lse_all;
-      const bool early = a.lm_early != 0;
+      const bool early = a_lm_early != 0;
       // where candidate (hypothesis rk, j-th symbol[, duration d]) goes and how it is numbered for the tie-break
-      const int nd = PAIRS ? a.ND : 1;
+      const int nd = PAIRS ? a_ND : 1;
       auto put = [&](int j, int token, double key, double val) {
         if constexpr (PAIRS) {
           for (int d = 0; d < nd; ++d) {
@@ -654,7 +661,7 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
           double bl = logp_b;
           if (use_gamma && logp_b < thr && !forced) bl = -INFINITY;
           key = sc + bl + x_blank;
-          val = (a.has_lm && !a.lm_rule3 && bl > -INFINITY) ? key + (double)a.lambda * bl : key;
+          val = (a_has_lm && !a_lm_rule3 && bl > -INFINITY) ? key + (double)a.lambda * bl : key;
           s.advt[rk] = adv_tok;
           s.advb[rk] = adv_blank;
         } else if (kind == 1) {
@@ -689,7 +696,7 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
     const bool my_live = my_score > -INFINITY;
     int t_cur = group_min_i<16>((my_live && my_t < T_b) ? my_t : T_b);
     t_cur = __builtin_amdgcn_readlane(t_cur, 0);
-    if (lane < K) s.kind[lane] = my_live ? ((my_t < T_b && (a.algo == 0 || my_t == t_cur)) ? 2 : 1) : 0;
+    if (lane < K) s.kind[lane] = my_live ? ((my_t < T_b && (a_algo == 0 || my_t == t_cur)) ? 2 : 1) : 0;
     return true;
   };
   if constexpr (MULTI) {
@@ -704,13 +711,13 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
     process_rows();
   }
 
-  const int n = K * (K + 1) * (PAIRS ? a.ND : 1);
+  const int n = K * (K + 1) * (PAIRS ? a_ND : 1);
   // ---- AES++, maximum-length prefix search (Sec. 2.2, "AES").  Hypotheses i and j expanded at this step in the
   // same frame with transcript(i) = transcript(j) + v: the step's own expansion (j, v), if it is among j's Beam best
   // tokens and stays in the frame, is credited to i for the RANKING of i's candidates; the new scores stay as they
   // are (the expansion competes on its own and meets i in the recombination; adding it to i's score too would count
   // that alignment twice).  Pairs are found through Eq. (1), like equal transcripts in the recombination.
-  const bool prefix = !PAIRS && a.prefix && a.algo == 1 && !a.lm_early;
+  const bool prefix = !PAIRS && a_prefix && a_algo == 1 && !a_lm_early;
   if constexpr (!PAIRS) {
     if (prefix) {
       if (lane < K) {
@@ -738,7 +745,7 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
   }
   // ---- the Beam best of all K * (K + 1) candidates, by (ranking value desc, (k, v) asc); the ranking
   // value is the new score itself except under early pruning and with a prefix credit
-  double *rank_of = (a.lm_early || prefix) ? s.rc_key : s.rc_val;
+  double *rank_of = (a_lm_early || prefix) ? s.rc_key : s.rc_val;
   // candidates a lane may own in the counting form below
   constexpr int kOwn = 1;  // (measured: from 65 candidates up the rounds below are faster than two owned candidates)
   if (n <= 64 * kOwn) {
@@ -998,7 +1005,12 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
 // registers).  The heavy forms are kept out of the kernels that do not need them.
 template <int FORMS, class Scratch = SelectScratch>
 __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
-  if constexpr (FORMS == 4) {  // one list per hypothesis (the materialised-logits path), any beam
+  if constexpr (FORMS == 12) {  // FORMS == 4 for AES++ on a plain RNN-T (no durations, LM, prune margin, prefix search)
+    if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true, 2>(a, b, s, cv);
+    else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true, 2>(a, b, s, cv);
+    else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true, 2>(a, b, s, cv);
+    else select_utterance<4, 1, 16, false, false, Scratch, true, 2>(a, b, s, cv);
+  } else if constexpr (FORMS == 4) {  // one list per hypothesis (the materialised-logits path), any beam
     if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true>(a, b, s, cv);
     else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true>(a, b, s, cv);
     else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true>(a, b, s, cv);
@@ -1011,6 +1023,12 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scra
       if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8, false, true, Scratch>(a, b, s, cv);
       else select_utterance<8, 0, 8, false, true, Scratch>(a, b, s, cv);
     }
+  } else if constexpr (FORMS == 5) {  // one form alone (the caller has checked 2 < K <= 4, n_chunks <= 48) ...
+    select_utterance<16, 3, 4>(a, b, s, cv);
+  } else if constexpr (FORMS == 11) {  // ... the same for ALSD++ on a plain RNN-T (no durations, no LM)
+    select_utterance<16, 3, 4, false, false, Scratch, false, 1>(a, b, s, cv);
+  } else if constexpr (FORMS == 6) {  // ... (4 < K <= 8, n_chunks <= 40): a kernel a third the size
+    select_utterance<8, 5, 8>(a, b, s, cv);
   } else if constexpr (FORMS == 2) {
     if (a.n_chunks <= 16 * 3) select_utterance<16, 3, 16, true>(a, b, s, cv);  // four hypotheses per pass
     else select_utterance<4, 0, 16>(a, b, s, cv);
@@ -1197,7 +1215,7 @@ struct MainArgs {
 // so that the [M, V + 1] logits never reach memory (LPH = 2 * WAVES lanes share a hypothesis, each holds 32 / LPH
 // columns; the best K are found in K rounds of an LPH-lane arg-max).  Lists and statistics are written with
 // device-coherent stores.  red: the block's reduction buffer (WAVES * 64 * kRedStride floats).
-template <int WAVES, int ITERS>
+template <int WAVES, int ITERS, bool WIDE = false>
 __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0, int rows, int done, float *red) {
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
@@ -1205,7 +1223,7 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
   // (shifted by the tile's index: the blocks with a folded column finish last, and the one that completes a tile
   // keeps its compute unit for the selection: on a different XCD for every tile this way)
   const int fold_c = (a.n_jchunks - 1 - chunk + m0 / rows) % a.n_jchunks;
-  const bool folds = ITERS > 0 && a.n_jchunks < a.n_chunks && fold_c <= a.ND;
+  const bool folds = WIDE && ITERS > 0 && a.n_jchunks < a.n_chunks && fold_c <= a.ND;
   {
     const int Np = a.n_chunks * 32;
     const float *wp = a.W + (size_t)(n0 + col) * 4;
@@ -1219,7 +1237,7 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
     };
     SplitKOperands<ITERS> op;
     splitk_load<WAVES, ITERS>(op, a_at, b_at, a.H);
-    if constexpr (ITERS > 0) {
+    if constexpr (WIDE && ITERS > 0) {
       if (folds) {  // (uniform over the block) the folded column's weights, requested behind the operands
         float4 xw[ITERS];
         const int kbeg = (tid >> 6) * (a.H / WAVES) + 4 * (lane >> 5);
@@ -1243,7 +1261,7 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
   const int m = m0 + j;
   const bool mvalid = j < rows && m < a.M;
   const int nz = 1 + a.ND;
-  if (folds && mvalid) {
+  if (WIDE && folds && mvalid) {
     if (e == 0) store_agent(a.zs + (size_t)m * nz + fold_c, extra_value<WAVES>(red, j) + a.bias[a.V + fold_c]);
     if (fold_c == 0) {  // ... and the empty lists of the chunk that has no block now
       const size_t pl = (size_t)m * a.n_chunks + a.n_chunks - 1;
@@ -1321,7 +1339,10 @@ __device__ __forceinline__ void joint_tile(const MainArgs &a, int chunk, int m0,
 // the selection, so it overlaps with it instead of following it.
 // TAIL = false: no selection in the kernel (a launch of its own follows): for beams wider than the
 // in-kernel forms take.
-template <int WAVES, int ITERS, bool TAIL = true>
+// WIDE: the forms for 256 slots and more (folded blank / duration columns, recurrent blocks of several slot tiles);
+// an instantiation of their own, because their code costs the smaller shapes 0.2 us per launch when it is only there.
+// SEL: the selection forms in the tail (0: every in-kernel form; 5, 6: one form, see select_dispatch).
+template <int WAVES, int ITERS, bool TAIL = true, bool WIDE = false, int SEL = 0>
 __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main(MainArgs a) {
   constexpr int kRedFloats = WAVES * 64 * kRedStride;
   constexpr int kScratchFloats = TAIL ? (int)((sizeof(SelectScratch) * WAVES + 3) / 4) : 1;
@@ -1335,7 +1356,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   const int role = xcd_item(a.map, blockIdx.x, chunk, ty);
   if (role < 0) return;
   if (role == 1) {
-    if constexpr (ITERS > 0) {
+    if constexpr (WIDE && ITERS > 0) {
       if (a.rec.group > 1) {
         recurrent_tiles<WAVES, ITERS, kRecGroup>(a.rec, chunk, ty, done, red);
         return;
@@ -1345,7 +1366,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
     return;
   }
 
-  joint_tile<WAVES, ITERS>(a, chunk, ty * a.rpt, a.rpt, done, red);
+  joint_tile<WAVES, ITERS, WIDE>(a, chunk, ty * a.rpt, a.rpt, done, red);
   if (done) return;
 
   if constexpr (!TAIL) {
@@ -1362,7 +1383,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   __syncthreads();
   if (tid == 0) {
     const int old = __hip_atomic_fetch_add(a.tile_ctr + ty, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const int last = old == a.n_jchunks - 1;
+    const int last = old == (WIDE ? a.n_jchunks : a.n_chunks) - 1;
     if (last) store_agent(a.tile_ctr + ty, 0);  // every other block of the tile has been counted
     s_is_last = last;
   }
@@ -1374,7 +1395,7 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   const int wave = tid >> 6;
   for (int u = wave; u < a.upt; u += WAVES) {
     const int b = ty * a.upt + u;
-    if (b < a.sel.B) select_dispatch<0>(a.sel, b, scratch[wave]);
+    if (b < a.sel.B) select_dispatch<SEL>(a.sel, b, scratch[wave]);
   }
   }  // TAIL
 }
@@ -1571,6 +1592,7 @@ __device__ __forceinline__ void lstm_cell(const float *__restrict__ R, const flo
   store_through(h_nxt + k4_index(u, m, Mp), h);
 }
 
+template <bool LM>
 __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict__ R, const float *__restrict__ G,
                                                         const float *__restrict__ h_cur,
                                                         const float *__restrict__ c_cur, float *__restrict__ h_nxt,
@@ -1578,13 +1600,15 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
                                                         const int *__restrict__ tok, int M, int Mp, int P,
                                                         const int *done, LmRowsArgs lmr, float *pre_clear,
                                                         int n_pre_clear) {
-  if (lmr.M > 0 && (int)blockIdx.x >= lmr.first_block) {
-    // (vocabularies whose row would take the projection launch's LDS: the rows ride here instead)
-    extern __shared__ float lm_row[];
-    __shared__ LmRowScratch lm_sc;
-    if (*reinterpret_cast<const volatile int *>(done)) return;
-    lm_row_block(lmr.view, lmr.ctx, lmr.len, lmr.out, (int)blockIdx.x - lmr.first_block, lm_row, lm_sc);
-    return;
+  if constexpr (LM) {  // (an instantiation of its own: the plain launch is faster without this code in it)
+    if (lmr.M > 0 && (int)blockIdx.x >= lmr.first_block) {
+      // (vocabularies whose row would take the projection launch's LDS: the rows ride here instead)
+      extern __shared__ float lm_row[];
+      __shared__ LmRowScratch lm_sc;
+      if (*reinterpret_cast<const volatile int *>(done)) return;
+      lm_row_block(lmr.view, lmr.ctx, lmr.len, lmr.out, (int)blockIdx.x - lmr.first_block, lm_row, lm_sc);
+      return;
+    }
   }
   const int gid = blockIdx.x * 256 + threadIdx.x;
   // (the projection launch that follows adds its two halves into pre: cleared here, n_pre_clear = 0 otherwise)
@@ -1664,10 +1688,13 @@ __device__ __forceinline__ void pred_proj_tile(const PredProjArgs &a, int tile, 
     store_through(a.pre + k4_index(o0 + q, me, a.Mp), tile_value<WAVES>(red, (tid % LPH) * VPL + q, j) + bv[q] + fv[q]);
 }
 
-template <int WAVES, int ITERS>
+// LM: the launch carries LM rows (an instantiation of its own: the test for them costs the plain launch 0.26 us)
+template <int WAVES, int ITERS, bool LM = false>
 __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
   __shared__ float red[WAVES * 64 * kRedStride];
-  if (pred_proj_lm_block(a)) return;
+  if constexpr (LM) {
+    if (pred_proj_lm_block(a)) return;
+  }
   int tile, mtile;
   const int role = xcd_item(a.map, blockIdx.x, tile, mtile);
   if (role < 0) return;
@@ -1686,12 +1713,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
 // on which block comes first.  Half the operands and half the matrix instructions per block: 3.0 instead of 4.8 us.
 // No recurrent tiles ride in this launch (they would set its duration); the main launch takes them all.
 // ITERS = P / 2 / WAVES / 8.
-template <int WAVES, int ITERS>
+template <int WAVES, int ITERS, bool LM = false>
 __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
   __shared__ float red[WAVES * 64 * kRedStride];
   constexpr int LPH = 2 * WAVES, VPL = 32 / LPH;
   const int tid = threadIdx.x, lane = tid & 63, col = lane & 31;
-  if (pred_proj_lm_block(a)) return;
+  if constexpr (LM) {
+    if (pred_proj_lm_block(a)) return;
+  }
   int tile, item;
   if (xcd_item(a.map, blockIdx.x, tile, item) != 0) return;
   const int mtile = item >> 1, half = item & 1;

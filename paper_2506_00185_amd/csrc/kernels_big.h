@@ -569,6 +569,8 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
 // it collected and ranked by counting).
 constexpr int kUttSurvivorCap = 128;
 
+// FORMS: 4, or 12 for AES++ on a plain RNN-T (see select_dispatch)
+template <int FORMS>
 __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
   __shared__ SelectScratchWide scratch;
   __shared__ uint64_t l_cand[kMaxBeam * kMaxBeam];
@@ -686,7 +688,7 @@ __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
       }
   }
   __syncthreads();
-  if (wave == 0) select_dispatch<4, SelectScratchWide>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
+  if (wave == 0) select_dispatch<FORMS, SelectScratchWide>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
   __syncthreads();
   // activations of the utterance's new hypotheses, from the selection's scratch (frame, token history)
   const int T_b = a.pre.lengths[b];

@@ -242,7 +242,7 @@ bool proj_split(const rnnt_config_t &c, int M) {
 // recurrent blocks run beside the joint blocks there, off the critical path.  (The kernels' fully unrolled form only.)
 int recurrent_group(const rnnt_config_t &c, int M) {
   const int m_tiles = (M + 31) / 32;
-  if (c.P != 640 || m_tiles < 8) return 1;
+  if (c.pred != RNNT_PRED_LSTM || c.P != 640 || c.H != 640 || m_tiles < 8) return 1;
   return m_tiles == 8 ? 4 : 2;
 }
 int recurrent_items(const rnnt_config_t &c, int M) {
@@ -488,7 +488,8 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
         lds = lm_row_bytes;
       }
       const bool split = proj_split(c, p.M);
-      hipLaunchKernelGGL(k_lstm_pointwise, dim3(n_blocks + lmr.M), dim3(256), lds, s, w.Rgates, h->G, w.h[cur],
+      auto k_cell = lmr.M ? k_lstm_pointwise<true> : k_lstm_pointwise<false>;
+      hipLaunchKernelGGL(k_cell, dim3(n_blocks + lmr.M), dim3(256), lds, s, w.Rgates, h->G, w.h[cur],
                          w.c[cur], w.h[cur ^ 1], w.c[cur ^ 1], w.src_row, w.tok, p.M, w.Mp, c.P, done, lmr,
                          split ? w.pre : nullptr, split ? c.H * w.Mp : 0);
     }
@@ -518,14 +519,24 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
         lds = lm_row_bytes;
       }
       const dim3 grid(n_tiles + a.lmr.M);
-#define RB_PRED(W, I) hipLaunchKernelGGL((k_pred_proj<W, I>), grid, dim3(W * 64), lds, s, a)
+#define RB_PRED(W, I)                                                                                        \
+  do {                                                                                                       \
+    if (a.lmr.M) hipLaunchKernelGGL((k_pred_proj<W, I, true>), grid, dim3(W * 64), lds, s, a);              \
+    else hipLaunchKernelGGL((k_pred_proj<W, I, false>), grid, dim3(W * 64), 0, s, a);                        \
+  } while (0)
+#define RB_PRED_HALF(I)                                                                                      \
+  do {                                                                                                       \
+    if (a.lmr.M) hipLaunchKernelGGL((k_pred_proj_half<8, I, true>), grid, dim3(512), lds, s, a);            \
+    else hipLaunchKernelGGL((k_pred_proj_half<8, I, false>), grid, dim3(512), 0, s, a);                      \
+  } while (0)
       if (proj_split(c, p.M)) {
-        if (c.P == 640) hipLaunchKernelGGL((k_pred_proj_half<8, 5>), grid, dim3(512), lds, s, a);
-        else hipLaunchKernelGGL((k_pred_proj_half<8, 0>), grid, dim3(512), lds, s, a);
+        if (c.P == 640) RB_PRED_HALF(5);
+        else RB_PRED_HALF(0);
       }
       else if (c.P == 640) RB_PRED(8, 10);
       else if (c.P % 64 == 0) RB_PRED(8, 0);
       else RB_PRED(4, 0);
+#undef RB_PRED_HALF
 #undef RB_PRED
     }
   } else if (p.big) {
@@ -665,7 +676,12 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       const dim3 grid(p.M), block(64 * kRowWaves);
       if (big_tail(h, p)) {
         if (a.lm) hipLaunchKernelGGL((k_row_select<true, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL(k_utt_select, dim3(p.B), dim3(64 * p.K), 0, s, a);  // one block per utterance
+        else {  // one block per utterance
+          const bool plain_aes = c.n_durations == 0 && p.algo == RNNT_AES && !std::isfinite(c.prune_margin) &&
+                                 !c.aes_prefix_search;  // (no LM on this branch)
+          auto k_sel = plain_aes ? k_utt_select<12> : k_utt_select<4>;
+          hipLaunchKernelGGL(k_sel, dim3(p.B), dim3(64 * p.K), 0, s, a);
+        }
       } else {
         if (a.lm) hipLaunchKernelGGL((k_row_select<false, false>), grid, block, 0, s, a);
         else hipLaunchKernelGGL((k_row_select<false, true>), grid, block, 0, s, a);
@@ -721,9 +737,27 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     if (tail) hipLaunchKernelGGL((k_step_main<W, I, true>), grid, dim3(W * 64), 0, s, a);         \
     else hipLaunchKernelGGL((k_step_main<W, I, false>), grid, dim3(W * 64), 0, s, a);             \
   } while (0)
+    const bool wide = fold || a.rec.group > 1;  // (both only with the fully unrolled form below)
     {
       ScopedKernelTime tm(h, s, KT_JOINT);
-      if (c.H == 640 && (!lstm || c.P == 640)) RB_MAIN(8, 10);
+      const bool full = c.H == 640 && (!lstm || c.P == 640);  // the fully unrolled form
+      // one selection form in the kernel where the shape is one of the two common ones (a third of the code)
+      // (11: form 5 for ALSD++ on a plain RNN-T, i.e. without durations and LM)
+      const bool plain = c.n_durations == 0 && !p.lm && p.algo == RNNT_ALSD;
+      const int sel = !(full && tail) ? 0 : (p.K > 2 && p.K <= 4 && a.n_chunks <= 48) ? (plain ? 11 : 5)
+                                          : (p.K > 4 && p.K <= 8 && a.n_chunks <= 40) ? 6 : 0;
+#define RB_MAIN_SEL(WIDE)                                                                                   \
+  do {                                                                                                      \
+    if (sel == 11) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 11>), grid, dim3(512), 0, s, a);      \
+    else if (sel == 5) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 5>), grid, dim3(512), 0, s, a);   \
+    else if (sel == 6) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 6>), grid, dim3(512), 0, s, a);   \
+    else hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 0>), grid, dim3(512), 0, s, a);                 \
+  } while (0)
+      if (wide && tail) RB_MAIN_SEL(true);
+      else if (wide) hipLaunchKernelGGL((k_step_main<8, 10, false, true>), grid, dim3(512), 0, s, a);
+      else if (full && tail) RB_MAIN_SEL(false);
+      else if (full) RB_MAIN(8, 10);
+#undef RB_MAIN_SEL
       else if (c.H % 64 == 0 && (!lstm || c.P % 64 == 0)) RB_MAIN(8, 0);
       else RB_MAIN(4, 0);
     }
