@@ -1025,8 +1025,14 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scra
     }
   } else if constexpr (FORMS == 5) {  // one form alone (the caller has checked 2 < K <= 4, n_chunks <= 48) ...
     select_utterance<16, 3, 4>(a, b, s, cv);
-  } else if constexpr (FORMS == 11) {  // ... the same for ALSD++ on a plain RNN-T (no durations, no LM)
+  } else if constexpr (FORMS == 11) {  // ... the same for ALSD++ on a plain RNN-T (no durations, no LM): beams 3, 4,
     select_utterance<16, 3, 4, false, false, Scratch, false, 1>(a, b, s, cv);
+  } else if constexpr (FORMS == 13) {  // ... 1, 2 (n_chunks <= 48),
+    select_utterance<16, 3, 2, false, false, Scratch, false, 1>(a, b, s, cv);
+  } else if constexpr (FORMS == 14) {  // ... 5 to 8 (n_chunks <= 40);
+    select_utterance<8, 5, 8, false, false, Scratch, false, 1>(a, b, s, cv);
+  } else if constexpr (FORMS == 15) {  // AES++ without prune margin and prefix search on a plain RNN-T, beams 3, 4
+    select_utterance<16, 3, 4, false, false, Scratch, false, 2>(a, b, s, cv);
   } else if constexpr (FORMS == 6) {  // ... (4 < K <= 8, n_chunks <= 40): a kernel a third the size
     select_utterance<8, 5, 8>(a, b, s, cv);
   } else if constexpr (FORMS == 2) {

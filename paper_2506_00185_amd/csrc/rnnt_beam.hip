@@ -744,11 +744,17 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       // one selection form in the kernel where the shape is one of the two common ones (a third of the code)
       // (11: form 5 for ALSD++ on a plain RNN-T, i.e. without durations and LM)
       const bool plain = c.n_durations == 0 && !p.lm && p.algo == RNNT_ALSD;
-      const int sel = !(full && tail) ? 0 : (p.K > 2 && p.K <= 4 && a.n_chunks <= 48) ? (plain ? 11 : 5)
-                                          : (p.K > 4 && p.K <= 8 && a.n_chunks <= 40) ? 6 : 0;
+      const bool plain_aes = c.n_durations == 0 && !p.lm && p.algo == RNNT_AES && !std::isfinite(c.prune_margin) &&
+                             !c.aes_prefix_search;
+      const int sel = !(full && tail) ? 0 : (p.K <= 2 && a.n_chunks <= 48 && plain) ? 13
+                                          : (p.K > 2 && p.K <= 4 && a.n_chunks <= 48) ? (plain ? 11 : plain_aes ? 15 : 5)
+                                          : (p.K > 4 && p.K <= 8 && a.n_chunks <= 40) ? (plain ? 14 : 6) : 0;
 #define RB_MAIN_SEL(WIDE)                                                                                   \
   do {                                                                                                      \
     if (sel == 11) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 11>), grid, dim3(512), 0, s, a);      \
+    else if (sel == 13) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 13>), grid, dim3(512), 0, s, a); \
+    else if (sel == 14) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 14>), grid, dim3(512), 0, s, a); \
+    else if (sel == 15) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 15>), grid, dim3(512), 0, s, a); \
     else if (sel == 5) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 5>), grid, dim3(512), 0, s, a);   \
     else if (sel == 6) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 6>), grid, dim3(512), 0, s, a);   \
     else hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 0>), grid, dim3(512), 0, s, a);                 \

@@ -211,6 +211,8 @@ def test_config1_tiny(amd, oracle, algo, beam):
                             durations=(0, 1, 2, 3, 4))),
     ("tdt_alsd", dict(B=4, T=30, T_min=10, beam=5, s=2, algo="alsd", model="tdt", durations=(0, 1, 2, 3, 4))),
     ("beam16", dict(B=3, T=12, T_min=6, beam=16, s=2, algo="alsd")),
+    ("rnnt_alsd_beam2", dict(B=5, T=16, T_min=6, beam=2, s=3, algo="alsd")),
+    ("rnnt_alsd_beam1", dict(B=4, T=16, T_min=6, beam=1, s=3, algo="alsd")),
 ])
 def test_full_width_model_small_batch(amd, oracle, name, kw):
     """Real layer widths (V = 1024 + blank spans 33 column chunks with a ragged tail), small batch."""
