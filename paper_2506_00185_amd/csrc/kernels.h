@@ -1005,11 +1005,12 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
 // registers).  The heavy forms are kept out of the kernels that do not need them.
 template <int FORMS, class Scratch = SelectScratch>
 __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
-  if constexpr (FORMS == 12) {  // FORMS == 4 for AES++ on a plain RNN-T (no durations, LM, prune margin, prefix search)
-    if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true, 2>(a, b, s, cv);
-    else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true, 2>(a, b, s, cv);
-    else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true, 2>(a, b, s, cv);
-    else select_utterance<4, 1, 16, false, false, Scratch, true, 2>(a, b, s, cv);
+  if constexpr (FORMS == 12 || FORMS == 16) {  // FORMS == 4 on a plain RNN-T (no durations, no LM): 12 for AES++
+    constexpr int P = FORMS == 12 ? 2 : 1;      // without prune margin and prefix search, 16 for ALSD++
+    if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true, P>(a, b, s, cv);
+    else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true, P>(a, b, s, cv);
+    else if (a.K <= 12) select_utterance<4, 1, 12, false, false, Scratch, true, P>(a, b, s, cv);
+    else select_utterance<4, 1, 16, false, false, Scratch, true, P>(a, b, s, cv);
   } else if constexpr (FORMS == 4) {  // one list per hypothesis (the materialised-logits path), any beam
     if (a.K <= 4) select_utterance<16, 1, 4, false, false, Scratch, true>(a, b, s, cv);
     else if (a.K <= 8) select_utterance<8, 1, 8, false, false, Scratch, true>(a, b, s, cv);
@@ -1443,6 +1444,7 @@ struct MergeSelectArgs {
 };
 constexpr int kMergeHeads = 8, kMergeCap = 128;
 
+template <int FORMS>  // 4, or 12 / 16 on a plain RNN-T (see select_dispatch)
 __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_merge_select(MergeSelectArgs a) {
   __shared__ SelectScratchWide scratch;
   __shared__ uint64_t l_cand[kMaxBeam * kMaxBeam];
@@ -1549,7 +1551,7 @@ __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_merge_select(MergeSelectA
     }
   }
   __syncthreads();
-  if (wave == 0) select_dispatch<4, SelectScratchWide>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
+  if (wave == 0) select_dispatch<FORMS, SelectScratchWide>(a.sel, b, scratch, CandView{l_cand, l_max, l_sum, l_zs, b * K});
 }
 
 // ---------------------------------------------------------------------------

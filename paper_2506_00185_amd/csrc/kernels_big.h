@@ -569,7 +569,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void k_row_select(RowSelectArgs a) 
 // it collected and ranked by counting).
 constexpr int kUttSurvivorCap = 128;
 
-// FORMS: 4, or 12 for AES++ on a plain RNN-T (see select_dispatch)
+// FORMS: 4, or 12 / 16 for AES++ / ALSD++ on a plain RNN-T (see select_dispatch)
 template <int FORMS>
 __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
   __shared__ SelectScratchWide scratch;

@@ -458,6 +458,15 @@ void fill_stateless_pre_big(rnnt_beam *h, const StepPlan &p, int bump, Stateless
   a.done = w.ctrl + 1; a.step_base = w.ctrl + 2; a.bump = bump;
 }
 
+// One-list selection forms: 16 / 12 for ALSD++ / AES++ (without prune margin and prefix search) on a plain RNN-T
+// (no durations, no LM), else the general 4.
+int plain_forms(const rnnt_beam *h, const StepPlan &p) {
+  const rnnt_config_t &c = h->cfg;
+  if (c.n_durations != 0 || p.lm) return 4;
+  if (p.algo == RNNT_ALSD) return 16;
+  return (!std::isfinite(c.prune_margin) && !c.aes_prefix_search) ? 12 : 4;
+}
+
 // fuse_lm: the LM rows of the new hypotheses ride in the projection launch, or in the cell-update launch when
 // the row is too large to sit in LDS beside the projection's tiles (LSTM models only; the caller then skips the
 // stand-alone LM launch)
@@ -606,7 +615,9 @@ void launch_select(rnnt_beam *h, hipStream_t s, const StepPlan &p, const SelectA
     ma.sel = sa;
     ma.sel.n_chunks = 1;
     ma.n_lists = n_chunks;
-    hipLaunchKernelGGL(k_utt_merge_select, dim3(p.B), dim3(64 * p.K), 0, s, ma);
+    const int forms = plain_forms(h, p);
+    auto k_sel = forms == 16 ? k_utt_merge_select<16> : forms == 12 ? k_utt_merge_select<12> : k_utt_merge_select<4>;
+    hipLaunchKernelGGL(k_sel, dim3(p.B), dim3(64 * p.K), 0, s, ma);
   } else if (select_needs_wide_forms(p.K, n_chunks)) hipLaunchKernelGGL(k_select_wide, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
   else hipLaunchKernelGGL(k_select, dim3((p.B + 3) / 4), dim3(256), 0, s, sa);
 }
@@ -677,9 +688,8 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       if (big_tail(h, p)) {
         if (a.lm) hipLaunchKernelGGL((k_row_select<true, false>), grid, block, 0, s, a);
         else {  // one block per utterance
-          const bool plain_aes = c.n_durations == 0 && p.algo == RNNT_AES && !std::isfinite(c.prune_margin) &&
-                                 !c.aes_prefix_search;  // (no LM on this branch)
-          auto k_sel = plain_aes ? k_utt_select<12> : k_utt_select<4>;
+          const int forms = plain_forms(h, p);
+          auto k_sel = forms == 16 ? k_utt_select<16> : forms == 12 ? k_utt_select<12> : k_utt_select<4>;
           hipLaunchKernelGGL(k_sel, dim3(p.B), dim3(64 * p.K), 0, s, a);
         }
       } else {
