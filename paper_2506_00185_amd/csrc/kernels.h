@@ -4,6 +4,8 @@
 // log-probabilities are injected; a stand-alone k_select / k_select_wide / k_select_pairs where the tail cannot
 // take the selection), and k_gemm_tiled (gemm.h) / k_init / k_backtrace run once per decode call.
 #pragma once
+#include <type_traits>
+
 #include "device_utils.h"
 #include "lm_device.h"
 
@@ -1162,13 +1164,19 @@ __device__ __forceinline__ void recurrent_tiles(const RecurrentArgs &a, int tile
   }
   if (done) return;
   const int j = tid / LPH, i0 = (tid % LPH) * VPL;
+  // one slot tile; G copies of this code, each with its register set known at compile time (a loop over g that can
+  // end early is kept as a loop by the compiler, with the next tile's loads waited for one by one inside it).
+  // (Reading the previous tile's sums back beside this tile's matrix instructions, from a second buffer, was slower:
+  // its stores then sit between the loads in the order that the wait counts follow.)
+  auto one_tile = [&](auto g_const) {
+    constexpr int g = decltype(g_const)::value;
+    if (g >= n_mt) return;
+    if constexpr (g + 1 < G) {
+      if (g + 1 < n_mt) {
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    if (g >= n_mt) break;
-    if (g + 1 < G && g + 1 < n_mt) {
-#pragma unroll
-      for (int i = 0; i < ITERS; ++i)
-        hb[(g + 1) & 1][i] = *reinterpret_cast<const float4 *>(hp + (size_t)(g + 1) * 32 * 4 + (size_t)(2 * i) * Mp * 4);
+        for (int i = 0; i < ITERS; ++i)
+          hb[(g + 1) & 1][i] = *reinterpret_cast<const float4 *>(hp + (size_t)(g + 1) * 32 * 4 + (size_t)(2 * i) * Mp * 4);
+      }
     }
     __builtin_amdgcn_sched_barrier(0);  // the next tile's loads are under way before the first matrix instruction
     floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -1191,7 +1199,12 @@ __device__ __forceinline__ void recurrent_tiles(const RecurrentArgs &a, int tile
       for (int q = 0; q < VPL; ++q)
         store_through(a.R + (size_t)m * R4 + tile * 32 + i0 + q, tile_value<WAVES>(red, i0 + q, j));
     }
-  }
+  };
+  static_assert(G == 4, "four copies below");
+  one_tile(std::integral_constant<int, 0>{});
+  one_tile(std::integral_constant<int, 1>{});
+  one_tile(std::integral_constant<int, 2>{});
+  one_tile(std::integral_constant<int, 3>{});
 }
 
 struct MainArgs {

@@ -658,7 +658,7 @@ __global__ __launch_bounds__(64 * kMaxBeam) void k_utt_select(RowSelectArgs a) {
   }
   // blank and duration logits from the bf16 activations: z[V + d] = Wspec[d] . a_m + bias; a lane takes 8 k at a time
   {
-    const int nz = 1 + a.ND;
+    const int nz = (FORMS == 12 || FORMS == 16) ? 1 : 1 + a.ND;  // (the plain forms: no durations)
     float acc[9];
 #pragma unroll
     for (int d = 0; d < 9; ++d) acc[d] = 0.f;
