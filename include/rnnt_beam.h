@@ -201,7 +201,8 @@ int rnnt_beam_decode_static(rnnt_beam_t *h, const float *enc, const int32_t *len
                             void *hip_stream);
 
 /*
- * Wait for the last decode and copy its n-best lists to host memory.  The transcripts are read off the
+ * Wait for the last decode and copy its n-best lists to host memory (the decode itself ends with one device-to-host
+ * copy of them into pinned memory of the handle; this call waits for it and copies from there).  The transcripts are read off the
  * hypothesis tree by following the parent pointers back from the final slots (Sec. 2.1, "Efficient
  * hypothesis storing"); no length normalisation is applied.  Host arrays, caller-owned: tokens [B, beam, cap]
  * (positions beyond the length are left untouched; transcripts longer than cap are truncated),

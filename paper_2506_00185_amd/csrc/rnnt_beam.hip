@@ -82,6 +82,22 @@ struct Workspace {
   int Mp = 0, S_max = 0, cap = 0, pc_chunks = 0, max_B = 0;
 };
 
+// The n-best lists of one decode of the handle's own workspace, packed behind the control words (ctrl is the slot
+// before out_tokens in the layout), so that one copy brings flags and results to the host: byte offsets from ctrl.
+struct OutPack {
+  size_t steps, lens, scores, tokens, bytes;
+};
+OutPack out_pack(int B, int K, int cap) {
+  OutPack o;
+  const size_t M = (size_t)B * K;
+  o.steps = 256;  // (ctrl's slot)
+  o.lens = o.steps + ((size_t)B * 4 + 7) / 8 * 8;
+  o.scores = o.lens + (M * 4 + 7) / 8 * 8;
+  o.tokens = o.scores + M * 8;
+  o.bytes = o.tokens + M * (size_t)cap * 4;
+  return o;
+}
+
 // Assigns the pointers of `w` inside [base, ..) for a model `c` and the maxima given, every array on a 256-byte
 // boundary, and returns the bytes needed.  base == nullptr: only the size is computed.  with_out: room for the
 // n-best lists too.  big: the arrays of the materialised-logits path (Npad_big columns, Hb padded k).
@@ -162,6 +178,9 @@ struct rnnt_beam {
   PersistCtl *pctl = nullptr;  // counters of the single-launch step loop
   int n_cus = 0, spin_limit = kSpinLimit;
   bool last_persistent = false;
+  char *h_out = nullptr;          // pinned: the last decode's control words and packed results (see out_pack)
+  size_t h_out_bytes = 0;
+  OutPack last_out{};
   int *h_done = nullptr, *h_done_dev = nullptr;  // pinned host word and its device alias
   // last decode
   bool have_result = false;
@@ -975,9 +994,20 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     a.cap = p.out_cap ? p.out_cap : w.cap;
     const size_t lds = (size_t)w.S_max * p.K * 2 * sizeof(int);
     a.out_tokens = w.out_tokens; a.out_lens = w.out_lens; a.out_scores = w.out_scores; a.out_steps = w.out_steps;
+    const bool own = p.ws == &h->ws;  // (the allocation-free entry point writes to the caller's arrays)
+    if (own) {
+      h->last_out = out_pack(p.B, p.K, a.cap);
+      char *base = reinterpret_cast<char *>(w.ctrl);
+      a.out_steps = reinterpret_cast<int *>(base + h->last_out.steps);
+      a.out_lens = reinterpret_cast<int *>(base + h->last_out.lens);
+      a.out_scores = reinterpret_cast<double *>(base + h->last_out.scores);
+      a.out_tokens = reinterpret_cast<int *>(base + h->last_out.tokens);
+    }
     ScopedKernelTime tm(h, s, KT_BACKTRACE);
     if (lds <= 64 * 1024) hipLaunchKernelGGL(k_backtrace<true>, dim3(p.B), dim3(kBacktraceThreads), lds, s, a);
     else hipLaunchKernelGGL(k_backtrace<false>, dim3(p.B), dim3(kBacktraceThreads), 0, s, a);
+    // flags and results to pinned host memory in one copy behind the back-trace: rnnt_beam_results then only waits
+    if (own) RB_HIP(h, hipMemcpyAsync(h->h_out, w.ctrl, h->last_out.bytes, hipMemcpyDeviceToHost, s));
   }
   RB_HIP(h, hipGetLastError());
   RB_HIP(h, hipEventRecord(h->ev_end, s));
@@ -1104,6 +1134,8 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
   if (!rc) {
     hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&h->h_done), 64, hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&h->h_done_dev), h->h_done, 0);
+    h->h_out_bytes = out_pack(c.max_B, c.max_beam, h->ws.cap).bytes;
+    if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&h->h_out), h->h_out_bytes, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
     for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&h->ev_chunk[i]);
@@ -1237,18 +1269,18 @@ int rnnt_beam_results(rnnt_beam_t *h, int32_t *tokens, int32_t cap, int32_t *len
   RB_HIP(h, hipStreamSynchronize(h->last_stream));
   const Workspace &w = h->ws;
   const int B = h->last_B, K = h->last_K;
-  int flags[2] = {0, 0};
-  RB_HIP(h, hipMemcpy(flags, w.ctrl + 3, sizeof(flags), hipMemcpyDeviceToHost));
-  if (lens) RB_HIP(h, hipMemcpy(lens, w.out_lens, sizeof(int) * B * K, hipMemcpyDeviceToHost));
-  if (scores) RB_HIP(h, hipMemcpy(scores, w.out_scores, sizeof(double) * B * K, hipMemcpyDeviceToHost));
-  if (n_steps) RB_HIP(h, hipMemcpy(n_steps, w.out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
+  // (the decode left flags and results in pinned memory, see run_decode)
+  const OutPack &o = h->last_out;
+  const int *flags = reinterpret_cast<const int *>(h->h_out) + 3;
+  const int *p_lens = reinterpret_cast<const int *>(h->h_out + o.lens);
+  if (lens) memcpy(lens, p_lens, sizeof(int) * B * K);
+  if (scores) memcpy(scores, h->h_out + o.scores, sizeof(double) * B * K);
+  if (n_steps) memcpy(n_steps, h->h_out + o.steps, sizeof(int) * B);
   if (tokens && cap > 0) {
-    std::vector<int> buf((size_t)B * K * w.cap), ln((size_t)B * K);
-    RB_HIP(h, hipMemcpy(buf.data(), w.out_tokens, sizeof(int) * buf.size(), hipMemcpyDeviceToHost));
-    RB_HIP(h, hipMemcpy(ln.data(), w.out_lens, sizeof(int) * ln.size(), hipMemcpyDeviceToHost));
-    for (size_t i = 0; i < ln.size(); ++i) {
-      const int n = ln[i] < cap ? ln[i] : cap;
-      for (int u = 0; u < n; ++u) tokens[i * cap + u] = buf[i * w.cap + u];
+    const int *buf = reinterpret_cast<const int *>(h->h_out + o.tokens);
+    for (size_t i = 0; i < (size_t)B * K; ++i) {
+      const int n = p_lens[i] < cap ? p_lens[i] : cap;
+      if (n > 0) memcpy(tokens + i * cap, buf + i * w.cap, sizeof(int) * n);
     }
   }
   if (h->last_persistent) {
@@ -1273,7 +1305,7 @@ int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t
   const Workspace &w = h->ws;
   const int B = h->last_B, K = h->last_K;
   std::vector<int> steps(B);
-  RB_HIP(h, hipMemcpy(steps.data(), w.out_steps, sizeof(int) * B, hipMemcpyDeviceToHost));
+  memcpy(steps.data(), h->h_out + h->last_out.steps, sizeof(int) * B);
   const int *src[3] = {w.tree_parent, w.tree_token, w.tree_merged};
   int32_t *dst[3] = {parent, token, merged_into};
   std::vector<int> buf((size_t)w.S_max * K);
@@ -1371,6 +1403,7 @@ void rnnt_beam_destroy(rnnt_beam_t *h) {
   for (auto &kv : h->graphs) hipGraphExecDestroy(kv.second.first);
   for (void *p : h->allocs) hipFree(p);
   if (h->h_done) hipHostFree(h->h_done);
+  if (h->h_out) hipHostFree(h->h_out);
   hipEvent_t evs[] = {h->ev_begin, h->ev_end, h->ev_chunk[0], h->ev_chunk[1], h->ev_chunk[2], h->ev_chunk[3]};
   for (hipEvent_t e : h->prof_events) hipEventDestroy(e);
   for (hipEvent_t e : evs)
