@@ -775,9 +775,12 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       const bool plain = c.n_durations == 0 && !p.lm && p.algo == RNNT_ALSD;
       const bool plain_aes = c.n_durations == 0 && !p.lm && p.algo == RNNT_AES && !std::isfinite(c.prune_margin) &&
                              !c.aes_prefix_search;
-      const int sel = !(full && tail) ? 0 : (p.K <= 2 && a.n_chunks <= 48 && plain) ? 13
-                                          : (p.K > 2 && p.K <= 4 && a.n_chunks <= 48) ? (plain ? 11 : plain_aes ? 15 : 5)
-                                          : (p.K > 4 && p.K <= 8 && a.n_chunks <= 40) ? (plain ? 14 : 6) : 0;
+      const int sel_any = !tail ? 0 : (p.K <= 2 && a.n_chunks <= 48 && plain) ? 13
+                                    : (p.K > 2 && p.K <= 4 && a.n_chunks <= 48) ? (plain ? 11 : plain_aes ? 15 : 5)
+                                    : (p.K > 4 && p.K <= 8 && a.n_chunks <= 40) ? (plain ? 14 : 6) : 0;
+      const int sel = full ? sel_any : 0;
+      // (the kernels for other widths: the ALSD++ forms for a plain RNN-T only)
+      const int sel_gen = (sel_any == 11 || sel_any == 13 || sel_any == 14) ? sel_any : 0;
 #define RB_MAIN_SEL(WIDE)                                                                                   \
   do {                                                                                                      \
     if (sel == 11) hipLaunchKernelGGL((k_step_main<8, 10, true, WIDE, 11>), grid, dim3(512), 0, s, a);      \
@@ -793,8 +796,16 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       else if (full && tail) RB_MAIN_SEL(false);
       else if (full) RB_MAIN(8, 10);
 #undef RB_MAIN_SEL
-      else if (c.H % 64 == 0 && (!lstm || c.P % 64 == 0)) RB_MAIN(8, 0);
-      else RB_MAIN(4, 0);
+#define RB_MAIN_GEN(W)                                                                                       \
+  do {                                                                                                       \
+    if (sel_gen == 11) hipLaunchKernelGGL((k_step_main<W, 0, true, false, 11>), grid, dim3(W * 64), 0, s, a); \
+    else if (sel_gen == 13) hipLaunchKernelGGL((k_step_main<W, 0, true, false, 13>), grid, dim3(W * 64), 0, s, a); \
+    else if (sel_gen == 14) hipLaunchKernelGGL((k_step_main<W, 0, true, false, 14>), grid, dim3(W * 64), 0, s, a); \
+    else RB_MAIN(W, 0);                                                                                      \
+  } while (0)
+      else if (c.H % 64 == 0 && (!lstm || c.P % 64 == 0)) RB_MAIN_GEN(8);
+      else RB_MAIN_GEN(4);
+#undef RB_MAIN_GEN
     }
 #undef RB_MAIN
     if (!tail) {
