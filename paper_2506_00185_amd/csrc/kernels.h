@@ -241,6 +241,7 @@ struct SelectArgs {
   // configuration
   int B, K, V, ND;
   int dur[8];
+  uint64_t dur_bytes;   // the same, one byte each (durations are at most 255): one scalar register pair instead of eight
   int algo, max_sym;
   float gamma;
   int has_lm;
@@ -414,7 +415,7 @@ __device__ __forceinline__ void rank_by_counting_n(const double *keys, const int
 // ONE: every hypothesis comes with exactly one list (n_chunks == 1, NCH == 1), known at compile time: the merge
 // of list heads and its registers drop out.
 template <int LPR, int NCH, int KMAX, bool MULTI = false, bool PAIRS = false, class Scratch = SelectScratch,
-          bool ONE = false, int PLAIN = 0>
+          bool ONE = false, int PLAIN = 0, bool DYNDUR = false>
 __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scratch &s, const CandView cv) {
   const int K = a.K, V = a.V, lane = threadIdx.x & 63;
   // PLAIN (the caller has checked): 1 = ALSD++, 2 = AES++ without prune margin and prefix search, both without
@@ -586,23 +587,70 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
     double x_tok = 0.0, x_blank = 0.0;
     int adv_tok = 0, adv_blank = 1;
     if (a_ND > 0) {
-      if (!a.normalized) {
-        float dmx = -INFINITY, sm = 0.f;
-        for (int d = 0; d < a_ND; ++d) dmx = fmaxf(dmx, dl[d]);
-        for (int d = 0; d < a_ND; ++d) sm += __expf(dl[d] - dmx);
-        const float l = dmx + __logf(sm);
-        for (int d = 0; d < a_ND; ++d) dl[d] -= l;
-      }
-      int best = -1, best_b = -1;
-      for (int d = 0; d < a_ND; ++d) {
-        if (best < 0 || dl[d] > dl[best]) best = d;
-        if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
-      }
-      if constexpr (!PAIRS) {  // one duration per candidate: the most likely one (for blank: that advances)
-        x_tok = (double)dl[best];
-        x_blank = (double)dl[best_b];
-        adv_tok = a.dur[best];
-        adv_blank = a.dur[best_b];
+      if constexpr (DYNDUR) {
+        // The form with indices computed at run time (every access a dependent load: 2.4 us at five durations).  Kept
+        // for the main kernel's instantiation for 256 slots and more, where the selection is not what the launch
+        // waits for and the kernel as a whole came out 0.9 us SLOWER with the form below (its joint blocks end 0.8 us
+        // later: the compiler's placement of the whole kernel, not this block's own time).
+        if (!a.normalized) {
+          float dmx = -INFINITY, sm = 0.f;
+          for (int d = 0; d < a_ND; ++d) dmx = fmaxf(dmx, dl[d]);
+          for (int d = 0; d < a_ND; ++d) sm += __expf(dl[d] - dmx);
+          const float l = dmx + __logf(sm);
+          for (int d = 0; d < a_ND; ++d) dl[d] -= l;
+        }
+        int best = -1, best_b = -1;
+        for (int d = 0; d < a_ND; ++d) {
+          if (best < 0 || dl[d] > dl[best]) best = d;
+          if (a.dur[d] >= 1 && (best_b < 0 || dl[d] > dl[best_b])) best_b = d;
+        }
+        if constexpr (!PAIRS) {
+          x_tok = (double)dl[best];
+          x_blank = (double)dl[best_b];
+          adv_tok = a.dur[best];
+          adv_blank = a.dur[best_b];
+        }
+      } else {
+        // (every index into dl and a.dur below is a compile-time constant: an index computed at run time turns each
+        // access into a dependent load from memory, 2.4 us for this block at five durations)
+        if (!a.normalized) {
+          float dmx = -INFINITY, sm = 0.f;
+#pragma unroll
+          for (int d = 0; d < 8; ++d)
+            if (d < a_ND) dmx = fmaxf(dmx, dl[d]);
+#pragma unroll
+          for (int d = 0; d < 8; ++d)
+            if (d < a_ND) sm += __expf(dl[d] - dmx);
+          const float l = dmx + __logf(sm);
+#pragma unroll
+          for (int d = 0; d < 8; ++d)
+            if (d < a_ND) dl[d] -= l;
+        }
+        // the most likely duration (the first of equal ones), and the most likely one that advances
+        bool have = false, have_b = false;
+        float best_v = 0.f, best_bv = 0.f;
+        int best_adv = 0, best_badv = 1;
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+          if (d < a_ND) {
+            const int du = (int)((a.dur_bytes >> (8 * d)) & 0xff);
+            if (!have || dl[d] > best_v) {
+              have = true;
+              best_v = dl[d];
+              best_adv = du;
+            }
+            if (du >= 1 && (!have_b || dl[d] > best_bv)) {
+              have_b = true;
+              best_bv = dl[d];
+              best_badv = du;
+            }
+          }
+        if constexpr (!PAIRS) {  // one duration per candidate: the most likely one (for blank: that advances)
+          x_tok = (double)best_v;
+          x_blank = (double)best_bv;
+          adv_tok = best_adv;
+          adv_blank = best_badv;
+        }
       }
     }
     wave_sync();  // s.kind / s.score / s.sym are needed per row from here on
@@ -1026,6 +1074,10 @@ __device__ __forceinline__ void select_dispatch(const SelectArgs &a, int b, Scra
       if (a.n_chunks <= 8 * 5) select_utterance<8, 5, 8, false, true, Scratch>(a, b, s, cv);
       else select_utterance<8, 0, 8, false, true, Scratch>(a, b, s, cv);
     }
+  } else if constexpr (FORMS == 17) {  // forms 5 and 6 with the durations' older code (see select_utterance)
+    select_utterance<16, 3, 4, false, false, Scratch, false, 0, true>(a, b, s, cv);
+  } else if constexpr (FORMS == 18) {
+    select_utterance<8, 5, 8, false, false, Scratch, false, 0, true>(a, b, s, cv);
   } else if constexpr (FORMS == 5) {  // one form alone (the caller has checked 2 < K <= 4, n_chunks <= 48) ...
     select_utterance<16, 3, 4>(a, b, s, cv);
   } else if constexpr (FORMS == 11) {  // ... the same for ALSD++ on a plain RNN-T (no durations, no LM): beams 3, 4,
@@ -1415,7 +1467,8 @@ __global__ __launch_bounds__(WAVES * 64, TAIL ? 1 : 16 / WAVES) void k_step_main
   const int wave = tid >> 6;
   for (int u = wave; u < a.upt; u += WAVES) {
     const int b = ty * a.upt + u;
-    if (b < a.sel.B) select_dispatch<SEL>(a.sel, b, scratch[wave]);
+    constexpr int kForms = WIDE ? (SEL == 5 ? 17 : SEL == 6 ? 18 : SEL) : SEL;
+    if (b < a.sel.B) select_dispatch<kForms>(a.sel, b, scratch[wave]);
   }
   }  // TAIL
 }

@@ -607,7 +607,11 @@ void fill_select_args(rnnt_beam *h, const StepPlan &p, int step_off, int n_chunk
   a.normalized = p.inj_tok ? 1 : 0;
   a.use_ctx = (c.pred == RNNT_PRED_STATELESS || p.lm) ? 1 : 0;
   a.B = p.B; a.K = p.K; a.V = c.V; a.ND = c.n_durations;
-  for (int i = 0; i < 8; ++i) a.dur[i] = c.durations[i];
+  a.dur_bytes = 0;
+  for (int i = 0; i < 8; ++i) {
+    a.dur[i] = c.durations[i];
+    a.dur_bytes |= (uint64_t)(c.durations[i] & 0xff) << (8 * i);
+  }
   a.algo = p.algo;
   a.max_sym = c.max_symbols;
   a.gamma = c.prune_margin;
@@ -1078,6 +1082,7 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     bool adv = false;
     for (int i = 0; i < c.n_durations; ++i) {
       if (c.durations[i] < 0) return bad("negative duration");
+      if (c.durations[i] > 255) return bad("duration above 255 frames");
       adv |= c.durations[i] >= 1;
     }
     if (!adv) return bad("TDT needs a duration >= 1");
