@@ -78,7 +78,7 @@ typedef struct {
                                 to bfloat16; sums, soft-max and the LSTM stay float32 */
   int32_t D, H, P, E, V;     /* encoder dim, joint hidden, prediction hidden, embedding dim, tokens */
   int32_t n_durations;       /* TDT: number of duration classes (<= 8), else 0 */
-  int32_t durations[8];      /* TDT: frames advanced by each class, e.g. {0,1,2,3,4} */
+  int32_t durations[8];      /* TDT: frames advanced by each class, e.g. {0,1,2,3,4}; each in 0..255, one >= 1 */
   int32_t stateless_context; /* stateless prediction network: tokens of context (<= 4) */
   int32_t max_B, max_T, max_beam; /* workspace sizing */
   int32_t max_symbols;       /* s: most tokens a hypothesis may emit without leaving a frame

@@ -608,6 +608,9 @@ def test_error_paths(amd):
         dec.decode(to_gpu(enc, torch.float32), to_gpu(L, torch.int32), beam=3)  # beyond max_beam
     with pytest.raises(RnntBeamError):
         amd.BeamDecoder(dict(c, H=33), w)  # unsupported width
+    ct = S.custom_config(B=2, T=8, D=32, H=32, P=32, E=32, V=10, beam=2, s=2, model="tdt", durations=(0, 1, 300))
+    with pytest.raises(RnntBeamError, match="255"):
+        amd.BeamDecoder(ct, S.make_weights(ct, 1))  # a duration that does not fit a byte
     bad = enc.copy()
     bad[1, 2, 3] = np.nan
     dec.decode(to_gpu(bad, torch.float32), to_gpu(L, torch.int32))
