@@ -1686,7 +1686,8 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   }
   const int gid = blockIdx.x * 256 + threadIdx.x;
   // (the projection launch that follows adds its two halves into pre: cleared here, n_pre_clear = 0 otherwise)
-  for (int i = gid; i < n_pre_clear; i += M * P) store_through(pre_clear + i, 0.f);
+  // (16 bytes per store; n_pre_clear is a multiple of 4 and the array 16-byte aligned)
+  for (int i = 4 * gid; i < n_pre_clear; i += 4 * M * P) store16_through(pre_clear + i, floatx4{0.f, 0.f, 0.f, 0.f});
   const int m = gid / P, u = gid % P;
   if (m >= M) return;
   const int done_flag = *reinterpret_cast<const volatile int *>(done);
