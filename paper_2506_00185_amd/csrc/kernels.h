@@ -989,11 +989,17 @@ __device__ __forceinline__ void select_utterance(const SelectArgs &a, int b, Scr
       // branches in between, so that the LDS reads go out together
       const uint32_t mh = s.n_hash[j];
       const int ml = s.n_len[j], mla = s.n_last[j], mt = s.n_t[j], ms = s.n_sym[j];
-      uint32_t same = 0;
+      // (the hashes first, read without branches in between; the other fields only of the few slots whose hash is equal)
+      uint32_t same_hash = 0;
 #pragma unroll
       for (int i = 0; i < KMAX; ++i) {
-        const bool e = (i < K) & (s.n_live[i] != 0) & (s.n_hash[i] == mh) & (s.n_len[i] == ml) & (s.n_last[i] == mla) &
-                       (s.n_t[i] == mt) & (s.n_sym[i] == ms);
+        const bool e = (i < K) & (s.n_live[i] != 0) & (s.n_hash[i] == mh);
+        same_hash |= (uint32_t)e << i;
+      }
+      uint32_t same = 1u << j;
+      for (uint32_t r = same_hash & ~(1u << j); r; r &= r - 1u) {
+        const int i = __builtin_ctz(r);
+        const bool e = (s.n_len[i] == ml) & (s.n_last[i] == mla) & (s.n_t[i] == mt) & (s.n_sym[i] == ms);
         same |= (uint32_t)e << i;
       }
       const uint32_t lower = same & ((1u << j) - 1u);
