@@ -99,7 +99,7 @@ typedef struct {
                                 the most likely one that advances).  1: every (symbol, duration) pair is a candidate
                                 of its own, blank only with durations >= 1: Beam x (V + 1) x n_durations candidates
                                 per utterance and step.  Needs max_beam <= 8 */
-  int32_t async_enqueue;     /* 0: rnnt_beam_decode enqueues chunks of 16 steps, at most two ahead of the device, and
+  int32_t async_enqueue;     /* 0: rnnt_beam_decode enqueues chunks of 16 steps, one chunk ahead of the device, and
                                 returns once the device has reported that every utterance has finished (the calling
                                 thread is blocked for most of the decode).  1: it enqueues the upper bound of
                                 T (max_symbols + 1) steps at once and returns without waiting; steps after the last

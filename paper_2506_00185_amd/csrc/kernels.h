@@ -1,5 +1,5 @@
 // Kernels of the per-step beam expansion (gfx950).  One step of the loop is
-//   k_step_main (joint + selection in its tail + part of W_hh h) -> k_lstm_pointwise (+ LM rows) -> k_pred_proj
+//   k_step_main (joint + selection in its tail + part of W_hh h) -> k_lstm_pointwise -> k_pred_proj (+ LM rows)
 // for LSTM models (k_stateless_pre instead of the last two for stateless ones; k_inject -> k_select when the
 // log-probabilities are injected; a stand-alone k_select / k_select_wide / k_select_pairs where the tail cannot
 // take the selection), and k_gemm_tiled (gemm.h) / k_init / k_backtrace run once per decode call.
