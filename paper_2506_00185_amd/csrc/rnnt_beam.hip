@@ -258,7 +258,9 @@ bool proj_split(const rnnt_config_t &c, int M) {
 // of its own.  Measured per shape (us per step, blocks of 1 / 2 / 4 tiles): 224 slots 36.6 / 38.7 / 38.2, 256 slots
 // 41.4 / 41.7 / 40.6 (4 tiles: two blocks per gate tile, all resident at once), 288 slots 44.3 / 41.2 / 44.6, 320 slots
 // 46.6 / 44.3 / 48.3, 512 slots 73.3 / 66.8 / 69.7; at 128 slots single tiles are better (26.0 / 27.0 / 26.9): the
-// recurrent blocks run beside the joint blocks there, off the critical path.  (The kernels' fully unrolled form only.)
+// recurrent blocks run beside the joint blocks there, off the critical path.  Blocks of 3 tiles at 256 slots (216 blocks,
+// which need 27 free compute units per XCD): 3 to 7 % slower at six shapes tried, 2.5 % faster with LM rows in the
+// projection launch only (beam 8, batch 32).  (The kernels' fully unrolled form only.)
 int recurrent_group(const rnnt_config_t &c, int M) {
   const int m_tiles = (M + 31) / 32;
   if (c.pred != RNNT_PRED_LSTM || c.P != 640 || c.H != 640 || m_tiles < 8) return 1;
