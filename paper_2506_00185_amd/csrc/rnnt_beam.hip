@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -465,6 +467,8 @@ struct ScopedKernelTime {
 
 // steps per graph launch (even: the state parity flips every step)
 constexpr int kChunkSteps = 16;
+// the next chunk of steps is enqueued at least this long before the running one ends (a graph launch takes some 20 us)
+constexpr int kEnqueueMarginUs = 150;
 
 // Materialised-logits path: selection and next activations in the tail of the row kernel (two launches per step)
 // unless a candidate rule needs a selection kernel of its own.
@@ -979,8 +983,17 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   // written by the selection tells the host when every utterance has finished, and kernels of steps enqueued
   // after that point return at once (the rest of the chunk that was running, and the one enqueued behind it).  `ahead`: the upper bound of steps is enqueued
   // without looking at that word, so the call returns without waiting for the device.
+  // The chunk behind the running one is held back until the running one is well under way (the device's own time
+  // for the chunk before it says how long it takes): a decode that ends in that first part is not followed by a
+  // chunk of steps that only find out that there is nothing left to do.
+  using HostClock = std::chrono::steady_clock;
+  HostClock::time_point hold_until{};
+  bool hold = false;
   int enq = 0, chunk_i = 0;
   while (enq < max_steps) {
+    if (!p.ahead && hold)
+      while (!*reinterpret_cast<volatile int *>(h->h_done) && HostClock::now() < hold_until) {
+      }
     if (!p.ahead && *reinterpret_cast<volatile int *>(h->h_done)) break;
     if (use_graph) {
       RB_HIP(h, hipGraphLaunch(exec, s));
@@ -993,7 +1006,23 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
       RB_HIP(h, hipEventRecord(h->ev_chunk[chunk_i & 3], s));
       // one chunk ahead of the device: the next one goes in while this one runs (a chunk takes 250 us and up, a graph
       // launch some 20 us of this thread); a step enqueued after the end costs about 7 us, a second chunk ahead 16 of them
-      if (chunk_i >= 1) RB_HIP(h, hipEventSynchronize(h->ev_chunk[(chunk_i - 1) & 3]));
+      if (chunk_i >= 1) {
+        const HostClock::time_point before = HostClock::now();
+        RB_HIP(h, hipEventSynchronize(h->ev_chunk[(chunk_i - 1) & 3]));
+        // (the chunk enqueued just now has started: what the one before it took is what this one will take)
+        const HostClock::time_point now = HostClock::now();
+        // (a call that did not wait: this thread is behind the device, and nothing is held back)
+        hold = false;
+        float took_ms = 0.f;
+        if (chunk_i >= 2 && now - before >= std::chrono::microseconds(20) &&
+            hipEventElapsedTime(&took_ms, h->ev_chunk[(chunk_i - 2) & 3], h->ev_chunk[(chunk_i - 1) & 3]) == hipSuccess) {
+          const float took_us = 1e3f * took_ms, margin_us = std::max(0.4f * took_us, (float)kEnqueueMarginUs);
+          if (took_us > margin_us) {
+            hold = true;
+            hold_until = now + std::chrono::microseconds((long)(took_us - margin_us));
+          }
+        }
+      }
     }
     ++chunk_i;
   }
