@@ -173,7 +173,10 @@ int rnnt_lm_create(int32_t order, int64_t n, const int32_t *ngram_tokens, const 
  * that every utterance has finished and the back-trace has been enqueued, i.e. it blocks the calling
  * thread for most of the decode's duration (config field async_enqueue: enqueue everything and return).
  * Steps enqueued after the last utterance finished (under two chunks of them) still run; their kernels return at once.
- * The chunk behind the running one is enqueued when the running one is about 60 % through (the thread spins meanwhile).
+ * The chunk behind the running one is enqueued when the running one is about 60 % through; the thread spins meanwhile
+ * on two words of pinned host memory that the device writes (every utterance finished; a chunk begins).  Environment
+ * variable RNNT_BEAM_TRACE_PACING (read at create): a line on stderr whenever that report does not arrive within
+ * 200 ms and the thread waits for the stream instead.
  * Results stay valid until the next decode.  Graphs captured for a decode hold the LM's device tables: an LM
  * must outlive every decode that uses it, and at most 8 graphs (distinct B, T, beam, algo, LM, LM weight) are
  * kept per handle, the oldest being dropped.

@@ -1700,6 +1700,14 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
   lstm_cell(R, G, h_cur, c_cur, h_nxt, c_nxt, src_row[m], tok[m], m, u, Mp, P, done_flag);
 }
 
+// Advances the step counter at the boundary of two chunks of steps (one thread of one launch per chunk) and tells
+// the enqueueing host thread, through a word of pinned host memory, that the next chunk begins.
+__device__ __forceinline__ void bump_step(int *step_base, int bump, volatile int *h_progress) {
+  const int next = *step_base + bump;
+  *step_base = next;
+  if (h_progress) *h_progress = next;
+}
+
 // pre[m] = f_proj[b, t_m] + W_pred h[m] + b_pred: the input of the joint's ReLU, written k4-major.
 // W_pred: k4-major [P][H]; h: k4-major [P][Mp]; f_proj: row-major [B * T, H].
 struct PredProjArgs {
@@ -1710,6 +1718,7 @@ struct PredProjArgs {
   const int *done;
   int *step_base;
   int bump;
+  volatile int *h_progress = nullptr;  // see bump_step
   RecurrentArgs rec;   // recurrent tiles of the new state ride along
   XcdMap map;          // role 0 = projection (tile of H, 32-row tile), role 1 = recurrent
   LmRowsArgs lmr;      // blocks from lmr.first_block on build LM rows (lmr.M = 0: none)
@@ -1784,7 +1793,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj(PredProjArgs a) {
     recurrent_tile<WAVES, ITERS>(a.rec, tile, mtile * 32, done_flag, red);
     return;
   }
-  if (!done_flag && a.bump && tile == 0 && mtile == 0 && threadIdx.x == 0) *a.step_base += a.bump;
+  if (!done_flag && a.bump && tile == 0 && mtile == 0 && threadIdx.x == 0) bump_step(a.step_base, a.bump, a.h_progress);
   pred_proj_tile<WAVES, ITERS>(a, tile, mtile * 32, done_flag, red);
 }
 
@@ -1836,7 +1845,7 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
     }
   }
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P / 2, red, round_ops);
-  if (a.bump && tile == 0 && item == 0 && tid == 0) *a.step_base += a.bump;
+  if (a.bump && tile == 0 && item == 0 && tid == 0) bump_step(a.step_base, a.bump, a.h_progress);
   if (me >= a.M) return;
 #pragma unroll
   for (int q = 0; q < VPL; ++q)
@@ -1855,12 +1864,13 @@ struct StatelessPreArgs {
   const int *done;
   int *step_base;
   int bump;
+  volatile int *h_progress = nullptr;  // see bump_step
 };
 
 __global__ __launch_bounds__(256) void k_stateless_pre(StatelessPreArgs a) {
   if (*reinterpret_cast<const volatile int *>(a.done)) return;
   const int gid = blockIdx.x * 256 + threadIdx.x;
-  if (a.bump && gid == 0) *a.step_base += a.bump;
+  if (a.bump && gid == 0) bump_step(a.step_base, a.bump, a.h_progress);
   const int H4 = a.H >> 2;
   const int m = gid / H4, o4 = gid % H4;
   if (m >= a.M) return;
@@ -1884,9 +1894,9 @@ __global__ void k_fill_int(int *p, int value, int n) {
 }
 
 // advances the step counter when no prediction projection closes the step (stateless, injected)
-__global__ void k_bump(int *step_base, int bump, const int *done) {
+__global__ void k_bump(int *step_base, int bump, const int *done, volatile int *h_progress) {
   if (*reinterpret_cast<const volatile int *>(done)) return;
-  if (threadIdx.x == 0 && blockIdx.x == 0) *step_base += bump;
+  if (threadIdx.x == 0 && blockIdx.x == 0) bump_step(step_base, bump, h_progress);
 }
 
 // ---------------------------------------------------------------------------

@@ -47,6 +47,7 @@ struct BigJointArgs {
   const int *done;
   int *step_base;      // advanced by `bump` before anything of this step reads it (first step of a chunk of steps,
   int bump;            // when the selection runs in the tail of the row kernel and no later launch closes the step)
+  volatile int *h_progress = nullptr;  // see bump_step
 };
 
 // Z[m][n] = W_out[n] . a_m + b_out[n] for a block of 32 * WAVES columns x 160 hypotheses.
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(64 * WAVES, 8 / WAVES) void k_joint_big(BigJointArg
   __shared__ __align__(16) unsigned char lds_raw[kRingBytes > kEpiBytes ? kRingBytes : kEpiBytes];
   u32x4 (*tile)[NP][64] = reinterpret_cast<u32x4 (*)[NP][64]>(lds_raw);
   const int done = *reinterpret_cast<const volatile int *>(a.done);
-  if (a.bump && !done && blockIdx.x == 0 && threadIdx.x == 0) *a.step_base += a.bump;
+  if (a.bump && !done && blockIdx.x == 0 && threadIdx.x == 0) bump_step(a.step_base, a.bump, a.h_progress);
   int nb, mb;
   if (xcd_item(a.map, blockIdx.x, nb, mb) != 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, kg = lane >> 5;
@@ -218,6 +219,7 @@ struct StatelessPreBigArgs {
   const int *done;
   int *step_base;
   int bump;
+  volatile int *h_progress = nullptr;  // see bump_step
 };
 
 // a_m[8 o8 .. + 7] for hypothesis m of utterance b standing at frame tt with token history toks (most recent first)
@@ -287,7 +289,7 @@ __device__ __forceinline__ void stateless_pre_big_pair(const StatelessPreBigArgs
 __global__ __launch_bounds__(256) void k_stateless_pre_big(StatelessPreBigArgs a) {
   if (*reinterpret_cast<const volatile int *>(a.done)) return;
   const int gid = blockIdx.x * 256 + threadIdx.x;
-  if (a.bump && gid == 0) *a.step_base += a.bump;
+  if (a.bump && gid == 0) bump_step(a.step_base, a.bump, a.h_progress);
   const int H8 = a.H >> 3;
   const int m = gid / H8, o8 = gid % H8;
   if (m >= a.M) return;

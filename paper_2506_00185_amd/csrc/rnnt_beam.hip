@@ -183,12 +183,16 @@ struct rnnt_beam {
   char *h_out = nullptr;          // pinned: the last decode's control words and packed results (see out_pack)
   size_t h_out_bytes = 0;
   OutPack last_out{};
-  int *h_done = nullptr, *h_done_dev = nullptr;  // pinned host word and its device alias
+  // pinned host words and their device alias: [0] every utterance has finished, [kProgressWord] the step counter as
+  // the device advances it from chunk to chunk
+  int *h_done = nullptr, *h_done_dev = nullptr;
   // last decode
   bool have_result = false;
   int last_B = 0, last_K = 0, last_T = 0;
   hipStream_t last_stream = nullptr;
-  hipEvent_t ev_begin = nullptr, ev_end = nullptr, ev_chunk[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev_begin = nullptr, ev_end = nullptr;
+  bool pace_by_stream = false;  // set when the device's report of a chunk did not arrive in time once
+  bool trace_pacing = false;  // environment RNNT_BEAM_TRACE_PACING: a line on stderr when the pacing falls back
   bool profiling = false;
   bool events_off = false;  // set while the allocation-free entry point enqueues (no event may be created)
   std::vector<hipEvent_t> prof_events;              // pool, two per timed launch
@@ -469,6 +473,10 @@ struct ScopedKernelTime {
 constexpr int kChunkSteps = 16;
 // the next chunk of steps is enqueued at least this long before the running one ends (a graph launch takes some 20 us)
 constexpr int kEnqueueMarginUs = 150;
+// the word of the pinned pair that carries the step counter (a cache line away from the "done" word)
+constexpr int kProgressWord = 16;
+// the enqueueing thread waits this long for the device to report the next chunk before it waits for the stream itself
+constexpr int kPaceLimitMs = 200;
 
 // Materialised-logits path: selection and next activations in the tail of the row kernel (two launches per step)
 // unless a candidate rule needs a selection kernel of its own.
@@ -481,6 +489,7 @@ void fill_stateless_pre_big(rnnt_beam *h, const StepPlan &p, int bump, Stateless
   a.Ab = w.Ab;
   a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
   a.done = w.ctrl + 1; a.step_base = w.ctrl + 2; a.bump = bump;
+  a.h_progress = h->h_done_dev + kProgressWord;
 }
 
 // One-list selection forms: 16 / 12 for ALSD++ / AES++ (without prune margin and prefix search) on a plain RNN-T
@@ -502,7 +511,8 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
   int *done = w.ctrl + 1, *step_base = w.ctrl + 2;
   const int m_tiles = (p.M + 31) / 32;
   if (p.inj_tok) {
-    if (bump) hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done);
+    if (bump)
+      hipLaunchKernelGGL(k_bump, dim3(1), dim3(64), 0, s, step_base, bump, done, h->h_done_dev + kProgressWord);
   } else if (c.pred == RNNT_PRED_LSTM) {
     LmRowsArgs lm_rows{};
     const size_t lm_row_bytes = sizeof(float) * (size_t)c.V;
@@ -534,7 +544,7 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       a.pre = w.pre;
       a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
       a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
-      a.done = done; a.step_base = step_base; a.bump = bump;
+      a.done = done; a.step_base = step_base; a.bump = bump; a.h_progress = h->h_done_dev + kProgressWord;
       a.rec.Whh = h->W_hh; a.rec.h = w.h[cur ^ 1]; a.rec.R = w.Rgates;
       a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp; a.rec.group = 1;
       a.map.a_tiles = c.H / 32; a.map.a_m = m_tiles;
@@ -584,7 +594,7 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
     a.f_proj = w.f_proj; a.tab = h->tab; a.ctx_tok = w.ctx; a.t = w.t; a.lengths = w.lengths;
     a.pre = w.pre;
     a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.H = c.H; a.V = c.V; a.n_ctx = c.stateless_context;
-    a.done = done; a.step_base = step_base; a.bump = bump;
+    a.done = done; a.step_base = step_base; a.bump = bump; a.h_progress = h->h_done_dev + kProgressWord;
     ScopedKernelTime tm(h, s, KT_STATELESS);
     const int n = p.M * (c.H / 4);
     hipLaunchKernelGGL(k_stateless_pre, dim3((n + 255) / 256), dim3(256), 0, s, a);
@@ -692,6 +702,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
       a.done = done;
       a.step_base = w.ctrl + 2;
       a.bump = (big_tail(h, p) && step_off == 0) ? kChunkSteps : 0;
+      a.h_progress = h->h_done_dev + kProgressWord;
       ScopedKernelTime tm(h, s, KT_JOINTBIG);
       const dim3 grid(xcd_grid(a.map));
       // the kernel's loop runs in whole groups of D stages of k = 32; the operands are padded to k % 64 == 0
@@ -919,6 +930,7 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     a.step_base = step_base; a.bad_arg = bad_arg;
     a.h_done = h->h_done_dev;
     *reinterpret_cast<volatile int *>(h->h_done) = 0;
+    *reinterpret_cast<volatile int *>(h->h_done + kProgressWord) = 0;
     ScopedKernelTime tm(h, s, KT_INIT);
     hipLaunchKernelGGL(k_fill_int, dim3(1), dim3(64), 0, s, bad_arg, 0, 2);  // bad_arg, nonfinite
     hipLaunchKernelGGL(k_init, dim3(256), dim3(256), 0, s, a);
@@ -983,18 +995,23 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   // written by the selection tells the host when every utterance has finished, and kernels of steps enqueued
   // after that point return at once (the rest of the chunk that was running, and the one enqueued behind it).  `ahead`: the upper bound of steps is enqueued
   // without looking at that word, so the call returns without waiting for the device.
-  // The chunk behind the running one is held back until the running one is well under way (the device's own time
-  // for the chunk before it says how long it takes): a decode that ends in that first part is not followed by a
-  // chunk of steps that only find out that there is nothing left to do.
+  // One chunk ahead of the device: the next chunk goes in while this one runs (a chunk takes 250 us and up, a graph
+  // launch some 20 us of this thread); a step enqueued after the end costs about 7 us, a second chunk ahead 16 of
+  // them.  The device reports the begin of a chunk through the second pinned word (bump_step): an event recorded
+  // between two chunks would cost the stream 4-5 us each time.
+  // The chunk behind the running one is held back until the running one is well under way (what the chunk before it
+  // took says how long): a decode that ends in that first part is not followed by a chunk of steps that only find
+  // out that there is nothing left to do.
   using HostClock = std::chrono::steady_clock;
-  HostClock::time_point hold_until{};
-  bool hold = false;
+  volatile int *host_done = h->h_done, *host_progress = h->h_done + kProgressWord;
+  HostClock::time_point chunk_began{}, hold_until{};
+  bool have_began = false, hold = false;
   int enq = 0, chunk_i = 0;
   while (enq < max_steps) {
     if (!p.ahead && hold)
-      while (!*reinterpret_cast<volatile int *>(h->h_done) && HostClock::now() < hold_until) {
+      while (!*host_done && HostClock::now() < hold_until) {
       }
-    if (!p.ahead && *reinterpret_cast<volatile int *>(h->h_done)) break;
+    if (!p.ahead && *host_done) break;
     if (use_graph) {
       RB_HIP(h, hipGraphLaunch(exec, s));
     } else {
@@ -1002,27 +1019,34 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
         if ((rc = launch_step(h, s, p, i, i & 1, i == kChunkSteps - 1 ? kChunkSteps : 0))) return rc;
     }
     enq += kChunkSteps;
-    if (!p.ahead) {
-      RB_HIP(h, hipEventRecord(h->ev_chunk[chunk_i & 3], s));
-      // one chunk ahead of the device: the next one goes in while this one runs (a chunk takes 250 us and up, a graph
-      // launch some 20 us of this thread); a step enqueued after the end costs about 7 us, a second chunk ahead 16 of them
-      if (chunk_i >= 1) {
-        const HostClock::time_point before = HostClock::now();
-        RB_HIP(h, hipEventSynchronize(h->ev_chunk[(chunk_i - 1) & 3]));
-        // (the chunk enqueued just now has started: what the one before it took is what this one will take)
-        const HostClock::time_point now = HostClock::now();
-        // (a call that did not wait: this thread is behind the device, and nothing is held back)
-        hold = false;
-        float took_ms = 0.f;
-        if (chunk_i >= 2 && now - before >= std::chrono::microseconds(20) &&
-            hipEventElapsedTime(&took_ms, h->ev_chunk[(chunk_i - 2) & 3], h->ev_chunk[(chunk_i - 1) & 3]) == hipSuccess) {
-          const float took_us = 1e3f * took_ms, margin_us = std::max(0.4f * took_us, (float)kEnqueueMarginUs);
-          if (took_us > margin_us) {
-            hold = true;
-            hold_until = now + std::chrono::microseconds((long)(took_us - margin_us));
-          }
+    if (!p.ahead && chunk_i >= 1) {
+      // until the chunk enqueued just now begins, i.e. the one before it is over
+      const int target = kChunkSteps * chunk_i;
+      bool waited = false;
+      const HostClock::time_point limit = HostClock::now() + std::chrono::milliseconds(kPaceLimitMs);
+      while (!*host_done && *host_progress < target) {
+        waited = true;
+        // (no report in time: whatever is enqueued is waited for instead, from then on without the wait for a report)
+        if (h->pace_by_stream || HostClock::now() > limit) {
+          RB_HIP(h, hipStreamSynchronize(s));
+          if (h->trace_pacing) fprintf(stderr, "rnnt_beam: pacing fell back to the stream at chunk %d\n", chunk_i);
+          h->pace_by_stream = true;
+          break;
         }
       }
+      // (a wait that found the chunk begun already: this thread is behind the device, and nothing is held back)
+      const HostClock::time_point now = HostClock::now();
+      hold = false;
+      if (waited && have_began) {
+        const auto took = now - chunk_began;
+        const auto margin = std::max<HostClock::duration>(took * 2 / 5, std::chrono::microseconds(kEnqueueMarginUs));
+        if (took > margin) {
+          hold = true;
+          hold_until = now + (took - margin);
+        }
+      }
+      have_began = waited;
+      chunk_began = now;
     }
     ++chunk_i;
   }
@@ -1179,13 +1203,13 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     rc = RNNT_E_NOMEM;
   }
   if (!rc) {
-    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&h->h_done), 64, hipHostMallocMapped);
+    hipError_t e = hipHostMalloc(reinterpret_cast<void **>(&h->h_done), 128, hipHostMallocMapped);
     if (e == hipSuccess) e = hipHostGetDevicePointer(reinterpret_cast<void **>(&h->h_done_dev), h->h_done, 0);
     h->h_out_bytes = out_pack(c.max_B, c.max_beam, h->ws.cap).bytes;
     if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&h->h_out), h->h_out_bytes, hipHostMallocDefault);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
-    for (int i = 0; i < 4 && e == hipSuccess; ++i) e = hipEventCreate(&h->ev_chunk[i]);
+    h->trace_pacing = getenv("RNNT_BEAM_TRACE_PACING") != nullptr;
     if (e == hipSuccess && c.persistent_kernel) {
       // the single-launch loop needs every one of its blocks resident at once: one block per compute unit
       int dev = 0, n_cu = 0, per_cu = 0;
@@ -1451,7 +1475,7 @@ void rnnt_beam_destroy(rnnt_beam_t *h) {
   for (void *p : h->allocs) hipFree(p);
   if (h->h_done) hipHostFree(h->h_done);
   if (h->h_out) hipHostFree(h->h_out);
-  hipEvent_t evs[] = {h->ev_begin, h->ev_end, h->ev_chunk[0], h->ev_chunk[1], h->ev_chunk[2], h->ev_chunk[3]};
+  hipEvent_t evs[] = {h->ev_begin, h->ev_end};
   for (hipEvent_t e : h->prof_events) hipEventDestroy(e);
   for (hipEvent_t e : evs)
     if (e) hipEventDestroy(e);

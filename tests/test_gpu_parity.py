@@ -547,6 +547,46 @@ def test_async_enqueue_gives_the_same_result(amd):
                 np.testing.assert_array_equal(r[key], ref[key])
 
 
+def test_enqueue_pacing_hears_from_every_kind_of_step(amd, capfd, monkeypatch):
+    """The enqueueing thread follows the device through a pinned word that one launch per chunk of 16 steps writes.
+    Every kind of step (full-width and generic LSTM models, stateless, materialised logits with and without an LM,
+    injected log-probabilities) must write it: a decode of several chunks never has to fall back to waiting for the
+    stream (the library reports a fall-back on stderr when RNNT_BEAM_TRACE_PACING is set at create), and decodes the
+    same as with everything enqueued up front."""
+    monkeypatch.setenv("RNNT_BEAM_TRACE_PACING", "1")
+    cases = [
+        (S.custom_config(B=3, T=30, T_min=20, D=64, H=640, P=640, E=640, V=300, beam=4, s=3, algo="alsd"), {}),
+        (S.custom_config(B=3, T=30, T_min=20, D=64, H=640, P=640, E=640, V=300, beam=4, s=3, algo="alsd",
+                         prec="bf16"), {}),
+        (S.custom_config(B=3, T=30, T_min=20, D=64, H=160, P=96, E=96, V=300, beam=4, s=3, algo="aes"), {}),
+        (S.custom_config(B=3, T=30, T_min=20, D=64, H=160, P=96, E=96, V=300, beam=4, s=3, pred="stateless",
+                         ctx=2), {}),
+        (S.custom_config(B=3, T=30, T_min=20, D=64, H=160, P=96, E=96, V=300, beam=4, s=3, pred="stateless", ctx=2,
+                         prec="bf16"), dict(joint_path="materialized")),
+        (S.custom_config(B=3, T=30, T_min=20, D=64, H=160, P=96, E=96, V=300, beam=12, s=3, pred="stateless", ctx=2,
+                         prec="bf16"), dict(joint_path="materialized")),
+    ]
+    for i, (c, kw) in enumerate(cases):
+        w, L, enc = _case(c, 1200 + i)
+        r = gpu_decode(amd.BeamDecoder(c, w, **kw), enc, L)
+        assert r["n_steps"].max() > 2 * 16
+        ref = gpu_decode(amd.BeamDecoder(c, w, async_enqueue=True, **kw), enc, L)
+        for key in ("tokens", "lens", "scores", "n_steps"):
+            np.testing.assert_array_equal(r[key], ref[key])
+    c = S.custom_config(B=3, T=30, T_min=20, D=64, H=160, P=96, E=96, V=300, beam=5, s=3, pred="stateless", ctx=2,
+                        prec="bf16")
+    w, L, enc = _case(c, 1210)
+    lm = amd.NGramLM(S.make_lm(V=c["V"], order=3, n_target=5000, zipf_s=1.1, seed=5))
+    r = gpu_decode(amd.BeamDecoder(c, w, joint_path="materialized"), enc, L, lm=lm, lm_weight=0.3)
+    assert r["n_steps"].max() > 2 * 16
+    B, T, C, V = 2, 40, 3, 6
+    c = S.custom_config(B=B, T=T, T_min=30, D=32, H=32, P=32, E=32, V=V, beam=4, s=3, algo="alsd")
+    tok, _ = S.make_injected(B, T, C, V, 0, seed=78, levels=200, blank_boost=10)
+    r = gpu_decode_injected(amd.BeamDecoder(c, S.make_weights(c, 1)), tok, None, S.make_lengths(c, 3))
+    assert r["n_steps"].max() > 2 * 16
+    assert "pacing fell back" not in capfd.readouterr().err
+
+
 def test_split_projection_at_a_generic_width(amd, oracle):
     """P = 128: the prediction projection is split in two along k across blocks with the generic (any P % 128 == 0)
     form of the kernel, and all gate tiles ride in the main launch."""
