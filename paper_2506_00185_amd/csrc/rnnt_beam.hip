@@ -179,6 +179,7 @@ struct rnnt_beam {
   Workspace ws;         // the handle's own workspace, laid out for max_B / max_T / max_beam in one allocation
   PersistCtl *pctl = nullptr;  // counters of the single-launch step loop
   int n_cus = 0, spin_limit = kSpinLimit;
+  int max_lds = 64 * 1024;  // LDS a block may ask for on this device
   bool last_persistent = false;
   char *h_out = nullptr;          // pinned: the last decode's control words and packed results (see out_pack)
   size_t h_out_bytes = 0;
@@ -1074,7 +1075,9 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
       a.out_tokens = reinterpret_cast<int *>(base + h->last_out.tokens);
     }
     ScopedKernelTime tm(h, s, KT_BACKTRACE);
-    if (lds <= 64 * 1024) hipLaunchKernelGGL(k_backtrace<true>, dim3(p.B), dim3(kBacktraceThreads), lds, s, a);
+    // (beside the tree the kernel holds 16.1 KB of tables in LDS)
+    if (lds + 17 * 1024 <= (size_t)h->max_lds)
+      hipLaunchKernelGGL(k_backtrace<true>, dim3(p.B), dim3(kBacktraceThreads), lds, s, a);
     else hipLaunchKernelGGL(k_backtrace<false>, dim3(p.B), dim3(kBacktraceThreads), 0, s, a);
     // flags and results to pinned host memory in one copy behind the back-trace: rnnt_beam_results then only waits
     if (own) RB_HIP(h, hipMemcpyAsync(h->h_out, w.ctrl, h->last_out.bytes, hipMemcpyDeviceToHost, s));
@@ -1210,6 +1213,12 @@ int rnnt_beam_create(const rnnt_config_t *cfg, const rnnt_weights_t *w, rnnt_bea
     if (e == hipSuccess) e = hipEventCreate(&h->ev_begin);
     if (e == hipSuccess) e = hipEventCreate(&h->ev_end);
     h->trace_pacing = getenv("RNNT_BEAM_TRACE_PACING") != nullptr;
+    {
+      int dev = 0, lds = 0;
+      if (hipGetDevice(&dev) == hipSuccess &&
+          hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && lds >= 64 * 1024)
+        h->max_lds = lds;
+    }
     if (e == hipSuccess && c.persistent_kernel) {
       // the single-launch loop needs every one of its blocks resident at once: one block per compute unit
       int dev = 0, n_cu = 0, per_cu = 0;

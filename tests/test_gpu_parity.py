@@ -145,11 +145,13 @@ def test_injected_merge_heavy_tables_are_bit_exact(amd, oracle, algo, beam, V, m
     assert np.sum((m >= 0) & (m != slots)) >= 3, "the table does not exercise recombination"
 
 
-def test_injected_long_utterances_walk_the_tree_in_memory(amd, oracle):
-    """A tree of more than 64 KiB per utterance (steps x beam x 8 bytes) is walked back where it lies, not from an
-    on-chip copy; a shorter one beside it in the same batch ends earlier."""
-    B, T, C, V, beam, s = 2, 130, 3, 6, 8, 7
-    assert T * (s + 1) * beam * 8 > 64 * 1024
+@pytest.mark.parametrize("T,beam,tree_kib", [(130, 8, 64), (150, 16, 144)])
+def test_injected_long_utterances_walk_the_tree_in_memory(amd, oracle, T, beam, tree_kib):
+    """Trees of more than 64 KiB per utterance (steps x beam x 8 bytes), and of more than the back-trace can hold in
+    LDS beside its tables (160 - 17 KiB), which is then walked back where it lies, not from an on-chip copy; a
+    shorter utterance beside it in the same batch ends earlier."""
+    B, C, V, s = 2, 3, 6, 7
+    assert T * (s + 1) * beam * 8 > tree_kib * 1024
     c = S.custom_config(B=B, T=T, T_min=3, D=32, H=32, P=32, E=32, V=V, beam=beam, s=s, algo="alsd")
     L = np.array([T, 41], np.int32)
     tok, _ = S.make_injected(B, T, C, V, 0, seed=77, levels=200, blank_boost=10)
