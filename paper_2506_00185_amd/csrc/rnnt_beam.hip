@@ -994,8 +994,9 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   }
   // The number of steps depends on the data.  Chunks of steps are enqueued ahead of the device; a pinned word
   // written by the selection tells the host when every utterance has finished, and kernels of steps enqueued
-  // after that point return at once (the rest of the chunk that was running, and the one enqueued behind it).  `ahead`: the upper bound of steps is enqueued
-  // without looking at that word, so the call returns without waiting for the device.
+  // after that point return at once (the rest of the chunk that was running, and the one enqueued behind it).
+  // `ahead`: the upper bound of steps is enqueued without looking at that word, so the call returns without waiting
+  // for the device.
   // One chunk ahead of the device: the next chunk goes in while this one runs (a chunk takes 250 us and up, a graph
   // launch some 20 us of this thread); a step enqueued after the end costs about 7 us, a second chunk ahead 16 of
   // them.  The device reports the begin of a chunk through the second pinned word (bump_step): an event recorded
