@@ -64,7 +64,9 @@ enum {
   RNNT_E_ARG = -1,       /* bad argument, or a shape beyond max_B / max_T / max_beam */
   RNNT_E_NOMEM = -2,     /* device or host allocation failed */
   RNNT_E_HIP = -3,       /* a HIP call failed */
-  RNNT_E_NONFINITE = -4, /* NaN or Inf found in the encoder projection of the last decode */
+  RNNT_E_NONFINITE = -4, /* NaN or Inf found in the encoder projection of the last decode (frames in use; those
+                            behind an utterance's length are looked at only where a tile of the product holds
+                            frames in use as well) */
   RNNT_E_NORESULT = -5   /* results requested before any decode */
 };
 
@@ -242,7 +244,8 @@ int rnnt_beam_dump_tree(rnnt_beam_t *h, int32_t *parent, int32_t *token, int32_t
 
 /*
  * Test hooks for single stages, all device float32, synchronous:
- *   rnnt_beam_debug_encproj : f_proj [B*T, H] of the last decode is copied to host `out`.
+ *   rnnt_beam_debug_encproj : f_proj [B*T, H] of the last decode is copied to host `out` (frames behind an
+ *                             utterance's length are not all computed: their rows hold anything).
  *   rnnt_beam_debug_lm      : LM scores (natural log) of every token after each of n contexts;
  *                             ctx_tokens host [n, order-1], most recent token first, -1 = none;
  *                             out host [n, V].

@@ -32,6 +32,11 @@ struct GemmArgs {
   int M, N, K;
   int n_mt, n_nt;  // tiles along M and N
   int *nonfinite;  // nullable: set to 1 when an output is NaN or Inf
+  // nullable: the rows are B utterances of T frames each and lengths[b] of them are in use (values outside 0..T are
+  // clamped here as the decode clamps them); a tile all of whose rows lie behind their utterance's last frame is
+  // left out (frame 0 of every utterance is always computed).  C keeps whatever it held in those rows.
+  const int *lengths;
+  int T;
 };
 
 __host__ inline int gemm_grid(int n_mt, int n_nt) { return 8 * ((n_mt + 7) / 8) * n_nt; }
@@ -47,6 +52,16 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(GemmArgs a) {
   const int mt = (s / a.n_nt) * 8 + x, nt = s % a.n_nt;
   if (mt >= a.n_mt) return;
   const int m0 = mt * BM, n0 = nt * BN;
+  if (a.lengths) {  // (uniform over the block)
+    const int last = min(m0 + BM, a.M) - 1;
+    bool needed = false;
+    for (int b = m0 / a.T; b <= last / a.T; ++b) {
+      const int first_t = max(m0 - b * a.T, 0);  // the utterance's first frame inside the tile
+      const int len = min(max(a.lengths[b], 1), a.T);
+      needed |= first_t < len;
+    }
+    if (!needed) return;
+  }
   const int wm0 = (wave >> 1) * 32 * WM, wn0 = (wave & 1) * 32 * WN;
   // staging: thread -> (row tid / 8 + 32 i, floats 4 (tid % 8) .. + 3) of the chunk
   const int srow = tid >> 3, sc4 = tid & 7;

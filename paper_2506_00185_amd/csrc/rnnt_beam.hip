@@ -291,8 +291,8 @@ int recurrent_split(const rnnt_config_t &c, int M) {
 
 // C = A B^T + bias through the LDS-tiled kernel; round_ops: bf16 operands on the bf16 matrix instructions
 int launch_gemm(rnnt_beam *h, hipStream_t s, const float *A, const float *B, const float *bias, float *C, int M, int N,
-                int K, int round_ops, int *nonfinite) {
-  GemmArgs a{A, B, bias, C, M, N, K, 0, 0, nonfinite};
+                int K, int round_ops, int *nonfinite, const int *lengths = nullptr, int T = 0) {
+  GemmArgs a{A, B, bias, C, M, N, K, 0, 0, nonfinite, lengths, T};
   auto go = [&](auto kernel, int bm, int bn, size_t lds) {
     a.n_mt = (M + bm - 1) / bm;
     a.n_nt = (N + bn - 1) / bn;
@@ -939,8 +939,9 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
   RB_HIP(h, hipGetLastError());
   if (!p.inj_tok) {
     ScopedKernelTime tm(h, s, KT_ENCPROJ);
+    // (the frames behind an utterance's last one are never read: tiles that hold nothing else are left out)
     int rc = launch_gemm(h, s, enc, h->W_enc, h->b_enc, w.f_proj, p.B * p.T, c.H, c.D,
-                         c.prec == RNNT_BF16_JOINT ? 1 : 0, nonfinite);
+                         c.prec == RNNT_BF16_JOINT ? 1 : 0, nonfinite, lengths, p.T);
     if (rc) return rc;
   }
   // every utterance has finished after at most T (s + 1) steps (the selection enforces it)

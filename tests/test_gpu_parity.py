@@ -48,20 +48,26 @@ def _case(c, seed, perturb=True, zero_len=False):
 
 # ---------------------------------------------------------------- single stages
 
-@pytest.mark.parametrize("prec,B,T,D,H", [("f32", 3, 37, 96, 64), ("bf16", 3, 37, 96, 64), ("f32", 5, 77, 160, 224),
-                                          ("bf16", 40, 60, 64, 160)])
-def test_encoder_projection_matches_oracle(amd, oracle, prec, B, T, D, H):
-    """Every frame of every utterance, ragged tiles along both axes; the bf16 variant rounds both operands to
-    nearest even (a truncating conversion would show at this tolerance) and takes the 128 x 128 tile from 2048
-    frames up."""
-    c = S.custom_config(B=B, T=T, T_min=T - 5, D=D, H=H, P=32, E=32, V=40, beam=2, s=2, prec=prec)
-    w, L, enc = _case(c, 300)
+@pytest.mark.parametrize("prec,B,T,T_min,D,H", [("f32", 3, 37, 32, 96, 64), ("bf16", 3, 37, 32, 96, 64),
+                                                ("f32", 5, 77, 72, 160, 224), ("bf16", 40, 60, 55, 64, 160),
+                                                ("f32", 7, 300, 3, 64, 96), ("bf16", 12, 300, 3, 64, 96)])
+def test_encoder_projection_matches_oracle(amd, oracle, prec, B, T, T_min, D, H):
+    """Every frame of every utterance up to its length (tiles of the product that hold nothing but frames behind
+    the ends of their utterances are left out: the last two cases have many), ragged tiles along both axes; the bf16
+    variant rounds both operands to nearest even (a truncating conversion would show at this tolerance) and takes
+    the 128 x 128 tile from 2048 frames up."""
+    c = S.custom_config(B=B, T=T, T_min=T_min, D=D, H=H, P=32, E=32, V=40, beam=2, s=1, prec=prec)
+    w, L, enc = _case(c, 300, zero_len=T_min < 10)
     dec = amd.BeamDecoder(c, w)
     gpu_decode(dec, enc, L, want_tree=False)
     f = dec.debug_encproj(c["B"], c["T"])
     rng = np.random.default_rng(5)
-    picks = [(0, 0), (B - 1, T - 1), (B // 2, T // 2)] + [(int(rng.integers(B)), int(rng.integers(T))) for _ in range(12)]
+    picks = [(0, 0), (B - 1, L[B - 1] - 1), (B // 2, L[B // 2] // 2)]
+    picks += [(b, L[b] - 1) for b in range(B) if L[b] > 0]                   # the last frame in use of each utterance
+    picks += [(b, int(rng.integers(max(L[b], 1)))) for b in rng.integers(B, size=12)]
     for b, t in picks:
+        if t < 0:
+            continue
         np.testing.assert_allclose(f[b * c["T"] + t], oracle.enc_proj(c, w, enc[b, t]), atol=2e-5, rtol=0)
 
 
