@@ -1926,10 +1926,15 @@ struct InitArgs {
 __global__ void k_init(InitArgs a) {
   const int gid = blockIdx.x * blockDim.x + threadIdx.x;
   const int M = a.B * a.K;
-  if (gid == 0) {
-    *a.step_base = a.step_base_init;
+  if (blockIdx.x == 0) {  // the utterances, one per thread of the first block (one thread for all took 0.2 us each)
+    __shared__ int s_nfin;
+    if (threadIdx.x == 0) {
+      s_nfin = 0;
+      *a.step_base = a.step_base_init;
+    }
+    __syncthreads();
     int nfin = 0;
-    for (int b = 0; b < a.B; ++b) {
+    for (int b = threadIdx.x; b < a.B; b += blockDim.x) {
       int L = a.lengths_in[b];
       if (L < 0 || L > a.T) {
         *a.bad_arg = 1;
@@ -1940,9 +1945,13 @@ __global__ void k_init(InitArgs a) {
       a.utt_steps[b] = L == 0 ? 0 : -1;
       nfin += L == 0;
     }
-    *a.n_finished = nfin;
-    *a.done = nfin == a.B;
-    *a.h_done = nfin == a.B;
+    if (nfin) atomicAdd(&s_nfin, nfin);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      *a.n_finished = s_nfin;
+      *a.done = s_nfin == a.B;
+      *a.h_done = s_nfin == a.B;
+    }
   }
   if (gid < M) {
     const int k = gid % a.K;
