@@ -192,7 +192,8 @@ struct rnnt_beam {
   int last_B = 0, last_K = 0, last_T = 0;
   hipStream_t last_stream = nullptr;
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
-  bool pace_by_stream = false;  // set when the device's report of a chunk did not arrive in time once
+  int pace_misses = 0;          // times the device's report of a chunk did not arrive in time
+  bool pace_by_stream = false;  // set at the third: from then on the stream is waited for at once
   bool trace_pacing = false;  // environment RNNT_BEAM_TRACE_PACING: a line on stderr when the pacing falls back
   bool profiling = false;
   bool events_off = false;  // set while the allocation-free entry point enqueues (no event may be created)
@@ -1029,11 +1030,11 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
       const HostClock::time_point limit = HostClock::now() + std::chrono::milliseconds(kPaceLimitMs);
       while (!*host_done && *host_progress < target) {
         waited = true;
-        // (no report in time: whatever is enqueued is waited for instead, from then on without the wait for a report)
+        // (no report in time: whatever is enqueued is waited for instead; from the third time on at once)
         if (h->pace_by_stream || HostClock::now() > limit) {
           RB_HIP(h, hipStreamSynchronize(s));
           if (h->trace_pacing) fprintf(stderr, "rnnt_beam: pacing fell back to the stream at chunk %d\n", chunk_i);
-          h->pace_by_stream = true;
+          if (++h->pace_misses >= 3) h->pace_by_stream = true;  // (a stall or two of the device changes nothing)
           break;
         }
       }
