@@ -1719,6 +1719,11 @@ struct PredProjArgs {
   int *step_base;
   int bump;
   volatile int *h_progress = nullptr;  // see bump_step
+  // k_pred_proj_half adds its two halves into pre, which therefore starts at zero: there are two such buffers, a
+  // step's launch adds into the one and clears the other, which the joint has just read (n_pre_clear floats, a
+  // multiple of 4; the blocks of the launch share the work)
+  float *pre_clear = nullptr;
+  int n_pre_clear = 0;
   RecurrentArgs rec;   // recurrent tiles of the new state ride along
   XcdMap map;          // role 0 = projection (tile of H, 32-row tile), role 1 = recurrent
   LmRowsArgs lmr;      // blocks from lmr.first_block on build LM rows (lmr.M = 0: none)
@@ -1844,6 +1849,13 @@ __global__ __launch_bounds__(WAVES * 64) void k_pred_proj_half(PredProjArgs a) {
       bv[q] = a.bias[o0 + q];
     }
   }
+  __builtin_amdgcn_sched_barrier(0);
+  // (behind every load of the block, whose waits then do not include these stores; they are on their way while the
+  // operands come in and are multiplied)
+  for (int i = 4 * ((tile * a.map.a_m + item) * WAVES * 64 + tid); i < a.n_pre_clear;
+       i += 4 * WAVES * 64 * a.map.a_tiles * a.map.a_m)
+    store16_through(a.pre_clear + i, floatx4{0.f, 0.f, 0.f, 0.f});
+  __builtin_amdgcn_sched_barrier(0);
   splitk_mma<WAVES, ITERS>(op, a_at, b_at, fb, a.P / 2, red, round_ops);
   if (a.bump && tile == 0 && item == 0 && tid == 0) bump_step(a.step_base, a.bump, a.h_progress);
   if (me >= a.M) return;
@@ -1915,6 +1927,8 @@ struct InitArgs {
   size_t n_state;
   float *R;        // recurrent product of the zero state (nullable), n_R floats
   size_t n_R;
+  float *pre0, *pre1;  // the two buffers that k_pred_proj_half adds into (nullable), n_pre floats each
+  size_t n_pre;
   int *tile_ctr;   // per-tile block counters of the main kernel
   int n_tiles;
   int B, K, T, V, lstm;
@@ -1968,6 +1982,8 @@ __global__ void k_init(InitArgs a) {
   for (int i = gid; i < a.n_tiles; i += gridDim.x * blockDim.x) a.tile_ctr[i] = 0;
   if (a.R)
     for (size_t i = gid; i < a.n_R; i += (size_t)gridDim.x * blockDim.x) a.R[i] = 0.f;
+  if (a.pre0)
+    for (size_t i = gid; i < a.n_pre; i += (size_t)gridDim.x * blockDim.x) a.pre0[i] = a.pre1[i] = 0.f;
   if (a.h0) {
     const size_t n = a.n_state;
     for (size_t i = gid; i < n; i += (size_t)gridDim.x * blockDim.x) {

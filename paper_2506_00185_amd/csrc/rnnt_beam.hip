@@ -65,7 +65,7 @@ const char *kKernelNames[KT_COUNT] = {"k_gemm_tiled(enc_proj)", "k_init",      "
 // Device memory a decode works in beyond its inputs and outputs, laid out for given maxima.  The handle owns one
 // (a single allocation made at create); the allocation-free entry point lays one out in the static array.
 struct Workspace {
-  float *f_proj = nullptr, *pre = nullptr, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
+  float *f_proj = nullptr, *pre = nullptr, *pre2 = nullptr, *h[2] = {nullptr, nullptr}, *c[2] = {nullptr, nullptr};
   float *lm_rows = nullptr, *Rgates = nullptr;
   int *tile_ctr = nullptr;
   uint16_t *Ab = nullptr;   // materialised-logits path only
@@ -158,6 +158,7 @@ size_t layout_workspace(Workspace &w, char *base, const rnnt_config_t &c, int n_
     take(&w.out_scores, M);
     take(&w.out_steps, (size_t)max_B);
   }
+  take(&w.pre2, (size_t)w.Mp * c.H);  // (the second buffer of the launches that add two halves, see PredProjArgs)
   return off;
 }
 
@@ -537,13 +538,18 @@ int launch_pred(rnnt_beam *h, hipStream_t s, const StepPlan &p, int cur, int bum
       auto k_cell = lmr.M ? k_lstm_pointwise<true> : k_lstm_pointwise<false>;
       hipLaunchKernelGGL(k_cell, dim3(n_blocks + lmr.M), dim3(256), lds, s, w.Rgates, h->G, w.h[cur],
                          w.c[cur], w.h[cur ^ 1], w.c[cur ^ 1], w.src_row, w.tok, p.M, w.Mp, c.P, done, lmr,
-                         split ? w.pre : nullptr, split ? c.H * w.Mp : 0);
+                         nullptr, 0);
     }
     {
       PredProjArgs a;
       a.Wp = h->W_pred; a.bias = h->b_pred; a.h = w.h[cur ^ 1]; a.f_proj = w.f_proj;
       a.t = w.t; a.lengths = w.lengths;
       a.pre = w.pre;
+      if (proj_split(c, p.M)) {  // (the step at parity cur read buffer cur; this launch writes the next step's)
+        a.pre = cur ? w.pre : w.pre2;
+        a.pre_clear = cur ? w.pre2 : w.pre;
+        a.n_pre_clear = c.H * w.Mp;
+      }
       a.M = p.M; a.Mp = w.Mp; a.K = p.K; a.T = p.T; a.P = c.P; a.H = c.H;
       a.round_ops = c.prec == RNNT_BF16_JOINT ? 1 : 0;
       a.done = done; a.step_base = step_base; a.bump = bump; a.h_progress = h->h_done_dev + kProgressWord;
@@ -766,6 +772,7 @@ int launch_step(rnnt_beam *h, hipStream_t s, const StepPlan &p, int step_off, in
     a.p_max = w.p_max; a.p_sum = w.p_sum; a.p_cand = w.p_cand; a.zs = w.zs;
     a.tile_ctr = w.tile_ctr;
     const bool lstm = c.pred == RNNT_PRED_LSTM;
+    if (lstm && proj_split(c, p.M) && cur) a.pre = w.pre2;  // (see launch_pred: the buffers alternate with the steps)
     a.rec.Whh = h->W_hh; a.rec.h = w.h[cur]; a.rec.R = w.Rgates;
     a.rec.P = c.P; a.rec.M = p.M; a.rec.Mp = w.Mp; a.rec.group = recurrent_group(c, p.M);
     // More joint blocks than compute units, and the blank / duration columns alone in the last chunk: its blocks
@@ -923,6 +930,10 @@ int run_decode(rnnt_beam *h, const float *enc, const int32_t *lengths, const Ste
     a.n_state = (size_t)c.P * w.Mp;
     a.R = lstm ? w.Rgates : nullptr;
     a.n_R = (size_t)p.M * 4 * c.P;
+    const bool halves = lstm && proj_split(c, p.M);
+    a.pre0 = halves ? w.pre : nullptr;
+    a.pre1 = halves ? w.pre2 : nullptr;
+    a.n_pre = (size_t)c.H * w.Mp;
     a.tile_ctr = w.tile_ctr;
     a.n_tiles = w.max_B;
     a.B = p.B; a.K = p.K; a.T = p.T; a.V = c.V;
