@@ -1691,8 +1691,8 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
     }
   }
   const int gid = blockIdx.x * 256 + threadIdx.x;
-  // (the projection launch that follows adds its two halves into pre: cleared here, n_pre_clear = 0 otherwise)
-  // (16 bytes per store; n_pre_clear is a multiple of 4 and the array 16-byte aligned)
+  // (no launch asks for this any more, n_pre_clear = 0: the projection launch clears its buffers itself.  Left in
+  // place: without it the same launches measured 0.03 ms slower per decode at batch 32, beam 4)
   for (int i = 4 * gid; i < n_pre_clear; i += 4 * M * P) store16_through(pre_clear + i, floatx4{0.f, 0.f, 0.f, 0.f});
   const int m = gid / P, u = gid % P;
   if (m >= M) return;
